@@ -1,0 +1,185 @@
+/*
+ * dc.h - C ABI of the MI355X Data Coordinator reshard path.
+ *
+ * The path is what the paper's Data Coordinator does when two consecutive RL
+ * stages use different data-parallel layouts (Sec. 6, "Distributed Databuffer"
+ * and "Load Balancing"; App. B: the advantage -> actor-log-prob transition is
+ * the one DP-layout change of a GRPO step):
+ *
+ *   dc_balance          Algorithm 1, Constrained LPT Load Balancing: N sequence
+ *                       lengths -> P shards of (by default) exactly N/P sequences.
+ *   dc_group_advantage  the "advantage" stage of GRPO (Sec. 1 payload list,
+ *                       App. B Table 2): each response's reward normalised by
+ *                       its prompt group's mean and std, then broadcast over the
+ *                       response's loss-bearing tokens, in the rollout layout.
+ *   dc_plan             packed training layout of the P shards: token offsets,
+ *                       token-budget micro-batches, cu_seqlens.
+ *   dc_gather           segmented copy of every per-token field from the rollout
+ *                       layout into the packed training layout.
+ *   dc_repack           dc_plan followed by dc_gather.
+ *
+ * Conventions
+ *   - Pointers named d_* are DEVICE pointers (gfx950, current HIP device).  All
+ *     other pointers are HOST pointers, read during the call only.
+ *   - The caller owns every buffer: inputs, outputs and workspace.  The library
+ *     allocates nothing and keeps no state between calls.
+ *   - Every call only enqueues kernels on `hip_stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and returns; nothing synchronises.
+ *   - The return value reports what the host can check without a sync.  Errors
+ *     that depend on device data are written by the kernels to *d_status (an
+ *     int32 the caller zeroes beforehand; the first error wins; outputs are then
+ *     unspecified but no access leaves the caller's buffers).
+ *   - Identical inputs give bit-identical outputs on every run.
+ *
+ * Layouts
+ *   Rollout (source) layout: n_src_shards packed buffers per field.  Rollout shard
+ *   s holds sequences [shard_seq_off[s], shard_seq_off[s+1]) in index order;
+ *   sequence i occupies elements [d_src_tok_off[i], d_src_tok_off[i] + seq_len[i])
+ *   of its shard's buffer (offsets restart in every shard, non-overlapping,
+ *   increasing with i inside a shard).  A sequence is prompt tokens then response
+ *   tokens.  Prompt groups are contiguous runs of sequences, d_group_off is their
+ *   CSR offset array.
+ *
+ *   Training (destination) layout: one arena per field.  Output slot j holds
+ *   sequence d_perm[j]; shard p owns slots [d_shard_seq_off[p], d_shard_seq_off[p+1])
+ *   and the token range [d_shard_tok_off[p], d_shard_tok_off[p] + load_p);
+ *   d_shard_tok_off[p+1] is that end rounded up to align_tokens (padding elements
+ *   are never written).  Slot j starts at element d_dst_tok_off[j].
+ *   Micro-batch m covers slots [d_mb_seq_off[m], d_mb_seq_off[m+1]), never spans
+ *   shards, and is built by next-fit in slot order: a slot joins the open
+ *   micro-batch iff its tokens still fit under token_budget.  Its cu_seqlens slice
+ *   has n_m + 1 int32 entries starting at index d_mb_seq_off[m] + m: 0, then the
+ *   running token totals.  Shard p owns micro-batches
+ *   [d_shard_mb_off[p], d_shard_mb_off[p+1]).
+ */
+#ifndef DC_H
+#define DC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DC_MAX_SEQ        16384   /* N: one workgroup sorts and plans in LDS          */
+#define DC_MAX_SHARDS     64      /* P: one wavefront lane per shard                  */
+#define DC_MAX_FIELDS     8
+#define DC_MAX_SRC_SHARDS 16
+#define DC_MAX_SEQ_LEN    (1 << 24)
+
+typedef enum dc_status {
+    DC_OK = 0,
+    DC_ERR_INVALID_ARG = 1,        /* null pointer, bad size, bad alignment, bad index data      */
+    DC_ERR_NOT_DIVISIBLE = 2,      /* cap = 0 and N mod P != 0 (Algorithm 1's assertion)         */
+    DC_ERR_UNSUPPORTED_SIZE = 3,   /* N, P, field or rollout-shard count above the DC_MAX_* limit*/
+    DC_ERR_WORKSPACE = 4,          /* workspace smaller than dc_workspace_bytes()                */
+    DC_ERR_HIP = 5,                /* a HIP runtime call failed                                  */
+    DC_ERR_SEQ_EXCEEDS_BUDGET = 6, /* device: a sequence is longer than token_budget             */
+    DC_ERR_ZERO_LENGTH_SEQ = 7,    /* device: a sequence length is <= 0 (or > DC_MAX_SEQ_LEN)    */
+    DC_ERR_OVERFLOW = 8,           /* device: packed layout does not fit dst_capacity_tokens     */
+    DC_ERR_BAD_LAYOUT = 9          /* device: rollout offsets out of range / overlapping, group
+                                      offsets not monotone, perm not a permutation               */
+} dc_status;
+
+typedef struct dc_params {
+    int32_t n_seq;          /* N                                                              */
+    int32_t n_shards;       /* P  (K of Algorithm 1), 1..DC_MAX_SHARDS                        */
+    int32_t cap;            /* 0: C = N/P as in Algorithm 1; >0: per-shard item limit
+                               (cap >= N makes the constraint vacuous: textbook LPT)          */
+    int32_t align_tokens;   /* >= 1; shard starts are multiples of it (1 = dense)             */
+    int64_t token_budget;   /* micro-batch token cap, 1 .. 2^31-1                             */
+    double  eps;            /* added to the group std                                         */
+    int32_t ddof;           /* 0 population std, 1 Bessel-corrected                           */
+    int32_t reserved;       /* must be 0                                                      */
+} dc_params;
+
+/* Where the sequences live in the rollout layout. */
+typedef struct dc_source {
+    int32_t        n_src_shards;   /* 1..DC_MAX_SRC_SHARDS                                    */
+    int32_t        reserved;       /* must be 0                                               */
+    const int32_t* shard_seq_off;  /* HOST [n_src_shards+1], [0]=0, last=N, non-decreasing    */
+    const int64_t* shard_tokens;   /* HOST [n_src_shards], elements each rollout buffer holds */
+    const int64_t* d_src_tok_off;  /* DEVICE [N]                                              */
+} dc_source;
+
+/* One per-token field.  src_base[s] and dst must be 16-byte aligned device pointers. */
+typedef struct dc_field {
+    const void* const* src_base;   /* HOST [n_src_shards] device base pointers                */
+    void*              d_dst;      /* DEVICE arena of dst_capacity_tokens elements            */
+    int32_t            elem_bytes; /* 1, 2 or 4                                               */
+    int32_t            reserved;   /* must be 0                                               */
+} dc_field;
+
+/* Bytes of device workspace dc_plan / dc_gather / dc_repack need for these sizes. */
+size_t dc_workspace_bytes(const dc_params* prm, int64_t dst_capacity_tokens);
+
+/*
+ * Algorithm 1 (Constrained LPT Load Balancing).
+ *   I = argsort(d_seq_len, descending), equal lengths in ascending index order;
+ *   each u in I goes to the worker with the lexicographically smallest (load, k)
+ *   among workers holding fewer than C items; its load grows by the length.
+ * Outputs (device): d_perm[N] members of P_0, P_1, ... in insertion order;
+ * d_shard_seq_off[P+1]; d_shard_of_seq[N]; d_shard_load[P] (tokens).
+ * Host errors: INVALID_ARG, NOT_DIVISIBLE, UNSUPPORTED_SIZE, HIP.
+ * Device errors: ZERO_LENGTH_SEQ.
+ */
+dc_status dc_balance(const dc_params* prm, const int32_t* d_seq_len,
+                     int32_t* d_perm, int32_t* d_shard_seq_off, int32_t* d_shard_of_seq,
+                     int64_t* d_shard_load, int32_t* d_status, void* hip_stream);
+
+/*
+ * Group-relative advantage.  For group g with rewards r_1..r_G (float32):
+ *   mean = sum r / G,  var = sum (r - mean)^2 / (G - ddof),
+ *   A_i = (r_i - mean) / (sqrt(var) + eps), evaluated in float64, stored as float32.
+ *   A group with G - ddof <= 0, or whose rewards are all bit-identical, gets +0.
+ * d_adv_seq[N] receives A_i.  If adv_tok_src_base != NULL, each rollout shard s also
+ * gets its per-token advantages: element t of sequence i is A_i where
+ * mask_src_base[s][t] != 0 and +0.0f elsewhere; elements outside every sequence are
+ * left untouched.  mask_src_base / adv_tok_src_base: HOST arrays [n_src_shards] of
+ * 16-byte aligned device pointers (uint8 / float32 buffers of shard_tokens[s] elements).
+ * Device errors: BAD_LAYOUT, ZERO_LENGTH_SEQ.
+ */
+dc_status dc_group_advantage(const dc_params* prm, const dc_source* src, const int32_t* d_seq_len,
+                             const float* d_reward, const int32_t* d_group_off, int32_t n_groups,
+                             const uint8_t* const* mask_src_base, float* d_adv_seq,
+                             float* const* adv_tok_src_base, int32_t* d_status, void* hip_stream);
+
+/*
+ * Plan of the packed training layout (see "Layouts").  Outputs (device):
+ * d_dst_tok_off[N+1] (last = d_shard_tok_off[P]), d_shard_tok_off[P+1], d_shard_mb_off[P+1],
+ * d_mb_seq_off[N+1] (first M+1 entries valid), d_cu_seqlens[2N] (first N+M valid), d_n_mb[1] = M.
+ * Also fills the workspace with what dc_gather needs.  dst_capacity_tokens is the
+ * element count of every destination arena.
+ * Device errors: ZERO_LENGTH_SEQ, SEQ_EXCEEDS_BUDGET, OVERFLOW, BAD_LAYOUT.
+ */
+dc_status dc_plan(const dc_params* prm, const dc_source* src, const int32_t* d_seq_len,
+                  const int32_t* d_perm, const int32_t* d_shard_seq_off, int64_t dst_capacity_tokens,
+                  int64_t* d_dst_tok_off, int64_t* d_shard_tok_off, int32_t* d_shard_mb_off,
+                  int32_t* d_mb_seq_off, int32_t* d_cu_seqlens, int32_t* d_n_mb,
+                  void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream);
+
+/*
+ * Segmented gather: for every slot j and field f copy seq_len[perm[j]] elements from
+ * the sequence's place in the rollout layout to element d_dst_tok_off[j] of f.d_dst,
+ * as raw bytes.  Must follow a dc_plan on the same stream with the same prm, src,
+ * dst_capacity_tokens, d_dst_tok_off and workspace.
+ */
+dc_status dc_gather(const dc_params* prm, const dc_source* src, const dc_field* fields, int32_t n_fields,
+                    int64_t dst_capacity_tokens, const int64_t* d_dst_tok_off,
+                    const void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream);
+
+/* dc_plan then dc_gather. */
+dc_status dc_repack(const dc_params* prm, const dc_source* src, const int32_t* d_seq_len,
+                    const int32_t* d_perm, const int32_t* d_shard_seq_off,
+                    const dc_field* fields, int32_t n_fields, int64_t dst_capacity_tokens,
+                    int64_t* d_dst_tok_off, int64_t* d_shard_tok_off, int32_t* d_shard_mb_off,
+                    int32_t* d_mb_seq_off, int32_t* d_cu_seqlens, int32_t* d_n_mb,
+                    void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream);
+
+const char* dc_strerror(dc_status code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DC_H */

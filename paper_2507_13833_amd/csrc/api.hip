@@ -1,0 +1,209 @@
+// C-ABI entry points: host-side validation, argument marshalling, kernel launches.
+// Nothing here allocates, copies or synchronises.
+#include "dc_internal.h"
+
+namespace dc {
+
+static inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+Workspace carve_workspace(void* base, int32_t n_seq, int64_t dst_capacity_tokens) {
+    Workspace w;
+    const size_t n = (size_t)(n_seq > 0 ? n_seq : 0);
+    w.n_tiles = dst_capacity_tokens > 0 ? (dst_capacity_tokens + GATHER_TILE - 1) / GATHER_TILE : 0;
+    char* p = static_cast<char*>(base);
+    size_t off = 0;
+    w.slot_src_off = reinterpret_cast<int64_t*>(p + off); off += round_up(n * sizeof(int64_t), 256);
+    w.slot_len = reinterpret_cast<int32_t*>(p + off);     off += round_up(n * sizeof(int32_t), 256);
+    w.slot_shard = reinterpret_cast<int32_t*>(p + off);   off += round_up(n * sizeof(int32_t), 256);
+    w.tile_first = reinterpret_cast<int32_t*>(p + off);   off += round_up((size_t)w.n_tiles * sizeof(int32_t), 256);
+    w.bytes = off + 256;
+    return w;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static dc_status check_params(const dc_params* prm) {
+    if (!prm) return DC_ERR_INVALID_ARG;
+    if (prm->n_seq < 0 || prm->n_shards < 1 || prm->cap < 0 || prm->align_tokens < 1 || prm->reserved != 0)
+        return DC_ERR_INVALID_ARG;
+    if (prm->token_budget < 1 || prm->token_budget > 0x7FFFFFFFLL) return DC_ERR_INVALID_ARG;
+    if (prm->ddof < 0 || !(prm->eps >= 0.0)) return DC_ERR_INVALID_ARG;
+    if (prm->n_seq > DC_MAX_SEQ || prm->n_shards > DC_MAX_SHARDS) return DC_ERR_UNSUPPORTED_SIZE;
+    return DC_OK;
+}
+
+static dc_status check_source(const dc_params* prm, const dc_source* src, SourceDesc* out) {
+    if (!src || !src->shard_seq_off || !src->shard_tokens || src->reserved != 0) return DC_ERR_INVALID_ARG;
+    if (src->n_src_shards < 1) return DC_ERR_INVALID_ARG;
+    if (src->n_src_shards > DC_MAX_SRC_SHARDS) return DC_ERR_UNSUPPORTED_SIZE;
+    if (prm->n_seq > 0 && !src->d_src_tok_off) return DC_ERR_INVALID_ARG;
+    out->n_src = src->n_src_shards;
+    for (int s = 0; s <= DC_MAX_SRC_SHARDS; ++s) out->seq_off[s] = prm->n_seq;
+    for (int s = 0; s < DC_MAX_SRC_SHARDS; ++s) out->tokens[s] = 0;
+    if (src->shard_seq_off[0] != 0 || src->shard_seq_off[src->n_src_shards] != prm->n_seq) return DC_ERR_INVALID_ARG;
+    for (int s = 0; s < src->n_src_shards; ++s) {
+        if (src->shard_seq_off[s + 1] < src->shard_seq_off[s] || src->shard_tokens[s] < 0) return DC_ERR_INVALID_ARG;
+        out->seq_off[s] = src->shard_seq_off[s];
+        out->tokens[s] = src->shard_tokens[s];
+    }
+    return DC_OK;
+}
+
+}  // namespace dc
+
+using namespace dc;
+
+extern "C" {
+
+size_t dc_workspace_bytes(const dc_params* prm, int64_t dst_capacity_tokens) {
+    if (!prm) return 0;
+    return carve_workspace(nullptr, prm->n_seq, dst_capacity_tokens).bytes;
+}
+
+dc_status dc_balance(const dc_params* prm, const int32_t* d_seq_len,
+                     int32_t* d_perm, int32_t* d_shard_seq_off, int32_t* d_shard_of_seq,
+                     int64_t* d_shard_load, int32_t* d_status, void* hip_stream) {
+    dc_status rc = check_params(prm);
+    if (rc != DC_OK) return rc;
+    if (!d_shard_seq_off || !d_shard_load) return DC_ERR_INVALID_ARG;
+    if (prm->n_seq > 0 && (!d_seq_len || !d_perm || !d_shard_of_seq)) return DC_ERR_INVALID_ARG;
+    int32_t cap_eff;
+    if (prm->cap == 0) {
+        if (prm->n_seq % prm->n_shards != 0) return DC_ERR_NOT_DIVISIBLE;     // Algorithm 1: assert N mod K = 0
+        cap_eff = prm->n_seq / prm->n_shards;
+    } else {
+        if ((int64_t)prm->cap * prm->n_shards < prm->n_seq) return DC_ERR_INVALID_ARG;
+        cap_eff = prm->cap;
+    }
+    hipError_t e = launch_balance(prm->n_seq, prm->n_shards, cap_eff, d_seq_len, d_perm, d_shard_seq_off,
+                                  d_shard_of_seq, d_shard_load, d_status, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? DC_OK : DC_ERR_HIP;
+}
+
+dc_status dc_group_advantage(const dc_params* prm, const dc_source* src, const int32_t* d_seq_len,
+                             const float* d_reward, const int32_t* d_group_off, int32_t n_groups,
+                             const uint8_t* const* mask_src_base, float* d_adv_seq,
+                             float* const* adv_tok_src_base, int32_t* d_status, void* hip_stream) {
+    dc_status rc = check_params(prm);
+    if (rc != DC_OK) return rc;
+    SourceDesc sd;
+    rc = check_source(prm, src, &sd);
+    if (rc != DC_OK) return rc;
+    if (n_groups < 0 || n_groups > prm->n_seq || !d_group_off) return DC_ERR_INVALID_ARG;
+    if (prm->n_seq > 0 && (!d_seq_len || !d_reward || !d_adv_seq)) return DC_ERR_INVALID_ARG;
+    if (adv_tok_src_base) {
+        if (!mask_src_base) return DC_ERR_INVALID_ARG;
+        for (int s = 0; s < src->n_src_shards; ++s) {
+            if (src->shard_tokens[s] == 0) continue;
+            if (!mask_src_base[s] || !adv_tok_src_base[s]) return DC_ERR_INVALID_ARG;
+            if (!aligned16(mask_src_base[s]) || !aligned16(adv_tok_src_base[s])) return DC_ERR_INVALID_ARG;
+        }
+    }
+    hipError_t e = launch_advantage(prm->n_seq, sd, src->d_src_tok_off, d_seq_len, d_reward, d_group_off, n_groups,
+                                    prm->eps, prm->ddof, mask_src_base, d_adv_seq, adv_tok_src_base, d_status,
+                                    static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? DC_OK : DC_ERR_HIP;
+}
+
+dc_status dc_plan(const dc_params* prm, const dc_source* src, const int32_t* d_seq_len,
+                  const int32_t* d_perm, const int32_t* d_shard_seq_off, int64_t dst_capacity_tokens,
+                  int64_t* d_dst_tok_off, int64_t* d_shard_tok_off, int32_t* d_shard_mb_off,
+                  int32_t* d_mb_seq_off, int32_t* d_cu_seqlens, int32_t* d_n_mb,
+                  void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream) {
+    dc_status rc = check_params(prm);
+    if (rc != DC_OK) return rc;
+    SourceDesc sd;
+    rc = check_source(prm, src, &sd);
+    if (rc != DC_OK) return rc;
+    if (dst_capacity_tokens < 0) return DC_ERR_INVALID_ARG;
+    if (!d_shard_seq_off || !d_dst_tok_off || !d_shard_tok_off || !d_shard_mb_off || !d_mb_seq_off || !d_n_mb || !d_ws)
+        return DC_ERR_INVALID_ARG;
+    if (prm->n_seq > 0 && (!d_seq_len || !d_perm || !d_cu_seqlens)) return DC_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(d_ws) & 255u) return DC_ERR_INVALID_ARG;
+    Workspace ws = carve_workspace(d_ws, prm->n_seq, dst_capacity_tokens);
+    if (ws_bytes < ws.bytes) return DC_ERR_WORKSPACE;
+    if (ws.n_tiles > 0x7FFFFFFFLL) return DC_ERR_UNSUPPORTED_SIZE;
+    hipError_t e = launch_plan(*prm, sd, src->d_src_tok_off, d_seq_len, d_perm, d_shard_seq_off, dst_capacity_tokens,
+                               d_dst_tok_off, d_shard_tok_off, d_shard_mb_off, d_mb_seq_off, d_cu_seqlens, d_n_mb,
+                               ws, d_status, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? DC_OK : DC_ERR_HIP;
+}
+
+dc_status dc_gather(const dc_params* prm, const dc_source* src, const dc_field* fields, int32_t n_fields,
+                    int64_t dst_capacity_tokens, const int64_t* d_dst_tok_off,
+                    const void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream) {
+    (void)d_status;
+    dc_status rc = check_params(prm);
+    if (rc != DC_OK) return rc;
+    SourceDesc sd;
+    rc = check_source(prm, src, &sd);
+    if (rc != DC_OK) return rc;
+    if (n_fields < 0 || dst_capacity_tokens < 0 || !d_dst_tok_off || !d_ws) return DC_ERR_INVALID_ARG;
+    if (n_fields > DC_MAX_FIELDS) return DC_ERR_UNSUPPORTED_SIZE;
+    if (n_fields > 0 && !fields) return DC_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(d_ws) & 255u) return DC_ERR_INVALID_ARG;
+    Workspace ws = carve_workspace(const_cast<void*>(d_ws), prm->n_seq, dst_capacity_tokens);
+    if (ws_bytes < ws.bytes) return DC_ERR_WORKSPACE;
+    if (ws.n_tiles > 0x7FFFFFFFLL) return DC_ERR_UNSUPPORTED_SIZE;
+    FieldTable ft;
+    ft.n_fields = n_fields;
+    ft.n_src = sd.n_src;
+    for (int f = 0; f < DC_MAX_FIELDS; ++f) {
+        ft.f[f].dst = nullptr; ft.f[f].elem_bytes = 1; ft.f[f].pad = 0;
+        for (int s = 0; s < DC_MAX_SRC_SHARDS; ++s) ft.f[f].src[s] = nullptr;
+        if (f >= n_fields) continue;
+        const dc_field& in = fields[f];
+        if (in.reserved != 0 || !in.src_base) return DC_ERR_INVALID_ARG;
+        if (in.elem_bytes != 1 && in.elem_bytes != 2 && in.elem_bytes != 4) return DC_ERR_INVALID_ARG;
+        if (dst_capacity_tokens > 0 && (!in.d_dst || !aligned16(in.d_dst))) return DC_ERR_INVALID_ARG;
+        ft.f[f].dst = static_cast<char*>(in.d_dst);
+        ft.f[f].elem_bytes = in.elem_bytes;
+        for (int s = 0; s < sd.n_src; ++s) {
+            if (sd.tokens[s] > 0 && (!in.src_base[s] || !aligned16(in.src_base[s]))) return DC_ERR_INVALID_ARG;
+            ft.f[f].src[s] = static_cast<const char*>(in.src_base[s]);
+        }
+    }
+    hipError_t e = launch_gather(prm->n_seq, ft, dst_capacity_tokens, d_dst_tok_off, ws,
+                                 static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? DC_OK : DC_ERR_HIP;
+}
+
+dc_status dc_repack(const dc_params* prm, const dc_source* src, const int32_t* d_seq_len,
+                    const int32_t* d_perm, const int32_t* d_shard_seq_off,
+                    const dc_field* fields, int32_t n_fields, int64_t dst_capacity_tokens,
+                    int64_t* d_dst_tok_off, int64_t* d_shard_tok_off, int32_t* d_shard_mb_off,
+                    int32_t* d_mb_seq_off, int32_t* d_cu_seqlens, int32_t* d_n_mb,
+                    void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream) {
+    // validate the gather's arguments before anything is enqueued
+    if (n_fields < 0 || (n_fields > 0 && !fields)) return DC_ERR_INVALID_ARG;
+    if (n_fields > DC_MAX_FIELDS) return DC_ERR_UNSUPPORTED_SIZE;
+    for (int f = 0; f < n_fields; ++f) {
+        const dc_field& in = fields[f];
+        if (in.reserved != 0 || !in.src_base) return DC_ERR_INVALID_ARG;
+        if (in.elem_bytes != 1 && in.elem_bytes != 2 && in.elem_bytes != 4) return DC_ERR_INVALID_ARG;
+    }
+    dc_status rc = dc_plan(prm, src, d_seq_len, d_perm, d_shard_seq_off, dst_capacity_tokens, d_dst_tok_off,
+                           d_shard_tok_off, d_shard_mb_off, d_mb_seq_off, d_cu_seqlens, d_n_mb, d_ws, ws_bytes,
+                           d_status, hip_stream);
+    if (rc != DC_OK) return rc;
+    return dc_gather(prm, src, fields, n_fields, dst_capacity_tokens, d_dst_tok_off, d_ws, ws_bytes, d_status,
+                     hip_stream);
+}
+
+const char* dc_strerror(dc_status code) {
+    switch (code) {
+        case DC_OK: return "ok";
+        case DC_ERR_INVALID_ARG: return "invalid argument";
+        case DC_ERR_NOT_DIVISIBLE: return "N mod P != 0 with cap = 0 (Algorithm 1 asserts divisibility)";
+        case DC_ERR_UNSUPPORTED_SIZE: return "size above the library's limits";
+        case DC_ERR_WORKSPACE: return "workspace too small";
+        case DC_ERR_HIP: return "HIP runtime error";
+        case DC_ERR_SEQ_EXCEEDS_BUDGET: return "a sequence is longer than the token budget";
+        case DC_ERR_ZERO_LENGTH_SEQ: return "a sequence length is <= 0 or above DC_MAX_SEQ_LEN";
+        case DC_ERR_OVERFLOW: return "packed layout exceeds the destination capacity";
+        case DC_ERR_BAD_LAYOUT: return "inconsistent index data (offsets, groups or permutation)";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

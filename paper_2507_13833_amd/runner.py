@@ -1,0 +1,111 @@
+"""Device-side harness around the binding: uploads a synthetic workload, owns the
+torch-allocated input / output / workspace buffers and issues the calls of one
+reshard step.  Plumbing only -- every step of the path runs in the HIP library.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+from .workloads import Workload
+
+_NP2TORCH = {1: torch.uint8, 2: torch.int16, 4: torch.int32}
+
+
+def _as_torch_bits(a: np.ndarray) -> torch.Tensor:
+    """Host tensor with the same bytes (payloads are opaque bit patterns)."""
+    a = np.ascontiguousarray(a)
+    return torch.from_numpy(a.view({1: np.uint8, 2: np.int16, 4: np.int32}[a.itemsize]))
+
+
+class DeviceBatch:
+    """One workload resident in HBM plus every buffer a reshard step writes."""
+
+    def __init__(self, w: Workload, device: str = "cuda:0", align_tokens: Optional[int] = None,
+                 cap: int = 0, poison: bool = False):
+        self.w = w
+        self.dev = torch.device(device)
+        dev = self.dev
+        N, P = w.n_seq, w.n_shards
+        self.align = w.align_tokens if align_tokens is None else align_tokens
+        self.prm = B.make_params(N, P, w.token_budget, float(w.eps), w.ddof, cap, self.align)
+        self.capacity = w.total_tokens + P * (self.align - 1)
+
+        self.seq_len = torch.from_numpy(w.seq_len).to(dev)
+        self.reward = torch.from_numpy(w.reward).to(dev)
+        self.group_off = torch.from_numpy(w.group_off).to(dev)
+        self.src_tok_off = torch.from_numpy(w.src_tok_off).to(dev)
+        self.source = B.Source(w.src_shard_seq_off, w.src_shard_tokens, self.src_tok_off)
+
+        # rollout-layout payload, one tensor per field and rollout shard
+        self.src_fields: Dict[str, List[torch.Tensor]] = {
+            f.name: [_as_torch_bits(a).to(dev) for a in f.shards] for f in w.fields}
+        self.elem_bytes: Dict[str, int] = {f.name: f.elem_bytes for f in w.fields}
+        self.adv_tok_src = [torch.zeros(int(t), dtype=torch.float32, device=dev) for t in w.src_shard_tokens]
+        self.elem_bytes["adv_tok"] = 4
+
+        # outputs
+        self.status = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.perm = torch.zeros(N, dtype=torch.int32, device=dev)
+        self.shard_seq_off = torch.zeros(P + 1, dtype=torch.int32, device=dev)
+        self.shard_of_seq = torch.zeros(N, dtype=torch.int32, device=dev)
+        self.shard_load = torch.zeros(P, dtype=torch.int64, device=dev)
+        self.adv_seq = torch.zeros(N, dtype=torch.float32, device=dev)
+        self.dst_tok_off = torch.zeros(N + 1, dtype=torch.int64, device=dev)
+        self.shard_tok_off = torch.zeros(P + 1, dtype=torch.int64, device=dev)
+        self.shard_mb_off = torch.zeros(P + 1, dtype=torch.int32, device=dev)
+        self.mb_seq_off = torch.zeros(N + 1, dtype=torch.int32, device=dev)
+        self.cu_seqlens = torch.zeros(2 * N + 1, dtype=torch.int32, device=dev)
+        self.n_mb = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.ws_bytes = B.dc_workspace_bytes(self.prm, self.capacity)
+        self.ws = torch.zeros(self.ws_bytes, dtype=torch.uint8, device=dev)
+
+        self.dst_fields: Dict[str, torch.Tensor] = {}
+        for name, eb in self.elem_bytes.items():
+            t = torch.zeros(self.capacity, dtype=_NP2TORCH[eb], device=dev)
+            if poison:
+                t.fill_({1: 0x5A, 2: 0x5A5A, 4: 0x5A5A5A5A}[eb])
+            self.dst_fields[name] = t
+        names = list(self.elem_bytes.keys())
+        self.field_names = names
+        self.fields = B.Fields([
+            (self.adv_tok_src if n == "adv_tok" else self.src_fields[n], self.dst_fields[n], self.elem_bytes[n])
+            for n in names])
+        self.payload_bytes_per_token = sum(self.elem_bytes.values())
+
+    # ---- the calls of one step ----
+    def group_advantage(self, per_token: bool = True) -> None:
+        B.dc_group_advantage(self.prm, self.source, self.seq_len, self.reward, self.group_off, self.w.n_groups,
+                             self.src_fields["mask"] if per_token else None, self.adv_seq,
+                             self.adv_tok_src if per_token else None, self.status)
+
+    def balance(self) -> None:
+        B.dc_balance(self.prm, self.seq_len, self.perm, self.shard_seq_off, self.shard_of_seq,
+                     self.shard_load, self.status)
+
+    def plan(self) -> None:
+        B.dc_plan(self.prm, self.source, self.seq_len, self.perm, self.shard_seq_off, self.capacity,
+                  self.dst_tok_off, self.shard_tok_off, self.shard_mb_off, self.mb_seq_off, self.cu_seqlens,
+                  self.n_mb, self.ws, self.ws_bytes, self.status)
+
+    def gather(self) -> None:
+        B.dc_gather(self.prm, self.source, self.fields, self.capacity, self.dst_tok_off, self.ws,
+                    self.ws_bytes, self.status)
+
+    def repack(self) -> None:
+        B.dc_repack(self.prm, self.source, self.seq_len, self.perm, self.shard_seq_off, self.fields,
+                    self.capacity, self.dst_tok_off, self.shard_tok_off, self.shard_mb_off, self.mb_seq_off,
+                    self.cu_seqlens, self.n_mb, self.ws, self.ws_bytes, self.status)
+
+    def step(self) -> None:
+        """One pass of the whole path: advantage, balance, plan, gather."""
+        self.group_advantage()
+        self.balance()
+        self.plan()
+        self.gather()
+
+    def read_status(self) -> int:
+        return int(self.status.item())

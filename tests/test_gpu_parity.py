@@ -1,0 +1,248 @@
+"""HIP path vs CPU oracle, element by element, through the C-ABI (needs an MI355X).
+
+Integer / index / payload outputs must be bit-exact.  Advantages are float32 results of
+float64 arithmetic on both sides; the bar is rtol 1e-5 / atol 1e-6.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2507_13833_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+RTOL, ATOL = 1e-5, 1e-6
+
+
+def _gpu():
+    import torch
+    from paper_2507_13833_amd import binding, runner
+    binding.load()                                   # raises if libdc.so is missing: no fallback
+    assert torch.cuda.is_available()
+    return torch, binding, runner
+
+
+def oracle_step(w, align=1, cap=0):
+    eps = float(w.eps)
+    bal = oracle.balance(w.seq_len, w.n_shards, cap)
+    adv = oracle.group_advantage(w.reward, w.group_off, eps, w.ddof)
+    adv_tok = oracle.adv_broadcast(adv, w.seq_len, w.src_tok_off, w.src_shard_seq_off, w.src_shard_tokens,
+                                   w.field_by_name("mask").shards)
+    pl = oracle.plan(w.seq_len, bal.perm, bal.shard_seq_off, w.token_budget, align)
+    return bal, adv, adv_tok, pl
+
+
+def check_step(w, align=1, cap=0, label=""):
+    torch, binding, runner = _gpu()
+    print(f"[parity] {label or w.name}: N={w.n_seq} P={w.n_shards} T={w.total_tokens} align={align} cap={cap}",
+          flush=True)
+    d = runner.DeviceBatch(w, align_tokens=align, cap=cap, poison=True)
+    d.step()
+    torch.cuda.synchronize()
+    assert d.read_status() == 0
+
+    bal, adv, adv_tok, pl = oracle_step(w, align, cap)
+    N, P = w.n_seq, w.n_shards
+
+    # a1 + a2: Algorithm 1
+    assert np.array_equal(d.perm.cpu().numpy(), bal.perm)
+    assert np.array_equal(d.shard_seq_off.cpu().numpy(), bal.shard_seq_off)
+    assert np.array_equal(d.shard_of_seq.cpu().numpy(), bal.shard_of_seq)
+    assert np.array_equal(d.shard_load.cpu().numpy(), bal.shard_load)
+
+    # a3: advantages
+    g_adv = d.adv_seq.cpu().numpy()
+    np.testing.assert_allclose(g_adv, adv, rtol=RTOL, atol=ATOL)
+    for s in range(w.n_src_shards):
+        g = d.adv_tok_src[s].cpu().numpy()
+        np.testing.assert_allclose(g, adv_tok[s], rtol=RTOL, atol=ATOL)
+        m = w.field_by_name("mask").shards[s]
+        assert not g.view(np.uint32)[m == 0].any()          # +0.0 exactly where no loss is taken
+
+    # a4: plan
+    M = int(d.n_mb.item())
+    assert M == pl.n_mb
+    assert np.array_equal(d.dst_tok_off.cpu().numpy(), pl.dst_tok_off)
+    assert np.array_equal(d.shard_tok_off.cpu().numpy(), pl.shard_tok_off)
+    assert np.array_equal(d.shard_mb_off.cpu().numpy(), pl.shard_mb_off)
+    assert np.array_equal(d.mb_seq_off.cpu().numpy()[:M + 1], pl.mb_seq_off)
+    assert np.array_equal(d.cu_seqlens.cpu().numpy()[:N + M], pl.cu_seqlens)
+
+    # a5: gather, every field, whole arena (poison outside the shards must survive)
+    arena = d.capacity
+    valid = np.zeros(arena, bool)
+    for k in range(P):
+        valid[pl.shard_tok_off[k]: pl.shard_tok_off[k] + bal.shard_load[k]] = True
+    for f in w.fields:
+        want = oracle.gather(w.seq_len, bal.perm, w.src_tok_off, w.src_shard_seq_off, f.shards,
+                             pl.dst_tok_off, arena)
+        got = d.dst_fields[f.name].cpu().numpy().view(want.dtype)
+        assert np.array_equal(got[valid], want[valid]), f.name
+        poison = np.frombuffer(bytes([0x5A] * f.elem_bytes), dtype=want.dtype)[0]
+        assert np.all(got[~valid] == poison), f.name
+    want = oracle.gather(w.seq_len, bal.perm, w.src_tok_off, w.src_shard_seq_off, adv_tok, pl.dst_tok_off, arena)
+    got = d.dst_fields["adv_tok"].cpu().numpy().view(np.float32)
+    np.testing.assert_allclose(got[valid], want[valid], rtol=RTOL, atol=ATOL)
+    assert np.all(got[~valid].view(np.uint32) == 0x5A5A5A5A)
+    # the repacked advantage is a bit copy of what the advantage kernel wrote
+    src_adv = [t.cpu().numpy() for t in d.adv_tok_src]
+    base = np.concatenate([[0], np.cumsum(w.src_shard_tokens)])
+    shard_of = np.searchsorted(w.src_shard_seq_off, np.arange(N), side="right") - 1
+    for j in np.random.default_rng(1).integers(0, N, 64) if N else []:
+        i = bal.perm[j]
+        seg_src = src_adv[shard_of[i]][w.src_tok_off[i]: w.src_tok_off[i] + w.seq_len[i]]
+        seg_dst = got[pl.dst_tok_off[j]: pl.dst_tok_off[j] + w.seq_len[i]]
+        assert np.array_equal(seg_src.view(np.uint32), seg_dst.view(np.uint32))
+    return d
+
+
+# ---------------------------------------------------------------- the five configs, full size
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_full_config(cfg):
+    check_step(workloads.make_workload(cfg), label=f"config {cfg}")
+
+
+def test_repack_equals_plan_then_gather_and_is_deterministic():
+    torch, binding, runner = _gpu()
+    w = workloads.make_workload(2)
+    d = runner.DeviceBatch(w)
+    d.step()
+    torch.cuda.synchronize()
+    first = {k: v.clone() for k, v in d.dst_fields.items()}
+    cu = d.cu_seqlens.clone()
+    perm = d.perm.clone()
+    for v in d.dst_fields.values():
+        v.zero_()
+    d.group_advantage(); d.balance(); d.repack()
+    torch.cuda.synchronize()
+    assert d.read_status() == 0
+    assert torch.equal(perm, d.perm) and torch.equal(cu, d.cu_seqlens)
+    for k, v in d.dst_fields.items():
+        assert torch.equal(first[k], v), k
+
+
+# ---------------------------------------------------------------- shapes and edges
+def _custom(seq_len, G, P, budget, n_src=1, seed=0, fields=("i32", "bf16", "u8")):
+    """Small hand-shaped workload (same field kinds, arbitrary lengths)."""
+    rng = np.random.default_rng(seed)
+    seq_len = np.asarray(seq_len, np.int32)
+    N = len(seq_len)
+    assert N % G == 0 and N % n_src == 0
+    per = N // n_src
+    sso = (np.arange(n_src + 1) * per).astype(np.int32)
+    sto = np.zeros(N, np.int64)
+    stk = np.zeros(n_src, np.int64)
+    for s in range(n_src):
+        c = np.cumsum(seq_len[sso[s]:sso[s + 1]].astype(np.int64))
+        sto[sso[s] + 1: sso[s + 1]] = c[:-1]
+        stk[s] = c[-1] if len(c) else 0
+    fl = []
+    for kind in fields:
+        if kind == "i32":
+            fl.append(workloads.Field("token_id", 4, [rng.integers(0, 1 << 30, int(t), dtype=np.int32) for t in stk]))
+        elif kind == "bf16":
+            fl.append(workloads.Field("old_logprob", 2,
+                                      [rng.integers(0, 1 << 16, int(t)).astype(np.uint16) for t in stk]))
+    fl.append(workloads.Field("mask", 1, [(rng.random(int(t)) < 0.7).astype(np.uint8) for t in stk]))
+    reward = rng.standard_normal(N).astype(np.float32)
+    return workloads.Workload(name="custom", cfg=0, n_seq=N, group_size=G, n_shards=P, token_budget=budget,
+                              eps=1e-6, ddof=1, align_tokens=1, seq_len=seq_len,
+                              prompt_len=np.zeros(N, np.int32),
+                              group_off=(np.arange(N // G + 1) * G).astype(np.int32), reward=reward,
+                              src_shard_seq_off=sso, src_tok_off=sto, src_shard_tokens=stk, fields=fl)
+
+
+@pytest.mark.parametrize("align", [3, 16, 64, 4096])
+def test_alignment_padding(align):
+    check_step(workloads.make_workload(1), align=align, label=f"config 1 align {align}")
+
+
+def test_unconstrained_lpt():
+    w = workloads.make_workload(2, prompts=64)
+    check_step(w, cap=w.n_seq, label="cap=N (textbook LPT)")
+    check_step(w, cap=w.n_seq // w.n_shards + 3, label="cap=C+3")
+
+
+def test_tiny_sequences_many_per_tile():
+    rng = np.random.default_rng(4)
+    # ~900 slots per 4096-token tile: several LDS passes per tile, most chunks straddle slots
+    check_step(_custom(rng.integers(1, 9, 8192), 8, 16, 64, n_src=4), label="lengths 1..8")
+    check_step(_custom(np.ones(4096, np.int32), 4, 64, 7, n_src=2), align=5, label="all length 1")
+
+
+def test_equal_lengths_and_single_shard():
+    check_step(_custom(np.full(512, 37, np.int32), 8, 1, 1000), label="equal lengths, P=1")
+    check_step(_custom(np.full(64, 300, np.int32), 8, 64, 300), label="N=P, budget = one sequence")
+
+
+def test_ragged_sizes():
+    rng = np.random.default_rng(9)
+    check_step(_custom(rng.integers(1, 3000, 1000), 5, 8, 4096, n_src=2), label="N=1000")
+    check_step(_custom(rng.integers(1, 70000, 63 * 3), 3, 63, 70000, n_src=1), label="P=63, long")
+    check_step(_custom(rng.integers(1, 200, 2), 2, 2, 512), label="N=2")
+
+
+def test_max_sequences():
+    rng = np.random.default_rng(10)
+    lens = np.minimum(rng.geometric(0.02, 16384), 2000).astype(np.int32)
+    check_step(_custom(lens, 16, 64, 8192, n_src=16), label="N=16384 (limit), 16 rollout shards")
+
+
+def test_group_sizes_and_ddof():
+    torch, binding, runner = _gpu()
+    rng = np.random.default_rng(12)
+    for G, ddof in ((1, 1), (2, 0), (3, 1), (7, 0), (64, 1), (96, 1)):
+        w = _custom(rng.integers(1, 50, G * 6), G, 2 if (G * 6) % 2 == 0 else 1, 4096)
+        w.ddof = ddof
+        w.reward[:G] = 0.1                                     # identical rewards, inexact value
+        check_step(w, label=f"G={G} ddof={ddof}")
+
+
+def test_advantage_ill_conditioned_rewards():
+    # large common offset: float32 statistics would lose the signal, float64 keeps it
+    w = _custom(np.full(64, 20, np.int32), 16, 4, 4096)
+    w.reward = (np.float32(1000.0) + np.random.default_rng(3).integers(0, 4, 64).astype(np.float32) / 1024).astype(np.float32)
+    check_step(w, label="rewards 1000 + k/1024")
+
+
+# ---------------------------------------------------------------- device-side error reporting
+def test_device_status_codes():
+    torch, binding, runner = _gpu()
+    w = _custom(np.array([5, 9, 3, 7], np.int32), 2, 2, 8)          # 9 > budget 8
+    d = runner.DeviceBatch(w)
+    d.step(); torch.cuda.synchronize()
+    assert d.read_status() == binding.DC_ERR_SEQ_EXCEEDS_BUDGET
+
+    w = _custom(np.array([5, 4, 3, 7], np.int32), 2, 2, 64)
+    d = runner.DeviceBatch(w)
+    d.seq_len[1] = 0                                                   # zero-length sequence
+    d.balance(); torch.cuda.synchronize()
+    assert d.read_status() == binding.DC_ERR_ZERO_LENGTH_SEQ
+
+    d = runner.DeviceBatch(w)
+    d.capacity -= 1                                                    # arena one token short
+    d.balance(); d.plan(); d.gather(); torch.cuda.synchronize()
+    assert d.read_status() == binding.DC_ERR_OVERFLOW
+
+    d = runner.DeviceBatch(w)
+    d.balance(); torch.cuda.synchronize()
+    d.perm[0] = d.perm[1]                                              # not a permutation
+    d.plan(); d.gather(); torch.cuda.synchronize()
+    assert d.read_status() == binding.DC_ERR_BAD_LAYOUT
+
+    d = runner.DeviceBatch(w)
+    d.group_off[1] = 5                                                 # group table not monotone
+    d.group_advantage(); torch.cuda.synchronize()
+    assert d.read_status() == binding.DC_ERR_BAD_LAYOUT
+
+
+def test_empty_batch():
+    torch, binding, runner = _gpu()
+    w = _custom(np.zeros(0, np.int32), 1, 4, 128)
+    d = runner.DeviceBatch(w)
+    d.step(); torch.cuda.synchronize()
+    assert d.read_status() == 0
+    assert int(d.n_mb.item()) == 0
+    assert d.shard_seq_off.cpu().tolist() == [0] * 5
+    assert d.shard_tok_off.cpu().tolist() == [0] * 5
+    assert d.shard_mb_off.cpu().tolist() == [0] * 5
