@@ -5,46 +5,141 @@
 //      (8-bit digits of max_len - len, only as many passes as the length range
 //      needs; ranks inside a wave by ballot matching, across waves by a scan of
 //      per-wave digit counters);
-//   b) the assignment loop on wave 0, lane k = worker k.  A lane keeps its worker's
-//      item count and a 32-bit key (load - base) << 6 | k, all-ones when the worker
-//      is full; "pop the minimum that is not full" is one DPP min-reduction over
-//      the 64 keys.  Loads of workers that are not full never differ by more than
-//      the longest sequence, so rebasing the keys when the minimum grows large keeps
-//      them in 32 bits for any total load;
-//   c) all lanes lay the P_k out one after the other (insertion order).
+//   b) the assignment on wave 0, lane k = worker k, in ROUNDS instead of one item
+//      per step.  A lane holds its worker's item count and a 32-bit key
+//      (load - base) << 6 | k (all-ones-ish when the worker is full).  A round
+//      sorts the 64 keys across lanes (bitonic network in DPP), hands the next
+//      items, in order, to the workers in key order, and accepts the longest
+//      prefix for which "worker of rank j is still the minimum after ranks < j took
+//      their items" holds - exactly the sequence of pop_min results Algorithm 1
+//      would produce, since rank j is popped next iff its key is below every
+//      updated key.  With descending lengths nearly every round places one item
+//      on every open worker, so N/P rounds replace N dependent steps.
+//      Loads of open workers never differ by more than the longest sequence, so
+//      rebasing the keys when the minimum grows keeps them in 32 bits for any
+//      total load;
+//   c) one more stable counting pass keyed by the worker of each step lays the
+//      P_k out one after the other in insertion order.
 #include "dc_device.h"
-#include "dc_internal.h"
+#include "dc_lanes.h"
 
 namespace dc {
 
 constexpr int BAL_BLOCK = 1024;
 constexpr int BAL_WAVES = BAL_BLOCK / WAVE;
 constexpr int BAL_ROUNDS = DC_MAX_SEQ / BAL_BLOCK;       // 64-item rounds per wave at the size limit
-constexpr uint32_t KEY_FULL = 0xFFFFFFFFu;
+constexpr uint32_t KEY_FULL = 0xFFFFFFC0u;               // | worker id: full (or absent) worker
 
 struct BalLds {
     int32_t  keys[DC_MAX_SEQ];            // sequence lengths (sanitised)
     uint16_t idx_a[DC_MAX_SEQ];           // sort ping
-    uint16_t idx_b[DC_MAX_SEQ];           // sort pong; after the sort: rank of step t inside its worker
-    uint32_t cnt[256 * BAL_WAVES];        // [digit][wave] counters; after the sort: worker of step t (bytes)
-    int64_t  load[DC_MAX_SHARDS];
-    int32_t  off[DC_MAX_SHARDS + 1];
+    uint16_t idx_b[DC_MAX_SEQ];           // sort pong; after the sort the free one holds the worker of each step
+    uint32_t cnt[256 * BAL_WAVES];        // [digit][wave] counters
     int32_t  red[2 * BAL_WAVES];
     uint32_t tmp32[16];
 };
 
-__device__ __forceinline__ uint32_t dpp_min_step(uint32_t v, uint32_t moved) { return moved < v ? moved : v; }
+// One stable counting pass over positions [0, N): position pos carries digit(pos) in
+// [0, 256); emit(pos, out) receives its output position.  Wave w owns the contiguous
+// positions [w*rounds*64, (w+1)*rounds*64), so (digit, wave, rank-in-wave) is the
+// stable order.  Every lane of the workgroup must call it.
+template <typename DigitFn, typename EmitFn>
+__device__ __forceinline__ void counting_pass(BalLds& L, int N, int rounds, DigitFn digit, EmitFn emit) {
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
+    const int wave_base = w * rounds * WAVE;
+    for (int i = tid; i < 256 * BAL_WAVES; i += BAL_BLOCK) L.cnt[i] = 0;
+    __syncthreads();
+    uint32_t packed[BAL_ROUNDS];                                  // digit << 16 | rank before me in my wave
+#pragma unroll
+    for (int r = 0; r < BAL_ROUNDS; ++r) {
+        packed[r] = 0;
+        if (r < rounds) {                                         // uniform
+            const int pos = wave_base + r * WAVE + lane;
+            const bool valid = pos < N;
+            uint32_t d = 0;
+            if (valid) d = digit(pos) & 0xFFu;
+            uint64_t peers = __ballot(valid);
+#pragma unroll
+            for (int b = 0; b < 8; ++b) {
+                const uint64_t bal = __ballot(valid && ((d >> b) & 1u));
+                peers &= ((d >> b) & 1u) ? bal : ~bal;
+            }
+            const uint64_t lt = (1ull << lane) - 1ull;
+            const int before = __popcll(peers & lt);
+            const int leader = valid ? (__ffsll((long long)peers) - 1) : lane;
+            uint32_t old = 0;
+            if (valid && lane == leader) {                        // one lane per distinct digit
+                uint32_t* c = &L.cnt[d * BAL_WAVES + w];
+                old = *c;
+                *c = old + (uint32_t)__popcll(peers);
+            }
+            old = (uint32_t)__shfl((int)old, leader, WAVE);
+            packed[r] = (d << 16) | (old + (uint32_t)before);
+        }
+    }
+    __syncthreads();
+    {   // exclusive scan of the 4096 counters in (digit, wave) order
+        uint32_t c4[4], s = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { c4[q] = L.cnt[tid * 4 + q]; s += c4[q]; }
+        uint32_t tot;
+        uint32_t run = block_excl_scan_add<uint32_t>(s, L.tmp32, &tot);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { L.cnt[tid * 4 + q] = run; run += c4[q]; }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < BAL_ROUNDS; ++r) {
+        if (r < rounds) {
+            const int pos = wave_base + r * WAVE + lane;
+            if (pos < N) {
+                const uint32_t d = packed[r] >> 16, rk = packed[r] & 0xFFFFu;
+                emit(pos, (int)(L.cnt[d * BAL_WAVES + w] + rk));
+            }
+        }
+    }
+    __syncthreads();
+}
 
-// Minimum of v over the 64 lanes, returned to every lane (uniform).
-__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
-    // lanes without a source keep their own value (old = v), which is harmless for min
-    v = dpp_min_step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x111, 0xF, 0xF, false));  // row_shr:1
-    v = dpp_min_step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x112, 0xF, 0xF, false));  // row_shr:2
-    v = dpp_min_step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x114, 0xF, 0xF, false));  // row_shr:4
-    v = dpp_min_step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x118, 0xF, 0xF, false));  // row_shr:8
-    v = dpp_min_step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x142, 0xF, 0xF, false));  // row_bcast:15
-    v = dpp_min_step(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x143, 0xF, 0xF, false));  // row_bcast:31
-    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+// The assignment rounds (wave 0 only).  WIDTH = 16, 32 or 64 >= P lanes take part in the sort.
+template <int WIDTH>
+__device__ __forceinline__ void lpt_rounds(int N, int P, int C, const int32_t* keys, const uint16_t* sorted,
+                                           uint8_t* step_worker, int64_t* __restrict__ shard_load) {
+    const uint32_t lane = threadIdx.x;
+    const uint32_t full = KEY_FULL | lane;
+    uint32_t key = ((int)lane < P && C > 0) ? lane : full;
+    int32_t count = 0;
+    int64_t load = 0;
+    int pos = 0;
+    while (pos < N) {
+        const int t = pos + (int)lane;
+        uint32_t s = 0;
+        if (t < N) s = (uint32_t)keys[sorted[t]];                 // item offered to rank `lane`
+        uint32_t sk = wave_sort_asc<WIDTH>(key);                  // lane r: r-th smallest key
+        const uint32_t min0 = (uint32_t)__builtin_amdgcn_readlane((int)sk, 0);
+        if (min0 >= 0x40000000u && min0 < KEY_FULL) {             // rebase: subtract the minimum load
+            const uint32_t sub = min0 & ~63u;
+            if (key < KEY_FULL) key -= sub;
+            if (sk < KEY_FULL) sk -= sub;
+        }
+        const bool valid = sk < KEY_FULL && t < N;
+        const uint32_t newk = valid ? sk + (s << 6) : 0xFFFFFFFFu;
+        const uint32_t pm = wave_excl_scan_umin(newk);            // smallest updated key among ranks below mine
+        const uint64_t acc = __ballot(valid && sk < pm);
+        const int m = (~acc == 0ull) ? WAVE : (__ffsll((long long)~acc) - 1);   // accepted prefix
+        if (m == 0) break;                                        // cannot happen: cap * P >= N
+        if ((int)lane < m) step_worker[t] = (uint8_t)(sk & 63u);
+        // back to worker lanes: rank r sends its updated key to lane (sk & 63)
+        const uint32_t recv = (uint32_t)__builtin_amdgcn_ds_permute((int)((sk & 63u) << 2), (int)newk);
+        const uint32_t thr = (uint32_t)__builtin_amdgcn_readlane((int)sk, m - 1);
+        if (key <= thr) {                                         // my worker is among the m smallest
+            load += (int64_t)((recv - key) >> 6);
+            count += 1;
+            key = (count == C) ? full : recv;
+        }
+        pos += m;
+    }
+    if ((int)lane < P) shard_load[lane] = load;
 }
 
 __global__ __launch_bounds__(BAL_BLOCK) void balance_kernel(int32_t N, int32_t P, int32_t C,
@@ -80,114 +175,38 @@ __global__ __launch_bounds__(BAL_BLOCK) void balance_kernel(int32_t N, int32_t P
 
     // ---- a) radix sort of indices by (mx - len) ascending, stable ----
     const int rounds = (N + BAL_BLOCK - 1) / BAL_BLOCK;           // <= BAL_ROUNDS
-    const int wave_base = w * rounds * WAVE;                      // wave w owns positions [wave_base, +rounds*64)
     for (int i = tid; i < N; i += BAL_BLOCK) L.idx_a[i] = (uint16_t)i;
     uint16_t* src = L.idx_a;
     uint16_t* dst = L.idx_b;
     __syncthreads();
     for (int pass = 0; pass < passes; ++pass) {
         const int shift = pass * 8;
-        for (int i = tid; i < 256 * BAL_WAVES; i += BAL_BLOCK) L.cnt[i] = 0;
-        __syncthreads();
-        uint32_t packed[BAL_ROUNDS];                              // digit << 16 | rank before me in my wave
-#pragma unroll
-        for (int r = 0; r < BAL_ROUNDS; ++r) {
-            packed[r] = 0;
-            if (r < rounds) {                                     // uniform
-                const int pos = wave_base + r * WAVE + lane;
-                const bool valid = pos < N;
-                uint32_t d = 0;
-                if (valid) d = (((uint32_t)(mx - L.keys[src[pos]])) >> shift) & 0xFFu;
-                uint64_t peers = __ballot(valid);
-#pragma unroll
-                for (int b = 0; b < 8; ++b) {
-                    const uint64_t bal = __ballot(valid && ((d >> b) & 1u));
-                    peers &= ((d >> b) & 1u) ? bal : ~bal;
-                }
-                const uint64_t lt = (1ull << lane) - 1ull;
-                const int before = __popcll(peers & lt);
-                const int leader = valid ? (__ffsll((long long)peers) - 1) : lane;
-                uint32_t old = 0;
-                if (valid && lane == leader) {                    // one lane per distinct digit
-                    uint32_t* c = &L.cnt[d * BAL_WAVES + w];
-                    old = *c;
-                    *c = old + (uint32_t)__popcll(peers);
-                }
-                old = (uint32_t)__shfl((int)old, leader, WAVE);
-                packed[r] = (d << 16) | (old + (uint32_t)before);
-            }
-        }
-        __syncthreads();
-        {   // exclusive scan of the 4096 counters in (digit, wave) order
-            uint32_t c4[4], s = 0;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) { c4[q] = L.cnt[tid * 4 + q]; s += c4[q]; }
-            uint32_t tot;
-            uint32_t run = block_excl_scan_add<uint32_t>(s, L.tmp32, &tot);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) { L.cnt[tid * 4 + q] = run; run += c4[q]; }
-        }
-        __syncthreads();
-#pragma unroll
-        for (int r = 0; r < BAL_ROUNDS; ++r) {
-            if (r < rounds) {
-                const int pos = wave_base + r * WAVE + lane;
-                if (pos < N) {
-                    const uint32_t d = packed[r] >> 16, rk = packed[r] & 0xFFFFu;
-                    dst[L.cnt[d * BAL_WAVES + w] + rk] = src[pos];
-                }
-            }
-        }
-        __syncthreads();
+        counting_pass(L, N, rounds,
+                      [&](int pos) { return ((uint32_t)(mx - L.keys[src[pos]])) >> shift; },
+                      [&](int pos, int out) { dst[out] = src[pos]; });
         uint16_t* t = src; src = dst; dst = t;
     }
-    // src: sorted indices.  dst: free -> rank inside worker per step.  cnt: free -> worker per step.
-    const uint16_t* sorted = src;
-    uint16_t* step_rank = dst;
-    uint8_t* step_worker = reinterpret_cast<uint8_t*>(L.cnt);     // 16 KiB >= DC_MAX_SEQ bytes
+    const uint16_t* sorted = src;                                 // I of Algorithm 1
+    uint8_t* step_worker = reinterpret_cast<uint8_t*>(dst);       // worker chosen for I[t]
 
-    // ---- b) assignment loop, wave 0 ----
+    // ---- b) assignment rounds, wave 0 ----
     if (w == 0) {
-        uint32_t key = lane < P ? (uint32_t)lane : KEY_FULL;
-        if (C == 0) key = KEY_FULL;
-        int32_t count = 0;
-        int64_t load = 0;
-        for (int base = 0; base < N; base += WAVE) {
-            int32_t my_s = 0;
-            if (base + lane < N) my_s = L.keys[sorted[base + lane]];
-            const int n_here = min(WAVE, N - base);
-            for (int q = 0; q < n_here; ++q) {
-                const uint32_t s = (uint32_t)__builtin_amdgcn_readlane(my_s, q);
-                const uint32_t m = wave_min_u32(key);
-                const int k = (int)(m & 63u);
-                if (lane == k) {
-                    step_rank[base + q] = (uint16_t)count;
-                    step_worker[base + q] = (uint8_t)k;
-                    count += 1;
-                    load += s;
-                    key = (count == C) ? KEY_FULL : key + (s << 6);
-                }
-                if (m >= 0x40000000u) {                           // rebase: subtract the minimum load
-                    const uint32_t sub = m & ~63u;
-                    if (key != KEY_FULL) key -= sub;
-                }
-            }
-        }
-        if (lane < P) { L.load[lane] = load; shard_load[lane] = load; }
-        const int32_t inc = wave_incl_scan_add<int32_t>(lane < P ? count : 0);
-        if (lane < P) L.off[lane + 1] = inc;
-        if (lane == 0) L.off[0] = 0;
+        if (P <= 16) lpt_rounds<16>(N, P, C, L.keys, sorted, step_worker, shard_load);
+        else if (P <= 32) lpt_rounds<32>(N, P, C, L.keys, sorted, step_worker, shard_load);
+        else lpt_rounds<64>(N, P, C, L.keys, sorted, step_worker, shard_load);
     }
     __syncthreads();
 
-    // ---- c) lay out P_0, P_1, ... ----
-    for (int t = tid; t < N; t += BAL_BLOCK) {
-        const int k = step_worker[t];
-        const int u = sorted[t];
-        perm[L.off[k] + step_rank[t]] = u;
-        shard_of_seq[u] = k;
-    }
-    if (tid <= P) shard_seq_off[tid] = L.off[tid];
+    // ---- c) lay out P_0, P_1, ... : stable by worker, steps already in insertion order ----
+    counting_pass(L, N, rounds,
+                  [&](int pos) { return (uint32_t)step_worker[pos]; },
+                  [&](int pos, int out) {
+                      const int u = sorted[pos];
+                      perm[out] = u;
+                      shard_of_seq[u] = step_worker[pos];
+                  });
+    if (tid < P) shard_seq_off[tid] = (int32_t)L.cnt[tid * BAL_WAVES];
+    if (tid == P) shard_seq_off[P] = N;
 }
 
 hipError_t launch_balance(int32_t n_seq, int32_t n_shards, int32_t cap_eff, const int32_t* d_seq_len,

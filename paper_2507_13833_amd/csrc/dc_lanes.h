@@ -1,0 +1,100 @@
+// Cross-lane primitives for wave64 on gfx950: partner exchange lane ^ J, a 64-lane
+// bitonic sort of unsigned keys, and min scans.  All data stays in VGPRs (DPP,
+// v_permlane*_swap); nothing touches LDS memory.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dc {
+
+// DPP controls
+constexpr int DPP_QUAD_PERM_1032 = 0xB1;    // lane ^ 1
+constexpr int DPP_QUAD_PERM_2301 = 0x4E;    // lane ^ 2
+constexpr int DPP_ROW_SHL4 = 0x104;         // lane i <- lane i+4 (within a row of 16)
+constexpr int DPP_ROW_SHR1 = 0x111;         // lane i <- lane i-1
+constexpr int DPP_ROW_SHR2 = 0x112;
+constexpr int DPP_ROW_SHR4 = 0x114;
+constexpr int DPP_ROW_SHR8 = 0x118;
+constexpr int DPP_ROW_ROR8 = 0x128;         // lane ^ 8
+constexpr int DPP_WAVE_SHR1 = 0x138;        // lane i <- lane i-1 across the whole wave
+constexpr int DPP_ROW_BCAST15 = 0x142;      // lane 15 of each row -> every lane of the next row
+constexpr int DPP_ROW_BCAST31 = 0x143;      // lane 31 -> every lane of rows 2 and 3
+
+template <int CTRL, int ROW_MASK = 0xF, int BANK_MASK = 0xF>
+__device__ __forceinline__ uint32_t dpp_mov(uint32_t old, uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)old, (int)v, CTRL, ROW_MASK, BANK_MASK, false);
+}
+
+// Value of lane (lane ^ J).
+template <int J>
+__device__ __forceinline__ uint32_t lane_xor(uint32_t v) {
+    static_assert(J == 1 || J == 2 || J == 4 || J == 8 || J == 16 || J == 32, "power of two below 64");
+    if constexpr (J == 1) return dpp_mov<DPP_QUAD_PERM_1032>(v, v);
+    else if constexpr (J == 2) return dpp_mov<DPP_QUAD_PERM_2301>(v, v);
+    else if constexpr (J == 4) {
+        // lanes with bit 2 clear (banks 0, 2) take lane+4, the others lane-4
+        uint32_t t = dpp_mov<DPP_ROW_SHL4, 0xF, 0x5>(v, v);
+        return dpp_mov<DPP_ROW_SHR4, 0xF, 0xA>(t, v);
+    } else if constexpr (J == 8) return dpp_mov<DPP_ROW_ROR8>(v, v);
+    else if constexpr (J == 16) {
+        // swap: a = [r0 r0 r2 r2], b = [r1 r1 r3 r3]; even rows want b, odd rows want a
+        auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+        return (threadIdx.x & 16) ? r[0] : r[1];
+    } else {
+        auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+        return (threadIdx.x & 32) ? r[0] : r[1];
+    }
+}
+
+template <int K, int J>
+__device__ __forceinline__ uint32_t bitonic_step(uint32_t v) {
+    const uint32_t p = lane_xor<J>(v);
+    const uint32_t lo = v < p ? v : p, hi = v < p ? p : v;
+    const uint32_t lane = threadIdx.x & 63u;
+    const bool lower = (lane & J) == 0;          // I am the lower lane of the pair
+    const bool asc = (lane & K) == 0;            // my block sorts ascending
+    return (lower == asc) ? lo : hi;
+}
+
+template <int K, int J>
+__device__ __forceinline__ uint32_t bitonic_merge(uint32_t v) {
+    v = bitonic_step<K, J>(v);
+    if constexpr (J > 1) v = bitonic_merge<K, J / 2>(v);
+    return v;
+}
+
+template <int K, int WIDTH>
+__device__ __forceinline__ uint32_t bitonic_sort_levels(uint32_t v) {
+    v = bitonic_merge<K, K / 2>(v);
+    if constexpr (K < WIDTH) v = bitonic_sort_levels<K * 2, WIDTH>(v);
+    return v;
+}
+
+// Bitonic sort of each aligned group of WIDTH lanes (WIDTH = 16, 32, 64): even groups
+// come out ascending (lane r of group 0 ends with the r-th smallest of lanes
+// 0..WIDTH-1), odd groups descending.  Keys need not be distinct.
+template <int WIDTH>
+__device__ __forceinline__ uint32_t wave_sort_asc(uint32_t v) {
+    return bitonic_sort_levels<2, WIDTH>(v);
+}
+
+__device__ __forceinline__ uint32_t umin32(uint32_t a, uint32_t b) { return a < b ? a : b; }
+
+// Inclusive min-scan over the 64 lanes (lane i: min of lanes 0..i).
+__device__ __forceinline__ uint32_t wave_incl_scan_umin(uint32_t v) {
+    const uint32_t ID = 0xFFFFFFFFu;
+    v = umin32(v, dpp_mov<DPP_ROW_SHR1>(ID, v));
+    v = umin32(v, dpp_mov<DPP_ROW_SHR2>(ID, v));
+    v = umin32(v, dpp_mov<DPP_ROW_SHR4>(ID, v));
+    v = umin32(v, dpp_mov<DPP_ROW_SHR8>(ID, v));
+    v = umin32(v, dpp_mov<DPP_ROW_BCAST15, 0xA>(ID, v));
+    v = umin32(v, dpp_mov<DPP_ROW_BCAST31, 0xC>(ID, v));
+    return v;
+}
+
+// Exclusive min-scan (lane 0 gets all-ones).
+__device__ __forceinline__ uint32_t wave_excl_scan_umin(uint32_t v) {
+    return dpp_mov<DPP_WAVE_SHR1>(0xFFFFFFFFu, wave_incl_scan_umin(v));
+}
+
+}  // namespace dc
