@@ -9,7 +9,7 @@ namespace dc {
 
 // Tokens of destination space one gather workgroup owns.  Also the granularity
 // of the per-tile "first slot" table the plan kernel leaves in the workspace.
-constexpr int GATHER_TILE = 4096;
+constexpr int GATHER_TILE = 2048;
 // Tokens of rollout space one advantage workgroup owns.
 constexpr int ADV_TILE = 8192;
 // Segment descriptors staged in LDS per pass over a tile, plus look-ahead so a

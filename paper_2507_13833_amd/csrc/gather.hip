@@ -59,89 +59,107 @@ __device__ __forceinline__ int count_below(const int64_t* start, int n, int64_t 
 }
 
 template <int ES>
-__device__ __forceinline__ void copy_elem(char* d, const char* s) {
-    if (ES == 4) *reinterpret_cast<uint32_t*>(d) = *reinterpret_cast<const uint32_t*>(s);
-    else if (ES == 2) *reinterpret_cast<uint16_t*>(d) = *reinterpret_cast<const uint16_t*>(s);
-    else *reinterpret_cast<uint8_t*>(d) = *reinterpret_cast<const uint8_t*>(s);
+__device__ __forceinline__ uint32_t load_elem(const char* s) {
+    if (ES == 4) return *reinterpret_cast<const uint32_t*>(s);
+    if (ES == 2) return *reinterpret_cast<const uint16_t*>(s);
+    return *reinterpret_cast<const uint8_t*>(s);
+}
+template <int ES>
+__device__ __forceinline__ void store_elem(char* d, uint32_t v) {
+    if (ES == 4) *reinterpret_cast<uint32_t*>(d) = v;
+    else if (ES == 2) *reinterpret_cast<uint16_t*>(d) = (uint16_t)v;
+    else *reinterpret_cast<uint8_t*>(d) = (uint8_t)v;
 }
 
-// All chunks of one field inside the current pass of the tile.
+// Where one 16-byte destination chunk comes from.  Shared by all fields of one element size.
+struct Chunk {
+    int     mode;      // 0: not mine in this pass, 1: inside one slot, 2: element by element
+    int     k;         // slot (index into the LDS batch) of the chunk's first token, or -1
+    int     shard;     // mode 1: rollout shard
+    int64_t elem;      // mode 1: source element index of the chunk's first token
+    int64_t c0;        // first destination token
+};
+
+template <int TPC>
+__device__ __forceinline__ Chunk classify(const SegLds& sg, int n_all, int chunk, int64_t tile_begin,
+                                          int64_t tile_end, int64_t pass_begin, int64_t pass_end) {
+    Chunk c;
+    c.c0 = tile_begin + (int64_t)chunk * TPC;
+    c.mode = 0; c.k = -1; c.shard = 0; c.elem = 0;
+    if (c.c0 >= pass_begin && c.c0 < pass_end) {
+        const int k = find_seg(sg.start, n_all, c.c0);
+        c.k = k;
+        c.mode = 2;
+        if (k >= 0) {
+            const int64_t st = sg.start[k];
+            if (c.c0 + TPC <= st + sg.len[k] && c.c0 + TPC <= tile_end) {
+                c.mode = 1;
+                c.shard = sg.shard[k];
+                c.elem = sg.src[k] + (c.c0 - st);
+            }
+        }
+    }
+    return c;
+}
+
+// 16 source bytes starting at byte address a (a multiple of ES): aligned-down dword loads.
 template <int ES>
-__device__ __forceinline__ void copy_field(const SegLds& sg, int n_all, char* dst, const char* const* src_base,
-                                           int64_t tile_begin, int64_t tile_end,
-                                           int64_t pass_begin, int64_t pass_end) {
-    constexpr int TPC = 16 / ES;                          // tokens per 16-byte chunk
-    constexpr int U = GATHER_TILE / TPC / GATHER_BLOCK;   // chunks per lane: 4, 2, 1
-    static_assert(U >= 1, "tile too small");
-    u32x4 v[U];
-    uint32_t x[U];
-    int mode[U];
-    int seg[U];
-    const char* sp[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int64_t c0 = tile_begin + (int64_t)(threadIdx.x + u * GATHER_BLOCK) * TPC;
-        mode[u] = 0;
-        seg[u] = -1;
-        sp[u] = nullptr;
-        if (c0 >= pass_begin && c0 < pass_end) {
-            const int k = find_seg(sg.start, n_all, c0);
-            seg[u] = k;
-            mode[u] = 2;
-            if (k >= 0) {
-                const int64_t st = sg.start[k];
-                if (c0 + TPC <= st + sg.len[k] && c0 + TPC <= tile_end) {
-                    mode[u] = 1;
-                    sp[u] = src_base[sg.shard[k]] + (sg.src[k] + (c0 - st)) * ES;
-                }
-            }
-        }
+__device__ __forceinline__ void load_chunk(const char* a, u32x4& v, uint32_t& x) {
+    if (ES == 4) {
+        v = load16_a4(a);
+        x = 0;
+    } else {
+        const uintptr_t u = reinterpret_cast<uintptr_t>(a);
+        const char* a4 = reinterpret_cast<const char*>(u & ~uintptr_t(3));
+        v = load16_a4(a4);
+        x = (u & 3) ? load4(a4 + 16) : 0u;
     }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        if (mode[u] == 1) {
-            if (ES == 4) {
-                v[u] = load16_a4(sp[u]);
-            } else {
-                const uintptr_t a = reinterpret_cast<uintptr_t>(sp[u]);
-                const char* a4 = reinterpret_cast<const char*>(a & ~uintptr_t(3));
-                v[u] = load16_a4(a4);
-                x[u] = (a & 3) ? load4(a4 + 16) : 0u;
-            }
-        }
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int64_t c0 = tile_begin + (int64_t)(threadIdx.x + u * GATHER_BLOCK) * TPC;
-        if (mode[u] == 1) {
-            u32x4 o = v[u];
-            if (ES != 4) {
-                const uint32_t sh = reinterpret_cast<uintptr_t>(sp[u]) & 3;
-                o.x = __builtin_amdgcn_alignbyte(v[u].y, v[u].x, sh);
-                o.y = __builtin_amdgcn_alignbyte(v[u].z, v[u].y, sh);
-                o.z = __builtin_amdgcn_alignbyte(v[u].w, v[u].z, sh);
-                o.w = __builtin_amdgcn_alignbyte(x[u], v[u].w, sh);
-            }
-            store16(dst + c0 * ES, o);
-        } else if (mode[u] == 2) {
-            int k = seg[u];
-            for (int e = 0; e < TPC; ++e) {
-                const int64_t tok = c0 + e;
-                if (tok >= tile_end) break;
-                while (k + 1 < n_all && sg.start[k + 1] <= tok) ++k;
-                if (k >= 0) {
-                    const int64_t st = sg.start[k];
-                    if (tok >= st && tok < st + sg.len[k])
-                        copy_elem<ES>(dst + tok * ES, src_base[sg.shard[k]] + (sg.src[k] + (tok - st)) * ES);
-                }
-            }
-        }
-    }
+}
+__device__ __forceinline__ u32x4 realign(u32x4 v, uint32_t x, uint32_t sh) {
+    u32x4 o;
+    o.x = __builtin_amdgcn_alignbyte(v.y, v.x, sh);
+    o.y = __builtin_amdgcn_alignbyte(v.z, v.y, sh);
+    o.z = __builtin_amdgcn_alignbyte(v.w, v.z, sh);
+    o.w = __builtin_amdgcn_alignbyte(x, v.w, sh);
+    return o;
+}
+
+constexpr int U4 = GATHER_TILE / 4 / GATHER_BLOCK;        // 16-byte chunks per lane, 4-byte fields
+constexpr int FIELD_GROUP = 4;                            // fields whose loads are in flight together
+static_assert(GATHER_TILE == 2048 && GATHER_BLOCK == 256, "lane/chunk mapping below assumes 2048 tokens x 256 lanes");
+
+struct FieldLds {
+    const char* base[DC_MAX_FIELDS][DC_MAX_SRC_SHARDS];
+    char*       dst[DC_MAX_FIELDS];
+    int32_t     es[DC_MAX_FIELDS];
+    int32_t     cls_nf[3];                       // fields of element size 4, 2, 1
+    int32_t     cls_field[3][DC_MAX_FIELDS];
+};
+
+// Chunks that cannot take the one-load-one-store path (they cross a slot boundary,
+// padding or the arena end), per element-size class.  Their elements are copied one
+// per lane afterwards, so a boundary costs one memory round trip, not one per element.
+struct BoundaryLds {
+    int32_t  count[3];
+    uint16_t chunk[3][GATHER_TILE / 4];
+};
+
+// Element (field, chunk, e) of a boundary chunk: find its slot, copy it.
+template <int ES>
+__device__ __forceinline__ void move_element(const SegLds& sg, int n_all, int64_t tok, int64_t tile_end,
+                                             char* dst, const char* const* src_base) {
+    if (tok >= tile_end) return;
+    const int k = find_seg(sg.start, n_all, tok);
+    if (k < 0) return;
+    const int64_t st = sg.start[k];
+    if (tok >= st + sg.len[k]) return;
+    store_elem<ES>(dst + tok * ES, load_elem<ES>(src_base[sg.shard[k]] + (sg.src[k] + (tok - st)) * ES));
 }
 
 __global__ __launch_bounds__(GATHER_BLOCK) void gather_kernel(GatherArgs a, FieldTable ft) {
     __shared__ SegLds sg;
-    __shared__ const char* s_base[DC_MAX_FIELDS][DC_MAX_SRC_SHARDS];
+    __shared__ FieldLds fl;
+    __shared__ BoundaryLds bl;
 
     const int64_t tile_begin = (int64_t)blockIdx.x * GATHER_TILE;
     const int64_t tile_end = min(tile_begin + (int64_t)GATHER_TILE, a.capacity);
@@ -151,12 +169,22 @@ __global__ __launch_bounds__(GATHER_BLOCK) void gather_kernel(GatherArgs a, Fiel
 
     if (threadIdx.x < DC_MAX_FIELDS * DC_MAX_SRC_SHARDS) {
         const int f = threadIdx.x / DC_MAX_SRC_SHARDS, s = threadIdx.x % DC_MAX_SRC_SHARDS;
-        s_base[f][s] = (f < ft.n_fields && s < ft.n_src) ? ft.f[f].src[s] : nullptr;
+        fl.base[f][s] = (f < ft.n_fields && s < ft.n_src) ? ft.f[f].src[s] : nullptr;
+        if (s == 0) { fl.dst[f] = ft.f[f].dst; fl.es[f] = ft.f[f].elem_bytes; }
     }
+    if (threadIdx.x < 3) {
+        const int es = 4 >> threadIdx.x;
+        int n = 0;
+        for (int f = 0; f < ft.n_fields; ++f)
+            if (ft.f[f].elem_bytes == es) fl.cls_field[threadIdx.x][n++] = f;
+        fl.cls_nf[threadIdx.x] = n;
+    }
+    const int nf = ft.n_fields;
+    const int tid = threadIdx.x;
 
     int64_t pass_begin = tile_begin;
     for (;;) {
-        for (int k = threadIdx.x; k < NSEG; k += GATHER_BLOCK) {
+        for (int k = tid; k < NSEG; k += GATHER_BLOCK) {
             const int64_t j = (int64_t)seg_base + k;
             int64_t st = INT64_MAX, so = 0;
             int32_t ln = 0, sh = 0;
@@ -168,17 +196,101 @@ __global__ __launch_bounds__(GATHER_BLOCK) void gather_kernel(GatherArgs a, Fiel
             }
             sg.start[k] = st; sg.src[k] = so; sg.len[k] = ln; sg.shard[k] = sh;
         }
+        if (tid < 3) bl.count[tid] = 0;
         __syncthreads();
         const int n_all = count_below(sg.start, NSEG, tile_end);
         const bool more = n_all > SEG_BATCH;               // slot SEG_BATCH also starts inside the tile
         const int64_t pass_end = more ? sg.start[SEG_BATCH] : tile_end;
 
-        for (int f = 0; f < ft.n_fields; ++f) {
-            char* dst = ft.f[f].dst;
-            const int es = ft.f[f].elem_bytes;
-            if (es == 4) copy_field<4>(sg, n_all, dst, s_base[f], tile_begin, tile_end, pass_begin, pass_end);
-            else if (es == 2) copy_field<2>(sg, n_all, dst, s_base[f], tile_begin, tile_end, pass_begin, pass_end);
-            else copy_field<1>(sg, n_all, dst, s_base[f], tile_begin, tile_end, pass_begin, pass_end);
+        // one lookup per element size, shared by every field of that size
+        Chunk c4[U4];
+#pragma unroll
+        for (int u = 0; u < U4; ++u)
+            c4[u] = classify<4>(sg, n_all, tid + u * GATHER_BLOCK, tile_begin, tile_end, pass_begin, pass_end);
+        const Chunk c2 = classify<8>(sg, n_all, tid, tile_begin, tile_end, pass_begin, pass_end);
+        Chunk c1 = classify<16>(sg, n_all, tid & 127, tile_begin, tile_end, pass_begin, pass_end);
+        if (tid >= 128) c1.mode = 0;
+#pragma unroll
+        for (int u = 0; u < U4; ++u)
+            if (c4[u].mode == 2) bl.chunk[0][atomicAdd(&bl.count[0], 1)] = (uint16_t)(tid + u * GATHER_BLOCK);
+        if (c2.mode == 2) bl.chunk[1][atomicAdd(&bl.count[1], 1)] = (uint16_t)tid;
+        if (c1.mode == 2) bl.chunk[2][atomicAdd(&bl.count[2], 1)] = (uint16_t)tid;
+        __syncthreads();
+
+        for (int f0 = 0; f0 < nf; f0 += FIELD_GROUP) {
+            u32x4 v[FIELD_GROUP][U4];
+            uint32_t x[FIELD_GROUP];
+            uint32_t sh[FIELD_GROUP];
+            // ---- all loads of the group ----
+#pragma unroll
+            for (int g = 0; g < FIELD_GROUP; ++g) {
+                const int f = f0 + g;
+                x[g] = 0; sh[g] = 0;
+                if (f < nf) {
+                    const int es = fl.es[f];
+                    if (es == 4) {
+#pragma unroll
+                        for (int u = 0; u < U4; ++u)
+                            if (c4[u].mode == 1) load_chunk<4>(fl.base[f][c4[u].shard] + c4[u].elem * 4, v[g][u], x[g]);
+                    } else if (es == 2) {
+                        if (c2.mode == 1) {
+                            const char* p = fl.base[f][c2.shard] + c2.elem * 2;
+                            sh[g] = reinterpret_cast<uintptr_t>(p) & 3;
+                            load_chunk<2>(p, v[g][0], x[g]);
+                        }
+                    } else {
+                        if (c1.mode == 1) {
+                            const char* p = fl.base[f][c1.shard] + c1.elem;
+                            sh[g] = reinterpret_cast<uintptr_t>(p) & 3;
+                            load_chunk<1>(p, v[g][0], x[g]);
+                        }
+                    }
+                }
+            }
+            // ---- all stores of the group ----
+#pragma unroll
+            for (int g = 0; g < FIELD_GROUP; ++g) {
+                const int f = f0 + g;
+                if (f < nf) {
+                    const int es = fl.es[f];
+                    char* dst = fl.dst[f];
+                    if (es == 4) {
+#pragma unroll
+                        for (int u = 0; u < U4; ++u)
+                            if (c4[u].mode == 1) store16(dst + c4[u].c0 * 4, v[g][u]);
+                    } else if (es == 2) {
+                        if (c2.mode == 1) store16(dst + c2.c0 * 2, realign(v[g][0], x[g], sh[g]));
+                    } else {
+                        if (c1.mode == 1) store16(dst + c1.c0, realign(v[g][0], x[g], sh[g]));
+                    }
+                }
+            }
+        }
+        // ---- boundary chunks: one element per lane and step ----
+        {
+            const int n4 = bl.count[0] * 4 * fl.cls_nf[0];
+            const int n2 = bl.count[1] * 8 * fl.cls_nf[1];
+            const int n1 = bl.count[2] * 16 * fl.cls_nf[2];
+            for (int wi = tid; wi < n4 + n2 + n1; wi += GATHER_BLOCK) {
+                if (wi < n4) {
+                    const int e = wi & 3, q = wi >> 2, nfc = fl.cls_nf[0];
+                    const int f = fl.cls_field[0][q % nfc];
+                    const int64_t tok = tile_begin + (int64_t)bl.chunk[0][q / nfc] * 4 + e;
+                    move_element<4>(sg, n_all, tok, tile_end, fl.dst[f], fl.base[f]);
+                } else if (wi < n4 + n2) {
+                    const int w2 = wi - n4;
+                    const int e = w2 & 7, q = w2 >> 3, nfc = fl.cls_nf[1];
+                    const int f = fl.cls_field[1][q % nfc];
+                    const int64_t tok = tile_begin + (int64_t)bl.chunk[1][q / nfc] * 8 + e;
+                    move_element<2>(sg, n_all, tok, tile_end, fl.dst[f], fl.base[f]);
+                } else {
+                    const int w1 = wi - n4 - n2;
+                    const int e = w1 & 15, q = w1 >> 4, nfc = fl.cls_nf[2];
+                    const int f = fl.cls_field[2][q % nfc];
+                    const int64_t tok = tile_begin + (int64_t)bl.chunk[2][q / nfc] * 16 + e;
+                    move_element<1>(sg, n_all, tok, tile_end, fl.dst[f], fl.base[f]);
+                }
+            }
         }
         if (!more) break;
         seg_base += SEG_BATCH;
