@@ -124,9 +124,12 @@ __device__ __forceinline__ u32x4 realign(u32x4 v, uint32_t x, uint32_t sh) {
     return o;
 }
 
-constexpr int U4 = GATHER_TILE / 4 / GATHER_BLOCK;        // 16-byte chunks per lane, 4-byte fields
-constexpr int FIELD_GROUP = 4;                            // fields whose loads are in flight together
-static_assert(GATHER_TILE == 2048 && GATHER_BLOCK == 256, "lane/chunk mapping below assumes 2048 tokens x 256 lanes");
+// 16-byte chunks of a tile per element size, and how many of them each lane owns
+constexpr int N4 = GATHER_TILE / 4, N2 = GATHER_TILE / 8, N1 = GATHER_TILE / 16;
+constexpr int U4 = (N4 + GATHER_BLOCK - 1) / GATHER_BLOCK;
+constexpr int U2 = (N2 + GATHER_BLOCK - 1) / GATHER_BLOCK;
+constexpr int U1 = (N1 + GATHER_BLOCK - 1) / GATHER_BLOCK;
+constexpr int FIELD_GROUP = 1;                            // fields whose loads are in flight together
 
 struct FieldLds {
     const char* base[DC_MAX_FIELDS][DC_MAX_SRC_SHARDS];
@@ -203,47 +206,61 @@ __global__ __launch_bounds__(GATHER_BLOCK) void gather_kernel(GatherArgs a, Fiel
         const int64_t pass_end = more ? sg.start[SEG_BATCH] : tile_end;
 
         // one lookup per element size, shared by every field of that size
-        Chunk c4[U4];
+        Chunk c4[U4], c2[U2], c1[U1];
 #pragma unroll
-        for (int u = 0; u < U4; ++u)
-            c4[u] = classify<4>(sg, n_all, tid + u * GATHER_BLOCK, tile_begin, tile_end, pass_begin, pass_end);
-        const Chunk c2 = classify<8>(sg, n_all, tid, tile_begin, tile_end, pass_begin, pass_end);
-        Chunk c1 = classify<16>(sg, n_all, tid & 127, tile_begin, tile_end, pass_begin, pass_end);
-        if (tid >= 128) c1.mode = 0;
+        for (int u = 0; u < U4; ++u) {
+            const int ch = tid + u * GATHER_BLOCK;
+            c4[u] = classify<4>(sg, n_all, ch, tile_begin, tile_end, pass_begin, pass_end);
+            if (ch >= N4) c4[u].mode = 0;
+            if (c4[u].mode == 2) bl.chunk[0][atomicAdd(&bl.count[0], 1)] = (uint16_t)ch;
+        }
 #pragma unroll
-        for (int u = 0; u < U4; ++u)
-            if (c4[u].mode == 2) bl.chunk[0][atomicAdd(&bl.count[0], 1)] = (uint16_t)(tid + u * GATHER_BLOCK);
-        if (c2.mode == 2) bl.chunk[1][atomicAdd(&bl.count[1], 1)] = (uint16_t)tid;
-        if (c1.mode == 2) bl.chunk[2][atomicAdd(&bl.count[2], 1)] = (uint16_t)tid;
+        for (int u = 0; u < U2; ++u) {
+            const int ch = tid + u * GATHER_BLOCK;
+            c2[u] = classify<8>(sg, n_all, ch, tile_begin, tile_end, pass_begin, pass_end);
+            if (ch >= N2) c2[u].mode = 0;
+            if (c2[u].mode == 2) bl.chunk[1][atomicAdd(&bl.count[1], 1)] = (uint16_t)ch;
+        }
+#pragma unroll
+        for (int u = 0; u < U1; ++u) {
+            const int ch = tid + u * GATHER_BLOCK;
+            c1[u] = classify<16>(sg, n_all, ch, tile_begin, tile_end, pass_begin, pass_end);
+            if (ch >= N1) c1[u].mode = 0;
+            if (c1[u].mode == 2) bl.chunk[2][atomicAdd(&bl.count[2], 1)] = (uint16_t)ch;
+        }
         __syncthreads();
 
         for (int f0 = 0; f0 < nf; f0 += FIELD_GROUP) {
             u32x4 v[FIELD_GROUP][U4];
-            uint32_t x[FIELD_GROUP];
-            uint32_t sh[FIELD_GROUP];
+            uint32_t x[FIELD_GROUP][U2];
+            uint32_t sh[FIELD_GROUP][U2];
             // ---- all loads of the group ----
 #pragma unroll
             for (int g = 0; g < FIELD_GROUP; ++g) {
                 const int f = f0 + g;
-                x[g] = 0; sh[g] = 0;
                 if (f < nf) {
                     const int es = fl.es[f];
                     if (es == 4) {
+                        uint32_t unused;
 #pragma unroll
                         for (int u = 0; u < U4; ++u)
-                            if (c4[u].mode == 1) load_chunk<4>(fl.base[f][c4[u].shard] + c4[u].elem * 4, v[g][u], x[g]);
+                            if (c4[u].mode == 1) load_chunk<4>(fl.base[f][c4[u].shard] + c4[u].elem * 4, v[g][u], unused);
                     } else if (es == 2) {
-                        if (c2.mode == 1) {
-                            const char* p = fl.base[f][c2.shard] + c2.elem * 2;
-                            sh[g] = reinterpret_cast<uintptr_t>(p) & 3;
-                            load_chunk<2>(p, v[g][0], x[g]);
-                        }
+#pragma unroll
+                        for (int u = 0; u < U2; ++u)
+                            if (c2[u].mode == 1) {
+                                const char* p = fl.base[f][c2[u].shard] + c2[u].elem * 2;
+                                sh[g][u] = reinterpret_cast<uintptr_t>(p) & 3;
+                                load_chunk<2>(p, v[g][u], x[g][u]);
+                            }
                     } else {
-                        if (c1.mode == 1) {
-                            const char* p = fl.base[f][c1.shard] + c1.elem;
-                            sh[g] = reinterpret_cast<uintptr_t>(p) & 3;
-                            load_chunk<1>(p, v[g][0], x[g]);
-                        }
+#pragma unroll
+                        for (int u = 0; u < U1; ++u)
+                            if (c1[u].mode == 1) {
+                                const char* p = fl.base[f][c1[u].shard] + c1[u].elem;
+                                sh[g][u] = reinterpret_cast<uintptr_t>(p) & 3;
+                                load_chunk<1>(p, v[g][u], x[g][u]);
+                            }
                     }
                 }
             }
@@ -259,9 +276,13 @@ __global__ __launch_bounds__(GATHER_BLOCK) void gather_kernel(GatherArgs a, Fiel
                         for (int u = 0; u < U4; ++u)
                             if (c4[u].mode == 1) store16(dst + c4[u].c0 * 4, v[g][u]);
                     } else if (es == 2) {
-                        if (c2.mode == 1) store16(dst + c2.c0 * 2, realign(v[g][0], x[g], sh[g]));
+#pragma unroll
+                        for (int u = 0; u < U2; ++u)
+                            if (c2[u].mode == 1) store16(dst + c2[u].c0 * 2, realign(v[g][u], x[g][u], sh[g][u]));
                     } else {
-                        if (c1.mode == 1) store16(dst + c1.c0, realign(v[g][0], x[g], sh[g]));
+#pragma unroll
+                        for (int u = 0; u < U1; ++u)
+                            if (c1[u].mode == 1) store16(dst + c1[u].c0, realign(v[g][u], x[g][u], sh[g][u]));
                     }
                 }
             }
