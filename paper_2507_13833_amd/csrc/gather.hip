@@ -20,9 +20,11 @@ namespace dc {
 
 constexpr int GATHER_BLOCK = 256;
 constexpr int NSEG = SEG_BATCH + SEG_AHEAD;
+constexpr int32_t REL_FAR = 1 << 30;            // "starts beyond this tile" in tile-relative tokens
 
 struct GatherArgs {
     int32_t        n_seq;
+    int32_t        n_tiles;
     int64_t        capacity;
     const int64_t* dst_tok_off;
     const int64_t* slot_src_off;
@@ -31,28 +33,31 @@ struct GatherArgs {
     const int32_t* tile_first;
 };
 
+// A batch of slot descriptors of the tile being moved.  Token positions are relative to
+// the tile's first token, so all searching is 32-bit.
 struct SegLds {
-    int64_t start[NSEG];
-    int64_t src[NSEG];
-    int32_t len[NSEG];
-    int32_t shard[NSEG];
+    int32_t start[NSEG];           // first destination token of the slot (REL_FAR: none / beyond the tile)
+    int32_t lensh[NSEG];           // length | rollout shard << 26
+    int64_t src[NSEG];             // source element offset inside the rollout shard
 };
+__device__ __forceinline__ int32_t seg_len(int32_t lensh) { return lensh & ((1 << 26) - 1); }
+__device__ __forceinline__ int32_t seg_shard(int32_t lensh) { return lensh >> 26; }
 
 // Largest k in [0, n) with start[k] <= tok, or -1.
-__device__ __forceinline__ int find_seg(const int64_t* start, int n, int64_t tok) {
+__device__ __forceinline__ int find_seg(const int32_t* start, int n, int32_t tok) {
     int lo = 0, hi = n;                       // first k with start[k] > tok
     while (lo < hi) {
-        int mid = (lo + hi) >> 1;
+        const int mid = (lo + hi) >> 1;
         if (start[mid] <= tok) lo = mid + 1; else hi = mid;
     }
     return lo - 1;
 }
 
 // Number of entries with start[k] < bound (start is non-decreasing).
-__device__ __forceinline__ int count_below(const int64_t* start, int n, int64_t bound) {
+__device__ __forceinline__ int count_below(const int32_t* start, int n, int32_t bound) {
     int lo = 0, hi = n;
     while (lo < hi) {
-        int mid = (lo + hi) >> 1;
+        const int mid = (lo + hi) >> 1;
         if (start[mid] < bound) lo = mid + 1; else hi = mid;
     }
     return lo;
@@ -73,29 +78,24 @@ __device__ __forceinline__ void store_elem(char* d, uint32_t v) {
 
 // Where one 16-byte destination chunk comes from.  Shared by all fields of one element size.
 struct Chunk {
-    int     mode;      // 0: not mine in this pass, 1: inside one slot, 2: element by element
-    int     k;         // slot (index into the LDS batch) of the chunk's first token, or -1
-    int     shard;     // mode 1: rollout shard
+    int32_t mode;      // 0: not mine in this pass, 1: inside one slot, 2: element by element; | shard << 2
     int64_t elem;      // mode 1: source element index of the chunk's first token
-    int64_t c0;        // first destination token
 };
 
 template <int TPC>
-__device__ __forceinline__ Chunk classify(const SegLds& sg, int n_all, int chunk, int64_t tile_begin,
-                                          int64_t tile_end, int64_t pass_begin, int64_t pass_end) {
+__device__ __forceinline__ Chunk classify(const SegLds& sg, int n_all, int chunk, int32_t tile_len,
+                                          int32_t pass_begin, int32_t pass_end) {
     Chunk c;
-    c.c0 = tile_begin + (int64_t)chunk * TPC;
-    c.mode = 0; c.k = -1; c.shard = 0; c.elem = 0;
-    if (c.c0 >= pass_begin && c.c0 < pass_end) {
-        const int k = find_seg(sg.start, n_all, c.c0);
-        c.k = k;
+    const int32_t c0 = chunk * TPC;
+    c.mode = 0; c.elem = 0;
+    if (c0 >= pass_begin && c0 < pass_end) {
+        const int k = find_seg(sg.start, n_all, c0);
         c.mode = 2;
         if (k >= 0) {
-            const int64_t st = sg.start[k];
-            if (c.c0 + TPC <= st + sg.len[k] && c.c0 + TPC <= tile_end) {
-                c.mode = 1;
-                c.shard = sg.shard[k];
-                c.elem = sg.src[k] + (c.c0 - st);
+            const int32_t st = sg.start[k], ls = sg.lensh[k];
+            if (c0 + TPC <= st + seg_len(ls) && c0 + TPC <= tile_len) {
+                c.mode = 1 | (seg_shard(ls) << 2);
+                c.elem = sg.src[k] + (c0 - st);
             }
         }
     }
@@ -129,7 +129,6 @@ constexpr int N4 = GATHER_TILE / 4, N2 = GATHER_TILE / 8, N1 = GATHER_TILE / 16;
 constexpr int U4 = (N4 + GATHER_BLOCK - 1) / GATHER_BLOCK;
 constexpr int U2 = (N2 + GATHER_BLOCK - 1) / GATHER_BLOCK;
 constexpr int U1 = (N1 + GATHER_BLOCK - 1) / GATHER_BLOCK;
-constexpr int FIELD_GROUP = 1;                            // fields whose loads are in flight together
 
 struct FieldLds {
     const char* base[DC_MAX_FIELDS][DC_MAX_SRC_SHARDS];
@@ -147,144 +146,124 @@ struct BoundaryLds {
     uint16_t chunk[3][GATHER_TILE / 4];
 };
 
-// Element (field, chunk, e) of a boundary chunk: find its slot, copy it.
+// Element `tok` (tile-relative) of a boundary chunk: find its slot, copy it.
 template <int ES>
-__device__ __forceinline__ void move_element(const SegLds& sg, int n_all, int64_t tok, int64_t tile_end,
-                                             char* dst, const char* const* src_base) {
-    if (tok >= tile_end) return;
+__device__ __forceinline__ void move_element(const SegLds& sg, int n_all, int32_t tok, int32_t tile_len,
+                                             int64_t tile_begin, char* dst, const char* const* src_base) {
+    if (tok >= tile_len) return;
     const int k = find_seg(sg.start, n_all, tok);
     if (k < 0) return;
-    const int64_t st = sg.start[k];
-    if (tok >= st + sg.len[k]) return;
-    store_elem<ES>(dst + tok * ES, load_elem<ES>(src_base[sg.shard[k]] + (sg.src[k] + (tok - st)) * ES));
+    const int32_t st = sg.start[k], ls = sg.lensh[k];
+    if (tok >= st + seg_len(ls)) return;
+    store_elem<ES>(dst + (tile_begin + tok) * ES,
+                   load_elem<ES>(src_base[seg_shard(ls)] + (sg.src[k] + (tok - st)) * ES));
 }
 
-__global__ __launch_bounds__(GATHER_BLOCK) void gather_kernel(GatherArgs a, FieldTable ft) {
-    __shared__ SegLds sg;
-    __shared__ FieldLds fl;
-    __shared__ BoundaryLds bl;
+// Descriptors of slots seg_base + lane and (lanes < SEG_AHEAD) seg_base + SEG_BATCH + lane,
+// relative to the tile that starts at token tile_begin.
+struct SlotRegs {
+    int32_t st[2], ls[2];
+    int64_t so[2];
+};
 
-    const int64_t tile_begin = (int64_t)blockIdx.x * GATHER_TILE;
-    const int64_t tile_end = min(tile_begin + (int64_t)GATHER_TILE, a.capacity);
-    if (tile_begin >= tile_end) return;
-    int seg_base = a.tile_first[blockIdx.x];
-    if (seg_base < 0 || seg_base >= a.n_seq) return;       // nothing reaches into this tile
-
-    if (threadIdx.x < DC_MAX_FIELDS * DC_MAX_SRC_SHARDS) {
-        const int f = threadIdx.x / DC_MAX_SRC_SHARDS, s = threadIdx.x % DC_MAX_SRC_SHARDS;
-        fl.base[f][s] = (f < ft.n_fields && s < ft.n_src) ? ft.f[f].src[s] : nullptr;
-        if (s == 0) { fl.dst[f] = ft.f[f].dst; fl.es[f] = ft.f[f].elem_bytes; }
-    }
-    if (threadIdx.x < 3) {
-        const int es = 4 >> threadIdx.x;
-        int n = 0;
-        for (int f = 0; f < ft.n_fields; ++f)
-            if (ft.f[f].elem_bytes == es) fl.cls_field[threadIdx.x][n++] = f;
-        fl.cls_nf[threadIdx.x] = n;
-    }
-    const int nf = ft.n_fields;
-    const int tid = threadIdx.x;
-
-    int64_t pass_begin = tile_begin;
-    for (;;) {
-        for (int k = tid; k < NSEG; k += GATHER_BLOCK) {
-            const int64_t j = (int64_t)seg_base + k;
-            int64_t st = INT64_MAX, so = 0;
-            int32_t ln = 0, sh = 0;
-            if (j < a.n_seq) {
-                st = a.dst_tok_off[j];
-                so = a.slot_src_off[j];
-                ln = a.slot_len[j];
-                sh = a.slot_shard[j];
-            }
-            sg.start[k] = st; sg.src[k] = so; sg.len[k] = ln; sg.shard[k] = sh;
+__device__ __forceinline__ void load_slots(const GatherArgs& a, int seg_base, int64_t tile_begin, SlotRegs& r) {
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int64_t j = (int64_t)seg_base + q * SEG_BATCH + (int)threadIdx.x;
+        r.st[q] = REL_FAR; r.so[q] = 0; r.ls[q] = 0;
+        if ((q == 0 || threadIdx.x < SEG_AHEAD) && seg_base >= 0 && j < a.n_seq) {
+            const int64_t d = a.dst_tok_off[j] - tile_begin;
+            r.st[q] = (int32_t)max((int64_t)-REL_FAR, min((int64_t)REL_FAR, d));
+            r.so[q] = a.slot_src_off[j];
+            r.ls[q] = a.slot_len[j] | (a.slot_shard[j] << 26);
         }
-        if (tid < 3) bl.count[tid] = 0;
-        __syncthreads();
-        const int n_all = count_below(sg.start, NSEG, tile_end);
+    }
+}
+
+__device__ __forceinline__ void stage_slots(SegLds& sg, const SlotRegs& r) {
+    static_assert(SEG_BATCH == GATHER_BLOCK, "one descriptor per lane plus the look-ahead");
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int k = q * SEG_BATCH + threadIdx.x;
+        if (q == 0 || threadIdx.x < SEG_AHEAD) { sg.start[k] = r.st[q]; sg.src[k] = r.so[q]; sg.lensh[k] = r.ls[q]; }
+    }
+}
+
+// One destination tile, all fields.  On entry the first batch of slot descriptors is
+// staged in sg and a barrier has made it (and bl.count = 0) visible.
+__device__ __forceinline__ void move_tile(const GatherArgs& a, SegLds& sg, const FieldLds& fl, BoundaryLds& bl,
+                                          int nf, int seg_base, int64_t tile_begin, int32_t tile_len) {
+    const int tid = threadIdx.x;
+    int32_t pass_begin = 0;
+    for (;;) {
+        const int n_all = count_below(sg.start, NSEG, tile_len);
         const bool more = n_all > SEG_BATCH;               // slot SEG_BATCH also starts inside the tile
-        const int64_t pass_end = more ? sg.start[SEG_BATCH] : tile_end;
+        const int32_t pass_end = more ? sg.start[SEG_BATCH] : tile_len;
 
         // one lookup per element size, shared by every field of that size
         Chunk c4[U4], c2[U2], c1[U1];
 #pragma unroll
         for (int u = 0; u < U4; ++u) {
             const int ch = tid + u * GATHER_BLOCK;
-            c4[u] = classify<4>(sg, n_all, ch, tile_begin, tile_end, pass_begin, pass_end);
+            c4[u] = classify<4>(sg, n_all, ch, tile_len, pass_begin, pass_end);
             if (ch >= N4) c4[u].mode = 0;
             if (c4[u].mode == 2) bl.chunk[0][atomicAdd(&bl.count[0], 1)] = (uint16_t)ch;
         }
 #pragma unroll
         for (int u = 0; u < U2; ++u) {
             const int ch = tid + u * GATHER_BLOCK;
-            c2[u] = classify<8>(sg, n_all, ch, tile_begin, tile_end, pass_begin, pass_end);
+            c2[u] = classify<8>(sg, n_all, ch, tile_len, pass_begin, pass_end);
             if (ch >= N2) c2[u].mode = 0;
             if (c2[u].mode == 2) bl.chunk[1][atomicAdd(&bl.count[1], 1)] = (uint16_t)ch;
         }
 #pragma unroll
         for (int u = 0; u < U1; ++u) {
             const int ch = tid + u * GATHER_BLOCK;
-            c1[u] = classify<16>(sg, n_all, ch, tile_begin, tile_end, pass_begin, pass_end);
+            c1[u] = classify<16>(sg, n_all, ch, tile_len, pass_begin, pass_end);
             if (ch >= N1) c1[u].mode = 0;
             if (c1[u].mode == 2) bl.chunk[2][atomicAdd(&bl.count[2], 1)] = (uint16_t)ch;
         }
         __syncthreads();
 
-        for (int f0 = 0; f0 < nf; f0 += FIELD_GROUP) {
-            u32x4 v[FIELD_GROUP][U4];
-            uint32_t x[FIELD_GROUP][U2];
-            uint32_t sh[FIELD_GROUP][U2];
-            // ---- all loads of the group ----
+        // ---- chunks inside one slot: one field at a time, loads then stores ----
+        for (int f = 0; f < nf; ++f) {
+            const int es = fl.es[f];
+            char* dst = fl.dst[f] + tile_begin * es;
+            if (es == 4) {
+                u32x4 v[U4];
+                uint32_t unused;
 #pragma unroll
-            for (int g = 0; g < FIELD_GROUP; ++g) {
-                const int f = f0 + g;
-                if (f < nf) {
-                    const int es = fl.es[f];
-                    if (es == 4) {
-                        uint32_t unused;
+                for (int u = 0; u < U4; ++u)
+                    if (c4[u].mode & 1) load_chunk<4>(fl.base[f][c4[u].mode >> 2] + c4[u].elem * 4, v[u], unused);
 #pragma unroll
-                        for (int u = 0; u < U4; ++u)
-                            if (c4[u].mode == 1) load_chunk<4>(fl.base[f][c4[u].shard] + c4[u].elem * 4, v[g][u], unused);
-                    } else if (es == 2) {
+                for (int u = 0; u < U4; ++u)
+                    if (c4[u].mode & 1) store16(dst + (tid + u * GATHER_BLOCK) * 16, v[u]);
+            } else if (es == 2) {
+                u32x4 v[U2];
+                uint32_t x[U2], sh[U2];
 #pragma unroll
-                        for (int u = 0; u < U2; ++u)
-                            if (c2[u].mode == 1) {
-                                const char* p = fl.base[f][c2[u].shard] + c2[u].elem * 2;
-                                sh[g][u] = reinterpret_cast<uintptr_t>(p) & 3;
-                                load_chunk<2>(p, v[g][u], x[g][u]);
-                            }
-                    } else {
-#pragma unroll
-                        for (int u = 0; u < U1; ++u)
-                            if (c1[u].mode == 1) {
-                                const char* p = fl.base[f][c1[u].shard] + c1[u].elem;
-                                sh[g][u] = reinterpret_cast<uintptr_t>(p) & 3;
-                                load_chunk<1>(p, v[g][u], x[g][u]);
-                            }
+                for (int u = 0; u < U2; ++u)
+                    if (c2[u].mode & 1) {
+                        const char* p = fl.base[f][c2[u].mode >> 2] + c2[u].elem * 2;
+                        sh[u] = reinterpret_cast<uintptr_t>(p) & 3;
+                        load_chunk<2>(p, v[u], x[u]);
                     }
-                }
-            }
-            // ---- all stores of the group ----
 #pragma unroll
-            for (int g = 0; g < FIELD_GROUP; ++g) {
-                const int f = f0 + g;
-                if (f < nf) {
-                    const int es = fl.es[f];
-                    char* dst = fl.dst[f];
-                    if (es == 4) {
+                for (int u = 0; u < U2; ++u)
+                    if (c2[u].mode & 1) store16(dst + (tid + u * GATHER_BLOCK) * 16, realign(v[u], x[u], sh[u]));
+            } else {
+                u32x4 v[U1];
+                uint32_t x[U1], sh[U1];
 #pragma unroll
-                        for (int u = 0; u < U4; ++u)
-                            if (c4[u].mode == 1) store16(dst + c4[u].c0 * 4, v[g][u]);
-                    } else if (es == 2) {
-#pragma unroll
-                        for (int u = 0; u < U2; ++u)
-                            if (c2[u].mode == 1) store16(dst + c2[u].c0 * 2, realign(v[g][u], x[g][u], sh[g][u]));
-                    } else {
-#pragma unroll
-                        for (int u = 0; u < U1; ++u)
-                            if (c1[u].mode == 1) store16(dst + c1[u].c0, realign(v[g][u], x[g][u], sh[g][u]));
+                for (int u = 0; u < U1; ++u)
+                    if (c1[u].mode & 1) {
+                        const char* p = fl.base[f][c1[u].mode >> 2] + c1[u].elem;
+                        sh[u] = reinterpret_cast<uintptr_t>(p) & 3;
+                        load_chunk<1>(p, v[u], x[u]);
                     }
-                }
+#pragma unroll
+                for (int u = 0; u < U1; ++u)
+                    if (c1[u].mode & 1) store16(dst + (tid + u * GATHER_BLOCK) * 16, realign(v[u], x[u], sh[u]));
             }
         }
         // ---- boundary chunks: one element per lane and step ----
@@ -296,28 +275,67 @@ __global__ __launch_bounds__(GATHER_BLOCK) void gather_kernel(GatherArgs a, Fiel
                 if (wi < n4) {
                     const int e = wi & 3, q = wi >> 2, nfc = fl.cls_nf[0];
                     const int f = fl.cls_field[0][q % nfc];
-                    const int64_t tok = tile_begin + (int64_t)bl.chunk[0][q / nfc] * 4 + e;
-                    move_element<4>(sg, n_all, tok, tile_end, fl.dst[f], fl.base[f]);
+                    const int32_t tok = (int32_t)bl.chunk[0][q / nfc] * 4 + e;
+                    move_element<4>(sg, n_all, tok, tile_len, tile_begin, fl.dst[f], fl.base[f]);
                 } else if (wi < n4 + n2) {
                     const int w2 = wi - n4;
                     const int e = w2 & 7, q = w2 >> 3, nfc = fl.cls_nf[1];
                     const int f = fl.cls_field[1][q % nfc];
-                    const int64_t tok = tile_begin + (int64_t)bl.chunk[1][q / nfc] * 8 + e;
-                    move_element<2>(sg, n_all, tok, tile_end, fl.dst[f], fl.base[f]);
+                    const int32_t tok = (int32_t)bl.chunk[1][q / nfc] * 8 + e;
+                    move_element<2>(sg, n_all, tok, tile_len, tile_begin, fl.dst[f], fl.base[f]);
                 } else {
                     const int w1 = wi - n4 - n2;
                     const int e = w1 & 15, q = w1 >> 4, nfc = fl.cls_nf[2];
                     const int f = fl.cls_field[2][q % nfc];
-                    const int64_t tok = tile_begin + (int64_t)bl.chunk[2][q / nfc] * 16 + e;
-                    move_element<1>(sg, n_all, tok, tile_end, fl.dst[f], fl.base[f]);
+                    const int32_t tok = (int32_t)bl.chunk[2][q / nfc] * 16 + e;
+                    move_element<1>(sg, n_all, tok, tile_len, tile_begin, fl.dst[f], fl.base[f]);
                 }
             }
         }
         if (!more) break;
+        // rare: more than SEG_BATCH slots start inside this tile - next batch, loaded in place
         seg_base += SEG_BATCH;
         pass_begin = pass_end;
         __syncthreads();
+        SlotRegs r;
+        load_slots(a, seg_base, tile_begin, r);
+        stage_slots(sg, r);
+        if (tid < 3) bl.count[tid] = 0;
+        __syncthreads();
     }
+}
+
+__global__ __launch_bounds__(GATHER_BLOCK) void gather_kernel(GatherArgs a, FieldTable ft) {
+    __shared__ SegLds sg;
+    __shared__ FieldLds fl;
+    __shared__ BoundaryLds bl;
+    const int tid = threadIdx.x;
+
+    const int64_t tile_begin = (int64_t)blockIdx.x * GATHER_TILE;
+    const int64_t left = a.capacity - tile_begin;
+    const int32_t tile_len = (int32_t)(left < GATHER_TILE ? left : GATHER_TILE);
+    if (tile_len <= 0) return;
+    const int seg_base = a.tile_first[blockIdx.x];
+    if (seg_base < 0 || seg_base >= a.n_seq) return;       // nothing reaches into this tile
+
+    SlotRegs r;
+    load_slots(a, seg_base, tile_begin, r);
+    if (tid < DC_MAX_FIELDS * DC_MAX_SRC_SHARDS) {
+        const int f = tid / DC_MAX_SRC_SHARDS, s = tid % DC_MAX_SRC_SHARDS;
+        fl.base[f][s] = (f < ft.n_fields && s < ft.n_src) ? ft.f[f].src[s] : nullptr;
+        if (s == 0) { fl.dst[f] = ft.f[f].dst; fl.es[f] = ft.f[f].elem_bytes; }
+    }
+    if (tid < 3) {
+        const int es = 4 >> tid;
+        int n = 0;
+        for (int f = 0; f < ft.n_fields; ++f)
+            if (ft.f[f].elem_bytes == es) fl.cls_field[tid][n++] = f;
+        fl.cls_nf[tid] = n;
+        bl.count[tid] = 0;
+    }
+    stage_slots(sg, r);
+    __syncthreads();
+    move_tile(a, sg, fl, bl, ft.n_fields, seg_base, tile_begin, tile_len);
 }
 
 hipError_t launch_gather(int32_t n_seq, const FieldTable& ft, int64_t dst_capacity,
@@ -331,6 +349,7 @@ hipError_t launch_gather(int32_t n_seq, const FieldTable& ft, int64_t dst_capaci
     a.slot_len = ws.slot_len;
     a.slot_shard = ws.slot_shard;
     a.tile_first = ws.tile_first;
+    a.n_tiles = (int32_t)ws.n_tiles;
     hipLaunchKernelGGL(gather_kernel, dim3((unsigned)ws.n_tiles), dim3(GATHER_BLOCK), 0, st, a, ft);
     return hipGetLastError();
 }
