@@ -2,22 +2,23 @@
 // are part of the payload the Data Coordinator moves, Sec. 1) fused with its
 // broadcast over the rollout layout's tokens.
 //
-// One launch.  Lanes 0..N-1 of the grid first write adv_seq[i].  Then every
-// workgroup owns one tile of ADV_TILE tokens of one rollout shard: it finds the
-// sequences that overlap the tile (binary search over the shard's increasing
-// offsets), recomputes their advantages from the group's rewards (G float64
-// additions each - cheaper than a second launch) into LDS, and streams the tile:
-// 4 mask bytes in, 16 bytes of float32 out per lane and step (5 B/token, HBM-bound).
+// One launch, one wavefront per sequence.  The wave finds the sequence's prompt group,
+// recomputes the group's mean and std from its G rewards (float64, in index order;
+// cheaper than a second launch or a grid-wide dependency), writes adv_seq[i] and then
+// streams the sequence's own token range: 4 mask bytes in, 16 bytes of float32 out per
+// lane and step (5 B/token, HBM-bound).  A sequence is one contiguous run in its
+// rollout shard, so no lane ever has to search for the sequence a token belongs to.
 #include "dc_device.h"
 #include "dc_internal.h"
 
 namespace dc {
 
 constexpr int ADV_BLOCK = 256;
-constexpr int ADV_NSEG = SEG_BATCH + 4;                 // a 4-token chunk can reach 3 segments ahead
+constexpr int ADV_WAVES = ADV_BLOCK / WAVE;
+constexpr int ADV_UNROLL = 16;                          // 4-token chunks in flight per lane
 
 struct AdvArgs {
-    int32_t        n_seq, n_groups, ddof, n_src;
+    int32_t        n_seq, n_groups, ddof, per_token;
     double         eps;
     const int64_t* src_tok_off;
     const int32_t* seq_len;
@@ -25,157 +26,123 @@ struct AdvArgs {
     const int32_t* group_off;
     float*         adv_seq;
     int32_t*       status;
-    int32_t        tile_off[DC_MAX_SRC_SHARDS + 1];     // first workgroup of each rollout shard
     const uint8_t* mask[DC_MAX_SRC_SHARDS];
     float*         adv_tok[DC_MAX_SRC_SHARDS];
 };
 
-// Advantage of sequence i (float64 arithmetic, one rounding to float32).
-__device__ float seq_advantage(const AdvArgs& a, int i) {
+// Advantage of sequence i, evaluated by a whole wave (all lanes return the same value):
+// float64 arithmetic in index order, one rounding to float32.  The group's rewards are
+// fetched one per lane (64 at a time) and then consumed in order from registers, so the
+// wave pays one memory round trip for them instead of one per reward.
+__device__ __forceinline__ float seq_advantage(const AdvArgs& a, int i) {
     if (a.n_groups <= 0) return 0.0f;
-    // group of i: last g with group_off[g] <= i
-    int lo = 0, hi = a.n_groups;                        // invariant: group_off[lo] <= i
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (a.group_off[mid] <= i) lo = mid; else hi = mid;
+    const int lane = threadIdx.x & (WAVE - 1);
+    // group of i: try the position it has when all groups have the same size, else bisect
+    int g = (int)(((int64_t)i * a.n_groups) / a.n_seq);
+    int g0 = a.group_off[g], g1 = a.group_off[g + 1];
+    if (i < g0 || i >= g1) {
+        int lo = 0, hi = a.n_groups;                    // invariant: group_off[lo] <= i
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (a.group_off[mid] <= i) lo = mid; else hi = mid;
+        }
+        g0 = a.group_off[lo];
+        g1 = a.group_off[lo + 1];
     }
-    const int g0 = a.group_off[lo], g1 = a.group_off[lo + 1];
     if (g0 < 0 || g1 > a.n_seq || i < g0 || i >= g1) return 0.0f;   // bad group table (flagged elsewhere)
     const int G = g1 - g0;
-    const float r0 = a.reward[g0];
+    const uint32_t r0 = __float_as_uint(a.reward[g0]);
+    const double ri = (double)a.reward[i];
+
     bool same = true;
     double sum = 0.0;
-    for (int q = g0; q < g1; ++q) {
-        const float r = a.reward[q];
-        same = same && (__float_as_uint(r) == __float_as_uint(r0));
-        sum += (double)r;
+    for (int base = g0; base < g1; base += WAVE) {
+        const int n = min(WAVE, g1 - base);
+        const float mine = lane < n ? a.reward[base + lane] : 0.0f;
+        for (int q = 0; q < n; ++q) {
+            const uint32_t bits = (uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(mine), q);
+            same = same && bits == r0;
+            sum += (double)__uint_as_float(bits);
+        }
     }
     if (same || G - a.ddof <= 0) return 0.0f;
     const double mean = sum / (double)G;
     double ss = 0.0;
-    for (int q = g0; q < g1; ++q) {
-        const double d = (double)a.reward[q] - mean;
-        ss += d * d;
+    for (int base = g0; base < g1; base += WAVE) {
+        const int n = min(WAVE, g1 - base);
+        const float mine = lane < n ? a.reward[base + lane] : 0.0f;
+        for (int q = 0; q < n; ++q) {
+            const double d = (double)__uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(mine), q)) - mean;
+            ss += d * d;
+        }
     }
     const double sd = sqrt(ss / (double)(G - a.ddof));
-    return (float)(((double)a.reward[i] - mean) / (sd + a.eps));
+    return (float)((ri - mean) / (sd + a.eps));
 }
 
-struct AdvLds {
-    int64_t start[ADV_NSEG];
-    int32_t len[ADV_NSEG];
-    float   adv[ADV_NSEG];
-};
+__device__ __forceinline__ u32x4 select_by_mask(uint32_t mk, uint32_t av) {
+    u32x4 o;
+    o.x = (mk & 0x000000FFu) ? av : 0u;
+    o.y = (mk & 0x0000FF00u) ? av : 0u;
+    o.z = (mk & 0x00FF0000u) ? av : 0u;
+    o.w = (mk & 0xFF000000u) ? av : 0u;
+    return o;
+}
 
 __global__ __launch_bounds__(ADV_BLOCK) void advantage_kernel(AdvArgs a, SourceDesc sd) {
-    __shared__ AdvLds L;
     const int N = a.n_seq;
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int64_t wv = (int64_t)blockIdx.x * ADV_WAVES + threadIdx.x / WAVE;   // one wave per sequence
 
-    // ---- per-sequence advantages + layout validation ----
-    const int64_t gid = (int64_t)blockIdx.x * ADV_BLOCK + threadIdx.x;
-    if (gid < N) {
-        const int i = (int)gid;
-        a.adv_seq[i] = seq_advantage(a, i);
-        int s = 0;
-        while (s + 1 < sd.n_src && i >= sd.seq_off[s + 1]) ++s;
-        const int64_t so = a.src_tok_off[i];
-        const int32_t ln = a.seq_len[i];
-        if (ln <= 0 || ln > DC_MAX_SEQ_LEN) set_status(a.status, DC_ERR_ZERO_LENGTH_SEQ);
-        else if (so < 0 || so + ln > sd.tokens[s]) set_status(a.status, DC_ERR_BAD_LAYOUT);
-        else if (i + 1 < sd.seq_off[s + 1] && a.src_tok_off[i + 1] < so + ln) set_status(a.status, DC_ERR_BAD_LAYOUT);
-    }
-    if (gid <= a.n_groups) {
-        const int g = (int)gid;
+    if (wv <= a.n_groups && lane == 0) {                 // group table: [0] = 0, non-decreasing, last = N
+        const int g = (int)wv;
         const int32_t v = a.group_off[g];
         bool bad = v < 0 || v > N || (g == 0 && v != 0) || (g == a.n_groups && v != N);
         if (g < a.n_groups && a.group_off[g + 1] < v) bad = true;
         if (bad) set_status(a.status, DC_ERR_BAD_LAYOUT);
     }
-    if (a.n_src == 0) return;                           // no per-token output requested
+    if (wv >= N) return;
+    const int i = (int)wv;
+    const float adv = seq_advantage(a, i);
+    if (lane == 0) a.adv_seq[i] = adv;
 
-    // ---- which rollout shard / tile is mine ----
     int s = 0;
-    while (s + 1 < a.n_src && (int)blockIdx.x >= a.tile_off[s + 1]) ++s;
-    if ((int)blockIdx.x >= a.tile_off[a.n_src]) return; // workgroup only served the per-sequence part
-    const int64_t shard_tokens = sd.tokens[s];
-    const int64_t tile_begin = (int64_t)(blockIdx.x - a.tile_off[s]) * ADV_TILE;
-    const int64_t tile_end = min(tile_begin + (int64_t)ADV_TILE, shard_tokens);
-    const int seq_lo = sd.seq_off[s], seq_hi = sd.seq_off[s + 1];
-    if (tile_begin >= tile_end || seq_lo >= seq_hi) return;
+    while (s + 1 < sd.n_src && i >= sd.seq_off[s + 1]) ++s;
+    const int64_t so = a.src_tok_off[i];
+    const int32_t ln = a.seq_len[i];
+    if (ln <= 0 || ln > DC_MAX_SEQ_LEN) {
+        if (lane == 0) set_status(a.status, DC_ERR_ZERO_LENGTH_SEQ);
+        return;
+    }
+    if (so < 0 || so + ln > sd.tokens[s] || (i + 1 < sd.seq_off[s + 1] && a.src_tok_off[i + 1] < so + ln)) {
+        if (lane == 0) set_status(a.status, DC_ERR_BAD_LAYOUT);   // outside its buffer or overlapping the next
+        return;
+    }
+    if (!a.per_token) return;
+
     const uint8_t* __restrict__ mask = a.mask[s];
     float* __restrict__ out = a.adv_tok[s];
-
-    // first sequence that can reach into the tile: last i with src_tok_off[i] <= tile_begin
-    int lo = seq_lo, hi = seq_hi;                       // first i with src_tok_off[i] > tile_begin
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (a.src_tok_off[mid] <= tile_begin) lo = mid + 1; else hi = mid;
-    }
-    int seg_base = max(lo - 1, seq_lo);
-
-    int64_t pass_begin = tile_begin;
-    for (;;) {
-        for (int k = threadIdx.x; k < ADV_NSEG; k += ADV_BLOCK) {
-            const int64_t i = (int64_t)seg_base + k;
-            int64_t st = INT64_MAX;
-            int32_t ln = 0;
-            float av = 0.0f;
-            if (i < seq_hi) {
-                st = a.src_tok_off[i];
-                ln = a.seq_len[i];
-                if (ln < 0) ln = 0;
-                if (st < tile_end && st + ln > tile_begin) av = seq_advantage(a, (int)i);
-            }
-            L.start[k] = st; L.len[k] = ln; L.adv[k] = av;
-        }
-        __syncthreads();
-        int n_all = 0;                                  // entries with start < tile_end
-        {
-            int l2 = 0, h2 = ADV_NSEG;
-            while (l2 < h2) { const int mid = (l2 + h2) >> 1; if (L.start[mid] < tile_end) l2 = mid + 1; else h2 = mid; }
-            n_all = l2;
-        }
-        const bool more = n_all > SEG_BATCH;
-        const int64_t pass_end = more ? L.start[SEG_BATCH] : tile_end;
-
-        constexpr int STEPS = ADV_TILE / 4 / ADV_BLOCK;  // 4-token chunks per lane
+    const uint32_t av = __float_as_uint(adv);
+    const int64_t end = so + ln;
+    const int64_t a4 = min(end, (so + 3) & ~int64_t(3));         // first 4-aligned token
+    const int64_t e4 = max(a4, end & ~int64_t(3));               // end of the 4-aligned body
+    // ragged head and tail: at most 3 tokens each
+    if (lane < 3 && so + lane < a4) out[so + lane] = mask[so + lane] ? adv : 0.0f;
+    if (lane >= 32 && lane < 35 && e4 + (lane - 32) < end) out[e4 + lane - 32] = mask[e4 + lane - 32] ? adv : 0.0f;
+    // body: 4 tokens per lane and step, ADV_UNROLL steps in flight
+    const int64_t c_end = e4 >> 2;
+    for (int64_t c = (a4 >> 2) + lane; c < c_end; c += WAVE * ADV_UNROLL) {
+        uint32_t mk[ADV_UNROLL];
 #pragma unroll
-        for (int u = 0; u < STEPS; ++u) {
-            const int64_t c0 = tile_begin + (int64_t)(threadIdx.x + u * ADV_BLOCK) * 4;
-            if (c0 < pass_begin || c0 >= pass_end) continue;
-            int l3 = 0, h3 = n_all;                     // largest k with start[k] <= c0
-            while (l3 < h3) { const int mid = (l3 + h3) >> 1; if (L.start[mid] <= c0) l3 = mid + 1; else h3 = mid; }
-            int k = l3 - 1;
-            bool whole = false;
-            if (k >= 0) {
-                const int64_t st = L.start[k];
-                whole = c0 + 4 <= st + L.len[k] && c0 + 4 <= tile_end;
-            }
-            if (whole) {
-                const uint32_t mk = load4(mask + c0);
-                const uint32_t av = __float_as_uint(L.adv[k]);
-                u32x4 o;
-                o.x = (mk & 0x000000FFu) ? av : 0u;
-                o.y = (mk & 0x0000FF00u) ? av : 0u;
-                o.z = (mk & 0x00FF0000u) ? av : 0u;
-                o.w = (mk & 0xFF000000u) ? av : 0u;
-                store16(out + c0, o);
-            } else {
-                for (int e = 0; e < 4; ++e) {
-                    const int64_t tok = c0 + e;
-                    if (tok >= tile_end) break;
-                    while (k + 1 < n_all && L.start[k + 1] <= tok) ++k;
-                    if (k >= 0) {
-                        const int64_t st = L.start[k];
-                        if (tok >= st && tok < st + L.len[k]) out[tok] = mask[tok] ? L.adv[k] : 0.0f;
-                    }
-                }
-            }
+        for (int u = 0; u < ADV_UNROLL; ++u) {
+            const int64_t cu = c + u * WAVE;
+            mk[u] = cu < c_end ? load4(mask + cu * 4) : 0u;
         }
-        if (!more) break;
-        seg_base += SEG_BATCH;
-        pass_begin = pass_end;
-        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < ADV_UNROLL; ++u) {
+            const int64_t cu = c + u * WAVE;
+            if (cu < c_end) store16(out + cu * 4, select_by_mask(mk[u], av));
+        }
     }
 }
 
@@ -188,23 +155,13 @@ hipError_t launch_advantage(int32_t n_seq, const SourceDesc& src, const int64_t*
     a.n_seq = n_seq; a.n_groups = n_groups; a.ddof = ddof; a.eps = eps;
     a.src_tok_off = d_src_tok_off; a.seq_len = d_seq_len; a.reward = d_reward; a.group_off = d_group_off;
     a.adv_seq = d_adv_seq; a.status = d_status;
-    const bool per_token = adv_tok_base != nullptr;
-    a.n_src = per_token ? src.n_src : 0;
-    int64_t blocks = 0;
+    a.per_token = adv_tok_base != nullptr;
     for (int s = 0; s < DC_MAX_SRC_SHARDS; ++s) {
-        a.tile_off[s] = (int32_t)blocks;
-        a.mask[s] = nullptr; a.adv_tok[s] = nullptr;
-        if (per_token && s < src.n_src) {
-            a.mask[s] = mask_base[s]; a.adv_tok[s] = adv_tok_base[s];
-            blocks += (src.tokens[s] + ADV_TILE - 1) / ADV_TILE;
-        }
+        a.mask[s] = (a.per_token && s < src.n_src) ? mask_base[s] : nullptr;
+        a.adv_tok[s] = (a.per_token && s < src.n_src) ? adv_tok_base[s] : nullptr;
     }
-    a.tile_off[DC_MAX_SRC_SHARDS] = (int32_t)blocks;
-    for (int s = src.n_src; s <= DC_MAX_SRC_SHARDS; ++s) a.tile_off[s] = (int32_t)blocks;
-    const int64_t need = ((int64_t)(n_seq > n_groups + 1 ? n_seq : n_groups + 1) + ADV_BLOCK - 1) / ADV_BLOCK;
-    const int64_t grid = blocks > need ? blocks : need;
-    if (grid == 0) return hipSuccess;
-    if (grid > 0x7FFFFFFF) return hipErrorInvalidValue;
+    const int64_t waves = n_seq > n_groups + 1 ? n_seq : n_groups + 1;
+    const int64_t grid = (waves + ADV_WAVES - 1) / ADV_WAVES;
     hipLaunchKernelGGL(advantage_kernel, dim3((unsigned)grid), dim3(ADV_BLOCK), 0, st, a, src);
     return hipGetLastError();
 }
