@@ -51,6 +51,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: 5, the largest)")
     ap.add_argument("--sets", type=int, default=3, help="rotating buffer sets (defeats cache reuse)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch a plain elementwise copy of known size (1 GiB read + 1 GiB written per "
+                         "launch): the yardstick that scales the HBM byte counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path runs on ONE GPU (all shards are logical shards on one device); "
@@ -93,6 +96,14 @@ def main() -> int:
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     gather_ms = sum(a.elapsed_time(b) for a, b in ev) / args.steps
     achieved = gather_bytes / (gather_ms * 1e-3) / 1e9
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.int32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1, out=dst)                  # one elementwise kernel: 2^30 B in, 2^30 B out
+        torch.cuda.synchronize()
+        del src, dst
 
     # per-stage device times (events around each call, outside the timed region)
     stage = {}

@@ -9,13 +9,14 @@ static inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 Workspace carve_workspace(void* base, int32_t n_seq, int64_t dst_capacity_tokens) {
     Workspace w;
     const size_t n = (size_t)(n_seq > 0 ? n_seq : 0);
-    w.n_tiles = dst_capacity_tokens > 0 ? (dst_capacity_tokens + GATHER_TILE - 1) / GATHER_TILE : 0;
+    w.n_gran = (dst_capacity_tokens > 0 ? (dst_capacity_tokens + GATHER_GRAN - 1) / GATHER_GRAN : 0) + GRAN_TABLE_PAD;
     char* p = static_cast<char*>(base);
     size_t off = 0;
     w.slot_src_off = reinterpret_cast<int64_t*>(p + off); off += round_up(n * sizeof(int64_t), 256);
     w.slot_len = reinterpret_cast<int32_t*>(p + off);     off += round_up(n * sizeof(int32_t), 256);
     w.slot_shard = reinterpret_cast<int32_t*>(p + off);   off += round_up(n * sizeof(int32_t), 256);
-    w.tile_first = reinterpret_cast<int32_t*>(p + off);   off += round_up((size_t)w.n_tiles * sizeof(int32_t), 256);
+    w.gran_first = reinterpret_cast<int32_t*>(p + off);   off += round_up((size_t)w.n_gran * sizeof(int32_t), 256);
+    w.gran_rec = reinterpret_cast<GranRec*>(p + off);     off += round_up((size_t)w.n_gran * sizeof(GranRec), 256);
     w.bytes = off + 256;
     return w;
 }
@@ -122,7 +123,7 @@ dc_status dc_plan(const dc_params* prm, const dc_source* src, const int32_t* d_s
     if (reinterpret_cast<uintptr_t>(d_ws) & 255u) return DC_ERR_INVALID_ARG;
     Workspace ws = carve_workspace(d_ws, prm->n_seq, dst_capacity_tokens);
     if (ws_bytes < ws.bytes) return DC_ERR_WORKSPACE;
-    if (ws.n_tiles > 0x7FFFFFFFLL) return DC_ERR_UNSUPPORTED_SIZE;
+    if (ws.n_gran > 0x7FFFFFFFLL) return DC_ERR_UNSUPPORTED_SIZE;
     hipError_t e = launch_plan(*prm, sd, src->d_src_tok_off, d_seq_len, d_perm, d_shard_seq_off, dst_capacity_tokens,
                                d_dst_tok_off, d_shard_tok_off, d_shard_mb_off, d_mb_seq_off, d_cu_seqlens, d_n_mb,
                                ws, d_status, static_cast<hipStream_t>(hip_stream));
@@ -144,7 +145,7 @@ dc_status dc_gather(const dc_params* prm, const dc_source* src, const dc_field* 
     if (reinterpret_cast<uintptr_t>(d_ws) & 255u) return DC_ERR_INVALID_ARG;
     Workspace ws = carve_workspace(const_cast<void*>(d_ws), prm->n_seq, dst_capacity_tokens);
     if (ws_bytes < ws.bytes) return DC_ERR_WORKSPACE;
-    if (ws.n_tiles > 0x7FFFFFFFLL) return DC_ERR_UNSUPPORTED_SIZE;
+    if (ws.n_gran > 0x7FFFFFFFLL) return DC_ERR_UNSUPPORTED_SIZE;
     FieldTable ft;
     ft.n_fields = n_fields;
     ft.n_src = sd.n_src;

@@ -7,9 +7,27 @@
 
 namespace dc {
 
-// Tokens of destination space one gather workgroup owns.  Also the granularity
-// of the per-tile "first slot" table the plan kernel leaves in the workspace.
-constexpr int GATHER_TILE = 2048;
+// Token granularity of the per-granule tables the plan leaves in the workspace.  A
+// 16-byte chunk of any field (4, 8 or 16 tokens) never crosses a granule boundary.
+constexpr int GATHER_GRAN = 1024;
+// The per-granule tables are longer than the arena needs, so a gather workgroup can read
+// the entries of a whole tile (and a few more) without a bounds test.
+constexpr int GRAN_TABLE_PAD = 16;
+// Slot descriptors kept inline per granule; granules that more slots reach into are
+// served from the per-slot arrays instead.
+constexpr int REC_SLOTS = 4;
+constexpr int32_t REL_FAR = 1 << 30;            // "no slot" / "beyond this granule" in relative tokens
+constexpr int LENSH_SHIFT = 26;                 // length | rollout shard << 26
+
+// The first REC_SLOTS slots that reach into a granule, relative to the granule's first
+// token.  Unused entries have start = REL_FAR.  64 bytes: one 16-dword scalar load.
+struct GranEntry {
+    int32_t start;           // first destination token of the slot minus the granule's first token (may be < 0)
+    int32_t lensh;           // length | rollout shard << LENSH_SHIFT
+    int64_t src_off;         // element offset of the slot's sequence in its rollout shard
+};
+struct GranRec { GranEntry e[REC_SLOTS]; };
+
 // Tokens of rollout space one advantage workgroup owns.
 constexpr int ADV_TILE = 8192;
 // Segment descriptors staged in LDS per pass over a tile, plus look-ahead so a
@@ -19,13 +37,15 @@ constexpr int SEG_AHEAD = 16;
 
 
 // Workspace carved by dc_plan for dc_gather: per-slot source descriptors
-// (validated, clamped) and the first slot of every destination tile.
+// (validated, clamped) and, for every granule boundary g * GATHER_GRAN of the
+// destination token axis, the first slot that ends after it.
 struct Workspace {
     int64_t* slot_src_off;   // [N]   element offset of the slot's sequence in its rollout shard
     int32_t* slot_len;       // [N]   tokens to copy (0 if the slot failed validation)
     int32_t* slot_shard;     // [N]   rollout shard of the slot's sequence
-    int32_t* tile_first;     // [n_tiles] first slot whose tokens reach into the tile (N if none)
-    int64_t  n_tiles;
+    int32_t* gran_first;     // [n_gran] first slot j with end(j) > g * GATHER_GRAN (N if none); non-decreasing
+    GranRec* gran_rec;       // [n_gran]
+    int64_t  n_gran;         // ceil(capacity / GATHER_GRAN) + GRAN_TABLE_PAD; entries past the arena hold N / no slot
     size_t   bytes;
 };
 Workspace carve_workspace(void* base, int32_t n_seq, int64_t dst_capacity_tokens);

@@ -3,16 +3,27 @@
 // differs).  HBM-bound; every destination byte is written once with aligned
 // 16-byte stores, every source byte is read once.
 //
-// Work decomposition: the destination token axis is cut into tiles of GATHER_TILE
-// tokens; one workgroup owns one tile for ALL fields, so no two workgroups ever
-// write the same cache line and the slot lookup is shared by the fields.  A tile's
-// slots are staged in LDS (start, length, source offset, rollout shard); each lane
-// then owns 16-byte destination chunks, finds the slot of its chunk's first token
-// by binary search in LDS and
-//   - if the chunk lies inside one slot: one (mis)aligned 16-byte source load
-//     (plus one dword and a byte funnel shift for 1- and 2-byte fields) and one
-//     aligned 16-byte store;
-//   - else (slot boundary, padding): element by element.
+// Work decomposition: FIELD-MAJOR.  The destination token axis is cut into tiles of 4096
+// tokens; the grid walks all tiles of field 0, then all tiles of field 1, ...  At any
+// moment the chip therefore streams one destination array (and the matching sequences of
+// one source array) instead of all fields at once, which keeps DRAM pages open longer than
+// a tile that touches every field.  One workgroup owns one tile of one field, one wavefront
+// a 1024-token granule of it (1, 2 or 4 16-byte chunks per lane for 1-, 2-, 4-byte
+// elements); no two workgroups ever write the same cache line.
+//
+// Where a chunk comes from:
+//   sparse tiles (at most REC_SLOTS slots reach into each granule: the usual case) - every
+//     wave works alone: it reads its granule's record (the plan left the first slots of
+//     every granule inline) with ONE scalar load, which does not queue behind the bulk
+//     traffic in the vector memory pipeline; when one slot covers all 64 chunks of a wave
+//     instruction the source address is scalar arithmetic, else every lane selects its
+//     slot with a few compares against scalar registers.  No LDS, no barrier;
+//   dense tiles (many short sequences) - the tile's slots are staged in LDS and each
+//     lane finds its chunk's slot by binary search.
+// A chunk inside one slot takes one (mis)aligned 16-byte source load (plus one dword
+// and a byte funnel shift for 1- and 2-byte fields) and one aligned 16-byte store;
+// a chunk that touches a slot boundary, padding or the arena end is copied element
+// by element.
 #include "dc_device.h"
 #include "dc_internal.h"
 
@@ -20,28 +31,32 @@ namespace dc {
 
 constexpr int GATHER_BLOCK = 256;
 constexpr int NSEG = SEG_BATCH + SEG_AHEAD;
-constexpr int32_t REL_FAR = 1 << 30;            // "starts beyond this tile" in tile-relative tokens
+constexpr int GRAN_PER_TILE = GATHER_BLOCK / WAVE;                    // one granule per wave
+constexpr int GATHER_TILE_TOKENS = GRAN_PER_TILE * GATHER_GRAN;
+constexpr int32_t LEN_MASK = (1 << LENSH_SHIFT) - 1;
+static_assert(GATHER_GRAN == WAVE * 16, "a wave covers its granule with 1, 2 or 4 chunks per lane");
+static_assert(GRAN_PER_TILE + 1 <= 8, "the tile's slice of the granule table is one 8-dword scalar load");
+static_assert(GRAN_TABLE_PAD >= 8, "that load never leaves the table");
+static_assert(sizeof(GranEntry) == 16, "one 16-byte load per record entry");
+static_assert(SEG_BATCH == GATHER_BLOCK, "one descriptor per lane plus the look-ahead");
 
 struct GatherArgs {
     int32_t        n_seq;
-    int32_t        n_tiles;
-    int64_t        capacity;
+    int64_t        capacity;                     // elements of every destination arena
     const int64_t* dst_tok_off;
     const int64_t* slot_src_off;
     const int32_t* slot_len;
     const int32_t* slot_shard;
-    const int32_t* tile_first;
+    const int32_t* gran_first;                   // padded: whole tiles plus GRAN_PER_TILE + 1 entries
+    const GranRec* gran_rec;                     // same length
 };
 
-// A batch of slot descriptors of the tile being moved.  Token positions are relative to
-// the tile's first token, so all searching is 32-bit.
+// Slot descriptors of the tile being moved, relative to the tile's first token.
 struct SegLds {
-    int32_t start[NSEG];           // first destination token of the slot (REL_FAR: none / beyond the tile)
-    int32_t lensh[NSEG];           // length | rollout shard << 26
-    int64_t src[NSEG];             // source element offset inside the rollout shard
+    int32_t start[NSEG];           // first destination token of the slot (REL_FAR: none)
+    int32_t end[NSEG];             // one past its last token
+    int64_t addr[NSEG];            // source byte address of tile-relative token 0 (may lie before the buffer)
 };
-__device__ __forceinline__ int32_t seg_len(int32_t lensh) { return lensh & ((1 << 26) - 1); }
-__device__ __forceinline__ int32_t seg_shard(int32_t lensh) { return lensh >> 26; }
 
 // Largest k in [0, n) with start[k] <= tok, or -1.
 __device__ __forceinline__ int find_seg(const int32_t* start, int n, int32_t tok) {
@@ -53,67 +68,45 @@ __device__ __forceinline__ int find_seg(const int32_t* start, int n, int32_t tok
     return lo - 1;
 }
 
-// Number of entries with start[k] < bound (start is non-decreasing).
-__device__ __forceinline__ int count_below(const int32_t* start, int n, int32_t bound) {
-    int lo = 0, hi = n;
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (start[mid] < bound) lo = mid + 1; else hi = mid;
-    }
-    return lo;
+// Payload pointers are rebuilt from integers (base + offset arithmetic in scalar registers
+// or LDS); typing them as global-address-space pointers keeps the accesses global_load /
+// global_store instead of flat ones.
+#define DC_GLOBAL __attribute__((address_space(1)))
+typedef const DC_GLOBAL char* gptr;
+typedef DC_GLOBAL char* gptr_w;
+
+// One element of 1 << lg bytes (lg is uniform).
+__device__ __forceinline__ uint32_t load_elem(int lg, gptr s) {
+    if (lg == 2) return *reinterpret_cast<const DC_GLOBAL uint32_t*>(s);
+    if (lg == 1) return *reinterpret_cast<const DC_GLOBAL uint16_t*>(s);
+    return *reinterpret_cast<const DC_GLOBAL uint8_t*>(s);
+}
+__device__ __forceinline__ void store_elem(int lg, gptr_w d, uint32_t v) {
+    if (lg == 2) *reinterpret_cast<DC_GLOBAL uint32_t*>(d) = v;
+    else if (lg == 1) *reinterpret_cast<DC_GLOBAL uint16_t*>(d) = (uint16_t)v;
+    else *reinterpret_cast<DC_GLOBAL uint8_t*>(d) = (uint8_t)v;
 }
 
-template <int ES>
-__device__ __forceinline__ uint32_t load_elem(const char* s) {
-    if (ES == 4) return *reinterpret_cast<const uint32_t*>(s);
-    if (ES == 2) return *reinterpret_cast<const uint16_t*>(s);
-    return *reinterpret_cast<const uint8_t*>(s);
+typedef DC_GLOBAL u32x4 g_u32x4;
+typedef DC_GLOBAL u32x4_a4 g_u32x4_a4;
+__device__ __forceinline__ u32x4 gload16_a4(gptr p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const g_u32x4_a4*>(p));
 }
-template <int ES>
-__device__ __forceinline__ void store_elem(char* d, uint32_t v) {
-    if (ES == 4) *reinterpret_cast<uint32_t*>(d) = v;
-    else if (ES == 2) *reinterpret_cast<uint16_t*>(d) = (uint16_t)v;
-    else *reinterpret_cast<uint8_t*>(d) = (uint8_t)v;
+__device__ __forceinline__ uint32_t gload4(gptr p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const DC_GLOBAL uint32_t*>(p));
 }
-
-// Where one 16-byte destination chunk comes from.  Shared by all fields of one element size.
-struct Chunk {
-    int32_t mode;      // 0: not mine in this pass, 1: inside one slot, 2: element by element; | shard << 2
-    int64_t elem;      // mode 1: source element index of the chunk's first token
-};
-
-template <int TPC>
-__device__ __forceinline__ Chunk classify(const SegLds& sg, int n_all, int chunk, int32_t tile_len,
-                                          int32_t pass_begin, int32_t pass_end) {
-    Chunk c;
-    const int32_t c0 = chunk * TPC;
-    c.mode = 0; c.elem = 0;
-    if (c0 >= pass_begin && c0 < pass_end) {
-        const int k = find_seg(sg.start, n_all, c0);
-        c.mode = 2;
-        if (k >= 0) {
-            const int32_t st = sg.start[k], ls = sg.lensh[k];
-            if (c0 + TPC <= st + seg_len(ls) && c0 + TPC <= tile_len) {
-                c.mode = 1 | (seg_shard(ls) << 2);
-                c.elem = sg.src[k] + (c0 - st);
-            }
-        }
-    }
-    return c;
+__device__ __forceinline__ void gstore16(gptr_w p, u32x4 v) {
+    __builtin_nontemporal_store(v, reinterpret_cast<g_u32x4*>(p));
 }
 
-// 16 source bytes starting at byte address a (a multiple of ES): aligned-down dword loads.
-template <int ES>
-__device__ __forceinline__ void load_chunk(const char* a, u32x4& v, uint32_t& x) {
-    if (ES == 4) {
-        v = load16_a4(a);
-        x = 0;
-    } else {
-        const uintptr_t u = reinterpret_cast<uintptr_t>(a);
-        const char* a4 = reinterpret_cast<const char*>(u & ~uintptr_t(3));
-        v = load16_a4(a4);
-        x = (u & 3) ? load4(a4 + 16) : 0u;
-    }
+// 16 source bytes starting at byte address a (any alignment): dword loads from the address
+// rounded down to 4, plus the following dword when a is not a multiple of 4; realign()
+// shifts them into place (a no-op for aligned sources, e.g. every 4-byte field).
+__device__ __forceinline__ void load_chunk(gptr a, u32x4& v, uint32_t& x) {
+    const uintptr_t u = reinterpret_cast<uintptr_t>(a);
+    gptr a4 = reinterpret_cast<gptr>(u & ~uintptr_t(3));
+    v = gload16_a4(a4);
+    x = (u & 3) ? gload4(a4 + 16) : 0u;
 }
 __device__ __forceinline__ u32x4 realign(u32x4 v, uint32_t x, uint32_t sh) {
     u32x4 o;
@@ -124,223 +117,246 @@ __device__ __forceinline__ u32x4 realign(u32x4 v, uint32_t x, uint32_t sh) {
     return o;
 }
 
-// 16-byte chunks of a tile per element size, and how many of them each lane owns
-constexpr int N4 = GATHER_TILE / 4, N2 = GATHER_TILE / 8, N1 = GATHER_TILE / 16;
-constexpr int U4 = (N4 + GATHER_BLOCK - 1) / GATHER_BLOCK;
-constexpr int U2 = (N2 + GATHER_BLOCK - 1) / GATHER_BLOCK;
-constexpr int U1 = (N1 + GATHER_BLOCK - 1) / GATHER_BLOCK;
-
-struct FieldLds {
-    const char* base[DC_MAX_FIELDS][DC_MAX_SRC_SHARDS];
-    char*       dst[DC_MAX_FIELDS];
-    int32_t     es[DC_MAX_FIELDS];
-    int32_t     cls_nf[3];                       // fields of element size 4, 2, 1
-    int32_t     cls_field[3][DC_MAX_FIELDS];
-};
-
-// Chunks that cannot take the one-load-one-store path (they cross a slot boundary,
-// padding or the arena end), per element-size class.  Their elements are copied one
-// per lane afterwards, so a boundary costs one memory round trip, not one per element.
-struct BoundaryLds {
-    int32_t  count[3];
-    uint16_t chunk[3][GATHER_TILE / 4];
-};
-
-// Element `tok` (tile-relative) of a boundary chunk: find its slot, copy it.
-template <int ES>
-__device__ __forceinline__ void move_element(const SegLds& sg, int n_all, int32_t tok, int32_t tile_len,
-                                             int64_t tile_begin, char* dst, const char* const* src_base) {
-    if (tok >= tile_len) return;
-    const int k = find_seg(sg.start, n_all, tok);
-    if (k < 0) return;
-    const int32_t st = sg.start[k], ls = sg.lensh[k];
-    if (tok >= st + seg_len(ls)) return;
-    store_elem<ES>(dst + (tile_begin + tok) * ES,
-                   load_elem<ES>(src_base[seg_shard(ls)] + (sg.src[k] + (tok - st)) * ES));
-}
-
-// Descriptors of slots seg_base + lane and (lanes < SEG_AHEAD) seg_base + SEG_BATCH + lane,
-// relative to the tile that starts at token tile_begin.
-struct SlotRegs {
-    int32_t st[2], ls[2];
-    int64_t so[2];
-};
-
-__device__ __forceinline__ void load_slots(const GatherArgs& a, int seg_base, int64_t tile_begin, SlotRegs& r) {
+// Stage descriptors of slots seg_base + lane and (lanes < SEG_AHEAD) seg_base + SEG_BATCH + lane,
+// up to slot seg_last, for the field whose rollout buffers are src[] and the tile that
+// starts at token tile_begin.
+__device__ __forceinline__ void stage_slots(const GatherArgs& a, SegLds& sg, const char* const* src, int lg,
+                                            int seg_base, int seg_last, int64_t tile_begin) {
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
-        const int64_t j = (int64_t)seg_base + q * SEG_BATCH + (int)threadIdx.x;
-        r.st[q] = REL_FAR; r.so[q] = 0; r.ls[q] = 0;
-        if ((q == 0 || threadIdx.x < SEG_AHEAD) && seg_base >= 0 && j < a.n_seq) {
-            const int64_t d = a.dst_tok_off[j] - tile_begin;
-            r.st[q] = (int32_t)max((int64_t)-REL_FAR, min((int64_t)REL_FAR, d));
-            r.so[q] = a.slot_src_off[j];
-            r.ls[q] = a.slot_len[j] | (a.slot_shard[j] << 26);
+        const int k = q * SEG_BATCH + (int)threadIdx.x;
+        const int j = seg_base + k;
+        if (q == 0 || threadIdx.x < SEG_AHEAD) {
+            int32_t st = REL_FAR, en = REL_FAR;
+            int64_t ad = 0;
+            if (j <= seg_last) {
+                const int64_t d = a.dst_tok_off[j] - tile_begin;
+                st = (int32_t)max((int64_t)-REL_FAR, min((int64_t)REL_FAR, d));
+                en = st + a.slot_len[j];
+                ad = reinterpret_cast<int64_t>(src[a.slot_shard[j]]) + ((a.slot_src_off[j] - d) << lg);
+            }
+            sg.start[k] = st; sg.end[k] = en; sg.addr[k] = ad;
         }
     }
 }
 
-__device__ __forceinline__ void stage_slots(SegLds& sg, const SlotRegs& r) {
-    static_assert(SEG_BATCH == GATHER_BLOCK, "one descriptor per lane plus the look-ahead");
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int k = q * SEG_BATCH + threadIdx.x;
-        if (q == 0 || threadIdx.x < SEG_AHEAD) { sg.start[k] = r.st[q]; sg.src[k] = r.so[q]; sg.lensh[k] = r.ls[q]; }
-    }
-}
-
-// One destination tile, all fields.  On entry the first batch of slot descriptors is
-// staged in sg and a barrier has made it (and bl.count = 0) visible.
-__device__ __forceinline__ void move_tile(const GatherArgs& a, SegLds& sg, const FieldLds& fl, BoundaryLds& bl,
-                                          int nf, int seg_base, int64_t tile_begin, int32_t tile_len) {
+// One destination tile of one field with element size 1 << lg, slots staged in LDS (whole
+// workgroup, barriers inside).  On return every lane has passed a barrier after its last LDS read.
+__device__ __forceinline__ void move_tile_dense(const GatherArgs& a, SegLds& sg, const char* const* src, int lg,
+                                                char* dst_field, int seg_first, int seg_last, int64_t tile_begin,
+                                                int32_t tile_len) {
+    const int tpc = 16 >> lg;                              // tokens per 16-byte chunk
     const int tid = threadIdx.x;
+    gptr_w dst = reinterpret_cast<gptr_w>(reinterpret_cast<uintptr_t>(dst_field) + (tile_begin << lg));
+    int seg_base = seg_first;
     int32_t pass_begin = 0;
     for (;;) {
-        const int n_all = count_below(sg.start, NSEG, tile_len);
-        const bool more = n_all > SEG_BATCH;               // slot SEG_BATCH also starts inside the tile
+        stage_slots(a, sg, src, lg, seg_base, seg_last, tile_begin);
+        __syncthreads();
+        const int n_left = seg_last - seg_base + 1;
+        const int n_all = min(n_left, NSEG);
+        // more than SEG_BATCH slots left and the next batch's first slot starts inside the tile
+        const bool more = n_left > SEG_BATCH && sg.start[SEG_BATCH] < tile_len;
         const int32_t pass_end = more ? sg.start[SEG_BATCH] : tile_len;
 
-        // one lookup per element size, shared by every field of that size
-        Chunk c4[U4], c2[U2], c1[U1];
-#pragma unroll
-        for (int u = 0; u < U4; ++u) {
-            const int ch = tid + u * GATHER_BLOCK;
-            c4[u] = classify<4>(sg, n_all, ch, tile_len, pass_begin, pass_end);
-            if (ch >= N4) c4[u].mode = 0;
-            if (c4[u].mode == 2) bl.chunk[0][atomicAdd(&bl.count[0], 1)] = (uint16_t)ch;
-        }
-#pragma unroll
-        for (int u = 0; u < U2; ++u) {
-            const int ch = tid + u * GATHER_BLOCK;
-            c2[u] = classify<8>(sg, n_all, ch, tile_len, pass_begin, pass_end);
-            if (ch >= N2) c2[u].mode = 0;
-            if (c2[u].mode == 2) bl.chunk[1][atomicAdd(&bl.count[1], 1)] = (uint16_t)ch;
-        }
-#pragma unroll
-        for (int u = 0; u < U1; ++u) {
-            const int ch = tid + u * GATHER_BLOCK;
-            c1[u] = classify<16>(sg, n_all, ch, tile_len, pass_begin, pass_end);
-            if (ch >= N1) c1[u].mode = 0;
-            if (c1[u].mode == 2) bl.chunk[2][atomicAdd(&bl.count[2], 1)] = (uint16_t)ch;
-        }
-        __syncthreads();
-
-        // ---- chunks inside one slot: one field at a time, loads then stores ----
-        for (int f = 0; f < nf; ++f) {
-            const int es = fl.es[f];
-            char* dst = fl.dst[f] + tile_begin * es;
-            if (es == 4) {
-                u32x4 v[U4];
-                uint32_t unused;
-#pragma unroll
-                for (int u = 0; u < U4; ++u)
-                    if (c4[u].mode & 1) load_chunk<4>(fl.base[f][c4[u].mode >> 2] + c4[u].elem * 4, v[u], unused);
-#pragma unroll
-                for (int u = 0; u < U4; ++u)
-                    if (c4[u].mode & 1) store16(dst + (tid + u * GATHER_BLOCK) * 16, v[u]);
-            } else if (es == 2) {
-                u32x4 v[U2];
-                uint32_t x[U2], sh[U2];
-#pragma unroll
-                for (int u = 0; u < U2; ++u)
-                    if (c2[u].mode & 1) {
-                        const char* p = fl.base[f][c2[u].mode >> 2] + c2[u].elem * 2;
-                        sh[u] = reinterpret_cast<uintptr_t>(p) & 3;
-                        load_chunk<2>(p, v[u], x[u]);
-                    }
-#pragma unroll
-                for (int u = 0; u < U2; ++u)
-                    if (c2[u].mode & 1) store16(dst + (tid + u * GATHER_BLOCK) * 16, realign(v[u], x[u], sh[u]));
+#pragma unroll 1
+        for (int u = 0; u < (1 << lg); ++u) {              // 1 << lg chunks per lane, one at a time: this path
+            const int32_t c0 = (tid + u * GATHER_BLOCK) * tpc;   // is the rare one and must not cost registers
+            if (c0 < pass_begin || c0 >= pass_end) continue;
+            int k = find_seg(sg.start, n_all, c0);
+            if (k >= 0 && c0 + tpc <= sg.end[k] && c0 + tpc <= tile_len) {
+                // inside one slot: one load, one store
+                gptr ad = reinterpret_cast<gptr>(sg.addr[k] + ((int64_t)c0 << lg));
+                u32x4 v;
+                uint32_t x;
+                load_chunk(ad, v, x);
+                gstore16(dst + (tid + u * GATHER_BLOCK) * 16, realign(v, x, (uint32_t)reinterpret_cast<uintptr_t>(ad) & 3u));
             } else {
-                u32x4 v[U1];
-                uint32_t x[U1], sh[U1];
-#pragma unroll
-                for (int u = 0; u < U1; ++u)
-                    if (c1[u].mode & 1) {
-                        const char* p = fl.base[f][c1[u].mode >> 2] + c1[u].elem;
-                        sh[u] = reinterpret_cast<uintptr_t>(p) & 3;
-                        load_chunk<1>(p, v[u], x[u]);
-                    }
-#pragma unroll
-                for (int u = 0; u < U1; ++u)
-                    if (c1[u].mode & 1) store16(dst + (tid + u * GATHER_BLOCK) * 16, realign(v[u], x[u], sh[u]));
-            }
-        }
-        // ---- boundary chunks: one element per lane and step ----
-        {
-            const int n4 = bl.count[0] * 4 * fl.cls_nf[0];
-            const int n2 = bl.count[1] * 8 * fl.cls_nf[1];
-            const int n1 = bl.count[2] * 16 * fl.cls_nf[2];
-            for (int wi = tid; wi < n4 + n2 + n1; wi += GATHER_BLOCK) {
-                if (wi < n4) {
-                    const int e = wi & 3, q = wi >> 2, nfc = fl.cls_nf[0];
-                    const int f = fl.cls_field[0][q % nfc];
-                    const int32_t tok = (int32_t)bl.chunk[0][q / nfc] * 4 + e;
-                    move_element<4>(sg, n_all, tok, tile_len, tile_begin, fl.dst[f], fl.base[f]);
-                } else if (wi < n4 + n2) {
-                    const int w2 = wi - n4;
-                    const int e = w2 & 7, q = w2 >> 3, nfc = fl.cls_nf[1];
-                    const int f = fl.cls_field[1][q % nfc];
-                    const int32_t tok = (int32_t)bl.chunk[1][q / nfc] * 8 + e;
-                    move_element<2>(sg, n_all, tok, tile_len, tile_begin, fl.dst[f], fl.base[f]);
-                } else {
-                    const int w1 = wi - n4 - n2;
-                    const int e = w1 & 15, q = w1 >> 4, nfc = fl.cls_nf[2];
-                    const int f = fl.cls_field[2][q % nfc];
-                    const int32_t tok = (int32_t)bl.chunk[2][q / nfc] * 16 + e;
-                    move_element<1>(sg, n_all, tok, tile_len, tile_begin, fl.dst[f], fl.base[f]);
+                // touches a slot boundary, padding or the arena end: per element
+                for (int e = 0; e < tpc; ++e) {
+                    const int32_t tok = c0 + e;
+                    if (tok >= tile_len) break;
+                    while (k + 1 < n_all && sg.start[k + 1] <= tok) ++k;
+                    if (k >= 0 && tok < sg.end[k])
+                        store_elem(lg, dst + ((int64_t)tok << lg),
+                                   load_elem(lg, reinterpret_cast<gptr>(sg.addr[k] + ((int64_t)tok << lg))));
                 }
             }
         }
+        __syncthreads();
         if (!more) break;
-        // rare: more than SEG_BATCH slots start inside this tile - next batch, loaded in place
+        // rare: more than SEG_BATCH slots start inside this tile - next batch
         seg_base += SEG_BATCH;
         pass_begin = pass_end;
-        __syncthreads();
-        SlotRegs r;
-        load_slots(a, seg_base, tile_begin, r);
-        stage_slots(sg, r);
-        if (tid < 3) bl.count[tid] = 0;
-        __syncthreads();
     }
 }
 
+// ---------------------------------------------------------------- sparse tiles: one wave, no LDS
+typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+#define DC_CONSTANT __attribute__((address_space(4)))
+
+// Uniform loads through the scalar data cache: they do not queue behind the bulk traffic in
+// the vector memory pipeline, and their results land in scalar registers.
+__device__ __forceinline__ u32x8 sload8(const void* p) {
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wold-style-cast"
+    return *(const DC_CONSTANT u32x8*)p;
+#pragma clang diagnostic pop
+}
+__device__ __forceinline__ u32x16 sload16(const void* p) {
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wold-style-cast"
+    return *(const DC_CONSTANT u32x16*)p;
+#pragma clang diagnostic pop
+}
+
+// One record entry as the selection needs it (all scalar): the slot's first token and end
+// relative to the granule, and the source byte address the granule's token 0 would have
+// inside the slot.
+struct SlotS {
+    int32_t st, en;
+    int64_t ad;
+};
+
+// The wave's granule (1024 tokens: es chunks per lane) of one tile, served from the granule's
+// record.  `limit` = tokens of the granule that exist in the arena (> 0).
+__device__ __forceinline__ void move_wave_sparse(const FieldDesc& fd, int n_src, int lg, const u32x16& rec,
+                                                 int64_t wave_begin, int32_t limit) {
+    const int es = 1 << lg;
+    const int tpc = 16 >> lg;                              // tokens per 16-byte chunk
+    const int tpi = WAVE * tpc;                            // tokens one wave instruction covers
+    const int lane = threadIdx.x & (WAVE - 1);
+    gptr_w dst = reinterpret_cast<gptr_w>(reinterpret_cast<uintptr_t>(fd.dst) + (wave_begin << lg));
+
+    SlotS e[REC_SLOTS];
+#pragma unroll
+    for (int k = 0; k < REC_SLOTS; ++k) {
+        const int32_t st = (int32_t)rec[4 * k], ls = (int32_t)rec[4 * k + 1];
+        const int64_t so = (int64_t)((uint64_t)rec[4 * k + 2] | ((uint64_t)rec[4 * k + 3] << 32));
+        const char* base = fd.src[0];
+        if (n_src > 1) base = fd.src[(ls >> LENSH_SHIFT) & (DC_MAX_SRC_SHARDS - 1)];
+        e[k].st = st;
+        e[k].en = st + (ls & LEN_MASK);
+        e[k].ad = reinterpret_cast<int64_t>(base) + ((so - st) << lg);
+    }
+
+    constexpr int MAXU = 4;                                // chunks per lane: es of them are used
+    uint32_t in_mask = 0, bnd_mask = 0;                    // bit u: chunk u is inside one slot / needs the element path
+    gptr from[MAXU];
+#pragma unroll
+    for (int u = 0; u < MAXU; ++u) {
+        from[u] = nullptr;
+        if (u < es) {                                      // uniform
+            const int32_t lo = u * tpi;                    // the instruction's first token inside the granule
+            const int32_t c0 = lo + lane * tpc;            // my chunk's first token
+            // scalar: the slot of the instruction's first token; does it cover all 64 chunks?
+            int32_t s_en = INT32_MIN;
+            int64_t s_ad = 0;
+#pragma unroll
+            for (int k = 0; k < REC_SLOTS; ++k)
+                if (lo >= e[k].st) { s_en = e[k].en; s_ad = e[k].ad; }
+            if (s_en >= lo + tpi && lo + tpi <= limit) {   // uniform: one slot, no search per lane
+                in_mask |= 1u << u;
+                from[u] = reinterpret_cast<gptr>(s_ad + ((int64_t)c0 << lg));
+            } else {
+                int32_t e_sel = INT32_MIN;
+                int64_t a_sel = 0;
+#pragma unroll
+                for (int k = 0; k < REC_SLOTS; ++k)
+                    if (c0 >= e[k].st) { e_sel = e[k].en; a_sel = e[k].ad; }
+                const bool in = c0 + tpc <= e_sel && c0 + tpc <= limit;
+                if (in) in_mask |= 1u << u;
+                else if (c0 < limit) bnd_mask |= 1u << u;
+                from[u] = reinterpret_cast<gptr>(a_sel + ((int64_t)c0 << lg));
+            }
+        }
+    }
+    // ---- chunks inside one slot: loads, then stores ----
+    u32x4 v[MAXU];
+    uint32_t x[MAXU];
+#pragma unroll
+    for (int u = 0; u < MAXU; ++u)
+        if (in_mask & (1u << u)) load_chunk(from[u], v[u], x[u]);
+#pragma unroll
+    for (int u = 0; u < MAXU; ++u)
+        if (in_mask & (1u << u)) {
+            const uint32_t sh = (uint32_t)reinterpret_cast<uintptr_t>(from[u]) & 3u;
+            gstore16(dst + (u * WAVE + lane) * 16, realign(v[u], x[u], sh));
+        }
+    // ---- chunks that touch a slot boundary, padding or the arena end: per element ----
+    if (__ballot(bnd_mask != 0) == 0ull) return;                            // uniform
+#pragma unroll 1
+    for (int u = 0; u < es; ++u) {
+        const bool mine = (bnd_mask >> u) & 1u;
+        if (__ballot(mine) == 0ull) continue;                               // uniform
+        const int32_t c0 = u * tpi + lane * tpc;
+        constexpr int EB = 4;                                               // elements in flight; divides 4, 8, 16
+#pragma unroll 1
+        for (int e0 = 0; e0 < tpc; e0 += EB) {
+            uint32_t val[EB];
+            bool ok[EB];
+#pragma unroll
+            for (int r = 0; r < EB; ++r) {
+                const int32_t t = c0 + e0 + r;
+                int32_t e_sel = INT32_MIN;
+                int64_t a_sel = 0;
+#pragma unroll
+                for (int k = 0; k < REC_SLOTS; ++k)
+                    if (t >= e[k].st) { e_sel = e[k].en; a_sel = e[k].ad; }
+                ok[r] = mine && t < e_sel && t < limit;
+                val[r] = 0;
+                if (ok[r]) val[r] = load_elem(lg, reinterpret_cast<gptr>(a_sel + ((int64_t)t << lg)));
+            }
+#pragma unroll
+            for (int r = 0; r < EB; ++r)
+                if (ok[r]) store_elem(lg, dst + ((int64_t)(c0 + e0 + r) << lg), val[r]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------- the kernel
+// One workgroup per tile of GATHER_TILE_TOKENS tokens of one field; blockIdx.y = field, so the
+// dispatch order is field-major.  Waves are short-lived on purpose: a wave that ends right
+// after issuing its stores does not hold its slot until they are acknowledged, which a
+// looping wave would (loads and stores retire through one in-order counter).
 __global__ __launch_bounds__(GATHER_BLOCK) void gather_kernel(GatherArgs a, FieldTable ft) {
     __shared__ SegLds sg;
-    __shared__ FieldLds fl;
-    __shared__ BoundaryLds bl;
-    const int tid = threadIdx.x;
+    __shared__ const char* src[DC_MAX_SRC_SHARDS];
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / WAVE));
+    const int N = a.n_seq;
+    const FieldDesc& fd = ft.f[blockIdx.y];
+    const int lg = fd.elem_bytes == 4 ? 2 : (fd.elem_bytes == 2 ? 1 : 0);
+    const int64_t tile_begin = (int64_t)blockIdx.x * GATHER_TILE_TOKENS;
+    const int64_t g0 = (int64_t)blockIdx.x * GRAN_PER_TILE;
 
-    const int64_t tile_begin = (int64_t)blockIdx.x * GATHER_TILE;
-    const int64_t left = a.capacity - tile_begin;
-    const int32_t tile_len = (int32_t)(left < GATHER_TILE ? left : GATHER_TILE);
-    if (tile_len <= 0) return;
-    const int seg_base = a.tile_first[blockIdx.x];
-    if (seg_base < 0 || seg_base >= a.n_seq) return;       // nothing reaches into this tile
+    // granule table of the tile: F[g] = first slot ending after granule g's first token; slots
+    // F[g] .. F[g+1] are the ones that can reach into granule g.  The tables are padded, so the
+    // entries of a whole tile (and one more) exist even for the last, partial tile.
+    const u32x8 F = sload8(a.gran_first + g0);
+    const u32x16 rec = sload16(a.gran_rec + g0 + w);
+    const int first = (int)F[0];
+    if (first < 0 || first >= N) return;                   // nothing reaches into this tile
+    bool dense = false;
+#pragma unroll
+    for (int i = 0; i < GRAN_PER_TILE; ++i)
+        dense = dense || ((int)F[i] < N && min((int)F[i + 1], N - 1) - (int)F[i] + 1 > REC_SLOTS);
 
-    SlotRegs r;
-    load_slots(a, seg_base, tile_begin, r);
-    if (tid < DC_MAX_FIELDS * DC_MAX_SRC_SHARDS) {
-        const int f = tid / DC_MAX_SRC_SHARDS, s = tid % DC_MAX_SRC_SHARDS;
-        fl.base[f][s] = (f < ft.n_fields && s < ft.n_src) ? ft.f[f].src[s] : nullptr;
-        if (s == 0) { fl.dst[f] = ft.f[f].dst; fl.es[f] = ft.f[f].elem_bytes; }
+    const int32_t limit = (int32_t)min((int64_t)GATHER_TILE_TOKENS, a.capacity - tile_begin);
+    if (!dense) {
+        const int32_t wave_limit = min(limit - w * GATHER_GRAN, GATHER_GRAN);
+        if (wave_limit > 0) move_wave_sparse(fd, ft.n_src, lg, rec, tile_begin + w * GATHER_GRAN, wave_limit);
+        return;
     }
-    if (tid < 3) {
-        const int es = 4 >> tid;
-        int n = 0;
-        for (int f = 0; f < ft.n_fields; ++f)
-            if (ft.f[f].elem_bytes == es) fl.cls_field[tid][n++] = f;
-        fl.cls_nf[tid] = n;
-        bl.count[tid] = 0;
-    }
-    stage_slots(sg, r);
+    const int last = min(max((int)F[GRAN_PER_TILE], first), N - 1);
+    if (threadIdx.x < DC_MAX_SRC_SHARDS) src[threadIdx.x] = fd.src[threadIdx.x];
     __syncthreads();
-    move_tile(a, sg, fl, bl, ft.n_fields, seg_base, tile_begin, tile_len);
+    move_tile_dense(a, sg, src, lg, fd.dst, first, last, tile_begin, limit);
 }
 
 hipError_t launch_gather(int32_t n_seq, const FieldTable& ft, int64_t dst_capacity,
                          const int64_t* d_dst_tok_off, const Workspace& ws, hipStream_t st) {
-    if (n_seq == 0 || ft.n_fields == 0 || ws.n_tiles == 0) return hipSuccess;
+    if (n_seq == 0 || ft.n_fields == 0 || dst_capacity == 0) return hipSuccess;
     GatherArgs a;
     a.n_seq = n_seq;
     a.capacity = dst_capacity;
@@ -348,9 +364,11 @@ hipError_t launch_gather(int32_t n_seq, const FieldTable& ft, int64_t dst_capaci
     a.slot_src_off = ws.slot_src_off;
     a.slot_len = ws.slot_len;
     a.slot_shard = ws.slot_shard;
-    a.tile_first = ws.tile_first;
-    a.n_tiles = (int32_t)ws.n_tiles;
-    hipLaunchKernelGGL(gather_kernel, dim3((unsigned)ws.n_tiles), dim3(GATHER_BLOCK), 0, st, a, ft);
+    a.gran_first = ws.gran_first;
+    a.gran_rec = ws.gran_rec;
+    const int64_t tiles = (dst_capacity + GATHER_TILE_TOKENS - 1) / GATHER_TILE_TOKENS;
+    if (tiles > 0x7FFFFFFFLL || tiles * GRAN_PER_TILE + GRAN_PER_TILE + 1 > ws.n_gran) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(gather_kernel, dim3((unsigned)tiles, (unsigned)ft.n_fields), dim3(GATHER_BLOCK), 0, st, a, ft);
     return hipGetLastError();
 }
 

@@ -1,7 +1,8 @@
 // Plan of the packed training layout: destination token offsets of every output
 // slot, shard token offsets, next-fit micro-batches under the token budget and the
 // per-micro-batch cu_seqlens, plus the gather's workspace (validated per-slot
-// source descriptors and the first slot of every destination tile).
+// source descriptors and the first slot ending after every granule boundary of the
+// destination token axis).
 //
 // O(N) integer work on at most DC_MAX_SEQ slots: latency-bound, so it runs as ONE
 // workgroup of 1024 lanes with everything staged in LDS:
@@ -21,7 +22,7 @@ constexpr int PLAN_IPT = DC_MAX_SEQ / PLAN_BLOCK;        // slots per lane at th
 
 struct PlanArgs {
     int32_t n_seq, n_shards, align;
-    int64_t budget, capacity, n_tiles;
+    int64_t budget, capacity, n_gran;
     const int64_t* src_tok_off;
     const int32_t* seq_len;
     const int32_t* perm;
@@ -35,7 +36,7 @@ struct PlanArgs {
     int64_t* slot_src_off;
     int32_t* slot_len;
     int32_t* slot_shard;
-    int32_t* tile_first;
+    int32_t* gran_first;
     int32_t* status;
 };
 
@@ -59,8 +60,8 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
     const int j0 = tid * ipt;
 
     for (int i = tid; i < DC_MAX_SEQ / 32; i += PLAN_BLOCK) { L.start_bits[i] = 0; L.seen_bits[i] = 0; }
-    // default: no slot reaches into the tile; step 4 overwrites the tiles that have one
-    for (int64_t t = tid; t < a.n_tiles; t += PLAN_BLOCK) a.tile_first[t] = N;
+    // default: no slot ends after the granule boundary; step 4 overwrites the others
+    for (int64_t t = tid; t < a.n_gran; t += PLAN_BLOCK) a.gran_first[t] = N;
     if (tid == 0) L.ok = 1;
     __syncthreads();
     if (tid <= P) {
@@ -185,7 +186,7 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
             const bool closes = (j + 1 == N) || ((L.start_bits[(j + 1) >> 5] >> ((j + 1) & 31)) & 1u);
             if (closes) a.cu_seqlens[j + m + 1] = (int32_t)(L.gpre[j + 1] - gs);
 
-            // destination tiles whose first token-bearing slot is j
+            // granule boundaries b with end(j-1) <= b < end(j): j is the first slot ending after b
             const int64_t ln = L.gpre[j + 1] - g;
             if (ln > 0) {
                 int64_t prev_end = 0;
@@ -194,8 +195,8 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
                     while (pp > 0 && j - 1 < L.shard_off[pp]) --pp;
                     prev_end = L.shard_base[pp] + (g - L.gpre[L.shard_off[pp]]);
                 }
-                int64_t t = (prev_end + GATHER_TILE - 1) / GATHER_TILE;
-                for (; t < a.n_tiles && t * GATHER_TILE < d + ln; ++t) a.tile_first[t] = j;
+                int64_t t = (prev_end + GATHER_GRAN - 1) / GATHER_GRAN;
+                for (; t < a.n_gran && t * GATHER_GRAN < d + ln; ++t) a.gran_first[t] = j;
             }
         }
     }
@@ -214,6 +215,50 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
     if (tid == 0) { *a.n_mb = M; a.mb_seq_off[M] = N; }
 }
 
+// Inline slot descriptors per granule (one lane per granule): the first REC_SLOTS slots
+// from gran_first[g] on, as long as they start before the granule's end.  Runs after
+// plan_kernel on the same stream.
+constexpr int REC_BLOCK = 256;
+
+struct RecArgs {
+    int32_t        n_seq;
+    int64_t        n_gran;
+    const int64_t* dst_tok_off;
+    const int64_t* slot_src_off;
+    const int32_t* slot_len;
+    const int32_t* slot_shard;
+    const int32_t* gran_first;
+    GranRec*       gran_rec;
+};
+
+__global__ __launch_bounds__(REC_BLOCK) void records_kernel(RecArgs a) {
+    const int64_t g = (int64_t)blockIdx.x * REC_BLOCK + threadIdx.x;
+    if (g >= a.n_gran) return;
+    const int N = a.n_seq;
+    const int first = a.gran_first[g];
+    const int next = g + 1 < a.n_gran ? a.gran_first[g + 1] : N;
+    const int last = min(next, N - 1);
+    const int64_t begin = g * GATHER_GRAN;
+    GranRec rec;
+#pragma unroll
+    for (int r = 0; r < REC_SLOTS; ++r) {
+        rec.e[r].start = REL_FAR; rec.e[r].lensh = 0; rec.e[r].src_off = 0;
+        const int j = first + r;
+        if (first >= 0 && first < N && j <= last) {
+            const int64_t d = a.dst_tok_off[j] - begin;
+            if (d < GATHER_GRAN) {
+                rec.e[r].start = (int32_t)max(d, (int64_t)-REL_FAR);
+                rec.e[r].lensh = a.slot_len[j] | (a.slot_shard[j] << LENSH_SHIFT);
+                rec.e[r].src_off = a.slot_src_off[j];
+            }
+        }
+    }
+    u32x4* out = reinterpret_cast<u32x4*>(&a.gran_rec[g]);
+    const u32x4* in = reinterpret_cast<const u32x4*>(&rec);
+#pragma unroll
+    for (int r = 0; r < REC_SLOTS; ++r) out[r] = in[r];
+}
+
 hipError_t launch_plan(const dc_params& prm, const SourceDesc& src, const int64_t* d_src_tok_off,
                        const int32_t* d_seq_len, const int32_t* d_perm, const int32_t* d_shard_seq_off,
                        int64_t dst_capacity, int64_t* d_dst_tok_off, int64_t* d_shard_tok_off,
@@ -221,13 +266,20 @@ hipError_t launch_plan(const dc_params& prm, const SourceDesc& src, const int64_
                        int32_t* d_n_mb, const Workspace& ws, int32_t* d_status, hipStream_t st) {
     PlanArgs a;
     a.n_seq = prm.n_seq; a.n_shards = prm.n_shards; a.align = prm.align_tokens;
-    a.budget = prm.token_budget; a.capacity = dst_capacity; a.n_tiles = ws.n_tiles;
+    a.budget = prm.token_budget; a.capacity = dst_capacity; a.n_gran = ws.n_gran;
     a.src_tok_off = d_src_tok_off; a.seq_len = d_seq_len; a.perm = d_perm; a.shard_seq_off = d_shard_seq_off;
     a.dst_tok_off = d_dst_tok_off; a.shard_tok_off = d_shard_tok_off; a.shard_mb_off = d_shard_mb_off;
     a.mb_seq_off = d_mb_seq_off; a.cu_seqlens = d_cu_seqlens; a.n_mb = d_n_mb;
     a.slot_src_off = ws.slot_src_off; a.slot_len = ws.slot_len; a.slot_shard = ws.slot_shard;
-    a.tile_first = ws.tile_first; a.status = d_status;
+    a.gran_first = ws.gran_first; a.status = d_status;
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(PLAN_BLOCK), 0, st, a, src);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    RecArgs r;
+    r.n_seq = prm.n_seq; r.n_gran = ws.n_gran; r.dst_tok_off = d_dst_tok_off;
+    r.slot_src_off = ws.slot_src_off; r.slot_len = ws.slot_len; r.slot_shard = ws.slot_shard;
+    r.gran_first = ws.gran_first; r.gran_rec = ws.gran_rec;
+    hipLaunchKernelGGL(records_kernel, dim3((unsigned)((ws.n_gran + REC_BLOCK - 1) / REC_BLOCK)), dim3(REC_BLOCK), 0, st, r);
     return hipGetLastError();
 }
 
