@@ -219,6 +219,38 @@ struct SlotS {
     int64_t ad;
 };
 
+// The elements of one 16-byte chunk that does not lie inside one slot, on their way.
+struct BoundaryChunk {
+    uint32_t val[16];
+    uint32_t ok;             // bit r: element r exists (belongs to a slot, inside the arena) and was loaded
+    int32_t  c0;             // the chunk's first token inside the granule
+};
+
+template <int LG>
+__device__ __forceinline__ void boundary_load(const SlotS (&e)[REC_SLOTS], bool mine, int32_t limit, BoundaryChunk& bc) {
+#pragma unroll
+    for (int r = 0; r < (16 >> LG); ++r) {
+        const int32_t t = bc.c0 + r;
+        int32_t e_sel = INT32_MIN;
+        int64_t a_sel = 0;
+#pragma unroll
+        for (int k = 0; k < REC_SLOTS; ++k)
+            if (t >= e[k].st) { e_sel = e[k].en; a_sel = e[k].ad; }
+        bc.val[r] = 0;
+        if (mine && t < e_sel && t < limit) {
+            bc.ok |= 1u << r;
+            bc.val[r] = load_elem(LG, reinterpret_cast<gptr>(a_sel + ((int64_t)t << LG)));
+        }
+    }
+}
+
+template <int LG>
+__device__ __forceinline__ void boundary_store(gptr_w dst, const BoundaryChunk& bc) {
+#pragma unroll
+    for (int r = 0; r < (16 >> LG); ++r)
+        if (bc.ok & (1u << r)) store_elem(LG, dst + ((int64_t)(bc.c0 + r) << LG), bc.val[r]);
+}
+
 // The wave's granule (1024 tokens: es chunks per lane) of one tile, served from the granule's
 // record.  `limit` = tokens of the granule that exist in the arena (> 0).
 __device__ __forceinline__ void move_wave_sparse(const FieldDesc& fd, int n_src, int lg, const u32x16& rec,
@@ -272,23 +304,41 @@ __device__ __forceinline__ void move_wave_sparse(const FieldDesc& fd, int n_src,
             }
         }
     }
-    // ---- chunks inside one slot: loads, then stores ----
+    // ---- chunks inside one slot: loads ----
     u32x4 v[MAXU];
     uint32_t x[MAXU];
 #pragma unroll
     for (int u = 0; u < MAXU; ++u)
         if (in_mask & (1u << u)) load_chunk(from[u], v[u], x[u]);
+    // ---- a chunk that touches a slot boundary, padding or the arena end is moved element by
+    // element; the loads of a lane's first such chunk go out with the loads above, so a wave
+    // with a sequence boundary in its granule (two waves in five) pays no second round trip
+    const bool any_bnd = __ballot(bnd_mask != 0) != 0ull;                   // uniform
+    BoundaryChunk bc;
+    bc.ok = 0; bc.c0 = 0;
+    if (any_bnd) {
+        bc.c0 = (bnd_mask ? __builtin_ctz(bnd_mask) : 0) * tpi + lane * tpc;
+        if (lg == 2) boundary_load<2>(e, bnd_mask != 0, limit, bc);
+        else if (lg == 1) boundary_load<1>(e, bnd_mask != 0, limit, bc);
+        else boundary_load<0>(e, bnd_mask != 0, limit, bc);
+    }
+    // ---- stores ----
 #pragma unroll
     for (int u = 0; u < MAXU; ++u)
         if (in_mask & (1u << u)) {
             const uint32_t sh = (uint32_t)reinterpret_cast<uintptr_t>(from[u]) & 3u;
             gstore16(dst + (u * WAVE + lane) * 16, realign(v[u], x[u], sh));
         }
-    // ---- chunks that touch a slot boundary, padding or the arena end: per element ----
-    if (__ballot(bnd_mask != 0) == 0ull) return;                            // uniform
+    if (!any_bnd) return;
+    if (lg == 2) boundary_store<2>(dst, bc);
+    else if (lg == 1) boundary_store<1>(dst, bc);
+    else boundary_store<0>(dst, bc);
+    // ---- further boundary chunks of the same lane (sequences shorter than a wave instruction) ----
+    const uint32_t rest = bnd_mask & (bnd_mask - 1);
+    if (__ballot(rest != 0) == 0ull) return;                                // uniform
 #pragma unroll 1
-    for (int u = 0; u < es; ++u) {
-        const bool mine = (bnd_mask >> u) & 1u;
+    for (int u = 1; u < es; ++u) {
+        const bool mine = (rest >> u) & 1u;
         if (__ballot(mine) == 0ull) continue;                               // uniform
         const int32_t c0 = u * tpi + lane * tpc;
         constexpr int EB = 4;                                               // elements in flight; divides 4, 8, 16
