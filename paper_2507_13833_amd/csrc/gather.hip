@@ -49,6 +49,8 @@ struct GatherArgs {
     const int32_t* slot_shard;
     const int32_t* gran_first;                   // padded: whole tiles plus GRAN_PER_TILE + 1 entries
     const GranRec* gran_rec;                     // same length
+    uint32_t       tiles;                        // tiles per field
+    uint32_t       n_wide, n_narrow;             // 4-byte fields (first in the field table), narrower ones
 };
 
 // Slot descriptors of the tile being moved, relative to the tile's first token.
@@ -366,8 +368,7 @@ __device__ __forceinline__ void move_wave_sparse(const FieldDesc& fd, int n_src,
 }
 
 // ---------------------------------------------------------------- the kernel
-// One workgroup per tile of GATHER_TILE_TOKENS tokens of one field; blockIdx.y = field, so the
-// dispatch order is field-major.  Waves are short-lived on purpose: a wave that ends right
+// One workgroup per tile of GATHER_TILE_TOKENS tokens of one field, field-major.  Waves are short-lived on purpose: a wave that ends right
 // after issuing its stores does not hold its slot until they are acknowledged, which a
 // looping wave would (loads and stores retire through one in-order counter).
 __global__ __launch_bounds__(GATHER_BLOCK) void gather_kernel(GatherArgs a, FieldTable ft) {
@@ -375,10 +376,20 @@ __global__ __launch_bounds__(GATHER_BLOCK) void gather_kernel(GatherArgs a, Fiel
     __shared__ const char* src[DC_MAX_SRC_SHARDS];
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / WAVE));
     const int N = a.n_seq;
-    const FieldDesc& fd = ft.f[blockIdx.y];
+    // Two streams share the grid: the 4-byte fields, field after field, and the narrower
+    // fields, field after field; of every n_fields consecutive workgroups n_wide continue the
+    // first stream and n_narrow the second.  A wave of a narrow field has only 1 or 2 KB in
+    // flight and cannot fill the memory pipeline alone; dealt in between the wide ones it
+    // rides along.
+    const uint32_t nf = a.n_wide + a.n_narrow;
+    const uint32_t q = blockIdx.x / nf, r = blockIdx.x % nf;
+    const bool wide = r < a.n_wide;
+    const uint32_t lin = wide ? q * a.n_wide + r : q * a.n_narrow + (r - a.n_wide);
+    const uint32_t tile = lin % a.tiles;
+    const FieldDesc& fd = ft.f[(wide ? 0u : a.n_wide) + lin / a.tiles];
     const int lg = fd.elem_bytes == 4 ? 2 : (fd.elem_bytes == 2 ? 1 : 0);
-    const int64_t tile_begin = (int64_t)blockIdx.x * GATHER_TILE_TOKENS;
-    const int64_t g0 = (int64_t)blockIdx.x * GRAN_PER_TILE;
+    const int64_t tile_begin = (int64_t)tile * GATHER_TILE_TOKENS;
+    const int64_t g0 = (int64_t)tile * GRAN_PER_TILE;
 
     // granule table of the tile: F[g] = first slot ending after granule g's first token; slots
     // F[g] .. F[g+1] are the ones that can reach into granule g.  The tables are padded, so the
@@ -416,9 +427,22 @@ hipError_t launch_gather(int32_t n_seq, const FieldTable& ft, int64_t dst_capaci
     a.slot_shard = ws.slot_shard;
     a.gran_first = ws.gran_first;
     a.gran_rec = ws.gran_rec;
+    a.n_wide = 0;
     const int64_t tiles = (dst_capacity + GATHER_TILE_TOKENS - 1) / GATHER_TILE_TOKENS;
-    if (tiles > 0x7FFFFFFFLL || tiles * GRAN_PER_TILE + GRAN_PER_TILE + 1 > ws.n_gran) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(gather_kernel, dim3((unsigned)tiles, (unsigned)ft.n_fields), dim3(GATHER_BLOCK), 0, st, a, ft);
+    if (tiles * ft.n_fields > 0x7FFFFFFFLL || tiles * GRAN_PER_TILE + GRAN_PER_TILE + 1 > ws.n_gran)
+        return hipErrorInvalidValue;
+    // field table with the 4-byte fields first
+    FieldTable sorted = ft;
+    int n = 0;
+    for (int pass = 0; pass < 2; ++pass)
+        for (int f = 0; f < ft.n_fields; ++f)
+            if ((ft.f[f].elem_bytes == 4) == (pass == 0)) {
+                sorted.f[n++] = ft.f[f];
+                if (pass == 0) a.n_wide = (uint32_t)n;
+            }
+    a.n_narrow = (uint32_t)ft.n_fields - a.n_wide;
+    a.tiles = (uint32_t)tiles;
+    hipLaunchKernelGGL(gather_kernel, dim3((unsigned)(tiles * ft.n_fields)), dim3(GATHER_BLOCK), 0, st, a, sorted);
     return hipGetLastError();
 }
 
