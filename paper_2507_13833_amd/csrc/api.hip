@@ -17,6 +17,7 @@ Workspace carve_workspace(void* base, int32_t n_seq, int64_t dst_capacity_tokens
     w.slot_shard = reinterpret_cast<int32_t*>(p + off);   off += round_up(n * sizeof(int32_t), 256);
     w.gran_first = reinterpret_cast<int32_t*>(p + off);   off += round_up((size_t)w.n_gran * sizeof(int32_t), 256);
     w.gran_rec = reinterpret_cast<GranRec*>(p + off);     off += round_up((size_t)w.n_gran * sizeof(GranRec), 256);
+    w.plan_ok = reinterpret_cast<int32_t*>(p + off);      off += 256;
     w.bytes = off + 256;
     return w;
 }

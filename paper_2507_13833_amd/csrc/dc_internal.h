@@ -18,6 +18,7 @@ constexpr int GRAN_TABLE_PAD = 16;
 constexpr int REC_SLOTS = 4;
 constexpr int32_t REL_FAR = 1 << 30;            // "no slot" / "beyond this granule" in relative tokens
 constexpr int LENSH_SHIFT = 26;                 // length | rollout shard << 26
+constexpr uint32_t DENSE_FLAG = 0x80000000u;    // in entry 0's lensh: more slots start inside the granule than the record holds
 
 // The first REC_SLOTS slots that reach into a granule, relative to the granule's first
 // token.  Unused entries have start = REL_FAR.  64 bytes: one 16-dword scalar load.
@@ -45,6 +46,7 @@ struct Workspace {
     int32_t* slot_shard;     // [N]   rollout shard of the slot's sequence
     int32_t* gran_first;     // [n_gran] first slot j with end(j) > g * GATHER_GRAN (N if none); non-decreasing
     GranRec* gran_rec;       // [n_gran]
+    int32_t* plan_ok;        // [1] 0 if the plan kernel found the shard table unusable and planned nothing
     int64_t  n_gran;         // ceil(capacity / GATHER_GRAN) + GRAN_TABLE_PAD; entries past the arena hold N / no slot
     size_t   bytes;
 };

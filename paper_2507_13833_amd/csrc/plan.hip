@@ -22,7 +22,7 @@ constexpr int PLAN_IPT = DC_MAX_SEQ / PLAN_BLOCK;        // slots per lane at th
 
 struct PlanArgs {
     int32_t n_seq, n_shards, align;
-    int64_t budget, capacity, n_gran;
+    int64_t budget, capacity;
     const int64_t* src_tok_off;
     const int32_t* seq_len;
     const int32_t* perm;
@@ -36,7 +36,7 @@ struct PlanArgs {
     int64_t* slot_src_off;
     int32_t* slot_len;
     int32_t* slot_shard;
-    int32_t* gran_first;
+    int32_t* plan_ok;
     int32_t* status;
 };
 
@@ -49,6 +49,7 @@ struct PlanLds {
     int32_t  lane_cnt[PLAN_BLOCK];          // exclusive count of starts before the lane's slots
     int64_t  tmp64[16];
     int32_t  tmp32[16];
+    int64_t  src_tokens[DC_MAX_SRC_SHARDS]; // elements each rollout buffer holds
     int32_t  ok;
 };
 
@@ -60,9 +61,8 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
     const int j0 = tid * ipt;
 
     for (int i = tid; i < DC_MAX_SEQ / 32; i += PLAN_BLOCK) { L.start_bits[i] = 0; L.seen_bits[i] = 0; }
-    // default: no slot ends after the granule boundary; step 4 overwrites the others
-    for (int64_t t = tid; t < a.n_gran; t += PLAN_BLOCK) a.gran_first[t] = N;
     if (tid == 0) L.ok = 1;
+    if (tid < DC_MAX_SRC_SHARDS) L.src_tokens[tid] = sd.tokens[tid];
     __syncthreads();
     if (tid <= P) {
         const int32_t v = a.shard_seq_off[tid];
@@ -72,34 +72,52 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
         if (bad) L.ok = 0;
     }
     __syncthreads();
+    if (tid == 0) *a.plan_ok = L.ok;                     // read by records_kernel
     if (!L.ok) {                                         // unusable shard table: plan nothing
         if (tid == 0) { set_status(a.status, DC_ERR_BAD_LAYOUT); *a.n_mb = 0; }
         return;
     }
 
     // ---- 1. slot lengths, validation, dense prefix ----
+    // the dependent global loads are grouped: all perm[j] of the lane, then all lengths and
+    // offsets, so the lane pays two memory round trips, not two per slot
+    int32_t seq[PLAN_IPT];
+#pragma unroll
+    for (int q = 0; q < PLAN_IPT; ++q) {
+        const int j = j0 + q;
+        seq[q] = (q < ipt && j < N) ? a.perm[j] : -1;
+    }
     int32_t len[PLAN_IPT];
+    int64_t sof[PLAN_IPT];
+#pragma unroll
+    for (int q = 0; q < PLAN_IPT; ++q) {
+        const bool ok = seq[q] >= 0 && seq[q] < N;
+        len[q] = ok ? a.seq_len[seq[q]] : 0;
+        sof[q] = ok ? a.src_tok_off[seq[q]] : 0;
+    }
     int64_t mine = 0;
 #pragma unroll
     for (int q = 0; q < PLAN_IPT; ++q) {
         const int j = j0 + q;
-        len[q] = 0;
         if (q < ipt && j < N) {
-            const int32_t i = a.perm[j];
-            int32_t ln = 0, sh = 0;
-            int64_t so = 0;
+            const int32_t i = seq[q];
+            int32_t ln = len[q], sh = 0;
+            int64_t so = sof[q];
             if (i < 0 || i >= N) {
                 set_status(a.status, DC_ERR_BAD_LAYOUT);
+                ln = 0; so = 0;
             } else if (atomicOr(&L.seen_bits[i >> 5], 1u << (i & 31)) & (1u << (i & 31))) {
                 set_status(a.status, DC_ERR_BAD_LAYOUT);
+                ln = 0; so = 0;
             } else {
-                ln = a.seq_len[i];
-                so = a.src_tok_off[i];
-                while (sh + 1 < sd.n_src && i >= sd.seq_off[sh + 1]) ++sh;
+                if (sd.n_src > 1) {                      // uniform; seq_off[s] = N from s = n_src on
+#pragma unroll
+                    for (int s = 1; s < DC_MAX_SRC_SHARDS; ++s) sh += i >= sd.seq_off[s] ? 1 : 0;
+                }
                 if (ln <= 0 || ln > DC_MAX_SEQ_LEN) {
                     set_status(a.status, DC_ERR_ZERO_LENGTH_SEQ);
                     ln = 0;
-                } else if (so < 0 || so + ln > sd.tokens[sh]) {
+                } else if (so < 0 || so + ln > L.src_tokens[sh]) {
                     set_status(a.status, DC_ERR_BAD_LAYOUT);
                     ln = 0;
                 } else if (ln > a.budget) {
@@ -111,6 +129,8 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
             a.slot_len[j] = ln;
             a.slot_shard[j] = sh;
             mine += ln;
+        } else {
+            len[q] = 0;
         }
     }
     int64_t total;
@@ -123,19 +143,31 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
     if (tid == 0) L.gpre[N] = total;
     __syncthreads();
 
-    // ---- 2. shard bases (alignment round-up is a serial dependency over <= 64 shards) ----
-    if (tid == 0) {
-        int64_t pos = 0;
-        for (int p = 0; p < P; ++p) {
-            L.shard_base[p] = pos;
-            a.shard_tok_off[p] = pos;
-            pos += L.gpre[L.shard_off[p + 1]] - L.gpre[L.shard_off[p]];
-            pos = (pos + a.align - 1) / a.align * a.align;
+    // ---- 2. shard bases: lane p of wave 0 takes shard p.  Dense layout: an exclusive scan of
+    // the shard loads; with alignment the round-up makes it a serial recurrence over <= 64 shards
+    if (tid < WAVE) {
+        const int64_t load = tid < P ? L.gpre[L.shard_off[tid + 1]] - L.gpre[L.shard_off[tid]] : 0;
+        int64_t base = 0, end = 0;
+        if (a.align == 1) {                              // uniform
+            const int64_t inc = wave_incl_scan_add<int64_t>(load);
+            base = inc - load;
+            end = __shfl(inc, WAVE - 1, WAVE);
+        } else {
+            int64_t pos = 0;
+            for (int p = 0; p < P; ++p) {
+                if (tid == p) base = pos;
+                pos += __shfl(load, p, WAVE);
+                pos = (pos + a.align - 1) / a.align * a.align;
+            }
+            end = pos;
         }
-        L.shard_base[P] = pos;
-        a.shard_tok_off[P] = pos;
-        a.dst_tok_off[N] = pos;
-        if (pos > a.capacity) set_status(a.status, DC_ERR_OVERFLOW);
+        if (tid < P) { L.shard_base[tid] = base; a.shard_tok_off[tid] = base; }
+        if (tid == 0) {
+            L.shard_base[P] = end;
+            a.shard_tok_off[P] = end;
+            a.dst_tok_off[N] = end;
+            if (end > a.capacity) set_status(a.status, DC_ERR_OVERFLOW);
+        }
     }
 
     // ---- 3. micro-batch starts: lane p walks shard p ----
@@ -186,18 +218,6 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
             const bool closes = (j + 1 == N) || ((L.start_bits[(j + 1) >> 5] >> ((j + 1) & 31)) & 1u);
             if (closes) a.cu_seqlens[j + m + 1] = (int32_t)(L.gpre[j + 1] - gs);
 
-            // granule boundaries b with end(j-1) <= b < end(j): j is the first slot ending after b
-            const int64_t ln = L.gpre[j + 1] - g;
-            if (ln > 0) {
-                int64_t prev_end = 0;
-                if (j > 0) {
-                    int pp = p;                          // shard of slot j-1
-                    while (pp > 0 && j - 1 < L.shard_off[pp]) --pp;
-                    prev_end = L.shard_base[pp] + (g - L.gpre[L.shard_off[pp]]);
-                }
-                int64_t t = (prev_end + GATHER_GRAN - 1) / GATHER_GRAN;
-                for (; t < a.n_gran && t * GATHER_GRAN < d + ln; ++t) a.gran_first[t] = j;
-            }
         }
     }
     if (tid <= P) {                                      // micro-batches before each shard's first slot
@@ -215,19 +235,21 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
     if (tid == 0) { *a.n_mb = M; a.mb_seq_off[M] = N; }
 }
 
-// Inline slot descriptors per granule (one lane per granule): the first REC_SLOTS slots
-// from gran_first[g] on, as long as they start before the granule's end.  Runs after
-// plan_kernel on the same stream.
+// Per-granule tables for the gather (one lane per granule, many workgroups; runs after
+// plan_kernel on the same stream): F[g] = first slot that ends after the granule's first
+// token, found by bisection over the slot starts, and the record of the first REC_SLOTS
+// slots from F[g] on that start before the granule's end.
 constexpr int REC_BLOCK = 256;
 
 struct RecArgs {
     int32_t        n_seq;
     int64_t        n_gran;
-    const int64_t* dst_tok_off;
+    const int64_t* dst_tok_off;      // [N+1]
     const int64_t* slot_src_off;
     const int32_t* slot_len;
     const int32_t* slot_shard;
-    const int32_t* gran_first;
+    const int32_t* plan_ok;
+    int32_t*       gran_first;
     GranRec*       gran_rec;
 };
 
@@ -235,16 +257,25 @@ __global__ __launch_bounds__(REC_BLOCK) void records_kernel(RecArgs a) {
     const int64_t g = (int64_t)blockIdx.x * REC_BLOCK + threadIdx.x;
     if (g >= a.n_gran) return;
     const int N = a.n_seq;
-    const int first = a.gran_first[g];
-    const int next = g + 1 < a.n_gran ? a.gran_first[g + 1] : N;
-    const int last = min(next, N - 1);
     const int64_t begin = g * GATHER_GRAN;
+    int first = N;
+    if (*a.plan_ok && N > 0) {
+        // first j whose successor starts after `begin` ...
+        int lo = 0, hi = N;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (a.dst_tok_off[mid + 1] > begin) hi = mid; else lo = mid + 1;
+        }
+        // ... and if `begin` lies in the padding behind that slot (or the slot is empty), the next one
+        while (lo < N && a.dst_tok_off[lo] + a.slot_len[lo] <= begin) ++lo;
+        first = lo;
+    }
     GranRec rec;
 #pragma unroll
     for (int r = 0; r < REC_SLOTS; ++r) {
         rec.e[r].start = REL_FAR; rec.e[r].lensh = 0; rec.e[r].src_off = 0;
         const int j = first + r;
-        if (first >= 0 && first < N && j <= last) {
+        if (j < N) {
             const int64_t d = a.dst_tok_off[j] - begin;
             if (d < GATHER_GRAN) {
                 rec.e[r].start = (int32_t)max(d, (int64_t)-REL_FAR);
@@ -253,6 +284,10 @@ __global__ __launch_bounds__(REC_BLOCK) void records_kernel(RecArgs a) {
             }
         }
     }
+    // a further slot that starts inside the granule: the record does not hold them all
+    if (first + REC_SLOTS < N && a.dst_tok_off[first + REC_SLOTS] - begin < GATHER_GRAN)
+        rec.e[0].lensh |= (int32_t)DENSE_FLAG;
+    a.gran_first[g] = first;
     u32x4* out = reinterpret_cast<u32x4*>(&a.gran_rec[g]);
     const u32x4* in = reinterpret_cast<const u32x4*>(&rec);
 #pragma unroll
@@ -266,19 +301,19 @@ hipError_t launch_plan(const dc_params& prm, const SourceDesc& src, const int64_
                        int32_t* d_n_mb, const Workspace& ws, int32_t* d_status, hipStream_t st) {
     PlanArgs a;
     a.n_seq = prm.n_seq; a.n_shards = prm.n_shards; a.align = prm.align_tokens;
-    a.budget = prm.token_budget; a.capacity = dst_capacity; a.n_gran = ws.n_gran;
+    a.budget = prm.token_budget; a.capacity = dst_capacity;
     a.src_tok_off = d_src_tok_off; a.seq_len = d_seq_len; a.perm = d_perm; a.shard_seq_off = d_shard_seq_off;
     a.dst_tok_off = d_dst_tok_off; a.shard_tok_off = d_shard_tok_off; a.shard_mb_off = d_shard_mb_off;
     a.mb_seq_off = d_mb_seq_off; a.cu_seqlens = d_cu_seqlens; a.n_mb = d_n_mb;
     a.slot_src_off = ws.slot_src_off; a.slot_len = ws.slot_len; a.slot_shard = ws.slot_shard;
-    a.gran_first = ws.gran_first; a.status = d_status;
+    a.plan_ok = ws.plan_ok; a.status = d_status;
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(PLAN_BLOCK), 0, st, a, src);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     RecArgs r;
     r.n_seq = prm.n_seq; r.n_gran = ws.n_gran; r.dst_tok_off = d_dst_tok_off;
     r.slot_src_off = ws.slot_src_off; r.slot_len = ws.slot_len; r.slot_shard = ws.slot_shard;
-    r.gran_first = ws.gran_first; r.gran_rec = ws.gran_rec;
+    r.plan_ok = ws.plan_ok; r.gran_first = ws.gran_first; r.gran_rec = ws.gran_rec;
     hipLaunchKernelGGL(records_kernel, dim3((unsigned)((ws.n_gran + REC_BLOCK - 1) / REC_BLOCK)), dim3(REC_BLOCK), 0, st, r);
     return hipGetLastError();
 }
