@@ -1,15 +1,16 @@
 #!/usr/bin/env python3
 """Benchmark of the Data Coordinator reshard path on one MI355X.
 
-A step is one pass of the whole path over one synthetic rollout batch already
-resident in HBM: dc_group_advantage, dc_balance, dc_plan, dc_gather.  Prints ONE
-JSON line: repacked tokens/s for the whole step, the gather kernel's achieved HBM
-bandwidth against the chip's peak (HIP events around every gather launch of the timed
-region), and the CPU oracle timed on the host as a reported baseline.
+A step is one pass of the whole path over one synthetic rollout batch already resident in
+HBM: dc_group_advantage (on a second stream, beside) dc_balance + dc_plan, then dc_gather.
+Prints ONE JSON line: repacked tokens/s for the whole step, the gather kernel's achieved HBM
+bandwidth against the chip's peak (HIP events around every gather launch of the timed region,
+on the stream it is launched on), and the CPU oracle timed on the host as a reported baseline.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -21,13 +22,29 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
+# HBM bytes per gather launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), each
+# scaled by what the same counter reads for the plain copy of --calibrate-copy (2^30 B in, 2^30 B
+# out); valid only for the kernel sources with the digest below (profiles/ has the runs).
+TRAFFIC = {
+    # config: (fetch bytes + write bytes, digest of csrc/gather.hip + csrc/dc_internal.h)
+}
+
+
+def kernel_digest() -> str:
+    h = hashlib.sha256()
+    for f in ("gather.hip", "dc_internal.h"):
+        with open(os.path.join(ROOT, "paper_2507_13833_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
 
 def cpu_baseline(w, budget_s: float = 12.0):
-    """Time the oracle (as it stands, single thread) on the same workload."""
+    """Time the oracle (as it stands, single thread) on the same workload: whole oracle steps
+    repeated until about budget_s seconds of CPU work are done."""
     import oracle
     mask = w.field_by_name("mask").shards
     reps, spent = 0, 0.0
-    while reps < 8 and (reps == 0 or spent < budget_s):
+    while reps == 0 or (spent < budget_s and reps < 1000):
         t0 = time.perf_counter()
         bal = oracle.balance(w.seq_len, w.n_shards)
         adv = oracle.group_advantage(w.reward, w.group_off, float(w.eps), w.ddof)
@@ -40,7 +57,8 @@ def cpu_baseline(w, budget_s: float = 12.0):
         spent += time.perf_counter() - t0
         reps += 1
     return {"value": w.total_tokens * reps / spent, "unit": "tokens/s", "cores": 1, "kind": "oracle",
-            "sample": f"whole workload ({w.total_tokens} tokens), {reps} full oracle steps, {spent:.1f} s"}
+            "sample": f"whole workload ({w.total_tokens} tokens per step), {reps} full oracle steps "
+                      f"(balance, advantage, plan, gather of every field), {spent:.1f} s, one thread"}
 
 
 def main() -> int:
@@ -51,6 +69,7 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: 5, the largest)")
     ap.add_argument("--sets", type=int, default=3, help="rotating buffer sets (defeats cache reuse)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--single-stream", action="store_true", help="issue the four calls on one stream")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise copy of known size (1 GiB read + 1 GiB written per "
                          "launch): the yardstick that scales the HBM byte counters of a rocprofv3 --pmc run")
@@ -73,8 +92,19 @@ def main() -> int:
     bpt = sets[0].payload_bytes_per_token             # payload incl. the per-token advantage
     gather_bytes = 2 * bpt * T                         # algorithmic: read once + write once
 
+    def one_step(b, ev=None):
+        if args.single_stream:
+            b.group_advantage(); b.balance(); b.plan()
+            if ev is not None:
+                ev[0].record()
+            b.gather()
+            if ev is not None:
+                ev[1].record()
+        else:
+            b.step_overlapped(ev)
+
     for i in range(args.warmup):
-        sets[i % len(sets)].step()
+        one_step(sets[i % len(sets)])
     torch.cuda.synchronize()
     assert all(s.read_status() == 0 for s in sets)
 
@@ -82,13 +112,7 @@ def main() -> int:
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        b = sets[i % len(sets)]
-        b.group_advantage()
-        b.balance()
-        b.plan()
-        ev[i][0].record()
-        b.gather()
-        ev[i][1].record()
+        one_step(sets[i % len(sets)], ev[i])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     assert all(s.read_status() == 0 for s in sets)
@@ -117,6 +141,10 @@ def main() -> int:
             tot += e0.elapsed_time(e1)
         stage[name + "_ms"] = round(tot / 6, 4)
 
+    traffic = None
+    if args.config in TRAFFIC and TRAFFIC[args.config][1] == kernel_digest():
+        traffic = TRAFFIC[args.config][0]
+
     out = {
         "metric": "repacked tokens/sec and achieved HBM GB/s (fraction of peak), 1 MI355X",
         "value": T / (ms_per_step * 1e-3),
@@ -128,9 +156,10 @@ def main() -> int:
         "config": {"workload": f"config {args.config} ({w.name}): {w.n_seq} sequences, {T} tokens, "
                                f"P={w.n_shards}, token budget {w.token_budget}, {bpt} payload B/token, "
                                f"{w.n_src_shards} rollout shard(s)",
-                   "buffer_sets": len(sets)},
+                   "buffer_sets": len(sets),
+                   "streams": 1 if args.single_stream else 2},
         "roofline": {"bound": "hbm", "kernel": "gather_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": gather_bytes, "avg_launch_ms": gather_ms},
         "stages": stage,
     }

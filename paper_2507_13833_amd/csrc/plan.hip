@@ -95,44 +95,50 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
         len[q] = ok ? a.seq_len[seq[q]] : 0;
         sof[q] = ok ? a.src_tok_off[seq[q]] : 0;
     }
+    // rollout shard of each sequence (seq_off[s] = N from s = n_src on)
+    int32_t shd[PLAN_IPT];
+#pragma unroll
+    for (int q = 0; q < PLAN_IPT; ++q) shd[q] = 0;
+    if (sd.n_src > 1) {                                  // uniform
+#pragma unroll
+        for (int q = 0; q < PLAN_IPT; ++q)
+#pragma unroll
+            for (int s = 1; s < DC_MAX_SRC_SHARDS; ++s) shd[q] += seq[q] >= sd.seq_off[s] ? 1 : 0;
+    }
+    // validation without divergent control flow; the lane reports its first error once
     int64_t mine = 0;
+    int32_t err = 0;
 #pragma unroll
     for (int q = 0; q < PLAN_IPT; ++q) {
         const int j = j0 + q;
-        if (q < ipt && j < N) {
-            const int32_t i = seq[q];
-            int32_t ln = len[q], sh = 0;
-            int64_t so = sof[q];
-            if (i < 0 || i >= N) {
-                set_status(a.status, DC_ERR_BAD_LAYOUT);
-                ln = 0; so = 0;
-            } else if (atomicOr(&L.seen_bits[i >> 5], 1u << (i & 31)) & (1u << (i & 31))) {
-                set_status(a.status, DC_ERR_BAD_LAYOUT);
-                ln = 0; so = 0;
-            } else {
-                if (sd.n_src > 1) {                      // uniform; seq_off[s] = N from s = n_src on
-#pragma unroll
-                    for (int s = 1; s < DC_MAX_SRC_SHARDS; ++s) sh += i >= sd.seq_off[s] ? 1 : 0;
-                }
-                if (ln <= 0 || ln > DC_MAX_SEQ_LEN) {
-                    set_status(a.status, DC_ERR_ZERO_LENGTH_SEQ);
-                    ln = 0;
-                } else if (so < 0 || so + ln > L.src_tokens[sh]) {
-                    set_status(a.status, DC_ERR_BAD_LAYOUT);
-                    ln = 0;
-                } else if (ln > a.budget) {
-                    set_status(a.status, DC_ERR_SEQ_EXCEEDS_BUDGET);   // still laid out, alone in its micro-batch
-                }
-            }
-            len[q] = ln;
+        const bool live = q < ipt && j < N;
+        const int32_t i = seq[q];
+        const bool in_range = live && i >= 0 && i < N;
+        bool dup = false;
+        if (in_range) dup = (atomicOr(&L.seen_bits[i >> 5], 1u << (i & 31)) >> (i & 31)) & 1u;
+        const bool placed = in_range && !dup;            // a sequence that exists, seen for the first time
+        int32_t ln = len[q];
+        const int64_t so = placed ? sof[q] : 0;
+        const int32_t sh = placed ? shd[q] : 0;
+        const bool bad_len = placed && (ln <= 0 || ln > DC_MAX_SEQ_LEN);
+        const bool bad_off = placed && !bad_len && (so < 0 || so + ln > L.src_tokens[sh]);
+        const bool over = placed && !bad_len && !bad_off && ln > a.budget;   // still laid out, alone in its micro-batch
+        const int32_t e = !live ? 0
+                          : !placed ? DC_ERR_BAD_LAYOUT
+                          : bad_len ? DC_ERR_ZERO_LENGTH_SEQ
+                          : bad_off ? DC_ERR_BAD_LAYOUT
+                          : over ? DC_ERR_SEQ_EXCEEDS_BUDGET : 0;
+        if (err == 0) err = e;
+        if (!placed || bad_len || bad_off) ln = 0;
+        len[q] = live ? ln : 0;
+        if (live) {
             a.slot_src_off[j] = so;
             a.slot_len[j] = ln;
             a.slot_shard[j] = sh;
-            mine += ln;
-        } else {
-            len[q] = 0;
         }
+        mine += len[q];
     }
+    if (err != 0) set_status(a.status, err);
     int64_t total;
     int64_t run = block_excl_scan_add<int64_t>(mine, L.tmp64, &total);
 #pragma unroll

@@ -28,6 +28,7 @@ class DeviceBatch:
                  cap: int = 0, poison: bool = False):
         self.w = w
         self.dev = torch.device(device)
+        self._side = None
         dev = self.dev
         N, P = w.n_seq, w.n_shards
         self.align = w.align_tokens if align_tokens is None else align_tokens
@@ -77,10 +78,10 @@ class DeviceBatch:
         self.payload_bytes_per_token = sum(self.elem_bytes.values())
 
     # ---- the calls of one step ----
-    def group_advantage(self, per_token: bool = True) -> None:
+    def group_advantage(self, per_token: bool = True, stream=None) -> None:
         B.dc_group_advantage(self.prm, self.source, self.seq_len, self.reward, self.group_off, self.w.n_groups,
                              self.src_fields["mask"] if per_token else None, self.adv_seq,
-                             self.adv_tok_src if per_token else None, self.status)
+                             self.adv_tok_src if per_token else None, self.status, stream)
 
     def balance(self) -> None:
         B.dc_balance(self.prm, self.seq_len, self.perm, self.shard_seq_off, self.shard_of_seq,
@@ -106,6 +107,29 @@ class DeviceBatch:
         self.balance()
         self.plan()
         self.gather()
+
+    def step_overlapped(self, gather_events=None) -> None:
+        """The same pass with the two independent halves on two HIP streams: the advantage
+        kernel (bandwidth-bound, whole chip) runs beside balance + plan (latency-bound, one
+        workgroup each); the gather waits for both.  Streams have the default priority.
+        gather_events: optional (start, end) torch events recorded around the gather launch."""
+        main = torch.cuda.current_stream(self.dev)
+        if self._side is None:
+            self._side = torch.cuda.Stream(device=self.dev)
+            self._ev_in = torch.cuda.Event()
+            self._ev_adv = torch.cuda.Event()
+        self._ev_in.record(main)                           # inputs (and the previous step) are ordered before both halves
+        self._side.wait_event(self._ev_in)
+        self.group_advantage(stream=self._side)
+        self._ev_adv.record(self._side)
+        self.balance()
+        self.plan()
+        main.wait_event(self._ev_adv)
+        if gather_events is not None:
+            gather_events[0].record(main)
+        self.gather()
+        if gather_events is not None:
+            gather_events[1].record(main)
 
     def read_status(self) -> int:
         return int(self.status.item())
