@@ -1,24 +1,30 @@
 // Plan of the packed training layout: destination token offsets of every output
 // slot, shard token offsets, next-fit micro-batches under the token budget and the
 // per-micro-batch cu_seqlens, plus the gather's workspace (validated per-slot
-// source descriptors and the first slot ending after every granule boundary of the
-// destination token axis).
+// source descriptors and, per 1024-token granule of the destination, the first slot
+// reaching into it and the record of the slots that do).
 //
-// O(N) integer work on at most DC_MAX_SEQ slots: latency-bound, so it runs as ONE
-// workgroup of 1024 lanes with everything staged in LDS:
-//   1. lane t owns slots [t*ipt, (t+1)*ipt): gathers len = seq_len[perm[j]],
-//      validates, block-wide exclusive scan -> dense prefix gpre[0..N] (int64, LDS);
-//   2. shard bases: serial over P <= 64 shards with the alignment round-up;
+// O(N) integer work on at most DC_MAX_SEQ slots: latency-bound, so the plan proper runs as
+// ONE workgroup of 1024 lanes with everything staged in LDS.  Lane t handles slots t,
+// t + 1024, ... (every global access is coalesced):
+//   1. len = seq_len[perm[j]] and the rollout offset, validated; wave scans + one scan of
+//      the 256 wave totals -> dense prefix gpre[0..N] (int64, LDS);
+//   2. shard bases: exclusive scan of the shard loads (with alignment: a serial recurrence
+//      over P <= 64 shards);
 //   3. micro-batch starts: one lane per shard hops from start to start, each hop a
-//      binary search for the last slot that still fits under the budget;
-//   4. start flags -> micro-batch index by a block scan; outputs written in parallel.
+//      bisection for the last slot that still fits under the budget -> start bits;
+//   4. per 32 slots: starts before the word and the last start before it (two scans over
+//      512 words); then every slot reads its micro-batch index and start from those and
+//      writes its outputs.
 #include "dc_device.h"
 #include "dc_internal.h"
 
 namespace dc {
 
 constexpr int PLAN_BLOCK = 1024;
+constexpr int PLAN_WAVES = PLAN_BLOCK / WAVE;
 constexpr int PLAN_IPT = DC_MAX_SEQ / PLAN_BLOCK;        // slots per lane at the size limit
+constexpr int PLAN_WORDS = DC_MAX_SEQ / 32;
 
 struct PlanArgs {
     int32_t n_seq, n_shards, align;
@@ -42,25 +48,29 @@ struct PlanArgs {
 
 struct PlanLds {
     int64_t  gpre[DC_MAX_SEQ + 1];          // dense exclusive prefix of slot lengths
-    uint32_t start_bits[DC_MAX_SEQ / 32];   // slot opens a micro-batch
-    uint32_t seen_bits[DC_MAX_SEQ / 32];    // sequence already placed (perm must be a permutation)
+    uint32_t start_bits[PLAN_WORDS];        // slot opens a micro-batch
+    uint32_t seen_bits[PLAN_WORDS];         // sequence already placed (perm must be a permutation)
+    int32_t  word_starts[PLAN_WORDS + 1];   // starts in the words before this one
+    int32_t  word_last[PLAN_WORDS];         // last start in the words before this one, or -1
+    int64_t  wave_pref[PLAN_IPT * PLAN_WAVES];  // tokens before the 64 slots a wave handles in one step
     int64_t  shard_base[DC_MAX_SHARDS + 1]; // aligned token offset of each shard
+    int64_t  shard_delta[DC_MAX_SHARDS];    // shard_base - dense prefix of the shard's first slot
     int32_t  shard_off[DC_MAX_SHARDS + 1];  // copy of shard_seq_off
-    int32_t  lane_cnt[PLAN_BLOCK];          // exclusive count of starts before the lane's slots
     int64_t  tmp64[16];
     int32_t  tmp32[16];
     int64_t  src_tokens[DC_MAX_SRC_SHARDS]; // elements each rollout buffer holds
     int32_t  ok;
 };
 
+__device__ __forceinline__ bool start_bit(const PlanLds& L, int j) { return (L.start_bits[j >> 5] >> (j & 31)) & 1u; }
+
 __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc sd) {
     __shared__ PlanLds L;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
     const int N = a.n_seq, P = a.n_shards;
-    const int ipt = max(1, (N + PLAN_BLOCK - 1) / PLAN_BLOCK);   // <= PLAN_IPT
-    const int j0 = tid * ipt;
+    const int nb = (N + PLAN_BLOCK - 1) / PLAN_BLOCK;    // steps of 1024 slots, <= PLAN_IPT
 
-    for (int i = tid; i < DC_MAX_SEQ / 32; i += PLAN_BLOCK) { L.start_bits[i] = 0; L.seen_bits[i] = 0; }
+    for (int i = tid; i < PLAN_WORDS; i += PLAN_BLOCK) { L.start_bits[i] = 0; L.seen_bits[i] = 0; }
     if (tid == 0) L.ok = 1;
     if (tid < DC_MAX_SRC_SHARDS) L.src_tokens[tid] = sd.tokens[tid];
     __syncthreads();
@@ -84,42 +94,41 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
     int32_t seq[PLAN_IPT];
 #pragma unroll
     for (int q = 0; q < PLAN_IPT; ++q) {
-        const int j = j0 + q;
-        seq[q] = (q < ipt && j < N) ? a.perm[j] : -1;
+        const int j = q * PLAN_BLOCK + tid;
+        seq[q] = -1;
+        if (q < nb) seq[q] = j < N ? a.perm[j] : -1;     // q < nb is uniform: unused steps cost a branch
     }
     int32_t len[PLAN_IPT];
     int64_t sof[PLAN_IPT];
 #pragma unroll
     for (int q = 0; q < PLAN_IPT; ++q) {
-        const bool ok = seq[q] >= 0 && seq[q] < N;
-        len[q] = ok ? a.seq_len[seq[q]] : 0;
-        sof[q] = ok ? a.src_tok_off[seq[q]] : 0;
-    }
-    // rollout shard of each sequence (seq_off[s] = N from s = n_src on)
-    int32_t shd[PLAN_IPT];
-#pragma unroll
-    for (int q = 0; q < PLAN_IPT; ++q) shd[q] = 0;
-    if (sd.n_src > 1) {                                  // uniform
-#pragma unroll
-        for (int q = 0; q < PLAN_IPT; ++q)
-#pragma unroll
-            for (int s = 1; s < DC_MAX_SRC_SHARDS; ++s) shd[q] += seq[q] >= sd.seq_off[s] ? 1 : 0;
+        len[q] = 0; sof[q] = 0;
+        if (q < nb) {
+            const bool ok = seq[q] >= 0 && seq[q] < N;
+            len[q] = ok ? a.seq_len[seq[q]] : 0;
+            sof[q] = ok ? a.src_tok_off[seq[q]] : 0;
+        }
     }
     // validation without divergent control flow; the lane reports its first error once
-    int64_t mine = 0;
     int32_t err = 0;
 #pragma unroll
     for (int q = 0; q < PLAN_IPT; ++q) {
-        const int j = j0 + q;
-        const bool live = q < ipt && j < N;
+        if (q >= nb) continue;                           // uniform
+        const int j = q * PLAN_BLOCK + tid;
+        const bool live = j < N;
         const int32_t i = seq[q];
         const bool in_range = live && i >= 0 && i < N;
         bool dup = false;
         if (in_range) dup = (atomicOr(&L.seen_bits[i >> 5], 1u << (i & 31)) >> (i & 31)) & 1u;
         const bool placed = in_range && !dup;            // a sequence that exists, seen for the first time
+        int32_t sh = 0;                                  // its rollout shard (seq_off[s] = N from s = n_src on)
+        if (sd.n_src > 1) {                              // uniform
+#pragma unroll
+            for (int s = 1; s < DC_MAX_SRC_SHARDS; ++s) sh += i >= sd.seq_off[s] ? 1 : 0;
+        }
+        if (!placed) sh = 0;
         int32_t ln = len[q];
         const int64_t so = placed ? sof[q] : 0;
-        const int32_t sh = placed ? shd[q] : 0;
         const bool bad_len = placed && (ln <= 0 || ln > DC_MAX_SEQ_LEN);
         const bool bad_off = placed && !bad_len && (so < 0 || so + ln > L.src_tokens[sh]);
         const bool over = placed && !bad_len && !bad_off && ln > a.budget;   // still laid out, alone in its micro-batch
@@ -129,35 +138,51 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
                           : bad_off ? DC_ERR_BAD_LAYOUT
                           : over ? DC_ERR_SEQ_EXCEEDS_BUDGET : 0;
         if (err == 0) err = e;
-        if (!placed || bad_len || bad_off) ln = 0;
-        len[q] = live ? ln : 0;
+        if (!live || !placed || bad_len || bad_off) ln = 0;
+        len[q] = ln;
         if (live) {
             a.slot_src_off[j] = so;
             a.slot_len[j] = ln;
             a.slot_shard[j] = sh;
         }
-        mine += len[q];
     }
     if (err != 0) set_status(a.status, err);
-    int64_t total;
-    int64_t run = block_excl_scan_add<int64_t>(mine, L.tmp64, &total);
+    // dense prefix: inclusive scan inside each wave step (a wave's 64 slots hold < 2^31 tokens) ...
+    int32_t inc[PLAN_IPT];
 #pragma unroll
     for (int q = 0; q < PLAN_IPT; ++q) {
-        const int j = j0 + q;
-        if (q < ipt && j < N) { L.gpre[j] = run; run += len[q]; }
+        inc[q] = 0;
+        if (q < nb) inc[q] = wave_incl_scan_add<int32_t>(len[q]);
+        if (lane == WAVE - 1) L.wave_pref[q * PLAN_WAVES + w] = inc[q];
     }
-    if (tid == 0) L.gpre[N] = total;
+    __syncthreads();
+    // ... an exclusive scan of the 256 step totals in slot order (step q, wave w) ...
+    {
+        const int64_t v = tid < PLAN_IPT * PLAN_WAVES ? L.wave_pref[tid] : 0;
+        int64_t total;
+        const int64_t ex = block_excl_scan_add<int64_t>(v, L.tmp64, &total);
+        if (tid < PLAN_IPT * PLAN_WAVES) L.wave_pref[tid] = ex;
+        if (tid == 0) L.gpre[N] = total;
+    }
+    __syncthreads();
+    // ... and their sum
+#pragma unroll
+    for (int q = 0; q < PLAN_IPT; ++q) {
+        const int j = q * PLAN_BLOCK + tid;
+        if (q < nb && j < N) L.gpre[j] = L.wave_pref[q * PLAN_WAVES + w] + (inc[q] - len[q]);
+    }
     __syncthreads();
 
     // ---- 2. shard bases: lane p of wave 0 takes shard p.  Dense layout: an exclusive scan of
     // the shard loads; with alignment the round-up makes it a serial recurrence over <= 64 shards
     if (tid < WAVE) {
-        const int64_t load = tid < P ? L.gpre[L.shard_off[tid + 1]] - L.gpre[L.shard_off[tid]] : 0;
+        const int64_t first = tid < P ? L.gpre[L.shard_off[tid]] : 0;
+        const int64_t load = tid < P ? L.gpre[L.shard_off[tid + 1]] - first : 0;
         int64_t base = 0, end = 0;
         if (a.align == 1) {                              // uniform
-            const int64_t inc = wave_incl_scan_add<int64_t>(load);
-            base = inc - load;
-            end = __shfl(inc, WAVE - 1, WAVE);
+            const int64_t in = wave_incl_scan_add<int64_t>(load);
+            base = in - load;
+            end = __shfl(in, WAVE - 1, WAVE);
         } else {
             int64_t pos = 0;
             for (int p = 0; p < P; ++p) {
@@ -167,7 +192,7 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
             }
             end = pos;
         }
-        if (tid < P) { L.shard_base[tid] = base; a.shard_tok_off[tid] = base; }
+        if (tid < P) { L.shard_base[tid] = base; L.shard_delta[tid] = base - first; a.shard_tok_off[tid] = base; }
         if (tid == 0) {
             L.shard_base[P] = end;
             a.shard_tok_off[P] = end;
@@ -194,48 +219,46 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
     __syncthreads();
 
     // ---- 4. micro-batch index per slot, outputs ----
-    int32_t n_start = 0, last_start = -1;
-#pragma unroll
-    for (int q = 0; q < PLAN_IPT; ++q) {
-        const int j = j0 + q;
-        if (q < ipt && j < N && ((L.start_bits[j >> 5] >> (j & 31)) & 1u)) { ++n_start; last_start = j; }
-    }
+    // per word of 32 slots: starts in the words before it, and the last start before it
     int32_t M;
-    int32_t m_before = block_excl_scan_add<int32_t>(n_start, L.tmp32, &M);
-    int32_t cur_start = block_excl_scan_max(last_start, L.tmp32);   // start slot of the batch open at j0
-    L.lane_cnt[tid] = m_before;
+    {
+        const uint32_t bits = tid < PLAN_WORDS ? L.start_bits[tid] : 0u;
+        const int32_t before = block_excl_scan_add<int32_t>((int32_t)__popc(bits), L.tmp32, &M);
+        const int32_t last = block_excl_scan_max(bits ? tid * 32 + 31 - __clz(bits) : -1, L.tmp32);
+        if (tid < PLAN_WORDS) { L.word_starts[tid] = before; L.word_last[tid] = last; }
+        if (tid == 0) L.word_starts[PLAN_WORDS] = M;
+    }
     __syncthreads();
-
-    int p = 0;                                           // shard of slot j0
-    if (j0 < N) while (p + 1 < P && j0 >= L.shard_off[p + 1]) ++p;
-    int32_t m = m_before - 1;                            // index of the micro-batch open at j0
-#pragma unroll
-    for (int q = 0; q < PLAN_IPT; ++q) {
-        const int j = j0 + q;
-        if (q < ipt && j < N) {
-            while (p + 1 < P && j >= L.shard_off[p + 1]) ++p;
-            const bool opens = (L.start_bits[j >> 5] >> (j & 31)) & 1u;
-            if (opens) { ++m; cur_start = j; a.mb_seq_off[m] = j; }
+#pragma unroll 2
+    for (int q = 0; q < nb; ++q) {
+        const int j = q * PLAN_BLOCK + tid;
+        if (j < N) {
+            const uint32_t bits = L.start_bits[j >> 5];
+            const uint32_t upto = bits & (0xFFFFFFFFu >> (31 - (j & 31)));           // starts at slots <= j of the word
+            const int32_t m = L.word_starts[j >> 5] + (int32_t)__popc(upto) - 1;     // my micro-batch
+            const int32_t cur_start = upto ? (j & ~31) + 31 - __clz(upto) : L.word_last[j >> 5];
+            if ((bits >> (j & 31)) & 1u) a.mb_seq_off[m] = j;
             const int64_t g = L.gpre[j];
-            const int64_t d = L.shard_base[p] + (g - L.gpre[L.shard_off[p]]);
+            int64_t d = g;
+            if (a.align != 1) {                          // uniform: shard of the slot, then its aligned base
+                int lo = 0, hi = P - 1;                  // largest p with shard_off[p] <= j
+                while (lo < hi) {
+                    const int mid = (lo + hi + 1) >> 1;
+                    if (L.shard_off[mid] <= j) lo = mid; else hi = mid - 1;
+                }
+                d = g + L.shard_delta[lo];
+            }
             a.dst_tok_off[j] = d;
-            const int64_t gs = L.gpre[cur_start];
+            const int64_t gs = L.gpre[cur_start >= 0 ? cur_start : 0];
             a.cu_seqlens[j + m] = (int32_t)(g - gs);
-            const bool closes = (j + 1 == N) || ((L.start_bits[(j + 1) >> 5] >> ((j + 1) & 31)) & 1u);
+            const bool closes = (j + 1 == N) || start_bit(L, j + 1);
             if (closes) a.cu_seqlens[j + m + 1] = (int32_t)(L.gpre[j + 1] - gs);
-
         }
     }
     if (tid <= P) {                                      // micro-batches before each shard's first slot
         const int js = L.shard_off[tid];
-        int32_t c;
-        if (js >= N) {
-            c = M;
-        } else {
-            const int owner = js / ipt;
-            c = L.lane_cnt[owner];
-            for (int j = owner * ipt; j < js; ++j) c += (L.start_bits[j >> 5] >> (j & 31)) & 1u;
-        }
+        int32_t c = M;
+        if (js < N) c = L.word_starts[js >> 5] + (int32_t)__popc(L.start_bits[js >> 5] & ((1u << (js & 31)) - 1u));
         a.shard_mb_off[tid] = c;
     }
     if (tid == 0) { *a.n_mb = M; a.mb_seq_off[M] = N; }
