@@ -24,18 +24,33 @@ template <int CTRL, int ROW_MASK = 0xF, int BANK_MASK = 0xF>
 __device__ __forceinline__ uint32_t dpp_mov(uint32_t old, uint32_t v) {
     return (uint32_t)__builtin_amdgcn_update_dpp((int)old, (int)v, CTRL, ROW_MASK, BANK_MASK, false);
 }
+// Every lane is written (full row and bank masks, every source lane exists): no previous value to keep.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_perm(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, CTRL, 0xF, 0xF, false);
+}
+
+// Median of three unsigned values in one instruction.  med3(a, b, 0) = min(a, b) and
+// med3(a, b, ~0) = max(a, b), so a per-lane constant chooses between the two.  (The compiler
+// treats the statement's output like any vector-ALU result and keeps the idle cycles a DPP
+// read of it needs.)
+__device__ __forceinline__ uint32_t umed3(uint32_t a, uint32_t b, uint32_t c) {
+    uint32_t r;
+    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
 
 // Value of lane (lane ^ J).
 template <int J>
 __device__ __forceinline__ uint32_t lane_xor(uint32_t v) {
     static_assert(J == 1 || J == 2 || J == 4 || J == 8 || J == 16 || J == 32, "power of two below 64");
-    if constexpr (J == 1) return dpp_mov<DPP_QUAD_PERM_1032>(v, v);
-    else if constexpr (J == 2) return dpp_mov<DPP_QUAD_PERM_2301>(v, v);
+    if constexpr (J == 1) return dpp_perm<DPP_QUAD_PERM_1032>(v);
+    else if constexpr (J == 2) return dpp_perm<DPP_QUAD_PERM_2301>(v);
     else if constexpr (J == 4) {
         // lanes with bit 2 clear (banks 0, 2) take lane+4, the others lane-4
         uint32_t t = dpp_mov<DPP_ROW_SHL4, 0xF, 0x5>(v, v);
         return dpp_mov<DPP_ROW_SHR4, 0xF, 0xA>(t, v);
-    } else if constexpr (J == 8) return dpp_mov<DPP_ROW_ROR8>(v, v);
+    } else if constexpr (J == 8) return dpp_perm<DPP_ROW_ROR8>(v);
     else if constexpr (J == 16) {
         // swap: a = [r0 r0 r2 r2], b = [r1 r1 r3 r3]; even rows want b, odd rows want a
         auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
@@ -49,11 +64,11 @@ __device__ __forceinline__ uint32_t lane_xor(uint32_t v) {
 template <int K, int J>
 __device__ __forceinline__ uint32_t bitonic_step(uint32_t v) {
     const uint32_t p = lane_xor<J>(v);
-    const uint32_t lo = v < p ? v : p, hi = v < p ? p : v;
     const uint32_t lane = threadIdx.x & 63u;
     const bool lower = (lane & J) == 0;          // I am the lower lane of the pair
     const bool asc = (lane & K) == 0;            // my block sorts ascending
-    return (lower == asc) ? lo : hi;
+    // the lower lane of an ascending pair keeps the smaller key, its partner the larger
+    return umed3(v, p, lower == asc ? 0u : 0xFFFFFFFFu);
 }
 
 template <int K, int J>
