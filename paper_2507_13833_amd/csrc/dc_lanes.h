@@ -107,6 +107,17 @@ __device__ __forceinline__ uint32_t wave_incl_scan_umin(uint32_t v) {
     return v;
 }
 
+// Inclusive add-scan over the 64 lanes (lane i: sum of lanes 0..i), same DPP ladder.
+__device__ __forceinline__ uint32_t wave_incl_scan_add_u32(uint32_t v) {
+    v += dpp_mov<DPP_ROW_SHR1>(0u, v);
+    v += dpp_mov<DPP_ROW_SHR2>(0u, v);
+    v += dpp_mov<DPP_ROW_SHR4>(0u, v);
+    v += dpp_mov<DPP_ROW_SHR8>(0u, v);
+    v += dpp_mov<DPP_ROW_BCAST15, 0xA>(0u, v);
+    v += dpp_mov<DPP_ROW_BCAST31, 0xC>(0u, v);
+    return v;
+}
+
 // Exclusive min-scan (lane 0 gets all-ones).
 __device__ __forceinline__ uint32_t wave_excl_scan_umin(uint32_t v) {
     return dpp_mov<DPP_WAVE_SHR1>(0xFFFFFFFFu, wave_incl_scan_umin(v));

@@ -7,8 +7,10 @@
 // O(N) integer work on at most DC_MAX_SEQ slots: latency-bound, so the plan proper runs as
 // ONE workgroup of 1024 lanes with everything staged in LDS.  Lane t handles slots t,
 // t + 1024, ... (every global access is coalesced):
-//   1. len = seq_len[perm[j]] and the rollout offset, validated; wave scans + one scan of
-//      the 256 wave totals -> dense prefix gpre[0..N] (int64, LDS);
+//   0. (slots_kernel, many workgroups) len = seq_len[perm[j]] and the rollout offset of every
+//      slot, validated: random gathers, which need more loads in flight than one CU has;
+//   1. slot lengths, check that perm is a permutation; wave scans + one scan of the 256 wave
+//      totals -> dense prefix gpre[0..N] (int64, LDS);
 //   2. shard bases: exclusive scan of the shard loads (with alignment: a serial recurrence
 //      over P <= 64 shards);
 //   3. micro-batch starts: one lane per shard hops from start to start, each hop a
@@ -18,6 +20,7 @@
 //      writes its outputs.
 #include "dc_device.h"
 #include "dc_internal.h"
+#include "dc_lanes.h"
 
 namespace dc {
 
@@ -58,9 +61,44 @@ struct PlanLds {
     int32_t  shard_off[DC_MAX_SHARDS + 1];  // copy of shard_seq_off
     int64_t  tmp64[16];
     int32_t  tmp32[16];
-    int64_t  src_tokens[DC_MAX_SRC_SHARDS]; // elements each rollout buffer holds
     int32_t  ok;
 };
+
+// Per-slot source descriptors (one lane per slot, many workgroups; runs before plan_kernel on
+// the same stream): the sequence behind each slot, its length and place in the rollout layout,
+// validated; a slot that fails a check gets length 0 and moves nothing.  These are random
+// gathers over seq_len / src_tok_off, which one workgroup alone could not keep in flight.
+constexpr int SLOTS_BLOCK = 256;
+
+__global__ __launch_bounds__(SLOTS_BLOCK) void slots_kernel(PlanArgs a, SourceDesc sd) {
+    const int j = blockIdx.x * SLOTS_BLOCK + threadIdx.x;
+    const int N = a.n_seq;
+    if (j >= N) return;
+    const int32_t i = a.perm[j];
+    const bool placed = i >= 0 && i < N;
+    int32_t ln = placed ? a.seq_len[i] : 0;
+    const int64_t so = placed ? a.src_tok_off[i] : 0;
+    int32_t sh = 0;                                      // rollout shard (seq_off[s] = N from s = n_src on)
+    if (sd.n_src > 1 && placed) {
+#pragma unroll
+        for (int s = 1; s < DC_MAX_SRC_SHARDS; ++s) sh += i >= sd.seq_off[s] ? 1 : 0;
+    }
+    int64_t tokens = sd.tokens[0];
+#pragma unroll
+    for (int s = 1; s < DC_MAX_SRC_SHARDS; ++s) tokens = sh == s ? sd.tokens[s] : tokens;
+    const bool bad_len = placed && (ln <= 0 || ln > DC_MAX_SEQ_LEN);
+    const bool bad_off = placed && !bad_len && (so < 0 || so + ln > tokens);
+    const bool over = placed && !bad_len && !bad_off && ln > a.budget;   // still laid out, alone in its micro-batch
+    const int32_t e = !placed ? DC_ERR_BAD_LAYOUT
+                      : bad_len ? DC_ERR_ZERO_LENGTH_SEQ
+                      : bad_off ? DC_ERR_BAD_LAYOUT
+                      : over ? DC_ERR_SEQ_EXCEEDS_BUDGET : 0;
+    if (e != 0) set_status(a.status, e);
+    if (!placed || bad_len || bad_off) ln = 0;
+    a.slot_src_off[j] = placed ? so : 0;
+    a.slot_len[j] = ln;
+    a.slot_shard[j] = sh;
+}
 
 __device__ __forceinline__ bool start_bit(const PlanLds& L, int j) { return (L.start_bits[j >> 5] >> (j & 31)) & 1u; }
 
@@ -72,7 +110,6 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
 
     for (int i = tid; i < PLAN_WORDS; i += PLAN_BLOCK) { L.start_bits[i] = 0; L.seen_bits[i] = 0; }
     if (tid == 0) L.ok = 1;
-    if (tid < DC_MAX_SRC_SHARDS) L.src_tokens[tid] = sd.tokens[tid];
     __syncthreads();
     if (tid <= P) {
         const int32_t v = a.shard_seq_off[tid];
@@ -88,71 +125,31 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
         return;
     }
 
-    // ---- 1. slot lengths, validation, dense prefix ----
-    // the dependent global loads are grouped: all perm[j] of the lane, then all lengths and
-    // offsets, so the lane pays two memory round trips, not two per slot
-    int32_t seq[PLAN_IPT];
+    // ---- 1. slot lengths (validated by slots_kernel), permutation check, dense prefix ----
+    int32_t seq[PLAN_IPT], len[PLAN_IPT];
 #pragma unroll
     for (int q = 0; q < PLAN_IPT; ++q) {
         const int j = q * PLAN_BLOCK + tid;
-        seq[q] = -1;
-        if (q < nb) seq[q] = j < N ? a.perm[j] : -1;     // q < nb is uniform: unused steps cost a branch
+        seq[q] = j < N ? a.perm[j] : -1;
+        len[q] = j < N ? a.slot_len[j] : 0;
     }
-    int32_t len[PLAN_IPT];
-    int64_t sof[PLAN_IPT];
+    uint32_t dup = 0;                                    // bit q: perm repeats an earlier entry at my slot of step q
 #pragma unroll
     for (int q = 0; q < PLAN_IPT; ++q) {
-        len[q] = 0; sof[q] = 0;
-        if (q < nb) {
-            const bool ok = seq[q] >= 0 && seq[q] < N;
-            len[q] = ok ? a.seq_len[seq[q]] : 0;
-            sof[q] = ok ? a.src_tok_off[seq[q]] : 0;
-        }
+        const int32_t i = seq[q];                        // -1 beyond N; out-of-range entries were emptied by slots_kernel
+        if (i >= 0 && i < N) dup |= ((atomicOr(&L.seen_bits[i >> 5], 1u << (i & 31)) >> (i & 31)) & 1u) << q;
     }
-    // validation without divergent control flow; the lane reports its first error once
-    int32_t err = 0;
+    if (__ballot(dup != 0) != 0ull) {                    // uniform, rare: perm is not a permutation; a repeat moves nothing
+        if (dup != 0) set_status(a.status, DC_ERR_BAD_LAYOUT);
 #pragma unroll
-    for (int q = 0; q < PLAN_IPT; ++q) {
-        if (q >= nb) continue;                           // uniform
-        const int j = q * PLAN_BLOCK + tid;
-        const bool live = j < N;
-        const int32_t i = seq[q];
-        const bool in_range = live && i >= 0 && i < N;
-        bool dup = false;
-        if (in_range) dup = (atomicOr(&L.seen_bits[i >> 5], 1u << (i & 31)) >> (i & 31)) & 1u;
-        const bool placed = in_range && !dup;            // a sequence that exists, seen for the first time
-        int32_t sh = 0;                                  // its rollout shard (seq_off[s] = N from s = n_src on)
-        if (sd.n_src > 1) {                              // uniform
-#pragma unroll
-            for (int s = 1; s < DC_MAX_SRC_SHARDS; ++s) sh += i >= sd.seq_off[s] ? 1 : 0;
-        }
-        if (!placed) sh = 0;
-        int32_t ln = len[q];
-        const int64_t so = placed ? sof[q] : 0;
-        const bool bad_len = placed && (ln <= 0 || ln > DC_MAX_SEQ_LEN);
-        const bool bad_off = placed && !bad_len && (so < 0 || so + ln > L.src_tokens[sh]);
-        const bool over = placed && !bad_len && !bad_off && ln > a.budget;   // still laid out, alone in its micro-batch
-        const int32_t e = !live ? 0
-                          : !placed ? DC_ERR_BAD_LAYOUT
-                          : bad_len ? DC_ERR_ZERO_LENGTH_SEQ
-                          : bad_off ? DC_ERR_BAD_LAYOUT
-                          : over ? DC_ERR_SEQ_EXCEEDS_BUDGET : 0;
-        if (err == 0) err = e;
-        if (!live || !placed || bad_len || bad_off) ln = 0;
-        len[q] = ln;
-        if (live) {
-            a.slot_src_off[j] = so;
-            a.slot_len[j] = ln;
-            a.slot_shard[j] = sh;
-        }
+        for (int q = 0; q < PLAN_IPT; ++q)
+            if ((dup >> q) & 1u) { len[q] = 0; a.slot_len[q * PLAN_BLOCK + tid] = 0; }
     }
-    if (err != 0) set_status(a.status, err);
     // dense prefix: inclusive scan inside each wave step (a wave's 64 slots hold < 2^31 tokens) ...
     int32_t inc[PLAN_IPT];
 #pragma unroll
     for (int q = 0; q < PLAN_IPT; ++q) {
-        inc[q] = 0;
-        if (q < nb) inc[q] = wave_incl_scan_add<int32_t>(len[q]);
+        inc[q] = (int32_t)wave_incl_scan_add_u32((uint32_t)len[q]);
         if (lane == WAVE - 1) L.wave_pref[q * PLAN_WAVES + w] = inc[q];
     }
     __syncthreads();
@@ -169,7 +166,7 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
 #pragma unroll
     for (int q = 0; q < PLAN_IPT; ++q) {
         const int j = q * PLAN_BLOCK + tid;
-        if (q < nb && j < N) L.gpre[j] = L.wave_pref[q * PLAN_WAVES + w] + (inc[q] - len[q]);
+        if (j < N) L.gpre[j] = L.wave_pref[q * PLAN_WAVES + w] + (inc[q] - len[q]);
     }
     __syncthreads();
 
@@ -336,6 +333,12 @@ hipError_t launch_plan(const dc_params& prm, const SourceDesc& src, const int64_
     a.mb_seq_off = d_mb_seq_off; a.cu_seqlens = d_cu_seqlens; a.n_mb = d_n_mb;
     a.slot_src_off = ws.slot_src_off; a.slot_len = ws.slot_len; a.slot_shard = ws.slot_shard;
     a.plan_ok = ws.plan_ok; a.status = d_status;
+    if (prm.n_seq > 0) {
+        hipLaunchKernelGGL(slots_kernel, dim3((unsigned)((prm.n_seq + SLOTS_BLOCK - 1) / SLOTS_BLOCK)), dim3(SLOTS_BLOCK),
+                           0, st, a, src);
+        hipError_t e0 = hipGetLastError();
+        if (e0 != hipSuccess) return e0;
+    }
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(PLAN_BLOCK), 0, st, a, src);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
