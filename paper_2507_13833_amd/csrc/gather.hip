@@ -33,6 +33,7 @@ constexpr int GATHER_BLOCK = 256;
 constexpr int NSEG = SEG_BATCH + SEG_AHEAD;
 constexpr int GRAN_PER_TILE = GATHER_BLOCK / WAVE;                    // one granule per wave
 constexpr int GATHER_TILE_TOKENS = GRAN_PER_TILE * GATHER_GRAN;
+constexpr int64_t GATHER_RIDE_MIN_WGS = 8192;                         // ~4 workgroups per wave slot of the chip
 constexpr int32_t LEN_MASK = (1 << LENSH_SHIFT) - 1;
 static_assert(GATHER_GRAN == WAVE * 16, "a wave covers its granule with 1, 2 or 4 chunks per lane");
 static_assert(GRAN_PER_TILE + 1 <= 8, "the tile's slice of the granule table is one 8-dword scalar load");
@@ -50,7 +51,7 @@ struct GatherArgs {
     const int32_t* gran_first;                   // padded: whole tiles plus GRAN_PER_TILE + 1 entries
     const GranRec* gran_rec;                     // same length
     uint32_t       tiles;                        // tiles per field
-    uint32_t       n_wide, n_narrow;             // 4-byte fields (first in the field table), narrower ones
+    uint32_t       n_carriers, n_riders;         // fields the grid walks (first in the field table), fields riding along
 };
 
 // Slot descriptors of the tile being moved, relative to the tile's first token.
@@ -376,18 +377,13 @@ __global__ __launch_bounds__(GATHER_BLOCK) void gather_kernel(GatherArgs a, Fiel
     __shared__ const char* src[DC_MAX_SRC_SHARDS];
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / WAVE));
     const int N = a.n_seq;
-    // Two streams share the grid: the 4-byte fields, field after field, and the narrower
-    // fields, field after field; of every n_fields consecutive workgroups n_wide continue the
-    // first stream and n_narrow the second.  A wave of a narrow field has only 1 or 2 KB in
-    // flight and cannot fill the memory pipeline alone; dealt in between the wide ones it
-    // rides along.
-    const uint32_t nf = a.n_wide + a.n_narrow;
-    const uint32_t q = blockIdx.x / nf, r = blockIdx.x % nf;
-    const bool wide = r < a.n_wide;
-    const uint32_t lin = wide ? q * a.n_wide + r : q * a.n_narrow + (r - a.n_wide);
-    const uint32_t tile = lin % a.tiles;
-    const FieldDesc& fd = ft.f[(wide ? 0u : a.n_wide) + lin / a.tiles];
-    const int lg = fd.elem_bytes == 4 ? 2 : (fd.elem_bytes == 2 ? 1 : 0);
+    // The grid walks the "carrier" fields, field after field (the 4-byte fields if there are
+    // any, else every field).  Narrower fields ride along: rider r is moved by the waves of
+    // carrier r mod n_carriers, right after their own data and from the same granule record.
+    // A wave of a narrow field has only 1 or 2 KB in flight; as a workgroup of its own it
+    // would hold a wave slot as long as a 4 KB one.
+    const uint32_t tile = blockIdx.x % a.tiles;
+    const uint32_t fc = blockIdx.x / a.tiles;              // carrier
     const int64_t tile_begin = (int64_t)tile * GATHER_TILE_TOKENS;
     const int64_t g0 = (int64_t)tile * GRAN_PER_TILE;
 
@@ -402,17 +398,23 @@ __global__ __launch_bounds__(GATHER_BLOCK) void gather_kernel(GatherArgs a, Fiel
 #pragma unroll
     for (int i = 0; i < GRAN_PER_TILE; ++i)
         dense = dense || ((int)F[i] < N && min((int)F[i + 1], N - 1) - (int)F[i] + 1 > REC_SLOTS);
-
     const int32_t limit = (int32_t)min((int64_t)GATHER_TILE_TOKENS, a.capacity - tile_begin);
-    if (!dense) {
-        const int32_t wave_limit = min(limit - w * GATHER_GRAN, GATHER_GRAN);
-        if (wave_limit > 0) move_wave_sparse(fd, ft.n_src, lg, rec, tile_begin + w * GATHER_GRAN, wave_limit);
-        return;
-    }
+    const int32_t wave_limit = min(limit - w * GATHER_GRAN, GATHER_GRAN);
     const int last = min(max((int)F[GRAN_PER_TILE], first), N - 1);
-    if (threadIdx.x < DC_MAX_SRC_SHARDS) src[threadIdx.x] = fd.src[threadIdx.x];
-    __syncthreads();
-    move_tile_dense(a, sg, src, lg, fd.dst, first, last, tile_begin, limit);
+
+    for (uint32_t f = fc; f < a.n_carriers + a.n_riders; f = f < a.n_carriers ? a.n_carriers + f : f + a.n_carriers) {
+        // f = fc, then the riders n_carriers + fc, n_carriers + fc + n_carriers, ...
+        const FieldDesc& fd = ft.f[f];
+        const int lg = fd.elem_bytes == 4 ? 2 : (fd.elem_bytes == 2 ? 1 : 0);
+        if (!dense) {
+            if (wave_limit > 0) move_wave_sparse(fd, ft.n_src, lg, rec, tile_begin + w * GATHER_GRAN, wave_limit);
+        } else {
+            __syncthreads();                               // the previous field's readers of src[] and sg are done
+            if (threadIdx.x < DC_MAX_SRC_SHARDS) src[threadIdx.x] = fd.src[threadIdx.x];
+            __syncthreads();
+            move_tile_dense(a, sg, src, lg, fd.dst, first, last, tile_begin, limit);
+        }
+    }
 }
 
 hipError_t launch_gather(int32_t n_seq, const FieldTable& ft, int64_t dst_capacity,
@@ -427,22 +429,25 @@ hipError_t launch_gather(int32_t n_seq, const FieldTable& ft, int64_t dst_capaci
     a.slot_shard = ws.slot_shard;
     a.gran_first = ws.gran_first;
     a.gran_rec = ws.gran_rec;
-    a.n_wide = 0;
     const int64_t tiles = (dst_capacity + GATHER_TILE_TOKENS - 1) / GATHER_TILE_TOKENS;
     if (tiles * ft.n_fields > 0x7FFFFFFFLL || tiles * GRAN_PER_TILE + GRAN_PER_TILE + 1 > ws.n_gran)
         return hipErrorInvalidValue;
-    // field table with the 4-byte fields first
+    // field table with the 4-byte fields first: they carry, the others ride
     FieldTable sorted = ft;
-    int n = 0;
+    int n = 0, n_wide = 0;
     for (int pass = 0; pass < 2; ++pass)
         for (int f = 0; f < ft.n_fields; ++f)
             if ((ft.f[f].elem_bytes == 4) == (pass == 0)) {
                 sorted.f[n++] = ft.f[f];
-                if (pass == 0) a.n_wide = (uint32_t)n;
+                if (pass == 0) n_wide = n;
             }
-    a.n_narrow = (uint32_t)ft.n_fields - a.n_wide;
+    // riding pays when the carriers alone give the chip several rounds of workgroups; a small
+    // batch needs every workgroup it can get
+    const bool ride = n_wide > 0 && tiles * n_wide >= GATHER_RIDE_MIN_WGS;
+    a.n_carriers = (uint32_t)(ride ? n_wide : ft.n_fields);
+    a.n_riders = (uint32_t)ft.n_fields - a.n_carriers;
     a.tiles = (uint32_t)tiles;
-    hipLaunchKernelGGL(gather_kernel, dim3((unsigned)(tiles * ft.n_fields)), dim3(GATHER_BLOCK), 0, st, a, sorted);
+    hipLaunchKernelGGL(gather_kernel, dim3((unsigned)(tiles * a.n_carriers)), dim3(GATHER_BLOCK), 0, st, a, sorted);
     return hipGetLastError();
 }
 

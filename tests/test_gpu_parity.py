@@ -188,6 +188,16 @@ def test_max_sequences():
     check_step(_custom(lens, 16, 64, 8192, n_src=16), label="N=16384 (limit), 16 rollout shards")
 
 
+def test_long_and_short_sequences_mixed():
+    # a big batch (the narrow fields ride on the 4-byte fields' workgroups) whose shards end in
+    # runs of very short sequences: tiles with more slots per granule than a record holds sit
+    # next to tiles inside one long sequence
+    rng = np.random.default_rng(11)
+    lens = np.concatenate([rng.integers(3500, 4500, 8192), rng.integers(1, 120, 8192)])
+    rng.shuffle(lens)
+    check_step(_custom(lens, 16, 64, 16384, n_src=2), label="8192 long + 8192 short")
+
+
 def test_group_sizes_and_ddof():
     torch, binding, runner = _gpu()
     rng = np.random.default_rng(12)
