@@ -26,7 +26,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # scaled by what the same counter reads for the plain copy of --calibrate-copy (2^30 B in, 2^30 B
 # out); valid only for the kernel sources with the digest below (profiles/ has the runs).
 TRAFFIC = {
-    # config: (fetch bytes + write bytes, digest of csrc/gather.hip + csrc/dc_internal.h)
+    # config: (fetch bytes + write bytes per gather launch, digest of csrc/gather.hip + csrc/dc_internal.h)
+    5: (1044713000 + 985079800, "663c35b469d79570"),     # profiles/hbm_traffic_config5_pmc.txt
 }
 
 

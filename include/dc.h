@@ -103,7 +103,9 @@ typedef struct dc_source {
     const int64_t* d_src_tok_off;  /* DEVICE [N]                                              */
 } dc_source;
 
-/* One per-token field.  src_base[s] and dst must be 16-byte aligned device pointers. */
+/* One per-token field.  src_base[s] and dst must be 16-byte aligned device pointers.  The
+ * rollout buffers are read in aligned 4-byte words: a buffer of 1- or 2-byte elements must be
+ * readable up to the next multiple of 4 bytes past its last element (never written). */
 typedef struct dc_field {
     const void* const* src_base;   /* HOST [n_src_shards] device base pointers                */
     void*              d_dst;      /* DEVICE arena of dst_capacity_tokens elements            */
@@ -111,7 +113,8 @@ typedef struct dc_field {
     int32_t            reserved;   /* must be 0                                               */
 } dc_field;
 
-/* Bytes of device workspace dc_plan / dc_gather / dc_repack need for these sizes. */
+/* Bytes of device workspace dc_plan / dc_gather / dc_repack need for these sizes
+ * (about 70 bytes per 1024 tokens of capacity plus 16 bytes per sequence). */
 size_t dc_workspace_bytes(const dc_params* prm, int64_t dst_capacity_tokens);
 
 /*
