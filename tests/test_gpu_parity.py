@@ -32,12 +32,15 @@ def oracle_step(w, align=1, cap=0):
     return bal, adv, adv_tok, pl
 
 
-def check_step(w, align=1, cap=0, label=""):
+def check_step(w, align=1, cap=0, label="", overlapped=False):
     torch, binding, runner = _gpu()
     print(f"[parity] {label or w.name}: N={w.n_seq} P={w.n_shards} T={w.total_tokens} align={align} cap={cap}",
           flush=True)
     d = runner.DeviceBatch(w, align_tokens=align, cap=cap, poison=True)
-    d.step()
+    if overlapped:
+        d.step_overlapped()                              # the launch configuration bench.py times: two streams
+    else:
+        d.step()
     torch.cuda.synchronize()
     assert d.read_status() == 0
 
@@ -100,6 +103,41 @@ def check_step(w, align=1, cap=0, label=""):
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
 def test_full_config(cfg):
     check_step(workloads.make_workload(cfg), label=f"config {cfg}")
+
+
+@pytest.mark.parametrize("cfg", [3, 5])
+def test_full_config_as_benchmarked(cfg):
+    """Same check on the two-stream step bench.py times (advantage beside balance + plan)."""
+    d = check_step(workloads.make_workload(cfg), label=f"config {cfg}, two streams", overlapped=True)
+    # a second pass over the same buffers must reproduce every output bit for bit
+    import torch
+    first = {k: v.clone() for k, v in d.dst_fields.items()}
+    perm, cu, dst = d.perm.clone(), d.cu_seqlens.clone(), d.dst_tok_off.clone()
+    d.step_overlapped()
+    torch.cuda.synchronize()
+    assert d.read_status() == 0
+    assert torch.equal(perm, d.perm) and torch.equal(cu, d.cu_seqlens) and torch.equal(dst, d.dst_tok_off)
+    for k, v in d.dst_fields.items():
+        assert torch.equal(first[k], v), k
+
+
+def test_padded_rollout_layout():
+    """The paper's batches are padded (Sec. 7.1: prompts left-padded to a fixed width, responses
+    right-padded): a sequence's valid tokens are one contiguous run inside its row, so the rollout
+    offsets express that layout directly; only valid tokens are read."""
+    rng = np.random.default_rng(21)
+    N, G, max_prompt, max_resp = 1024, 8, 512, 1024
+    p_len = np.repeat(rng.integers(16, max_prompt + 1, N // G), G)
+    r_len = rng.integers(1, max_resp + 1, N)
+    row = max_prompt + max_resp
+    w = _custom((p_len + r_len).astype(np.int32), G, 8, 4096, n_src=2)
+    per = N // 2
+    w.src_tok_off = ((np.arange(N) % per) * row + (max_prompt - p_len)).astype(np.int64)
+    w.src_shard_tokens = np.array([per * row, per * row], np.int64)
+    for f in w.fields:                                    # padded buffers: sentinel bytes in the padding
+        dt = f.shards[0].dtype
+        f.shards = [rng.integers(0, 200, per * row).astype(dt) for _ in range(2)]
+    check_step(w, label="padded rows of 1536 tokens")
 
 
 def test_repack_equals_plan_then_gather_and_is_deterministic():
