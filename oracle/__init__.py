@@ -44,7 +44,8 @@ def _load():
     global _lib
     if _lib is None:
         _lib = C.CDLL(build())
-        for name in ("dco_balance", "dco_group_advantage", "dco_adv_broadcast", "dco_plan", "dco_gather"):
+        for name in ("dco_balance", "dco_group_advantage", "dco_adv_broadcast", "dco_plan", "dco_gather",
+                     "dco_scatter"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -152,3 +153,21 @@ def gather(seq_len, perm, src_tok_off, src_shard_seq_off, src_shards: Sequence[n
     _chk(_load().dco_gather(_p(S), C.c_int32(N), _p(pm), _p(sto), _p(sso), C.c_int32(len(srcs)), ptrs,
                             _p(dst), C.c_int32(dt.itemsize), _p(dto)))
     return dst
+
+
+def scatter(seq_len, perm, src_tok_off, src_shard_seq_off, arena: np.ndarray, dst_tok_off,
+            rollout_shards: Sequence[np.ndarray]) -> List[np.ndarray]:
+    """Reverse of gather for one field: training arena -> copies of the given rollout buffers
+    (one per rollout shard; elements outside every sequence keep the given values)."""
+    S = _i32(seq_len)
+    N = len(S)
+    pm = _i32(perm)
+    sto = np.ascontiguousarray(src_tok_off, dtype=np.int64)
+    sso = _i32(src_shard_seq_off)
+    dto = np.ascontiguousarray(dst_tok_off, dtype=np.int64)
+    ar = np.ascontiguousarray(arena)
+    outs = [np.array(x, dtype=ar.dtype, copy=True, order="C") for x in rollout_shards]
+    ptrs = (C.c_void_p * len(outs))(*[x.ctypes.data for x in outs])
+    _chk(_load().dco_scatter(_p(S), C.c_int32(N), _p(pm), _p(sto), _p(sso), C.c_int32(len(outs)), ptrs,
+                             _p(ar), C.c_int32(ar.dtype.itemsize), _p(dto)))
+    return outs

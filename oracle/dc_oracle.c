@@ -24,6 +24,10 @@
  *                        sizes differ; the packing itself is this build's
  *                        reading, the paper pads.)
  *   dco_gather           per-sequence copy rollout layout -> training layout.
+ *   dco_scatter          the same copy backwards (training layout -> rollout
+ *                        layout), for fields a training-layout stage produced
+ *                        (App. B, Table 2: the collect / concat side of a stage
+ *                        transition).
  *
  * Return value: 0 on success, a small positive code on invalid input.
  */
@@ -276,6 +280,28 @@ int dco_gather(const int32_t* S, int32_t N, const int32_t* perm, const int64_t* 
         if (s == n_src) return DCO_BAD_ARG;
         const char* from = (const char*)src_base[s] + src_tok_off[i] * elem_bytes;
         char* to = (char*)dst + dst_tok_off[j] * elem_bytes;
+        memcpy(to, from, (size_t)S[i] * (size_t)elem_bytes);
+    }
+    return DCO_OK;
+}
+
+/*
+ * Reverse of dco_gather for one field: slot j (sequence perm[j]) is copied, byte for
+ * byte, from element dst_tok_off[j] of the training arena to the sequence's place in
+ * its rollout buffer.  Elements of the rollout buffers that belong to no sequence
+ * (padding between rows) are not touched.
+ */
+int dco_scatter(const int32_t* S, int32_t N, const int32_t* perm, const int64_t* src_tok_off,
+                const int32_t* src_shard_seq_off, int32_t n_src, void* const* rollout_base,
+                const void* arena, int32_t elem_bytes, const int64_t* dst_tok_off) {
+    if (elem_bytes < 1) return DCO_BAD_ARG;
+    for (int32_t j = 0; j < N; ++j) {
+        int32_t i = perm[j];
+        int32_t s = 0;
+        while (s < n_src && !(src_shard_seq_off[s] <= i && i < src_shard_seq_off[s + 1])) ++s;
+        if (s == n_src) return DCO_BAD_ARG;
+        char* to = (char*)rollout_base[s] + src_tok_off[i] * elem_bytes;
+        const char* from = (const char*)arena + dst_tok_off[j] * elem_bytes;
         memcpy(to, from, (size_t)S[i] * (size_t)elem_bytes);
     }
     return DCO_OK;

@@ -160,3 +160,65 @@ def test_gather_preserves_nan_payload_bits():
     x = bits.view(np.float32)
     o = oracle.gather(S, [1, 0], [0, 2], [0, 2], [x], [0, 3, 5], 5)
     assert o.view(np.uint32).tolist() == [0xFFC12345, 0x7F800000, 0x00000001, 0x7FC00001, 0x80000000]
+
+
+# ---------------------------------------------------------------- reverse path (scatter)
+def _scatter_case(seed, n=60, K=4, n_src=3, pad=7):
+    """Small rollout batch with gaps between sequences (padded rows) in several rollout shards."""
+    rng = np.random.default_rng(seed)
+    n = n // (K * n_src) * (K * n_src)
+    S = rng.integers(1, 40, n).astype(np.int32)
+    per = n // n_src
+    sso = (np.arange(n_src + 1) * per).astype(np.int32)
+    sto = np.zeros(n, np.int64)
+    stk = np.zeros(n_src, np.int64)
+    for s in range(n_src):
+        pos = int(rng.integers(0, pad))
+        for i in range(sso[s], sso[s + 1]):
+            sto[i] = pos
+            pos += int(S[i]) + int(rng.integers(0, pad))
+        stk[s] = pos
+    bal = oracle.balance(S, K)
+    pl = oracle.plan(S, bal.perm, bal.shard_seq_off, 100)
+    return S, sso, sto, stk, bal, pl
+
+
+@pytest.mark.parametrize("dtype", [np.uint8, np.uint16, np.int32])
+def test_scatter_undoes_gather(dtype):
+    S, sso, sto, stk, bal, pl = _scatter_case(3)
+    rng = np.random.default_rng(5)
+    src = [rng.integers(1, 200, int(t)).astype(dtype) for t in stk]
+    arena = oracle.gather(S, bal.perm, sto, sso, src, pl.dst_tok_off, int(pl.shard_tok_off[-1]))
+    blank = [np.full(int(t), 255, dtype) for t in stk]
+    back = oracle.scatter(S, bal.perm, sto, sso, arena, pl.dst_tok_off, blank)
+    for s in range(len(stk)):
+        valid = np.zeros(int(stk[s]), bool)
+        for i in range(sso[s], sso[s + 1]):
+            valid[sto[i]: sto[i] + S[i]] = True
+        assert np.array_equal(back[s][valid], src[s][valid])       # every token back where it came from
+        assert np.all(back[s][~valid] == 255)                      # gaps between sequences untouched
+
+
+def test_scatter_against_index_formulation():
+    # independent formulation: build the token-level map arena index -> (shard, rollout index) with
+    # NumPy and apply it with fancy indexing
+    S, sso, sto, stk, bal, pl = _scatter_case(9, n=96, K=8, n_src=2)
+    T = int(pl.shard_tok_off[-1])
+    arena = np.arange(T, dtype=np.int32) * 3 + 1
+    blank = [np.full(int(t), -1, np.int32) for t in stk]
+    got = oracle.scatter(S, bal.perm, sto, sso, arena, pl.dst_tok_off, blank)
+    want = [b.copy() for b in blank]
+    shard_of = np.searchsorted(sso, np.arange(len(S)), side="right") - 1
+    for j, i in enumerate(bal.perm):
+        idx = np.arange(S[i])
+        want[shard_of[i]][sto[i] + idx] = arena[pl.dst_tok_off[j] + idx]
+    for a, b in zip(got, want):
+        assert np.array_equal(a, b)
+
+
+def test_scatter_hand_example():
+    # S = [2, 3], one shard, perm = [1, 0] (longest first): arena = [b0 b1 b2 | a0 a1]
+    S = np.array([2, 3], np.int32)
+    arena = np.array([10, 11, 12, 20, 21], np.int32)
+    out = oracle.scatter(S, [1, 0], [1, 4], [0, 2], arena, [0, 3, 5], [np.zeros(8, np.int32)])[0]
+    assert out.tolist() == [0, 20, 21, 0, 10, 11, 12, 0]
