@@ -142,6 +142,23 @@ def main() -> int:
             tot += e0.elapsed_time(e1)
         stage[name + "_ms"] = round(tot / 6, 4)
 
+    # the reverse path (training layout -> rollout layout), whole dc_scatter call, outside the timed region
+    tot = 0.0
+    for i in range(6):
+        b = sets[i % len(sets)]
+        if not hasattr(b, "back"):
+            b.prepare_scatter()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); b.scatter(); e1.record()
+        torch.cuda.synchronize()
+        if i >= 2:
+            tot += e0.elapsed_time(e1)
+    assert all(s.read_status() == 0 for s in sets)
+    scatter_ms = tot / 4
+    reverse = {"call": "dc_scatter", "ms": round(scatter_ms, 4), "algorithmic_bytes": gather_bytes,
+               "achieved": gather_bytes / (scatter_ms * 1e-3) / 1e9, "unit": "GB/s",
+               "frac": gather_bytes / (scatter_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
     traffic = None
     if args.config in TRAFFIC and TRAFFIC[args.config][1] == kernel_digest():
         traffic = TRAFFIC[args.config][0]
@@ -163,6 +180,7 @@ def main() -> int:
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": gather_bytes, "avg_launch_ms": gather_ms},
         "stages": stage,
+        "reverse": reverse,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)

@@ -17,6 +17,10 @@
  *   dc_gather           segmented copy of every per-token field from the rollout
  *                       layout into the packed training layout.
  *   dc_repack           dc_plan followed by dc_gather.
+ *   dc_scatter          the reverse path: per-token fields a training-layout stage
+ *                       produced go back from the packed training layout to the
+ *                       rollout layout (the collect / concat side of a stage
+ *                       transition, App. B Table 2).
  *
  * Conventions
  *   - Pointers named d_* are DEVICE pointers (gfx950, current HIP device).  All
@@ -179,6 +183,25 @@ dc_status dc_repack(const dc_params* prm, const dc_source* src, const int32_t* d
                     int64_t* d_dst_tok_off, int64_t* d_shard_tok_off, int32_t* d_shard_mb_off,
                     int32_t* d_mb_seq_off, int32_t* d_cu_seqlens, int32_t* d_n_mb,
                     void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream);
+
+/* Bytes of device workspace dc_scatter needs (256-byte aligned, like dc_plan's). */
+size_t dc_scatter_workspace_bytes(const dc_params* prm, const dc_source* src);
+
+/*
+ * Reverse of dc_gather.  For every slot j and field f, seq_len[perm[j]] elements go from element
+ * d_dst_tok_off[j] of the field's training arena to the sequence's place in its rollout buffer, as
+ * raw bytes.  In each dc_field the roles are swapped: d_dst is the training arena (READ, 16-byte
+ * aligned, dst_capacity_tokens elements, readable in whole 4-byte words) and src_base[s] are the
+ * rollout buffers (WRITTEN, 16-byte aligned).  Elements of a rollout buffer that belong to no sequence
+ * (padding between rows) are left untouched.  d_dst_tok_off: as dc_plan wrote it for the same prm,
+ * src and d_perm.  Sequences must not overlap in the rollout layout.
+ * Device errors: BAD_LAYOUT (perm entry or offsets out of range, overlapping sequences),
+ * ZERO_LENGTH_SEQ, OVERFLOW (a slot reaches beyond dst_capacity_tokens); a slot that fails a check
+ * moves nothing.
+ */
+dc_status dc_scatter(const dc_params* prm, const dc_source* src, const int32_t* d_seq_len, const int32_t* d_perm,
+                     const dc_field* fields, int32_t n_fields, int64_t dst_capacity_tokens,
+                     const int64_t* d_dst_tok_off, void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream);
 
 const char* dc_strerror(dc_status code);
 

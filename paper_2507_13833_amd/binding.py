@@ -31,7 +31,7 @@ DC_ERR_OVERFLOW = 8
 DC_ERR_BAD_LAYOUT = 9
 
 EXPORTS = ("dc_workspace_bytes", "dc_balance", "dc_group_advantage", "dc_plan", "dc_gather",
-           "dc_repack", "dc_strerror")
+           "dc_repack", "dc_scatter_workspace_bytes", "dc_scatter", "dc_strerror")
 
 
 class dc_params(C.Structure):
@@ -88,6 +88,11 @@ def load() -> C.CDLL:
         lib.dc_repack.argtypes = [C.POINTER(dc_params), C.POINTER(dc_source), vp, vp, vp,
                                   C.POINTER(dc_field), C.c_int32, C.c_int64,
                                   vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp, vp]
+        lib.dc_scatter_workspace_bytes.restype = C.c_size_t
+        lib.dc_scatter_workspace_bytes.argtypes = [C.POINTER(dc_params), C.POINTER(dc_source)]
+        lib.dc_scatter.restype = C.c_int
+        lib.dc_scatter.argtypes = [C.POINTER(dc_params), C.POINTER(dc_source), vp, vp, C.POINTER(dc_field), C.c_int32,
+                                   C.c_int64, vp, vp, C.c_size_t, vp, vp]
         _lib = lib
     return _lib
 
@@ -209,3 +214,16 @@ def dc_repack(prm: dc_params, src: Source, d_seq_len, d_perm, d_shard_seq_off, f
                             _ptr(d_shard_tok_off), _ptr(d_shard_mb_off), _ptr(d_mb_seq_off), _ptr(d_cu_seqlens),
                             _ptr(d_n_mb), _ptr(d_ws), int(ws_bytes), _ptr(d_status), _stream(stream)),
            "dc_repack")
+
+
+def dc_scatter_workspace_bytes(prm: dc_params, src: Source) -> int:
+    return int(load().dc_scatter_workspace_bytes(C.byref(prm), C.byref(src.struct)))
+
+
+def dc_scatter(prm: dc_params, src: Source, d_seq_len, d_perm, fields: Fields, dst_capacity_tokens: int,
+               d_dst_tok_off, d_ws, ws_bytes: int, d_status, stream=None) -> None:
+    """fields: as for dc_gather, with the roles swapped (dst = training arena read, srcs = rollout buffers written)."""
+    _check(load().dc_scatter(C.byref(prm), C.byref(src.struct), _ptr(d_seq_len), _ptr(d_perm), fields.array, fields.n,
+                             int(dst_capacity_tokens), _ptr(d_dst_tok_off), _ptr(d_ws), int(ws_bytes),
+                             _ptr(d_status), _stream(stream)),
+           "dc_scatter")

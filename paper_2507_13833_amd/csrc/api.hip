@@ -34,11 +34,11 @@ static dc_status check_params(const dc_params* prm) {
     return DC_OK;
 }
 
-static dc_status check_source(const dc_params* prm, const dc_source* src, SourceDesc* out) {
+static dc_status check_source(const dc_params* prm, const dc_source* src, SourceDesc* out, bool need_offsets = true) {
     if (!src || !src->shard_seq_off || !src->shard_tokens || src->reserved != 0) return DC_ERR_INVALID_ARG;
     if (src->n_src_shards < 1) return DC_ERR_INVALID_ARG;
     if (src->n_src_shards > DC_MAX_SRC_SHARDS) return DC_ERR_UNSUPPORTED_SIZE;
-    if (prm->n_seq > 0 && !src->d_src_tok_off) return DC_ERR_INVALID_ARG;
+    if (need_offsets && prm->n_seq > 0 && !src->d_src_tok_off) return DC_ERR_INVALID_ARG;
     out->n_src = src->n_src_shards;
     for (int s = 0; s <= DC_MAX_SRC_SHARDS; ++s) out->seq_off[s] = prm->n_seq;
     for (int s = 0; s < DC_MAX_SRC_SHARDS; ++s) out->tokens[s] = 0;
@@ -47,6 +47,30 @@ static dc_status check_source(const dc_params* prm, const dc_source* src, Source
         if (src->shard_seq_off[s + 1] < src->shard_seq_off[s] || src->shard_tokens[s] < 0) return DC_ERR_INVALID_ARG;
         out->seq_off[s] = src->shard_seq_off[s];
         out->tokens[s] = src->shard_tokens[s];
+    }
+    return DC_OK;
+}
+
+// Field descriptors as the kernels take them (by value), with every pointer checked.
+static dc_status fill_field_table(const dc_field* fields, int32_t n_fields, const SourceDesc& sd,
+                                  int64_t dst_capacity_tokens, FieldTable* out) {
+    FieldTable& ft = *out;
+    ft.n_fields = n_fields;
+    ft.n_src = sd.n_src;
+    for (int f = 0; f < DC_MAX_FIELDS; ++f) {
+        ft.f[f].dst = nullptr; ft.f[f].elem_bytes = 1; ft.f[f].pad = 0;
+        for (int s = 0; s < DC_MAX_SRC_SHARDS; ++s) ft.f[f].src[s] = nullptr;
+        if (f >= n_fields) continue;
+        const dc_field& in = fields[f];
+        if (in.reserved != 0 || !in.src_base) return DC_ERR_INVALID_ARG;
+        if (in.elem_bytes != 1 && in.elem_bytes != 2 && in.elem_bytes != 4) return DC_ERR_INVALID_ARG;
+        if (dst_capacity_tokens > 0 && (!in.d_dst || !aligned16(in.d_dst))) return DC_ERR_INVALID_ARG;
+        ft.f[f].dst = static_cast<char*>(in.d_dst);
+        ft.f[f].elem_bytes = in.elem_bytes;
+        for (int s = 0; s < sd.n_src; ++s) {
+            if (sd.tokens[s] > 0 && (!in.src_base[s] || !aligned16(in.src_base[s]))) return DC_ERR_INVALID_ARG;
+            ft.f[f].src[s] = static_cast<const char*>(in.src_base[s]);
+        }
     }
     return DC_OK;
 }
@@ -148,23 +172,8 @@ dc_status dc_gather(const dc_params* prm, const dc_source* src, const dc_field* 
     if (ws_bytes < ws.bytes) return DC_ERR_WORKSPACE;
     if (ws.n_gran > 0x7FFFFFFFLL) return DC_ERR_UNSUPPORTED_SIZE;
     FieldTable ft;
-    ft.n_fields = n_fields;
-    ft.n_src = sd.n_src;
-    for (int f = 0; f < DC_MAX_FIELDS; ++f) {
-        ft.f[f].dst = nullptr; ft.f[f].elem_bytes = 1; ft.f[f].pad = 0;
-        for (int s = 0; s < DC_MAX_SRC_SHARDS; ++s) ft.f[f].src[s] = nullptr;
-        if (f >= n_fields) continue;
-        const dc_field& in = fields[f];
-        if (in.reserved != 0 || !in.src_base) return DC_ERR_INVALID_ARG;
-        if (in.elem_bytes != 1 && in.elem_bytes != 2 && in.elem_bytes != 4) return DC_ERR_INVALID_ARG;
-        if (dst_capacity_tokens > 0 && (!in.d_dst || !aligned16(in.d_dst))) return DC_ERR_INVALID_ARG;
-        ft.f[f].dst = static_cast<char*>(in.d_dst);
-        ft.f[f].elem_bytes = in.elem_bytes;
-        for (int s = 0; s < sd.n_src; ++s) {
-            if (sd.tokens[s] > 0 && (!in.src_base[s] || !aligned16(in.src_base[s]))) return DC_ERR_INVALID_ARG;
-            ft.f[f].src[s] = static_cast<const char*>(in.src_base[s]);
-        }
-    }
+    rc = fill_field_table(fields, n_fields, sd, dst_capacity_tokens, &ft);
+    if (rc != DC_OK) return rc;
     hipError_t e = launch_gather(prm->n_seq, ft, dst_capacity_tokens, d_dst_tok_off, ws,
                                  static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? DC_OK : DC_ERR_HIP;
@@ -190,6 +199,36 @@ dc_status dc_repack(const dc_params* prm, const dc_source* src, const int32_t* d
     if (rc != DC_OK) return rc;
     return dc_gather(prm, src, fields, n_fields, dst_capacity_tokens, d_dst_tok_off, d_ws, ws_bytes, d_status,
                      hip_stream);
+}
+
+size_t dc_scatter_workspace_bytes(const dc_params* prm, const dc_source* src) {
+    if (!prm || check_params(prm) != DC_OK) return 0;
+    SourceDesc sd;
+    if (check_source(prm, src, &sd, false) != DC_OK) return 0;
+    return carve_scatter_workspace(nullptr, prm->n_seq, sd).bytes;
+}
+
+dc_status dc_scatter(const dc_params* prm, const dc_source* src, const int32_t* d_seq_len, const int32_t* d_perm,
+                     const dc_field* fields, int32_t n_fields, int64_t dst_capacity_tokens,
+                     const int64_t* d_dst_tok_off, void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream) {
+    dc_status rc = check_params(prm);
+    if (rc != DC_OK) return rc;
+    SourceDesc sd;
+    rc = check_source(prm, src, &sd);
+    if (rc != DC_OK) return rc;
+    if (n_fields < 0 || dst_capacity_tokens < 0 || !d_dst_tok_off || !d_ws) return DC_ERR_INVALID_ARG;
+    if (prm->n_seq > 0 && (!d_seq_len || !d_perm)) return DC_ERR_INVALID_ARG;
+    if (n_fields > DC_MAX_FIELDS) return DC_ERR_UNSUPPORTED_SIZE;
+    if (n_fields > 0 && !fields) return DC_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(d_ws) & 255u) return DC_ERR_INVALID_ARG;
+    ScatterWorkspace ws = carve_scatter_workspace(d_ws, prm->n_seq, sd);
+    if (ws_bytes < ws.bytes) return DC_ERR_WORKSPACE;
+    FieldTable ft;
+    rc = fill_field_table(fields, n_fields, sd, dst_capacity_tokens, &ft);
+    if (rc != DC_OK) return rc;
+    hipError_t e = launch_scatter(prm->n_seq, sd, src->d_src_tok_off, d_seq_len, d_perm, ft, dst_capacity_tokens,
+                                  d_dst_tok_off, ws, d_status, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? DC_OK : DC_ERR_HIP;
 }
 
 const char* dc_strerror(dc_status code) {

@@ -89,4 +89,28 @@ hipError_t launch_plan(const dc_params& prm, const SourceDesc& src, const int64_
 hipError_t launch_gather(int32_t n_seq, const FieldTable& ft, int64_t dst_capacity,
                          const int64_t* d_dst_tok_off, const Workspace& ws, hipStream_t st);
 
+// Granule tables (ws.gran_first, ws.gran_rec) from slot starts d_dst_tok_off[0..n_seq] and the
+// per-slot descriptors in ws; *ws.plan_ok == 0 makes them empty.
+hipError_t launch_records(int32_t n_seq, const int64_t* d_dst_tok_off, const Workspace& ws, hipStream_t st);
+
+// Workspace of the reverse path: the rollout layout seen as a destination.  Sequence i of
+// rollout shard s is "slot" i of that shard; r_dst_off has one more entry per shard (its end).
+struct ScatterWorkspace {
+    int64_t* r_dst_off;      // [N + n_src] slot start in the rollout buffer, shard s at index seq_off[s] + s
+    int64_t* r_src_off;      // [N] element offset of the sequence in the training arena
+    int32_t* r_len;          // [N] tokens to move (0 if a check failed or perm does not place the sequence)
+    int32_t* r_shard;        // [N] zeros: the arena is the only "source shard"
+    int32_t* ok;             // [1] constant 1
+    int32_t* gran_first[DC_MAX_SRC_SHARDS];
+    GranRec* gran_rec[DC_MAX_SRC_SHARDS];
+    int64_t  n_gran[DC_MAX_SRC_SHARDS];
+    size_t   bytes;
+};
+ScatterWorkspace carve_scatter_workspace(void* base, int32_t n_seq, const SourceDesc& src);
+
+hipError_t launch_scatter(int32_t n_seq, const SourceDesc& src, const int64_t* d_src_tok_off,
+                          const int32_t* d_seq_len, const int32_t* d_perm, const FieldTable& ft,
+                          int64_t dst_capacity, const int64_t* d_dst_tok_off, const ScatterWorkspace& ws,
+                          int32_t* d_status, hipStream_t st);
+
 }  // namespace dc

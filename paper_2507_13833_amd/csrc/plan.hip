@@ -342,8 +342,12 @@ hipError_t launch_plan(const dc_params& prm, const SourceDesc& src, const int64_
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(PLAN_BLOCK), 0, st, a, src);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    return launch_records(prm.n_seq, d_dst_tok_off, ws, st);
+}
+
+hipError_t launch_records(int32_t n_seq, const int64_t* d_dst_tok_off, const Workspace& ws, hipStream_t st) {
     RecArgs r;
-    r.n_seq = prm.n_seq; r.n_gran = ws.n_gran; r.dst_tok_off = d_dst_tok_off;
+    r.n_seq = n_seq; r.n_gran = ws.n_gran; r.dst_tok_off = d_dst_tok_off;
     r.slot_src_off = ws.slot_src_off; r.slot_len = ws.slot_len; r.slot_shard = ws.slot_shard;
     r.plan_ok = ws.plan_ok; r.gran_first = ws.gran_first; r.gran_rec = ws.gran_rec;
     hipLaunchKernelGGL(records_kernel, dim3((unsigned)((ws.n_gran + REC_BLOCK - 1) / REC_BLOCK)), dim3(REC_BLOCK), 0, st, r);

@@ -131,5 +131,24 @@ class DeviceBatch:
         if gather_events is not None:
             gather_events[1].record(main)
 
+    def prepare_scatter(self, names: Optional[List[str]] = None, fill: int = 0x5A) -> None:
+        """Rollout-layout buffers to scatter the named training-layout fields back into."""
+        names = self.field_names if names is None else names
+        self.back_names = names
+        self.back_fields: Dict[str, List[torch.Tensor]] = {}
+        for n in names:
+            eb = self.elem_bytes[n]
+            pat = {1: fill, 2: fill * 0x0101, 4: fill * 0x01010101}[eb]
+            self.back_fields[n] = [torch.full((int(t),), pat, dtype=_NP2TORCH[eb], device=self.dev)
+                                   for t in self.w.src_shard_tokens]
+        self.back = B.Fields([(self.back_fields[n], self.dst_fields[n], self.elem_bytes[n]) for n in names])
+        self.sws_bytes = B.dc_scatter_workspace_bytes(self.prm, self.source)
+        self.sws = torch.zeros(self.sws_bytes, dtype=torch.uint8, device=self.dev)
+
+    def scatter(self) -> None:
+        """Reverse path: training arenas -> rollout buffers (after plan / gather of the same step)."""
+        B.dc_scatter(self.prm, self.source, self.seq_len, self.perm, self.back, self.capacity, self.dst_tok_off,
+                     self.sws, self.sws_bytes, self.status)
+
     def read_status(self) -> int:
         return int(self.status.item())

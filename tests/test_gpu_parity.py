@@ -253,6 +253,79 @@ def test_advantage_ill_conditioned_rewards():
     check_step(w, label="rewards 1000 + k/1024")
 
 
+# ---------------------------------------------------------------- reverse path
+def check_scatter(w, label=""):
+    """gather, then scatter the training arenas back: every rollout buffer must equal what the
+    oracle's scatter writes (bit-exact), gaps between sequences untouched."""
+    torch, binding, runner = _gpu()
+    print(f"[parity] scatter {label or w.name}: N={w.n_seq} T={w.total_tokens}", flush=True)
+    d = runner.DeviceBatch(w)
+    d.step()
+    d.prepare_scatter()
+    d.scatter()
+    torch.cuda.synchronize()
+    assert d.read_status() == 0
+    bal = oracle.balance(w.seq_len, w.n_shards)
+    pl = oracle.plan(w.seq_len, bal.perm, bal.shard_seq_off, w.token_budget)
+    for name in d.back_names:
+        arena = d.dst_fields[name].cpu().numpy()             # what the gather produced (checked elsewhere)
+        blank = [np.full(int(t), {1: 0x5A, 2: 0x5A5A, 4: 0x5A5A5A5A}[arena.dtype.itemsize], arena.dtype)
+                 for t in w.src_shard_tokens]
+        want = oracle.scatter(w.seq_len, bal.perm, w.src_tok_off, w.src_shard_seq_off, arena, pl.dst_tok_off, blank)
+        for s_, (g, x) in enumerate(zip(d.back_fields[name], want)):
+            assert np.array_equal(g.cpu().numpy(), x), (name, s_)
+    # and the round trip restores the rollout payload itself
+    for f in w.fields:
+        for s_, src in enumerate(f.shards):
+            got = d.back_fields[f.name][s_].cpu().numpy().view(src.dtype)
+            valid = np.zeros(len(src), bool)
+            for i in range(w.src_shard_seq_off[s_], w.src_shard_seq_off[s_ + 1]):
+                valid[w.src_tok_off[i]: w.src_tok_off[i] + w.seq_len[i]] = True
+            assert np.array_equal(got[valid], src[valid]), (f.name, s_)
+    return d
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 4, 5])
+def test_scatter_full_config(cfg):
+    check_scatter(workloads.make_workload(cfg), label=f"config {cfg}")
+
+
+def test_scatter_shapes():
+    rng = np.random.default_rng(31)
+    check_scatter(_custom(rng.integers(1, 9, 8192), 8, 16, 64, n_src=4), label="lengths 1..8")
+    check_scatter(_custom(rng.integers(1, 3000, 1000), 5, 8, 4096, n_src=2), label="N=1000")
+    check_scatter(_custom(rng.integers(1, 200, 2), 2, 2, 512), label="N=2")
+    lens = np.concatenate([rng.integers(3500, 4500, 8192), rng.integers(1, 120, 8192)])
+    rng.shuffle(lens)
+    check_scatter(_custom(lens, 16, 64, 16384, n_src=2), label="8192 long + 8192 short")
+
+
+def test_scatter_padded_rows_and_errors():
+    torch, binding, runner = _gpu()
+    rng = np.random.default_rng(33)
+    N, G, row = 512, 8, 700
+    lens = rng.integers(1, row + 1, N).astype(np.int32)
+    w = _custom(lens, G, 8, 4096, n_src=2)
+    per = N // 2
+    w.src_tok_off = ((np.arange(N) % per) * row + rng.integers(0, row - lens + 1)).astype(np.int64)
+    w.src_shard_tokens = np.array([per * row, per * row], np.int64)
+    for f in w.fields:
+        f.shards = [rng.integers(0, 200, per * row).astype(f.shards[0].dtype) for _ in range(2)]
+    check_scatter(w, label="padded rows")
+    # overlapping sequences in the rollout layout are refused (nothing of the first one is written)
+    d = runner.DeviceBatch(w)
+    d.step(); d.prepare_scatter(); torch.cuda.synchronize()
+    d.src_tok_off[1] = d.src_tok_off[0]
+    d.scatter(); torch.cuda.synchronize()
+    assert d.read_status() == binding.DC_ERR_BAD_LAYOUT
+    # a slot beyond the arena is refused
+    d = runner.DeviceBatch(w)
+    d.step(); d.prepare_scatter(); torch.cuda.synchronize()
+    d.dst_tok_off[3] = d.capacity
+    d.scatter(); torch.cuda.synchronize()
+    assert d.read_status() == binding.DC_ERR_OVERFLOW
+
+
 # ---------------------------------------------------------------- device-side error reporting
 def test_device_status_codes():
     torch, binding, runner = _gpu()
