@@ -13,6 +13,8 @@ constexpr int GATHER_GRAN = 1024;
 // The per-granule tables are longer than the arena needs, so a gather workgroup can read
 // the entries of a whole tile (and a few more) without a bounds test.
 constexpr int GRAN_TABLE_PAD = 16;
+constexpr int GRAN_PER_TILE = 4;                 // granules (waves) per gather tile
+constexpr int GATHER_TILE_TOKENS = GRAN_PER_TILE * GATHER_GRAN;
 // Slot descriptors kept inline per granule; granules that more slots reach into are
 // served from the per-slot arrays instead.
 constexpr int REC_SLOTS = 4;
@@ -95,18 +97,34 @@ hipError_t launch_records(int32_t n_seq, const int64_t* d_dst_tok_off, const Wor
 
 // Workspace of the reverse path: the rollout layout seen as a destination.  Sequence i of
 // rollout shard s is "slot" i of that shard; r_dst_off has one more entry per shard (its end).
+// The granule tables of the rollout buffers lie one behind the other, each padded like the
+// forward path's.
 struct ScatterWorkspace {
     int64_t* r_dst_off;      // [N + n_src] slot start in the rollout buffer, shard s at index seq_off[s] + s
     int64_t* r_src_off;      // [N] element offset of the sequence in the training arena
     int32_t* r_len;          // [N] tokens to move (0 if a check failed or perm does not place the sequence)
     int32_t* r_shard;        // [N] zeros: the arena is the only "source shard"
-    int32_t* ok;             // [1] constant 1
-    int32_t* gran_first[DC_MAX_SRC_SHARDS];
-    GranRec* gran_rec[DC_MAX_SRC_SHARDS];
-    int64_t  n_gran[DC_MAX_SRC_SHARDS];
+    int32_t* gran_first;     // [n_gran_all]
+    GranRec* gran_rec;       // [n_gran_all]
+    int64_t  n_gran_all;
     size_t   bytes;
 };
 ScatterWorkspace carve_scatter_workspace(void* base, int32_t n_seq, const SourceDesc& src);
+
+// The rollout buffers as destination segments of one launch: segment s owns tiles
+// [tile_end[s-1], tile_end[s]) of the grid and granules [gran_base[s], gran_base[s+1]) of the tables.
+struct BackSegs {
+    int32_t  n_seg;
+    int32_t  first_seq[DC_MAX_SRC_SHARDS];
+    int32_t  n_seq[DC_MAX_SRC_SHARDS];
+    uint32_t tile_end[DC_MAX_SRC_SHARDS];      // running total; entries from n_seg on repeat the grand total
+    int64_t  gran_base[DC_MAX_SRC_SHARDS + 1];
+    int64_t  tokens[DC_MAX_SRC_SHARDS];
+};
+BackSegs make_back_segs(const SourceDesc& src);
+
+hipError_t launch_records_back(const BackSegs& bs, const ScatterWorkspace& ws, hipStream_t st);
+hipError_t launch_gather_back(const BackSegs& bs, const FieldTable& ft, const ScatterWorkspace& ws, hipStream_t st);
 
 hipError_t launch_scatter(int32_t n_seq, const SourceDesc& src, const int64_t* d_src_tok_off,
                           const int32_t* d_seq_len, const int32_t* d_perm, const FieldTable& ft,

@@ -31,8 +31,7 @@ namespace dc {
 
 constexpr int GATHER_BLOCK = 256;
 constexpr int NSEG = SEG_BATCH + SEG_AHEAD;
-constexpr int GRAN_PER_TILE = GATHER_BLOCK / WAVE;                    // one granule per wave
-constexpr int GATHER_TILE_TOKENS = GRAN_PER_TILE * GATHER_GRAN;
+static_assert(GRAN_PER_TILE == GATHER_BLOCK / WAVE, "one granule per wave");
 constexpr int64_t GATHER_RIDE_MIN_WGS = 8192;                         // ~4 workgroups per wave slot of the chip
 constexpr int32_t LEN_MASK = (1 << LENSH_SHIFT) - 1;
 static_assert(GATHER_GRAN == WAVE * 16, "a wave covers its granule with 1, 2 or 4 chunks per lane");
@@ -256,21 +255,23 @@ __device__ __forceinline__ void boundary_store(gptr_w dst, const BoundaryChunk& 
 
 // The wave's granule (1024 tokens: es chunks per lane) of one tile, served from the granule's
 // record.  `limit` = tokens of the granule that exist in the arena (> 0).
-__device__ __forceinline__ void move_wave_sparse(const FieldDesc& fd, int n_src, int lg, const u32x16& rec,
-                                                 int64_t wave_begin, int32_t limit) {
+// BACK: destination and only source are given (back_dst, back_src) instead of fd's.
+template <bool BACK>
+__device__ __forceinline__ void move_wave_sparse(const FieldDesc& fd, int n_src, char* back_dst, const char* back_src,
+                                                 int lg, const u32x16& rec, int64_t wave_begin, int32_t limit) {
     const int es = 1 << lg;
     const int tpc = 16 >> lg;                              // tokens per 16-byte chunk
     const int tpi = WAVE * tpc;                            // tokens one wave instruction covers
     const int lane = threadIdx.x & (WAVE - 1);
-    gptr_w dst = reinterpret_cast<gptr_w>(reinterpret_cast<uintptr_t>(fd.dst) + (wave_begin << lg));
+    gptr_w dst = reinterpret_cast<gptr_w>(reinterpret_cast<uintptr_t>(BACK ? back_dst : fd.dst) + (wave_begin << lg));
 
     SlotS e[REC_SLOTS];
 #pragma unroll
     for (int k = 0; k < REC_SLOTS; ++k) {
         const int32_t st = (int32_t)rec[4 * k], ls = (int32_t)rec[4 * k + 1];
         const int64_t so = (int64_t)((uint64_t)rec[4 * k + 2] | ((uint64_t)rec[4 * k + 3] << 32));
-        const char* base = fd.src[0];
-        if (n_src > 1) base = fd.src[(ls >> LENSH_SHIFT) & (DC_MAX_SRC_SHARDS - 1)];
+        const char* base = BACK ? back_src : fd.src[0];
+        if (!BACK && n_src > 1) base = fd.src[(ls >> LENSH_SHIFT) & (DC_MAX_SRC_SHARDS - 1)];
         e[k].st = st;
         e[k].en = st + (ls & LEN_MASK);
         e[k].ad = reinterpret_cast<int64_t>(base) + ((so - st) << lg);
@@ -369,21 +370,15 @@ __device__ __forceinline__ void move_wave_sparse(const FieldDesc& fd, int n_src,
 }
 
 // ---------------------------------------------------------------- the kernel
-// One workgroup per tile of GATHER_TILE_TOKENS tokens of one field, field-major.  Waves are short-lived on purpose: a wave that ends right
-// after issuing its stores does not hold its slot until they are acknowledged, which a
-// looping wave would (loads and stores retire through one in-order counter).
-__global__ __launch_bounds__(GATHER_BLOCK) void gather_kernel(GatherArgs a, FieldTable ft) {
+// The tile `tile` of carrier field fc.  BACK = false: the forward direction, fields as the
+// table gives them.  BACK = true: the reverse direction, destination = the field's rollout
+// buffer of segment seg, only source = its training arena.
+template <bool BACK>
+__device__ __forceinline__ void move_tile(const GatherArgs& a, const FieldTable& ft, uint32_t tile, uint32_t fc, int seg) {
     __shared__ SegLds sg;
     __shared__ const char* src[DC_MAX_SRC_SHARDS];
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / WAVE));
     const int N = a.n_seq;
-    // The grid walks the "carrier" fields, field after field (the 4-byte fields if there are
-    // any, else every field).  Narrower fields ride along: rider r is moved by the waves of
-    // carrier r mod n_carriers, right after their own data and from the same granule record.
-    // A wave of a narrow field has only 1 or 2 KB in flight; as a workgroup of its own it
-    // would hold a wave slot as long as a 4 KB one.
-    const uint32_t tile = blockIdx.x % a.tiles;
-    const uint32_t fc = blockIdx.x / a.tiles;              // carrier
     const int64_t tile_begin = (int64_t)tile * GATHER_TILE_TOKENS;
     const int64_t g0 = (int64_t)tile * GRAN_PER_TILE;
 
@@ -406,15 +401,69 @@ __global__ __launch_bounds__(GATHER_BLOCK) void gather_kernel(GatherArgs a, Fiel
         // f = fc, then the riders n_carriers + fc, n_carriers + fc + n_carriers, ...
         const FieldDesc& fd = ft.f[f];
         const int lg = fd.elem_bytes == 4 ? 2 : (fd.elem_bytes == 2 ? 1 : 0);
+        char* back_dst = BACK ? const_cast<char*>(fd.src[seg]) : nullptr;
+        const char* back_src = BACK ? fd.dst : nullptr;
         if (!dense) {
-            if (wave_limit > 0) move_wave_sparse(fd, ft.n_src, lg, rec, tile_begin + w * GATHER_GRAN, wave_limit);
+            if (wave_limit > 0)
+                move_wave_sparse<BACK>(fd, ft.n_src, back_dst, back_src, lg, rec, tile_begin + w * GATHER_GRAN, wave_limit);
         } else {
             __syncthreads();                               // the previous field's readers of src[] and sg are done
-            if (threadIdx.x < DC_MAX_SRC_SHARDS) src[threadIdx.x] = fd.src[threadIdx.x];
+            if (threadIdx.x < DC_MAX_SRC_SHARDS) src[threadIdx.x] = BACK ? back_src : fd.src[threadIdx.x];
             __syncthreads();
-            move_tile_dense(a, sg, src, lg, fd.dst, first, last, tile_begin, limit);
+            move_tile_dense(a, sg, src, lg, BACK ? back_dst : fd.dst, first, last, tile_begin, limit);
         }
     }
+}
+
+// One workgroup per tile of GATHER_TILE_TOKENS tokens of one field, field-major.  Waves are short-lived on purpose: a wave that ends right
+// after issuing its stores does not hold its slot until they are acknowledged, which a
+// looping wave would (loads and stores retire through one in-order counter).
+__global__ __launch_bounds__(GATHER_BLOCK) void gather_kernel(GatherArgs a, FieldTable ft) {
+    // The grid walks the "carrier" fields, field after field (the 4-byte fields if there are
+    // any, else every field).  Narrower fields ride along: rider r is moved by the waves of
+    // carrier r mod n_carriers, right after their own data and from the same granule record.
+    // A wave of a narrow field has only 1 or 2 KB in flight; as a workgroup of its own it
+    // would hold a wave slot as long as a 4 KB one.
+    move_tile<false>(a, ft, blockIdx.x % a.tiles, blockIdx.x / a.tiles, 0);
+}
+
+// Reverse direction: the same grid over the tiles of all rollout buffers, one behind the other.
+// a.dst_tok_off, a.slot_* and the granule tables arrive as the arrays of all segments; the
+// workgroup narrows them to its segment's part.
+__global__ __launch_bounds__(GATHER_BLOCK) void gather_back_kernel(GatherArgs a, FieldTable ft, BackSegs bs) {
+    const uint32_t t = blockIdx.x % a.tiles;
+    int seg = 0;
+#pragma unroll
+    for (int q = 0; q + 1 < DC_MAX_SRC_SHARDS; ++q) seg += t >= bs.tile_end[q] ? 1 : 0;   // t < tile_end[last]
+    const uint32_t tile = t - (seg > 0 ? bs.tile_end[seg - 1] : 0u);
+    const int first_seq = bs.first_seq[seg];
+    a.n_seq = bs.n_seq[seg];
+    a.capacity = bs.tokens[seg];
+    a.dst_tok_off += first_seq + seg;
+    a.slot_src_off += first_seq;
+    a.slot_len += first_seq;
+    a.slot_shard += first_seq;
+    a.gran_first += bs.gran_base[seg];
+    a.gran_rec += bs.gran_base[seg];
+    move_tile<true>(a, ft, tile, blockIdx.x / a.tiles, seg);
+}
+
+// Field table with the 4-byte fields first (they carry, the others ride) and the grid's shape.
+static void order_fields(const FieldTable& ft, int64_t tiles, FieldTable* sorted, GatherArgs* a) {
+    *sorted = ft;
+    int n = 0, n_wide = 0;
+    for (int pass = 0; pass < 2; ++pass)
+        for (int f = 0; f < ft.n_fields; ++f)
+            if ((ft.f[f].elem_bytes == 4) == (pass == 0)) {
+                sorted->f[n++] = ft.f[f];
+                if (pass == 0) n_wide = n;
+            }
+    // riding pays when the carriers alone give the chip several rounds of workgroups; a small
+    // batch needs every workgroup it can get
+    const bool ride = n_wide > 0 && tiles * n_wide >= GATHER_RIDE_MIN_WGS;
+    a->n_carriers = (uint32_t)(ride ? n_wide : ft.n_fields);
+    a->n_riders = (uint32_t)ft.n_fields - a->n_carriers;
+    a->tiles = (uint32_t)tiles;
 }
 
 hipError_t launch_gather(int32_t n_seq, const FieldTable& ft, int64_t dst_capacity,
@@ -432,22 +481,34 @@ hipError_t launch_gather(int32_t n_seq, const FieldTable& ft, int64_t dst_capaci
     const int64_t tiles = (dst_capacity + GATHER_TILE_TOKENS - 1) / GATHER_TILE_TOKENS;
     if (tiles * ft.n_fields > 0x7FFFFFFFLL || tiles * GRAN_PER_TILE + GRAN_PER_TILE + 1 > ws.n_gran)
         return hipErrorInvalidValue;
-    // field table with the 4-byte fields first: they carry, the others ride
-    FieldTable sorted = ft;
-    int n = 0, n_wide = 0;
-    for (int pass = 0; pass < 2; ++pass)
-        for (int f = 0; f < ft.n_fields; ++f)
-            if ((ft.f[f].elem_bytes == 4) == (pass == 0)) {
-                sorted.f[n++] = ft.f[f];
-                if (pass == 0) n_wide = n;
-            }
-    // riding pays when the carriers alone give the chip several rounds of workgroups; a small
-    // batch needs every workgroup it can get
-    const bool ride = n_wide > 0 && tiles * n_wide >= GATHER_RIDE_MIN_WGS;
-    a.n_carriers = (uint32_t)(ride ? n_wide : ft.n_fields);
-    a.n_riders = (uint32_t)ft.n_fields - a.n_carriers;
-    a.tiles = (uint32_t)tiles;
+    FieldTable sorted;
+    order_fields(ft, tiles, &sorted, &a);
     hipLaunchKernelGGL(gather_kernel, dim3((unsigned)(tiles * a.n_carriers)), dim3(GATHER_BLOCK), 0, st, a, sorted);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_back(const BackSegs& bs, const FieldTable& ft, const ScatterWorkspace& ws, hipStream_t st) {
+    const int64_t tiles = bs.tile_end[DC_MAX_SRC_SHARDS - 1];
+    if (ft.n_fields == 0 || tiles == 0) return hipSuccess;
+    if (tiles * ft.n_fields > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+    for (int s = 0; s < DC_MAX_SRC_SHARDS; ++s) {           // every segment's tables hold its tiles plus the padding
+        const int64_t seg_tiles = bs.tile_end[s] - (s > 0 ? bs.tile_end[s - 1] : 0u);
+        if (seg_tiles > 0 && seg_tiles * GRAN_PER_TILE + GRAN_PER_TILE + 1 > bs.gran_base[s + 1] - bs.gran_base[s])
+            return hipErrorInvalidValue;
+    }
+    if (bs.gran_base[DC_MAX_SRC_SHARDS] > ws.n_gran_all) return hipErrorInvalidValue;
+    GatherArgs a;
+    a.n_seq = 0;
+    a.capacity = 0;
+    a.dst_tok_off = ws.r_dst_off;
+    a.slot_src_off = ws.r_src_off;
+    a.slot_len = ws.r_len;
+    a.slot_shard = ws.r_shard;
+    a.gran_first = ws.gran_first;
+    a.gran_rec = ws.gran_rec;
+    FieldTable sorted;
+    order_fields(ft, tiles, &sorted, &a);
+    hipLaunchKernelGGL(gather_back_kernel, dim3((unsigned)(tiles * a.n_carriers)), dim3(GATHER_BLOCK), 0, st, a, sorted, bs);
     return hipGetLastError();
 }
 

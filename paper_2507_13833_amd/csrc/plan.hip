@@ -279,21 +279,22 @@ struct RecArgs {
     GranRec*       gran_rec;
 };
 
-__global__ __launch_bounds__(REC_BLOCK) void records_kernel(RecArgs a) {
-    const int64_t g = (int64_t)blockIdx.x * REC_BLOCK + threadIdx.x;
-    if (g >= a.n_gran) return;
-    const int N = a.n_seq;
+// Tables of granule g of a token axis holding N slots (starts[N+1], the last entry its end);
+// usable = false leaves the granule empty.
+__device__ __forceinline__ void build_record(int N, bool usable, const int64_t* starts, const int64_t* slot_src_off,
+                                             const int32_t* slot_len, const int32_t* slot_shard, int64_t g,
+                                             int32_t* first_out, GranRec* rec_out) {
     const int64_t begin = g * GATHER_GRAN;
     int first = N;
-    if (*a.plan_ok && N > 0) {
+    if (usable && N > 0) {
         // first j whose successor starts after `begin` ...
         int lo = 0, hi = N;
         while (lo < hi) {
             const int mid = (lo + hi) >> 1;
-            if (a.dst_tok_off[mid + 1] > begin) hi = mid; else lo = mid + 1;
+            if (starts[mid + 1] > begin) hi = mid; else lo = mid + 1;
         }
         // ... and if `begin` lies in the padding behind that slot (or the slot is empty), the next one
-        while (lo < N && a.dst_tok_off[lo] + a.slot_len[lo] <= begin) ++lo;
+        while (lo < N && starts[lo] + slot_len[lo] <= begin) ++lo;
         first = lo;
     }
     GranRec rec;
@@ -302,22 +303,46 @@ __global__ __launch_bounds__(REC_BLOCK) void records_kernel(RecArgs a) {
         rec.e[r].start = REL_FAR; rec.e[r].lensh = 0; rec.e[r].src_off = 0;
         const int j = first + r;
         if (j < N) {
-            const int64_t d = a.dst_tok_off[j] - begin;
+            const int64_t d = starts[j] - begin;
             if (d < GATHER_GRAN) {
                 rec.e[r].start = (int32_t)max(d, (int64_t)-REL_FAR);
-                rec.e[r].lensh = a.slot_len[j] | (a.slot_shard[j] << LENSH_SHIFT);
-                rec.e[r].src_off = a.slot_src_off[j];
+                rec.e[r].lensh = slot_len[j] | (slot_shard[j] << LENSH_SHIFT);
+                rec.e[r].src_off = slot_src_off[j];
             }
         }
     }
     // a further slot that starts inside the granule: the record does not hold them all
-    if (first + REC_SLOTS < N && a.dst_tok_off[first + REC_SLOTS] - begin < GATHER_GRAN)
+    if (first + REC_SLOTS < N && starts[first + REC_SLOTS] - begin < GATHER_GRAN)
         rec.e[0].lensh |= (int32_t)DENSE_FLAG;
-    a.gran_first[g] = first;
-    u32x4* out = reinterpret_cast<u32x4*>(&a.gran_rec[g]);
+    *first_out = first;
+    u32x4* out = reinterpret_cast<u32x4*>(rec_out);
     const u32x4* in = reinterpret_cast<const u32x4*>(&rec);
 #pragma unroll
     for (int r = 0; r < REC_SLOTS; ++r) out[r] = in[r];
+}
+
+__global__ __launch_bounds__(REC_BLOCK) void records_kernel(RecArgs a) {
+    const int64_t g = (int64_t)blockIdx.x * REC_BLOCK + threadIdx.x;
+    if (g >= a.n_gran) return;
+    build_record(a.n_seq, *a.plan_ok != 0, a.dst_tok_off, a.slot_src_off, a.slot_len, a.slot_shard, g,
+                 a.gran_first + g, a.gran_rec + g);
+}
+
+// The same for the reverse path: the granule tables of every rollout buffer, one behind the
+// other; a.dst_tok_off holds the slot starts of segment s from index first_seq[s] + s on.
+__global__ __launch_bounds__(REC_BLOCK) void records_back_kernel(RecArgs a, BackSegs bs) {
+    const int64_t g = (int64_t)blockIdx.x * REC_BLOCK + threadIdx.x;
+    if (g >= a.n_gran) return;
+    int s = 0;
+#pragma unroll
+    for (int q = 1; q < DC_MAX_SRC_SHARDS; ++q) s += (q < bs.n_seg && g >= bs.gran_base[q]) ? 1 : 0;
+    int32_t first_seq = bs.first_seq[0], n = bs.n_seq[0];
+    int64_t gb = bs.gran_base[0];
+#pragma unroll
+    for (int q = 1; q < DC_MAX_SRC_SHARDS; ++q)
+        if (s == q) { first_seq = bs.first_seq[q]; n = bs.n_seq[q]; gb = bs.gran_base[q]; }
+    build_record(n, true, a.dst_tok_off + first_seq + s, a.slot_src_off + first_seq, a.slot_len + first_seq,
+                 a.slot_shard + first_seq, g - gb, a.gran_first + g, a.gran_rec + g);
 }
 
 hipError_t launch_plan(const dc_params& prm, const SourceDesc& src, const int64_t* d_src_tok_off,
@@ -351,6 +376,17 @@ hipError_t launch_records(int32_t n_seq, const int64_t* d_dst_tok_off, const Wor
     r.slot_src_off = ws.slot_src_off; r.slot_len = ws.slot_len; r.slot_shard = ws.slot_shard;
     r.plan_ok = ws.plan_ok; r.gran_first = ws.gran_first; r.gran_rec = ws.gran_rec;
     hipLaunchKernelGGL(records_kernel, dim3((unsigned)((ws.n_gran + REC_BLOCK - 1) / REC_BLOCK)), dim3(REC_BLOCK), 0, st, r);
+    return hipGetLastError();
+}
+
+hipError_t launch_records_back(const BackSegs& bs, const ScatterWorkspace& ws, hipStream_t st) {
+    RecArgs r;
+    r.n_seq = 0; r.n_gran = ws.n_gran_all; r.dst_tok_off = ws.r_dst_off;
+    r.slot_src_off = ws.r_src_off; r.slot_len = ws.r_len; r.slot_shard = ws.r_shard;
+    r.plan_ok = nullptr; r.gran_first = ws.gran_first; r.gran_rec = ws.gran_rec;
+    if (ws.n_gran_all <= 0) return hipSuccess;
+    hipLaunchKernelGGL(records_back_kernel, dim3((unsigned)((ws.n_gran_all + REC_BLOCK - 1) / REC_BLOCK)), dim3(REC_BLOCK),
+                       0, st, r, bs);
     return hipGetLastError();
 }
 

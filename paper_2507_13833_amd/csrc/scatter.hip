@@ -7,10 +7,10 @@
 // costs twice what random reads cost.  Instead the rollout layout is treated as the
 // DESTINATION of a gather: sequence i of rollout shard s is "slot" i of that shard, it starts
 // at its rollout offset and comes from element dst_tok_off[slot of i] of the training arena.
-// Two small kernels write those per-sequence descriptors, records_kernel builds the granule
-// tables of every rollout buffer's token axis, and gather_kernel moves the data: linear,
-// aligned 16-byte stores into the rollout buffers, one (mis)aligned load per chunk from the
-// arena.
+// Two small kernels write those per-sequence descriptors, one launch builds the granule tables
+// of every rollout buffer's token axis, and one launch of the gather's tile mover (the rollout
+// buffers being destination segments of one grid) moves the data: linear, aligned 16-byte
+// stores into the rollout buffers, one (mis)aligned load per chunk from the arena.
 #include "dc_device.h"
 #include "dc_internal.h"
 
@@ -29,7 +29,6 @@ struct ScatArgs {
     int64_t*       r_src_off;
     int32_t*       r_len;
     int32_t*       r_shard;
-    int32_t*       ok;
     int32_t*       status;
 };
 
@@ -52,7 +51,6 @@ __device__ __forceinline__ int64_t shard_tokens(const SourceDesc& sd, int sh) {
 // move yet; one lane per rollout shard: the end of the buffer behind its last sequence.
 __global__ __launch_bounds__(SCAT_BLOCK) void scatter_init_kernel(ScatArgs a, SourceDesc sd) {
     const int i = blockIdx.x * SCAT_BLOCK + threadIdx.x;
-    if (i == 0) *a.ok = 1;
     if (i < sd.n_src) a.r_dst_off[sd.seq_off[i + 1] + i] = sd.tokens[i];
     if (i >= a.n_seq) return;
     const int sh = rollout_shard(sd, i);
@@ -84,6 +82,28 @@ __global__ __launch_bounds__(SCAT_BLOCK) void scatter_slots_kernel(ScatArgs a, S
     a.r_len[i] = ln;
 }
 
+BackSegs make_back_segs(const SourceDesc& src) {
+    BackSegs b;
+    b.n_seg = src.n_src;
+    uint32_t tiles = 0;
+    int64_t gran = 0;
+    for (int s = 0; s < DC_MAX_SRC_SHARDS; ++s) {
+        const bool live = s < src.n_src && src.seq_off[s + 1] > src.seq_off[s] && src.tokens[s] > 0;
+        b.first_seq[s] = s < src.n_src ? src.seq_off[s] : 0;
+        b.n_seq[s] = live ? src.seq_off[s + 1] - src.seq_off[s] : 0;
+        b.tokens[s] = live ? src.tokens[s] : 0;
+        b.gran_base[s] = gran;
+        if (live) {
+            tiles += (uint32_t)((src.tokens[s] + GATHER_TILE_TOKENS - 1) / GATHER_TILE_TOKENS);
+            // whole tiles plus the padding the tile mover's table loads need; a multiple of 4 entries
+            gran += ((src.tokens[s] + GATHER_GRAN - 1) / GATHER_GRAN + GRAN_TABLE_PAD + 3) / 4 * 4;
+        }
+        b.tile_end[s] = tiles;
+    }
+    b.gran_base[DC_MAX_SRC_SHARDS] = gran;
+    return b;
+}
+
 ScatterWorkspace carve_scatter_workspace(void* base, int32_t n_seq, const SourceDesc& src) {
     auto round_up = [](size_t x, size_t a) { return (x + a - 1) / a * a; };
     ScatterWorkspace w;
@@ -94,14 +114,9 @@ ScatterWorkspace carve_scatter_workspace(void* base, int32_t n_seq, const Source
     w.r_src_off = reinterpret_cast<int64_t*>(p + off); off += round_up(n * sizeof(int64_t), 256);
     w.r_len = reinterpret_cast<int32_t*>(p + off);     off += round_up(n * sizeof(int32_t), 256);
     w.r_shard = reinterpret_cast<int32_t*>(p + off);   off += round_up(n * sizeof(int32_t), 256);
-    w.ok = reinterpret_cast<int32_t*>(p + off);        off += 256;
-    for (int s = 0; s < DC_MAX_SRC_SHARDS; ++s) {
-        w.n_gran[s] = 0; w.gran_first[s] = nullptr; w.gran_rec[s] = nullptr;
-        if (s >= src.n_src) continue;
-        w.n_gran[s] = (src.tokens[s] + GATHER_GRAN - 1) / GATHER_GRAN + GRAN_TABLE_PAD;
-        w.gran_first[s] = reinterpret_cast<int32_t*>(p + off); off += round_up((size_t)w.n_gran[s] * sizeof(int32_t), 256);
-        w.gran_rec[s] = reinterpret_cast<GranRec*>(p + off);   off += round_up((size_t)w.n_gran[s] * sizeof(GranRec), 256);
-    }
+    w.n_gran_all = make_back_segs(src).gran_base[DC_MAX_SRC_SHARDS];
+    w.gran_first = reinterpret_cast<int32_t*>(p + off); off += round_up((size_t)w.n_gran_all * sizeof(int32_t), 256);
+    w.gran_rec = reinterpret_cast<GranRec*>(p + off);   off += round_up((size_t)w.n_gran_all * sizeof(GranRec), 256);
     w.bytes = off + 256;
     return w;
 }
@@ -114,7 +129,7 @@ hipError_t launch_scatter(int32_t n_seq, const SourceDesc& src, const int64_t* d
     ScatArgs a;
     a.n_seq = n_seq; a.capacity = dst_capacity; a.src_tok_off = d_src_tok_off; a.seq_len = d_seq_len;
     a.perm = d_perm; a.dst_tok_off = d_dst_tok_off; a.r_dst_off = ws.r_dst_off; a.r_src_off = ws.r_src_off;
-    a.r_len = ws.r_len; a.r_shard = ws.r_shard; a.ok = ws.ok; a.status = d_status;
+    a.r_len = ws.r_len; a.r_shard = ws.r_shard; a.status = d_status;
     const unsigned grid = (unsigned)((n_seq + SCAT_BLOCK - 1) / SCAT_BLOCK);
     hipLaunchKernelGGL(scatter_init_kernel, dim3(grid), dim3(SCAT_BLOCK), 0, st, a, src);
     hipError_t e = hipGetLastError();
@@ -122,38 +137,10 @@ hipError_t launch_scatter(int32_t n_seq, const SourceDesc& src, const int64_t* d
     hipLaunchKernelGGL(scatter_slots_kernel, dim3(grid), dim3(SCAT_BLOCK), 0, st, a, src);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-
-    for (int s = 0; s < src.n_src; ++s) {
-        const int32_t first = src.seq_off[s], count = src.seq_off[s + 1] - src.seq_off[s];
-        if (count <= 0 || src.tokens[s] <= 0) continue;
-        // the rollout buffer of shard s as the destination of a gather from the arena
-        Workspace v;
-        v.slot_src_off = ws.r_src_off + first;
-        v.slot_len = ws.r_len + first;
-        v.slot_shard = ws.r_shard + first;
-        v.gran_first = ws.gran_first[s];
-        v.gran_rec = ws.gran_rec[s];
-        v.plan_ok = ws.ok;
-        v.n_gran = ws.n_gran[s];
-        v.bytes = 0;
-        const int64_t* starts = ws.r_dst_off + first + s;               // count + 1 entries
-        e = launch_records(count, starts, v, st);
-        if (e != hipSuccess) return e;
-        FieldTable back;
-        back.n_fields = ft.n_fields;
-        back.n_src = 1;
-        for (int f = 0; f < DC_MAX_FIELDS; ++f) {
-            back.f[f].dst = nullptr; back.f[f].elem_bytes = 1; back.f[f].pad = 0;
-            for (int q = 0; q < DC_MAX_SRC_SHARDS; ++q) back.f[f].src[q] = nullptr;
-            if (f >= ft.n_fields) continue;
-            back.f[f].dst = const_cast<char*>(ft.f[f].src[s]);          // rollout buffer: written
-            back.f[f].src[0] = ft.f[f].dst;                             // training arena: read
-            back.f[f].elem_bytes = ft.f[f].elem_bytes;
-        }
-        e = launch_gather(count, back, src.tokens[s], starts, v, st);
-        if (e != hipSuccess) return e;
-    }
-    return hipSuccess;
+    const BackSegs bs = make_back_segs(src);
+    e = launch_records_back(bs, ws, st);
+    if (e != hipSuccess) return e;
+    return launch_gather_back(bs, ft, ws, st);
 }
 
 }  // namespace dc
