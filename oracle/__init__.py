@@ -11,7 +11,7 @@ import ctypes as C
 import os
 import subprocess
 from dataclasses import dataclass
-from typing import List, Sequence
+from typing import Optional, List, Sequence
 
 import numpy as np
 
@@ -45,7 +45,7 @@ def _load():
     if _lib is None:
         _lib = C.CDLL(build())
         for name in ("dco_balance", "dco_group_advantage", "dco_adv_broadcast", "dco_plan", "dco_gather",
-                     "dco_scatter"):
+                     "dco_scatter", "dco_gae"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -107,6 +107,31 @@ def adv_broadcast(adv_seq, seq_len, src_tok_off, src_shard_seq_off, src_shard_to
                                        C.c_int32(int(src_shard_seq_off[s + 1])), _p(m), _p(out)))
         outs.append(out)
     return outs
+
+
+def gae(reward, seq_len, src_tok_off, src_shard_seq_off, src_shard_tokens, value_shards: Sequence[np.ndarray],
+        mask_shards: Sequence[np.ndarray], gamma: float, lam: float, kl_coef: float = 0.0,
+        logp_shards: Optional[Sequence[np.ndarray]] = None, ref_shards: Optional[Sequence[np.ndarray]] = None):
+    """Generalized advantage estimation over the loss-bearing tokens of every sequence, rollout
+    layout.  Returns (adv_tok shards, return shards), float32."""
+    r = np.ascontiguousarray(reward, dtype=np.float32)
+    S = _i32(seq_len)
+    sto = np.ascontiguousarray(src_tok_off, dtype=np.int64)
+    advs, rets = [], []
+    for s, (v, m) in enumerate(zip(value_shards, mask_shards)):
+        v = np.ascontiguousarray(v, dtype=np.float32)
+        m = np.ascontiguousarray(m, dtype=np.uint8)
+        lp = np.ascontiguousarray(logp_shards[s], dtype=np.float32) if logp_shards is not None else None
+        rf = np.ascontiguousarray(ref_shards[s], dtype=np.float32) if ref_shards is not None else None
+        n = int(src_shard_tokens[s])
+        adv, ret = np.zeros(n, np.float32), np.zeros(n, np.float32)
+        _chk(_load().dco_gae(_p(r), _p(S), _p(sto), C.c_int32(int(src_shard_seq_off[s])),
+                             C.c_int32(int(src_shard_seq_off[s + 1])), _p(v), _p(m),
+                             _p(lp) if lp is not None else None, _p(rf) if rf is not None else None,
+                             C.c_double(gamma), C.c_double(lam), C.c_double(kl_coef), _p(adv), _p(ret)))
+        advs.append(adv)
+        rets.append(ret)
+    return advs, rets
 
 
 @dataclass

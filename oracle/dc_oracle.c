@@ -17,6 +17,11 @@
  *                        (App. B, Table 2 "advantage") but prints no formula;
  *                        the readings taken are listed at each function.
  *   dco_adv_broadcast    per-token advantage in the rollout layout.
+ *   dco_gae              the PPO counterpart of the two above (Sec. 7.1 evaluates
+ *                        PPO with a critic; the paper prints no formula):
+ *                        generalized advantage estimation, Schulman et al. 2016
+ *                        (arXiv 1506.02438) eqs. 11-16, over the loss-bearing
+ *                        tokens of each sequence; float64, rounded once.
  *   dco_plan             packed training layout: shard token offsets,
  *                        next-fit micro-batches under a token budget,
  *                        per-micro-batch cu_seqlens.  (Sec. 6 "Distributed
@@ -202,6 +207,46 @@ int dco_adv_broadcast(const float* adv_seq, const int32_t* S, const int64_t* src
         int64_t base = src_tok_off[i];
         for (int32_t t = 0; t < S[i]; ++t)
             adv_tok[base + t] = mask[base + t] ? adv_seq[i] : 0.0f;
+    }
+    return DCO_OK;
+}
+
+/*
+ * Generalized advantage estimation inside ONE rollout shard holding sequences
+ * [seq_begin, seq_end).  Let t_1 < ... < t_m be the loss-bearing tokens (mask != 0)
+ * of sequence i; tokens without loss are transparent (the recursion steps over them).
+ *   r_k     = -kl_coef * (logp[t_k] - ref_logp[t_k])     (per-token KL penalty, if kl_coef != 0)
+ *             + reward[i] if k = m                       (the sequence's score sits on its last token)
+ *   delta_k = r_k + gamma * V[t_{k+1}] - V[t_k],  V[t_{m+1}] = 0      (TD residual, eq. 11 / 16)
+ *   A_k     = delta_k + gamma * lambda * A_{k+1}, A_{m+1} = 0         (= sum_l (gamma lambda)^l delta_{k+l}, eq. 16)
+ *   ret_k   = A_k + V[t_k]                                            (value target)
+ * adv_tok / ret_tok get A_k / ret_k at t_k and +0.0 at every other token of the
+ * sequence.  All arithmetic in float64, each output rounded once to float32.
+ * logp / ref_logp may be NULL when kl_coef == 0.
+ */
+int dco_gae(const float* reward, const int32_t* S, const int64_t* src_tok_off,
+            int32_t seq_begin, int32_t seq_end, const float* value, const uint8_t* mask,
+            const float* logp, const float* ref_logp, double gamma, double lambda, double kl_coef,
+            float* adv_tok, float* ret_tok) {
+    if (kl_coef != 0.0 && (!logp || !ref_logp)) return DCO_BAD_ARG;
+    for (int32_t i = seq_begin; i < seq_end; ++i) {
+        const int64_t base = src_tok_off[i];
+        double next_A = 0.0, next_V = 0.0;
+        int seen_last = 0;
+        for (int32_t t = S[i] - 1; t >= 0; --t) {
+            const int64_t x = base + t;
+            if (!mask[x]) { adv_tok[x] = 0.0f; ret_tok[x] = 0.0f; continue; }
+            double r = 0.0;
+            if (kl_coef != 0.0) r = -kl_coef * ((double)logp[x] - (double)ref_logp[x]);
+            if (!seen_last) { r += (double)reward[i]; seen_last = 1; }
+            const double V = (double)value[x];
+            const double delta = r + gamma * next_V - V;
+            const double A = delta + gamma * lambda * next_A;
+            adv_tok[x] = (float)A;
+            ret_tok[x] = (float)(A + V);
+            next_A = A;
+            next_V = V;
+        }
     }
     return DCO_OK;
 }
