@@ -153,6 +153,29 @@ dc_status dc_group_advantage(const dc_params* prm, const dc_source* src, const i
                              float* const* adv_tok_src_base, int32_t* d_status, void* hip_stream);
 
 /*
+ * Generalized advantage estimation (Schulman et al. 2016, arXiv 1506.02438, eqs. 11-16): the
+ * advantage stage of PPO (Sec. 7.1 evaluates PPO with a critic; App. B Table 2 "advantage"), per
+ * token, in the rollout layout.  With t_1 < ... < t_m the tokens of sequence i whose mask byte is
+ * non-zero (tokens without loss are stepped over):
+ *   r_k     = -kl_coef * (logp[t_k] - ref_logp[t_k])  + (k == m ? d_reward[i] : 0)
+ *   delta_k = r_k + gamma * V[t_{k+1}] - V[t_k],   V[t_{m+1}] = 0
+ *   A_k     = delta_k + gamma * lambda * A_{k+1},  A_{m+1} = 0;   ret_k = A_k + V[t_k]
+ * evaluated in float64 and rounded once to float32.  adv_tok / ret_tok get A_k / ret_k at t_k and
+ * +0.0 at every other token of the sequence; elements that belong to no sequence are left alone.
+ * value_src_base[s] (float32), mask_src_base[s] (uint8), adv_tok_src_base[s], ret_tok_src_base[s]
+ * (float32, written): host arrays of src->n_src_shards device pointers to 16-byte aligned buffers
+ * of src->shard_tokens[s] elements.  logp_src_base / ref_logp_src_base (float32, same shape) are
+ * read only when kl_coef != 0 and may be NULL otherwise.
+ * Device errors: BAD_LAYOUT, ZERO_LENGTH_SEQ.
+ */
+dc_status dc_gae(const dc_params* prm, const dc_source* src, const int32_t* d_seq_len, const float* d_reward,
+                 const float* const* value_src_base, const uint8_t* const* mask_src_base,
+                 const float* const* logp_src_base, const float* const* ref_logp_src_base,
+                 double gamma, double lambda, double kl_coef,
+                 float* const* adv_tok_src_base, float* const* ret_tok_src_base,
+                 int32_t* d_status, void* hip_stream);
+
+/*
  * Plan of the packed training layout (see "Layouts").  Outputs (device):
  * d_dst_tok_off[N+1] (last = d_shard_tok_off[P]), d_shard_tok_off[P+1], d_shard_mb_off[P+1],
  * d_mb_seq_off[N+1] (first M+1 entries valid), d_cu_seqlens[2N] (first N+M valid), d_n_mb[1] = M.

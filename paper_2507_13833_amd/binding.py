@@ -31,7 +31,7 @@ DC_ERR_OVERFLOW = 8
 DC_ERR_BAD_LAYOUT = 9
 
 EXPORTS = ("dc_workspace_bytes", "dc_balance", "dc_group_advantage", "dc_plan", "dc_gather",
-           "dc_repack", "dc_scatter_workspace_bytes", "dc_scatter", "dc_strerror")
+           "dc_repack", "dc_scatter_workspace_bytes", "dc_scatter", "dc_gae", "dc_strerror")
 
 
 class dc_params(C.Structure):
@@ -93,6 +93,10 @@ def load() -> C.CDLL:
         lib.dc_scatter.restype = C.c_int
         lib.dc_scatter.argtypes = [C.POINTER(dc_params), C.POINTER(dc_source), vp, vp, C.POINTER(dc_field), C.c_int32,
                                    C.c_int64, vp, vp, C.c_size_t, vp, vp]
+        lib.dc_gae.restype = C.c_int
+        lib.dc_gae.argtypes = [C.POINTER(dc_params), C.POINTER(dc_source), vp, vp, C.POINTER(vp), C.POINTER(vp),
+                               C.POINTER(vp), C.POINTER(vp), C.c_double, C.c_double, C.c_double,
+                               C.POINTER(vp), C.POINTER(vp), vp, vp]
         _lib = lib
     return _lib
 
@@ -227,3 +231,15 @@ def dc_scatter(prm: dc_params, src: Source, d_seq_len, d_perm, fields: Fields, d
                              int(dst_capacity_tokens), _ptr(d_dst_tok_off), _ptr(d_ws), int(ws_bytes),
                              _ptr(d_status), _stream(stream)),
            "dc_scatter")
+
+
+def dc_gae(prm: dc_params, src: Source, d_seq_len, d_reward, value_src: Sequence, mask_src: Sequence,
+           logp_src: Optional[Sequence], ref_src: Optional[Sequence], gamma: float, lam: float, kl_coef: float,
+           adv_tok_src: Sequence, ret_tok_src: Sequence, d_status, stream=None) -> None:
+    def arr(x):
+        return C.cast(_ptr_array(x), C.POINTER(C.c_void_p)) if x is not None else None
+    keep = [arr(value_src), arr(mask_src), arr(logp_src), arr(ref_src), arr(adv_tok_src), arr(ret_tok_src)]
+    _check(load().dc_gae(C.byref(prm), C.byref(src.struct), _ptr(d_seq_len), _ptr(d_reward), keep[0], keep[1],
+                         keep[2], keep[3], float(gamma), float(lam), float(kl_coef), keep[4], keep[5],
+                         _ptr(d_status), _stream(stream)),
+           "dc_gae")

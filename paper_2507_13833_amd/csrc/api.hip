@@ -131,6 +131,35 @@ dc_status dc_group_advantage(const dc_params* prm, const dc_source* src, const i
     return e == hipSuccess ? DC_OK : DC_ERR_HIP;
 }
 
+dc_status dc_gae(const dc_params* prm, const dc_source* src, const int32_t* d_seq_len, const float* d_reward,
+                 const float* const* value_src_base, const uint8_t* const* mask_src_base,
+                 const float* const* logp_src_base, const float* const* ref_logp_src_base,
+                 double gamma, double lambda, double kl_coef,
+                 float* const* adv_tok_src_base, float* const* ret_tok_src_base,
+                 int32_t* d_status, void* hip_stream) {
+    dc_status rc = check_params(prm);
+    if (rc != DC_OK) return rc;
+    SourceDesc sd;
+    rc = check_source(prm, src, &sd);
+    if (rc != DC_OK) return rc;
+    if (!(gamma == gamma) || !(lambda == lambda) || !(kl_coef == kl_coef)) return DC_ERR_INVALID_ARG;   // NaN
+    if (!value_src_base || !mask_src_base || !adv_tok_src_base || !ret_tok_src_base) return DC_ERR_INVALID_ARG;
+    if (kl_coef != 0.0 && (!logp_src_base || !ref_logp_src_base)) return DC_ERR_INVALID_ARG;
+    if (prm->n_seq > 0 && (!d_seq_len || !d_reward)) return DC_ERR_INVALID_ARG;
+    for (int s = 0; s < src->n_src_shards; ++s) {
+        if (src->shard_tokens[s] == 0) continue;
+        const void* need[6] = {value_src_base[s], mask_src_base[s], adv_tok_src_base[s], ret_tok_src_base[s],
+                               kl_coef != 0.0 ? logp_src_base[s] : value_src_base[s],
+                               kl_coef != 0.0 ? ref_logp_src_base[s] : value_src_base[s]};
+        for (const void* p : need)
+            if (!p || !aligned16(p)) return DC_ERR_INVALID_ARG;
+    }
+    hipError_t e = launch_gae(prm->n_seq, sd, src->d_src_tok_off, d_seq_len, d_reward, value_src_base, mask_src_base,
+                              logp_src_base, ref_logp_src_base, gamma, lambda, kl_coef, adv_tok_src_base,
+                              ret_tok_src_base, d_status, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? DC_OK : DC_ERR_HIP;
+}
+
 dc_status dc_plan(const dc_params* prm, const dc_source* src, const int32_t* d_seq_len,
                   const int32_t* d_perm, const int32_t* d_shard_seq_off, int64_t dst_capacity_tokens,
                   int64_t* d_dst_tok_off, int64_t* d_shard_tok_off, int32_t* d_shard_mb_off,

@@ -131,4 +131,10 @@ hipError_t launch_scatter(int32_t n_seq, const SourceDesc& src, const int64_t* d
                           int64_t dst_capacity, const int64_t* d_dst_tok_off, const ScatterWorkspace& ws,
                           int32_t* d_status, hipStream_t st);
 
+hipError_t launch_gae(int32_t n_seq, const SourceDesc& src, const int64_t* d_src_tok_off, const int32_t* d_seq_len,
+                      const float* d_reward, const float* const* value_base, const uint8_t* const* mask_base,
+                      const float* const* logp_base, const float* const* ref_base, double gamma, double lambda,
+                      double kl_coef, float* const* adv_base, float* const* ret_base, int32_t* d_status,
+                      hipStream_t st);
+
 }  // namespace dc

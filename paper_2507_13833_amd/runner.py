@@ -150,5 +150,21 @@ class DeviceBatch:
         B.dc_scatter(self.prm, self.source, self.seq_len, self.perm, self.back, self.capacity, self.dst_tok_off,
                      self.sws, self.sws_bytes, self.status)
 
+    def prepare_gae(self) -> None:
+        """Rollout-layout outputs of the PPO advantage stage (needs float32 value and, with the KL
+        penalty, old_logprob / ref_logprob fields)."""
+        self.gae_adv = [torch.full((int(t),), float("nan"), dtype=torch.float32, device=self.dev)
+                        for t in self.w.src_shard_tokens]
+        self.gae_ret = [torch.full((int(t),), float("nan"), dtype=torch.float32, device=self.dev)
+                        for t in self.w.src_shard_tokens]
+
+    def gae(self, gamma: float = 1.0, lam: float = 0.95, kl_coef: float = 0.0, stream=None) -> None:
+        as_f32 = lambda ts: [t.view(torch.float32) for t in ts]
+        B.dc_gae(self.prm, self.source, self.seq_len, self.reward, as_f32(self.src_fields["value"]),
+                 self.src_fields["mask"],
+                 as_f32(self.src_fields["old_logprob"]) if kl_coef != 0.0 else None,
+                 as_f32(self.src_fields["ref_logprob"]) if kl_coef != 0.0 else None,
+                 gamma, lam, kl_coef, self.gae_adv, self.gae_ret, self.status, stream)
+
     def read_status(self) -> int:
         return int(self.status.item())

@@ -326,6 +326,84 @@ def test_scatter_padded_rows_and_errors():
     assert d.read_status() == binding.DC_ERR_OVERFLOW
 
 
+# ---------------------------------------------------------------- PPO advantage stage (GAE)
+GAE_RTOL, GAE_ATOL = 1e-5, 1e-6          # both sides: float64 arithmetic, one rounding to float32
+
+
+def _with_ppo_fields(w, seed=0):
+    """Give a hand-shaped workload the float32 fields the PPO advantage stage reads."""
+    rng = np.random.default_rng(seed)
+    for name, gen in (("value", lambda n: rng.standard_normal(n)),
+                      ("old_logprob", lambda n: -np.abs(rng.standard_normal(n))),
+                      ("ref_logprob", lambda n: -np.abs(rng.standard_normal(n)))):
+        w.fields = [f for f in w.fields if f.name != name]
+        w.fields.append(workloads.Field(name, 4, [gen(int(t)).astype(np.float32) for t in w.src_shard_tokens]))
+    return w
+
+
+def check_gae(w, gamma, lam, kl_coef, label=""):
+    torch, binding, runner = _gpu()
+    print(f"[parity] gae {label or w.name}: N={w.n_seq} T={w.total_tokens} gamma={gamma} lambda={lam} kl={kl_coef}",
+          flush=True)
+    d = runner.DeviceBatch(w)
+    d.prepare_gae()
+    d.gae(gamma, lam, kl_coef)
+    torch.cuda.synchronize()
+    assert d.read_status() == 0
+    f32 = lambda name: [a.view(np.float32) for a in w.field_by_name(name).shards]
+    want_adv, want_ret = oracle.gae(w.reward, w.seq_len, w.src_tok_off, w.src_shard_seq_off, w.src_shard_tokens,
+                                    f32("value"), w.field_by_name("mask").shards, gamma, lam, kl_coef,
+                                    f32("old_logprob") if kl_coef else None, f32("ref_logprob") if kl_coef else None)
+    for s_ in range(w.n_src_shards):
+        inside = np.zeros(int(w.src_shard_tokens[s_]), bool)
+        for i in range(w.src_shard_seq_off[s_], w.src_shard_seq_off[s_ + 1]):
+            inside[w.src_tok_off[i]: w.src_tok_off[i] + w.seq_len[i]] = True
+        m = w.field_by_name("mask").shards[s_] != 0
+        for got_t, want in ((d.gae_adv[s_], want_adv[s_]), (d.gae_ret[s_], want_ret[s_])):
+            got = got_t.cpu().numpy()
+            np.testing.assert_allclose(got[inside], want[inside], rtol=GAE_RTOL, atol=GAE_ATOL)
+            assert not got[inside & ~m].view(np.uint32).any()        # +0.0 exactly where no loss
+            assert np.isnan(got[~inside]).all()                      # elements of no sequence: untouched
+    return d
+
+
+@pytest.mark.parametrize("cfg", [3, 4, 5])
+def test_gae_full_config(cfg):
+    w = workloads.make_workload(cfg)
+    check_gae(w, 1.0, 0.95, 0.0, label=f"config {cfg}")
+    check_gae(w, 0.99, 0.9, 0.05, label=f"config {cfg} with KL penalty")
+
+
+def test_gae_shapes_and_special_cases():
+    rng = np.random.default_rng(41)
+    w = _with_ppo_fields(_custom(rng.integers(1, 9, 8192), 8, 16, 64, n_src=4))
+    check_gae(w, 1.0, 1.0, 0.0, label="lengths 1..8, gamma=lambda=1")
+    check_gae(w, 0.9, 0.0, 0.1, label="lengths 1..8, lambda=0")
+    w = _with_ppo_fields(_custom(rng.integers(1, 3000, 1000), 5, 8, 4096, n_src=2))
+    check_gae(w, 0.97, 0.8, 0.02, label="N=1000")
+    w = _with_ppo_fields(_custom(np.array([255, 256, 257, 1, 513, 4, 3, 1024]), 2, 2, 4096))
+    check_gae(w, 1.0, 0.95, 0.0, label="block-edge lengths")
+    # sequences without any loss-bearing token, and one whose loss-bearing tokens are all in the middle
+    w = _with_ppo_fields(_custom(np.array([300, 700, 64, 1000]), 2, 2, 4096))
+    mk = w.field_by_name("mask").shards[0]
+    mk[:300] = 0
+    mk[300:600] = 0; mk[700:1000] = 0
+    check_gae(w, 0.99, 0.95, 0.0, label="fully and partly masked sequences")
+
+
+def test_gae_padded_rows():
+    rng = np.random.default_rng(43)
+    N, row = 512, 700
+    lens = rng.integers(1, row + 1, N).astype(np.int32)
+    w = _custom(lens, 8, 8, 4096, n_src=2)
+    per = N // 2
+    w.src_tok_off = ((np.arange(N) % per) * row + rng.integers(0, row - lens + 1)).astype(np.int64)
+    w.src_shard_tokens = np.array([per * row, per * row], np.int64)
+    for f in w.fields:
+        f.shards = [rng.integers(0, 2, per * row).astype(f.shards[0].dtype) for _ in range(2)]
+    check_gae(_with_ppo_fields(w), 1.0, 0.95, 0.01, label="padded rows")
+
+
 # ---------------------------------------------------------------- device-side error reporting
 def test_device_status_codes():
     torch, binding, runner = _gpu()
