@@ -159,6 +159,28 @@ def main() -> int:
                "achieved": gather_bytes / (scatter_ms * 1e-3) / 1e9, "unit": "GB/s",
                "frac": gather_bytes / (scatter_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
+    # PPO advantage stage (dc_gae) on the same batch, where the workload has a value field; outside the timed region
+    ppo = None
+    if "value" in sets[0].src_fields and sets[0].elem_bytes.get("value") == 4:
+        res = {}
+        for tag, klc, bpt_gae in (("no_kl", 0.0, 13), ("kl", 0.05, 21)):
+            tot = 0.0
+            for i in range(6):
+                b = sets[i % len(sets)]
+                if not hasattr(b, "gae_adv"):
+                    b.prepare_gae()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(); b.gae(1.0, 0.95, klc); e1.record()
+                torch.cuda.synchronize()
+                if i >= 2:
+                    tot += e0.elapsed_time(e1)
+            ms = tot / 4
+            res[tag] = {"ms": round(ms, 4), "algorithmic_bytes": bpt_gae * T,
+                        "achieved": bpt_gae * T / (ms * 1e-3) / 1e9, "unit": "GB/s",
+                        "frac": bpt_gae * T / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        assert all(s.read_status() == 0 for s in sets)
+        ppo = {"call": "dc_gae", **res}
+
     traffic = None
     if args.config in TRAFFIC and TRAFFIC[args.config][1] == kernel_digest():
         traffic = TRAFFIC[args.config][0]
@@ -181,6 +203,7 @@ def main() -> int:
                      "algorithmic_bytes_per_launch": gather_bytes, "avg_launch_ms": gather_ms},
         "stages": stage,
         "reverse": reverse,
+        "ppo_advantage": ppo,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
