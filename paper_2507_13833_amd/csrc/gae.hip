@@ -22,8 +22,9 @@
 // Measured rationale: one wave per sequence left the longest sequence (36 K tokens, 141 dependent
 // blocks) running alone for 160 us; anything derived from a loaded mask word at load time makes
 // the wave wait for the loads it has just issued (the prefetch ring keeps the raw words);
-// plain loads with streaming stores beat both all-plain and all-streaming accesses by a third
-// (every line of the value array is touched by two load instructions, 32 bytes apart per lane).
+// with the arrays resident in the last-level cache, plain loads with streaming stores beat both
+// all-plain and all-streaming accesses by a third (every line of the value array is touched by
+// two load instructions, 32 bytes apart per lane); from HBM the three are equal.
 #include "dc_device.h"
 #include "dc_internal.h"
 #include "dc_lanes.h"
@@ -131,7 +132,7 @@ __device__ __forceinline__ double readlane_f64(double v, int src) {
 }
 
 // Iterations whose loads are in flight ahead of the one worked on.
-template <bool KL> constexpr int GAE_AHEAD = 1;
+template <bool KL> constexpr int GAE_AHEAD = 2;
 
 // One workgroup of NW waves per sequence.  An iteration covers NW * 512 tokens, wave 0 the
 // latest 512 of them, lane 0 of a wave its latest 8.  The waves exchange two things through LDS:
