@@ -125,6 +125,46 @@ def test_group_advantage_host_errors(lib):
     assert e.value.code == B.DC_ERR_INVALID_ARG
 
 
+def test_scatter_host_errors(lib):
+    prm = B.make_params(8, 4, 100)
+    src = B.Source([0, 8], [64], FAKE)
+    ws = B.dc_scatter_workspace_bytes(prm, src)
+    assert ws > 0 and ws % 256 == 0
+    ok = B.Fields([([0x2000], 0x3000, 4)])
+    with pytest.raises(B.DcError) as e:                      # workspace too small
+        B.dc_scatter(prm, src, FAKE, FAKE, ok, 64, FAKE, 0x10000, 16, FAKE, stream=0)
+    assert e.value.code == B.DC_ERR_WORKSPACE
+    with pytest.raises(B.DcError) as e:                      # workspace misaligned
+        B.dc_scatter(prm, src, FAKE, FAKE, ok, 64, FAKE, 0x10010, ws, FAKE, stream=0)
+    assert e.value.code == B.DC_ERR_INVALID_ARG
+    with pytest.raises(B.DcError) as e:                      # rollout buffer not 16-byte aligned
+        B.dc_scatter(prm, src, FAKE, FAKE, B.Fields([([0x2008], 0x3000, 2)]), 64, FAKE, 0x10000, ws, FAKE, stream=0)
+    assert e.value.code == B.DC_ERR_INVALID_ARG
+    with pytest.raises(B.DcError) as e:                      # no permutation
+        B.dc_scatter(prm, src, FAKE, None, ok, 64, FAKE, 0x10000, ws, FAKE, stream=0)
+    assert e.value.code == B.DC_ERR_INVALID_ARG
+    # a rollout shard table that does not cover N has no workspace size
+    assert B.dc_scatter_workspace_bytes(prm, B.Source([0, 5], [64], FAKE)) == 0
+
+
+def test_gae_host_errors(lib):
+    prm = B.make_params(8, 4, 100)
+    src = B.Source([0, 8], [64], FAKE)
+    buf = [0x4000]
+    with pytest.raises(B.DcError) as e:                      # KL penalty without the log-prob fields
+        B.dc_gae(prm, src, FAKE, FAKE, buf, buf, None, None, 1.0, 0.95, 0.1, buf, buf, FAKE, stream=0)
+    assert e.value.code == B.DC_ERR_INVALID_ARG
+    with pytest.raises(B.DcError) as e:                      # misaligned output
+        B.dc_gae(prm, src, FAKE, FAKE, buf, buf, None, None, 1.0, 0.95, 0.0, [0x4004], buf, FAKE, stream=0)
+    assert e.value.code == B.DC_ERR_INVALID_ARG
+    with pytest.raises(B.DcError) as e:                      # NaN discount
+        B.dc_gae(prm, src, FAKE, FAKE, buf, buf, None, None, float("nan"), 0.95, 0.0, buf, buf, FAKE, stream=0)
+    assert e.value.code == B.DC_ERR_INVALID_ARG
+    with pytest.raises(B.DcError) as e:                      # no rewards
+        B.dc_gae(prm, src, FAKE, None, buf, buf, None, None, 1.0, 0.95, 0.0, buf, buf, FAKE, stream=0)
+    assert e.value.code == B.DC_ERR_INVALID_ARG
+
+
 def test_product_does_not_reach_the_oracle():
     pkg = os.path.join(ROOT, "paper_2507_13833_amd")
     for dirpath, _, files in os.walk(pkg):

@@ -253,6 +253,37 @@ def test_advantage_ill_conditioned_rewards():
     check_step(w, label="rewards 1000 + k/1024")
 
 
+# ---------------------------------------------------------------- unchanged DP layout: plan in place, move nothing
+def test_identity_plan_describes_the_rollout_layout_in_place():
+    """Next stage with the same DP size (the paper's local-cache case, Sec. 6): no balancing, no gather.
+    dc_plan with the identity permutation and the rollout shards as training shards yields offsets that
+    ARE the packed rollout layout, so cu_seqlens and micro-batches apply to the rollout buffers as they lie."""
+    torch, binding, runner = _gpu()
+    w = workloads.make_workload(4)                                   # 8 packed rollout shards
+    d = runner.DeviceBatch(w)
+    P = w.n_src_shards
+    prm = binding.make_params(w.n_seq, P, w.token_budget)
+    d.perm.copy_(torch.arange(w.n_seq, dtype=torch.int32, device=d.dev))
+    sso = torch.from_numpy(np.asarray(w.src_shard_seq_off, np.int32)).to(d.dev)
+    shard_tok_off = torch.zeros(P + 1, dtype=torch.int64, device=d.dev)
+    shard_mb_off = torch.zeros(P + 1, dtype=torch.int32, device=d.dev)
+    ws_bytes = binding.dc_workspace_bytes(prm, d.capacity)
+    ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=d.dev)
+    binding.dc_plan(prm, d.source, d.seq_len, d.perm, sso, d.capacity, d.dst_tok_off, shard_tok_off, shard_mb_off,
+                    d.mb_seq_off, d.cu_seqlens, d.n_mb, ws, ws_bytes, d.status)
+    torch.cuda.synchronize()
+    assert d.read_status() == 0
+    pl = oracle.plan(w.seq_len, np.arange(w.n_seq, dtype=np.int32), w.src_shard_seq_off, w.token_budget)
+    assert np.array_equal(d.dst_tok_off.cpu().numpy(), pl.dst_tok_off)
+    M = int(d.n_mb.item())
+    assert M == pl.n_mb and np.array_equal(d.cu_seqlens.cpu().numpy()[: w.n_seq + M], pl.cu_seqlens)
+    # offset inside its shard == offset inside its rollout buffer: nothing has to move
+    sto = shard_tok_off.cpu().numpy()
+    shard_of = np.repeat(np.arange(P), np.diff(w.src_shard_seq_off))
+    assert np.array_equal(d.dst_tok_off.cpu().numpy()[:-1] - sto[shard_of], w.src_tok_off)
+    assert np.array_equal(np.diff(sto), w.src_shard_tokens)
+
+
 # ---------------------------------------------------------------- reverse path
 def check_scatter(w, label=""):
     """gather, then scatter the training arenas back: every rollout buffer must equal what the
