@@ -226,6 +226,22 @@ def test_max_sequences():
     check_step(_custom(lens, 16, 64, 8192, n_src=16), label="N=16384 (limit), 16 rollout shards")
 
 
+def test_longest_sequence_and_most_fields():
+    # two sequences of DC_MAX_SEQ_LEN tokens next to tiny ones (LPT keys, 32-bit offsets inside a tile, int64 outside)
+    L = 1 << 24
+    w = _custom(np.array([L, 5, L - 3, 100], np.int32), 2, 2, 1 << 25, fields=("i32", "u8"))
+    check_step(w, label="sequences of 2^24 tokens")
+    # DC_MAX_FIELDS fields in one gather: seven payload fields of mixed widths plus the per-token advantage
+    rng = np.random.default_rng(13)
+    w = _custom(rng.integers(1, 700, 2048), 8, 8, 4096, n_src=2)
+    for k, (eb, dt) in enumerate(((4, np.int32), (2, np.uint16), (1, np.uint8), (4, np.int32))):
+        w.fields.insert(0, workloads.Field(f"extra{k}", eb,
+                                           [rng.integers(0, 200, int(t)).astype(dt) for t in w.src_shard_tokens]))
+    assert len(w.fields) + 1 == 8
+    check_step(w, label="8 fields")
+    check_scatter(w, label="8 fields")
+
+
 def test_long_and_short_sequences_mixed():
     # a big batch (the narrow fields ride on the 4-byte fields' workgroups) whose shards end in
     # runs of very short sequences: tiles with more slots per granule than a record holds sit
