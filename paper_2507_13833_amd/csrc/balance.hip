@@ -18,8 +18,9 @@
 //      Loads of open workers never differ by more than the longest sequence, so
 //      rebasing the keys when the minimum grows keeps them in 32 bits for any
 //      total load;
-//   c) one more stable counting pass keyed by the worker of each step lays the
-//      P_k out one after the other in insertion order.
+//   c) a worker that takes an item notes the item's place inside P_k (its item count before) and
+//      its own id; when all items are placed, a scan of the workers' counts gives the start of
+//      every P_k and one pass writes perm: P_0, P_1, ... each in insertion order.
 #include "dc_device.h"
 #include "dc_lanes.h"
 
@@ -34,7 +35,7 @@ struct BalLds {
     int32_t  keys[DC_MAX_SEQ];            // sequence lengths (sanitised)
     uint16_t idx_a[DC_MAX_SEQ];           // sort ping
     uint16_t idx_b[DC_MAX_SEQ];           // sort pong; after the sort the free one holds the worker of each step
-    uint32_t cnt[256 * BAL_WAVES];        // [digit][wave] counters
+    uint32_t cnt[256 * BAL_WAVES];        // [digit][wave] counters of the sort passes; afterwards the workers' tables
     int32_t  red[2 * BAL_WAVES];
     uint32_t tmp32[16];
 };
@@ -102,9 +103,12 @@ __device__ __forceinline__ void counting_pass(BalLds& L, int N, int rounds, Digi
 }
 
 // The assignment rounds (wave 0 only).  WIDTH = 16, 32 or 64 >= P lanes take part in the sort.
+// step_slot[t] = place of item I[t] inside its worker's partition; shard_of_seq gets the worker
+// of every placed sequence; worker_count[k] = |P_k|.  Returns the number of items placed (N).
 template <int WIDTH>
-__device__ __forceinline__ void lpt_rounds(int N, int P, int C, const int32_t* keys, const uint16_t* sorted,
-                                           uint8_t* step_worker, int64_t* __restrict__ shard_load) {
+__device__ __forceinline__ int lpt_rounds(int N, int P, int C, const int32_t* keys, const uint16_t* sorted,
+                                          uint16_t* step_slot, int32_t* __restrict__ shard_of_seq,
+                                          int32_t* worker_count, int64_t* __restrict__ shard_load) {
     const uint32_t lane = threadIdx.x;
     const uint32_t full = KEY_FULL | lane;
     uint32_t key = ((int)lane < P && C > 0) ? lane : full;
@@ -128,18 +132,24 @@ __device__ __forceinline__ void lpt_rounds(int N, int P, int C, const int32_t* k
         const uint64_t acc = __ballot(valid && sk < pm);
         const int m = (~acc == 0ull) ? WAVE : (__ffsll((long long)~acc) - 1);   // accepted prefix
         if (m == 0) break;                                        // cannot happen: cap * P >= N
-        if ((int)lane < m) step_worker[t] = (uint8_t)(sk & 63u);
-        // back to worker lanes: rank r sends its updated key to lane (sk & 63)
-        const uint32_t recv = (uint32_t)__builtin_amdgcn_ds_permute((int)((sk & 63u) << 2), (int)newk);
+        // back to worker lanes: rank r sends its updated key, its own rank in place of the worker id,
+        // to lane (sk & 63)
+        const uint32_t recv = (uint32_t)__builtin_amdgcn_ds_permute((int)((sk & 63u) << 2), (int)((newk & ~63u) | lane));
         const uint32_t thr = (uint32_t)__builtin_amdgcn_readlane((int)sk, m - 1);
         if (key <= thr) {                                         // my worker is among the m smallest
-            load += (int64_t)((recv - key) >> 6);
+            const uint32_t nk = (recv & ~63u) | lane;
+            const int mine = pos + (int)(recv & 63u);             // the item I took
+            step_slot[mine] = (uint16_t)count;
+            shard_of_seq[sorted[mine]] = (int32_t)lane;
+            load += (int64_t)((nk - key) >> 6);
             count += 1;
-            key = (count == C) ? full : recv;
+            key = (count == C) ? full : nk;
         }
         pos += m;
     }
     if ((int)lane < P) shard_load[lane] = load;
+    worker_count[lane] = count;
+    return pos;
 }
 
 __global__ __launch_bounds__(BAL_BLOCK) void balance_kernel(int32_t N, int32_t P, int32_t C,
@@ -187,26 +197,34 @@ __global__ __launch_bounds__(BAL_BLOCK) void balance_kernel(int32_t N, int32_t P
         uint16_t* t = src; src = dst; dst = t;
     }
     const uint16_t* sorted = src;                                 // I of Algorithm 1
-    uint8_t* step_worker = reinterpret_cast<uint8_t*>(dst);       // worker chosen for I[t]
+    uint16_t* step_slot = dst;                                    // place of I[t] inside its worker's partition
+    int32_t* worker_count = reinterpret_cast<int32_t*>(L.cnt);    // [64] |P_k|, then their exclusive scan
+    int32_t* placed = reinterpret_cast<int32_t*>(L.cnt) + 2 * WAVE;
 
     // ---- b) assignment rounds, wave 0 ----
     if (w == 0) {
-        if (P <= 16) lpt_rounds<16>(N, P, C, L.keys, sorted, step_worker, shard_load);
-        else if (P <= 32) lpt_rounds<32>(N, P, C, L.keys, sorted, step_worker, shard_load);
-        else lpt_rounds<64>(N, P, C, L.keys, sorted, step_worker, shard_load);
+        int n_placed;
+        if (P <= 16) n_placed = lpt_rounds<16>(N, P, C, L.keys, sorted, step_slot, shard_of_seq, worker_count, shard_load);
+        else if (P <= 32) n_placed = lpt_rounds<32>(N, P, C, L.keys, sorted, step_slot, shard_of_seq, worker_count, shard_load);
+        else n_placed = lpt_rounds<64>(N, P, C, L.keys, sorted, step_slot, shard_of_seq, worker_count, shard_load);
+        // start of every P_k inside perm
+        const int32_t c = worker_count[lane];
+        const int32_t inc = (int32_t)wave_incl_scan_add_u32((uint32_t)c);
+        worker_count[WAVE + lane] = inc - c;
+        if (lane < P) shard_seq_off[lane] = inc - c;
+        if (lane == 0) { shard_seq_off[P] = N; *placed = n_placed; }
+        __threadfence_block();                                    // shard_of_seq: read back by the whole workgroup below
     }
     __syncthreads();
 
-    // ---- c) lay out P_0, P_1, ... : stable by worker, steps already in insertion order ----
-    counting_pass(L, N, rounds,
-                  [&](int pos) { return (uint32_t)step_worker[pos]; },
-                  [&](int pos, int out) {
-                      const int u = sorted[pos];
-                      perm[out] = u;
-                      shard_of_seq[u] = step_worker[pos];
-                  });
-    if (tid < P) shard_seq_off[tid] = (int32_t)L.cnt[tid * BAL_WAVES];
-    if (tid == P) shard_seq_off[P] = N;
+    // ---- c) lay out P_0, P_1, ... each in insertion order ----
+    const int32_t* part_off = worker_count + WAVE;
+    const int n_placed = *placed;
+    for (int t = tid; t < n_placed; t += BAL_BLOCK) {
+        const int u = sorted[t];
+        const int k = shard_of_seq[u];
+        perm[part_off[k] + step_slot[t]] = u;
+    }
 }
 
 hipError_t launch_balance(int32_t n_seq, int32_t n_shards, int32_t cap_eff, const int32_t* d_seq_len,
