@@ -67,7 +67,8 @@ extern "C" {
 #endif
 
 #define DC_MAX_SEQ        16384   /* N: one workgroup sorts and plans in LDS          */
-#define DC_MAX_SHARDS     64      /* P: one wavefront lane per shard                  */
+#define DC_MAX_SHARDS     1024    /* P: one lane per shard (one wavefront up to 64,   */
+                                  /*    the whole workgroup above)                    */
 #define DC_MAX_FIELDS     8
 #define DC_MAX_SRC_SHARDS 16
 #define DC_MAX_SEQ_LEN    (1 << 24)

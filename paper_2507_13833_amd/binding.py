@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdc.so")
 
 DC_MAX_SEQ = 16384
-DC_MAX_SHARDS = 64
+DC_MAX_SHARDS = 1024
 DC_MAX_FIELDS = 8
 DC_MAX_SRC_SHARDS = 16
 

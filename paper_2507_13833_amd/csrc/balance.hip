@@ -1,6 +1,6 @@
 // Algorithm 1, Constrained LPT Load Balancing (Sec. 6 "Load Balancing").
 //
-// One workgroup, everything in LDS (N <= DC_MAX_SEQ, P <= 64):
+// One workgroup, everything in LDS (N <= DC_MAX_SEQ, P <= DC_MAX_SHARDS):
 //   a) stable LSD radix sort of the sequence indices by descending length
 //      (8-bit digits of max_len - len, only as many passes as the length range
 //      needs; ranks inside a wave by ballot matching, across waves by a scan of
@@ -18,6 +18,10 @@
 //      Loads of open workers never differ by more than the longest sequence, so
 //      rebasing the keys when the minimum grows keeps them in 32 bits for any
 //      total load;
+//      With more than 64 workers the same rounds run on the whole workgroup, thread k = worker
+//      k, 64-bit keys load << 10 | k: every thread ranks its key by counting the smaller ones,
+//      the accepted prefix comes from a workgroup-wide min-scan, and keys travel between rank
+//      order and worker order through LDS;
 //   c) a worker that takes an item notes the item's place inside P_k (its item count before) and
 //      its own id; when all items are placed, a scan of the workers' counts gives the start of
 //      every P_k and one pass writes perm: P_0, P_1, ... each in insertion order.
@@ -35,10 +39,18 @@ struct BalLds {
     int32_t  keys[DC_MAX_SEQ];            // sequence lengths (sanitised)
     uint16_t idx_a[DC_MAX_SEQ];           // sort ping
     uint16_t idx_b[DC_MAX_SEQ];           // sort pong; after the sort the free one holds the worker of each step
-    uint32_t cnt[256 * BAL_WAVES];        // [digit][wave] counters of the sort passes; afterwards the workers' tables
+    alignas(16) uint32_t cnt[256 * BAL_WAVES];   // [digit][wave] counters of the sort passes; afterwards the workers' tables
     int32_t  red[2 * BAL_WAVES];
     uint32_t tmp32[16];
+    uint64_t tmp64[BAL_WAVES];
 };
+static_assert(sizeof(uint32_t) * 256 * BAL_WAVES >= 2 * sizeof(uint64_t) * DC_MAX_SHARDS, "two key tables fit the counters");
+static_assert(DC_MAX_SHARDS <= BAL_BLOCK, "one thread per worker");
+
+// Where the tables of the assignment live inside BalLds::cnt once the sort is done.
+constexpr int PART_OFF_AT = 0;                         // int32 [P + 1]: start of every P_k inside perm
+constexpr int PLACED_AT = DC_MAX_SHARDS + 8;           // int32: items placed
+constexpr int WCOUNT_AT = DC_MAX_SHARDS + 16;          // int32 [64]: |P_k| of the one-wave path
 
 // One stable counting pass over positions [0, N): position pos carries digit(pos) in
 // [0, 256); emit(pos, out) receives its output position.  Wave w owns the contiguous
@@ -152,6 +164,90 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, const int32_t* ke
     return pos;
 }
 
+// The same rounds for 64 < P <= DC_MAX_SHARDS workers, run by the whole workgroup: thread k keeps
+// worker k (64-bit key load << 10 | k, all-ones-ish when full or absent), thread r also plays
+// rank r of the sorted order.  Every thread of the workgroup must call it (barriers inside).
+// Returns the number of items placed; part_off[0..P] gets the start of every P_k.
+constexpr int WIDE_ID_BITS = 10;
+constexpr uint64_t WIDE_ID_MASK = (1ull << WIDE_ID_BITS) - 1ull;
+constexpr uint64_t WIDE_FULL = ~WIDE_ID_MASK;          // | worker id: full (or absent) worker
+static_assert(DC_MAX_SHARDS <= (1 << WIDE_ID_BITS), "worker id fits the key's low bits");
+
+__device__ __forceinline__ uint64_t umin64(uint64_t a, uint64_t b) { return a < b ? a : b; }
+
+__device__ __forceinline__ int lpt_rounds_wide(BalLds& L, int N, int P, int C, const uint16_t* sorted, uint16_t* step_slot,
+                                               int32_t* __restrict__ shard_of_seq, int32_t* __restrict__ shard_seq_off,
+                                               int64_t* __restrict__ shard_load) {
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
+    uint64_t* kbuf = reinterpret_cast<uint64_t*>(L.cnt);              // keys in worker order; then the keys sent back
+    uint64_t* sbuf = kbuf + DC_MAX_SHARDS;                            // keys in rank order
+    const uint64_t full = WIDE_FULL | (uint64_t)tid;
+    uint64_t key = (tid < P && C > 0) ? (uint64_t)tid : full;
+    int32_t count = 0;
+    int64_t load = 0;
+    int pos = 0;
+    while (pos < N) {                                                 // pos is the same in every thread
+        kbuf[tid] = key;
+        __syncthreads();
+        // my rank = keys below mine (keys are distinct: the worker id sits in the low bits)
+        if (tid < P) {
+            int rank = 0;
+            for (int j = 0; j < P; ++j) rank += kbuf[j] < key ? 1 : 0;
+            sbuf[rank] = key;
+        }
+        __syncthreads();
+        // ---- rank view: thread r offers item I[pos + r] to the worker with the r-th smallest key ----
+        const uint64_t sk = tid < P ? sbuf[tid] : ~0ull;
+        const int t = pos + tid;
+        const bool valid = tid < P && sk < WIDE_FULL && t < N;
+        const uint64_t s = valid ? (uint64_t)(uint32_t)L.keys[sorted[t]] : 0ull;
+        const uint64_t newk = valid ? sk + (s << WIDE_ID_BITS) : ~0ull;
+        // smallest updated key among the ranks below mine
+        uint64_t inc = newk;
+#pragma unroll
+        for (int d = 1; d < WAVE; d <<= 1) {
+            const uint64_t o = __shfl_up(inc, d, WAVE);
+            if (lane >= d) inc = umin64(inc, o);
+        }
+        uint64_t pm = __shfl_up(inc, 1, WAVE);
+        if (lane == 0) pm = ~0ull;
+        if (lane == WAVE - 1) L.tmp64[w] = inc;
+        __syncthreads();
+        for (int q = 0; q < w; ++q) pm = umin64(pm, L.tmp64[q]);
+        // accepted prefix: ranks below the first one whose worker is no longer the minimum
+        const uint64_t fail = __ballot(!(valid && sk < pm));
+        if (lane == 0) L.red[w] = fail ? w * WAVE + (__ffsll((long long)fail) - 1) : BAL_BLOCK;
+        __syncthreads();
+        int m = BAL_BLOCK;
+        for (int q = 0; q < BAL_WAVES; ++q) m = min(m, L.red[q]);
+        if (m == 0) break;                                            // cannot happen: cap * P >= N (uniform)
+        // back to the workers: rank r sends its updated key, its own rank in place of the worker id
+        if (tid < m) kbuf[sk & WIDE_ID_MASK] = (newk & ~WIDE_ID_MASK) | (uint64_t)tid;
+        const uint64_t thr = sbuf[m - 1];
+        __syncthreads();
+        if (tid < P && key <= thr) {                                  // my worker is among the m smallest
+            const uint64_t recv = kbuf[tid];
+            const uint64_t nk = (recv & ~WIDE_ID_MASK) | (uint64_t)tid;
+            const int mine = pos + (int)(recv & WIDE_ID_MASK);        // the item I took
+            step_slot[mine] = (uint16_t)count;
+            shard_of_seq[sorted[mine]] = tid;
+            load += (int64_t)((nk - key) >> WIDE_ID_BITS);
+            count += 1;
+            key = (count == C) ? full : nk;
+        }
+        pos += m;
+        // the next round's first barrier separates these reads of kbuf from its rewriting by other threads:
+        // a thread only overwrites its own entry before that barrier
+    }
+    __syncthreads();                                                  // kbuf / sbuf are done with: the tables take their place
+    int32_t total;
+    const int32_t off = block_excl_scan_add<int32_t>(count, reinterpret_cast<int32_t*>(L.tmp32), &total);
+    int32_t* part_off = reinterpret_cast<int32_t*>(L.cnt) + PART_OFF_AT;
+    if (tid < P) { part_off[tid] = off; shard_seq_off[tid] = off; shard_load[tid] = load; }
+    if (tid == 0) { part_off[P] = total; shard_seq_off[P] = N; }
+    return pos;
+}
+
 __global__ __launch_bounds__(BAL_BLOCK) void balance_kernel(int32_t N, int32_t P, int32_t C,
                                                             const int32_t* __restrict__ seq_len,
                                                             int32_t* __restrict__ perm,
@@ -198,11 +294,15 @@ __global__ __launch_bounds__(BAL_BLOCK) void balance_kernel(int32_t N, int32_t P
     }
     const uint16_t* sorted = src;                                 // I of Algorithm 1
     uint16_t* step_slot = dst;                                    // place of I[t] inside its worker's partition
-    int32_t* worker_count = reinterpret_cast<int32_t*>(L.cnt);    // [64] |P_k|, then their exclusive scan
-    int32_t* placed = reinterpret_cast<int32_t*>(L.cnt) + 2 * WAVE;
+    int32_t* part_off = reinterpret_cast<int32_t*>(L.cnt) + PART_OFF_AT;
+    int32_t* placed = reinterpret_cast<int32_t*>(L.cnt) + PLACED_AT;
 
-    // ---- b) assignment rounds, wave 0 ----
-    if (w == 0) {
+    // ---- b) assignment rounds: wave 0 for up to 64 workers, else the whole workgroup ----
+    if (P > WAVE) {
+        const int n_placed = lpt_rounds_wide(L, N, P, C, sorted, step_slot, shard_of_seq, shard_seq_off, shard_load);
+        if (tid == 0) *placed = n_placed;
+    } else if (w == 0) {
+        int32_t* worker_count = reinterpret_cast<int32_t*>(L.cnt) + WCOUNT_AT;
         int n_placed;
         if (P <= 16) n_placed = lpt_rounds<16>(N, P, C, L.keys, sorted, step_slot, shard_of_seq, worker_count, shard_load);
         else if (P <= 32) n_placed = lpt_rounds<32>(N, P, C, L.keys, sorted, step_slot, shard_of_seq, worker_count, shard_load);
@@ -210,15 +310,14 @@ __global__ __launch_bounds__(BAL_BLOCK) void balance_kernel(int32_t N, int32_t P
         // start of every P_k inside perm
         const int32_t c = worker_count[lane];
         const int32_t inc = (int32_t)wave_incl_scan_add_u32((uint32_t)c);
-        worker_count[WAVE + lane] = inc - c;
+        part_off[lane] = inc - c;
         if (lane < P) shard_seq_off[lane] = inc - c;
         if (lane == 0) { shard_seq_off[P] = N; *placed = n_placed; }
-        __threadfence_block();                                    // shard_of_seq: read back by the whole workgroup below
     }
+    __threadfence_block();                                        // shard_of_seq: read back by the whole workgroup below
     __syncthreads();
 
     // ---- c) lay out P_0, P_1, ... each in insertion order ----
-    const int32_t* part_off = worker_count + WAVE;
     const int n_placed = *placed;
     for (int t = tid; t < n_placed; t += BAL_BLOCK) {
         const int u = sorted[t];

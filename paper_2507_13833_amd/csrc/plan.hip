@@ -11,8 +11,8 @@
 //      slot, validated: random gathers, which need more loads in flight than one CU has;
 //   1. slot lengths, check that perm is a permutation; wave scans + one scan of the 256 wave
 //      totals -> dense prefix gpre[0..N] (int64, LDS);
-//   2. shard bases: exclusive scan of the shard loads (with alignment: a serial recurrence
-//      over P <= 64 shards);
+//   2. shard bases: exclusive scan of the shard loads, each rounded up to the alignment (a base is
+//      always a multiple of it, so rounding the running sum equals summing the rounded loads);
 //   3. micro-batch starts: one lane per shard hops from start to start, each hop a
 //      bisection for the last slot that still fits under the budget -> start bits;
 //   4. per 32 slots: starts before the word and the last start before it (two scans over
@@ -57,7 +57,6 @@ struct PlanLds {
     int32_t  word_last[PLAN_WORDS];         // last start in the words before this one, or -1
     int64_t  wave_pref[PLAN_IPT * PLAN_WAVES];  // tokens before the 64 slots a wave handles in one step
     int64_t  shard_base[DC_MAX_SHARDS + 1]; // aligned token offset of each shard
-    int64_t  shard_delta[DC_MAX_SHARDS];    // shard_base - dense prefix of the shard's first slot
     int32_t  shard_off[DC_MAX_SHARDS + 1];  // copy of shard_seq_off
     int64_t  tmp64[16];
     int32_t  tmp32[16];
@@ -111,11 +110,11 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
     for (int i = tid; i < PLAN_WORDS; i += PLAN_BLOCK) { L.start_bits[i] = 0; L.seen_bits[i] = 0; }
     if (tid == 0) L.ok = 1;
     __syncthreads();
-    if (tid <= P) {
-        const int32_t v = a.shard_seq_off[tid];
-        L.shard_off[tid] = v;
-        bool bad = v < 0 || v > N || (tid == 0 && v != 0) || (tid == P && v != N);
-        if (tid < P && a.shard_seq_off[tid + 1] < v) bad = true;
+    for (int p = tid; p <= P; p += PLAN_BLOCK) {         // P + 1 entries, P up to the block size
+        const int32_t v = a.shard_seq_off[p];
+        L.shard_off[p] = v;
+        bool bad = v < 0 || v > N || (p == 0 && v != 0) || (p == P && v != N);
+        if (p < P && a.shard_seq_off[p + 1] < v) bad = true;
         if (bad) L.ok = 0;
     }
     __syncthreads();
@@ -170,26 +169,14 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
     }
     __syncthreads();
 
-    // ---- 2. shard bases: lane p of wave 0 takes shard p.  Dense layout: an exclusive scan of
-    // the shard loads; with alignment the round-up makes it a serial recurrence over <= 64 shards
-    if (tid < WAVE) {
+    // ---- 2. shard bases: lane p takes shard p; exclusive scan of the loads rounded up to the alignment ----
+    {
         const int64_t first = tid < P ? L.gpre[L.shard_off[tid]] : 0;
         const int64_t load = tid < P ? L.gpre[L.shard_off[tid + 1]] - first : 0;
-        int64_t base = 0, end = 0;
-        if (a.align == 1) {                              // uniform
-            const int64_t in = wave_incl_scan_add<int64_t>(load);
-            base = in - load;
-            end = __shfl(in, WAVE - 1, WAVE);
-        } else {
-            int64_t pos = 0;
-            for (int p = 0; p < P; ++p) {
-                if (tid == p) base = pos;
-                pos += __shfl(load, p, WAVE);
-                pos = (pos + a.align - 1) / a.align * a.align;
-            }
-            end = pos;
-        }
-        if (tid < P) { L.shard_base[tid] = base; L.shard_delta[tid] = base - first; a.shard_tok_off[tid] = base; }
+        const int64_t padded = (load + a.align - 1) / a.align * a.align;
+        int64_t end;
+        const int64_t base = block_excl_scan_add<int64_t>(padded, L.tmp64, &end);
+        if (tid < P) { L.shard_base[tid] = base; a.shard_tok_off[tid] = base; }
         if (tid == 0) {
             L.shard_base[P] = end;
             a.shard_tok_off[P] = end;
@@ -243,7 +230,7 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
                     const int mid = (lo + hi + 1) >> 1;
                     if (L.shard_off[mid] <= j) lo = mid; else hi = mid - 1;
                 }
-                d = g + L.shard_delta[lo];
+                d = g + (L.shard_base[lo] - L.gpre[L.shard_off[lo]]);
             }
             a.dst_tok_off[j] = d;
             const int64_t gs = L.gpre[cur_start >= 0 ? cur_start : 0];
@@ -252,11 +239,11 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
             if (closes) a.cu_seqlens[j + m + 1] = (int32_t)(L.gpre[j + 1] - gs);
         }
     }
-    if (tid <= P) {                                      // micro-batches before each shard's first slot
-        const int js = L.shard_off[tid];
+    for (int p = tid; p <= P; p += PLAN_BLOCK) {         // micro-batches before each shard's first slot
+        const int js = L.shard_off[p];
         int32_t c = M;
         if (js < N) c = L.word_starts[js >> 5] + (int32_t)__popc(L.start_bits[js >> 5] & ((1u << (js & 31)) - 1u));
-        a.shard_mb_off[tid] = c;
+        a.shard_mb_off[p] = c;
     }
     if (tid == 0) { *a.n_mb = M; a.mb_seq_off[M] = N; }
 }

@@ -59,7 +59,7 @@ def test_balance_host_errors(lib):
         B.dc_balance(B.make_params(10, 4, 100), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, stream=0)
     assert e.value.code == B.DC_ERR_NOT_DIVISIBLE
     for prm, code in ((B.make_params(8, 0, 100), B.DC_ERR_INVALID_ARG),
-                      (B.make_params(8, 65, 100), B.DC_ERR_UNSUPPORTED_SIZE),
+                      (B.make_params(2050, 1025, 100), B.DC_ERR_UNSUPPORTED_SIZE),
                       (B.make_params(B.DC_MAX_SEQ + 64, 64, 100), B.DC_ERR_UNSUPPORTED_SIZE),
                       (B.make_params(8, 4, 0), B.DC_ERR_INVALID_ARG),
                       (B.make_params(8, 4, 100, cap=1), B.DC_ERR_INVALID_ARG),

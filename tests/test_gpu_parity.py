@@ -226,6 +226,23 @@ def test_max_sequences():
     check_step(_custom(lens, 16, 64, 8192, n_src=16), label="N=16384 (limit), 16 rollout shards")
 
 
+def test_more_than_64_shards():
+    """More workers than a wavefront has lanes: the assignment rounds run on the whole workgroup."""
+    rng = np.random.default_rng(14)
+    lens = np.minimum(rng.geometric(0.01, 16384), 3000).astype(np.int32)
+    check_step(_custom(lens, 16, 128, 8192, n_src=4), label="N=16384 P=128")
+    check_step(_custom(lens, 16, 1024, 8192, n_src=4), label="N=16384 P=1024 (limit)")
+    lens = rng.integers(1, 5000, 65 * 48).astype(np.int32)
+    check_step(_custom(lens, 8, 65, 16384), label="P=65")
+    check_step(_custom(lens, 8, 65, 16384), align=16, label="P=65 align 16")
+    lens = np.concatenate([rng.integers(2000, 2100, 2048), np.ones(2048, np.int64)]).astype(np.int32)   # heavy ties
+    w = _custom(lens, 16, 256, 4096, n_src=2)
+    check_step(w, label="P=256 ties")
+    check_step(w, cap=w.n_seq, label="P=256 cap=N (textbook LPT)")
+    check_step(w, cap=w.n_seq // 256 + 2, label="P=256 cap=C+2")
+    check_step(_custom(rng.integers(1, 300, 200), 2, 200, 512), label="N=P=200")
+
+
 def test_longest_sequence_and_most_fields():
     # two sequences of DC_MAX_SEQ_LEN tokens next to tiny ones (LPT keys, 32-bit offsets inside a tile, int64 outside)
     L = 1 << 24
