@@ -17,7 +17,8 @@
 //      on every open worker, so N/P rounds replace N dependent steps.
 //      Loads of open workers never differ by more than the longest sequence, so
 //      rebasing the keys when the minimum grows keeps them in 32 bits for any
-//      total load;
+//      total load (the minimum grows by at most one longest sequence per round, so
+//      the check runs every so many rounds, not in each);
 //      With more than 64 workers the same rounds run on the whole workgroup, thread k = worker
 //      k, 64-bit keys load << 10 | k: every thread ranks its key by counting the smaller ones,
 //      the accepted prefix comes from a workgroup-wide min-scan, and keys travel between rank
@@ -119,24 +120,36 @@ __device__ __forceinline__ void counting_pass(BalLds& L, int N, int rounds, Digi
 // of every placed sequence; worker_count[k] = |P_k|.  Returns the number of items placed (N).
 template <int WIDTH>
 __device__ __forceinline__ int lpt_rounds(int N, int P, int C, const int32_t* keys, const uint16_t* sorted,
-                                          uint16_t* step_slot, int32_t* __restrict__ shard_of_seq,
+                                          int32_t max_len, uint16_t* step_slot, int32_t* __restrict__ shard_of_seq,
                                           int32_t* worker_count, int64_t* __restrict__ shard_load) {
     const uint32_t lane = threadIdx.x;
+    // Keys of open workers lie within one longest sequence (G, in key units) of the smallest, which
+    // grows by at most G per round.  A check that leaves the smallest below 2^30 therefore keeps every
+    // key below 2^30 + (R + 1) G for the next R rounds; R is chosen so that this stays below 2^32
+    // with one G to spare.
+    const uint32_t G = (uint32_t)max_len << 6;                    // max_len <= 2^24
+    const uint32_t fit = (3u << 30) / max(G, 1u);                 // >= 3
+    const int check_every = (int)min(64u, fit - 2u);
+    int until_check = 1;
     const uint32_t full = KEY_FULL | lane;
     uint32_t key = ((int)lane < P && C > 0) ? lane : full;
     int32_t count = 0;
     int64_t load = 0;
     int pos = 0;
+    // the item offered to rank `lane` is fetched one round ahead (two dependent LDS reads), as soon as the
+    // accepted prefix is known, so the reads overlap the hand-back of the keys instead of delaying the sort
+    uint32_t s = N > 0 ? (uint32_t)keys[sorted[min((int)lane, N - 1)]] : 0u;
     while (pos < N) {
         const int t = pos + (int)lane;
-        uint32_t s = 0;
-        if (t < N) s = (uint32_t)keys[sorted[t]];                 // item offered to rank `lane`
         uint32_t sk = wave_sort_asc<WIDTH>(key);                  // lane r: r-th smallest key
-        const uint32_t min0 = (uint32_t)__builtin_amdgcn_readlane((int)sk, 0);
-        if (min0 >= 0x40000000u && min0 < KEY_FULL) {             // rebase: subtract the minimum load
-            const uint32_t sub = min0 & ~63u;
-            if (key < KEY_FULL) key -= sub;
-            if (sk < KEY_FULL) sk -= sub;
+        if (--until_check == 0) {                                 // uniform
+            until_check = check_every;
+            const uint32_t min0 = (uint32_t)__builtin_amdgcn_readlane((int)sk, 0);
+            if (min0 >= 0x40000000u && min0 < KEY_FULL) {         // rebase: subtract the minimum load
+                const uint32_t sub = min0 & ~63u;
+                if (key < KEY_FULL) key -= sub;
+                if (sk < KEY_FULL) sk -= sub;
+            }
         }
         const bool valid = sk < KEY_FULL && t < N;
         const uint32_t newk = valid ? sk + (s << 6) : 0xFFFFFFFFu;
@@ -144,10 +157,12 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, const int32_t* ke
         const uint64_t acc = __ballot(valid && sk < pm);
         const int m = (~acc == 0ull) ? WAVE : (__ffsll((long long)~acc) - 1);   // accepted prefix
         if (m == 0) break;                                        // cannot happen: cap * P >= N
+        const uint32_t next_idx = sorted[min(t + m, N - 1)];      // next round's item: first read
         // back to worker lanes: rank r sends its updated key, its own rank in place of the worker id,
         // to lane (sk & 63)
         const uint32_t recv = (uint32_t)__builtin_amdgcn_ds_permute((int)((sk & 63u) << 2), (int)((newk & ~63u) | lane));
         const uint32_t thr = (uint32_t)__builtin_amdgcn_readlane((int)sk, m - 1);
+        const uint32_t next_s = (uint32_t)keys[next_idx];         // second read
         if (key <= thr) {                                         // my worker is among the m smallest
             const uint32_t nk = (recv & ~63u) | lane;
             const int mine = pos + (int)(recv & 63u);             // the item I took
@@ -158,6 +173,7 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, const int32_t* ke
             key = (count == C) ? full : nk;
         }
         pos += m;
+        s = next_s;
     }
     if ((int)lane < P) shard_load[lane] = load;
     worker_count[lane] = count;
@@ -304,9 +320,9 @@ __global__ __launch_bounds__(BAL_BLOCK) void balance_kernel(int32_t N, int32_t P
     } else if (w == 0) {
         int32_t* worker_count = reinterpret_cast<int32_t*>(L.cnt) + WCOUNT_AT;
         int n_placed;
-        if (P <= 16) n_placed = lpt_rounds<16>(N, P, C, L.keys, sorted, step_slot, shard_of_seq, worker_count, shard_load);
-        else if (P <= 32) n_placed = lpt_rounds<32>(N, P, C, L.keys, sorted, step_slot, shard_of_seq, worker_count, shard_load);
-        else n_placed = lpt_rounds<64>(N, P, C, L.keys, sorted, step_slot, shard_of_seq, worker_count, shard_load);
+        if (P <= 16) n_placed = lpt_rounds<16>(N, P, C, L.keys, sorted, mx, step_slot, shard_of_seq, worker_count, shard_load);
+        else if (P <= 32) n_placed = lpt_rounds<32>(N, P, C, L.keys, sorted, mx, step_slot, shard_of_seq, worker_count, shard_load);
+        else n_placed = lpt_rounds<64>(N, P, C, L.keys, sorted, mx, step_slot, shard_of_seq, worker_count, shard_load);
         // start of every P_k inside perm
         const int32_t c = worker_count[lane];
         const int32_t inc = (int32_t)wave_incl_scan_add_u32((uint32_t)c);

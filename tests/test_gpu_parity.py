@@ -259,6 +259,14 @@ def test_longest_sequence_and_most_fields():
     check_scatter(w, label="8 fields")
 
 
+def test_loads_beyond_the_32_bit_keys():
+    # 20 M tokens per shard: (load << 6) passes 2^30 many times over, so the assignment's keys are rebased
+    # again and again, with the check running only every 64th round (sequences of ~10 K tokens)
+    rng = np.random.default_rng(15)
+    w = _custom(rng.integers(8000, 12000, 4096), 2, 2, 1 << 20, fields=("i32", "u8"))
+    check_step(w, label="P=2, 20 M tokens per shard")
+
+
 def test_long_and_short_sequences_mixed():
     # a big batch (the narrow fields ride on the 4-byte fields' workgroups) whose shards end in
     # runs of very short sequences: tiles with more slots per granule than a record holds sit
