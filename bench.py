@@ -6,6 +6,9 @@ HBM: dc_group_advantage (on a second stream, beside) dc_balance + dc_plan, then 
 Prints ONE JSON line: repacked tokens/s for the whole step, the gather kernel's achieved HBM
 bandwidth against the chip's peak (HIP events around every gather launch of the timed region,
 on the stream it is launched on), and the CPU oracle timed on the host as a reported baseline.
+Outside the timed region it also times each call of the step on its own, the reverse path
+(dc_scatter) and the PPO advantage stage (dc_gae) on the same batch ("stages", "reverse",
+"ppo_advantage").
 """
 from __future__ import annotations
 

@@ -506,6 +506,19 @@ def test_device_status_codes():
     d.group_advantage(); torch.cuda.synchronize()
     assert d.read_status() == binding.DC_ERR_BAD_LAYOUT
 
+    # the PPO advantage stage refuses the same things, and writes nothing for the sequence it refuses
+    wp = _with_ppo_fields(_custom(np.array([5, 4, 3, 7], np.int32), 2, 2, 64))
+    d = runner.DeviceBatch(wp); d.prepare_gae()
+    d.seq_len[2] = -3
+    d.gae(); torch.cuda.synchronize()
+    assert d.read_status() == binding.DC_ERR_ZERO_LENGTH_SEQ
+    assert torch.isnan(d.gae_adv[0][9:12]).all() and not torch.isnan(d.gae_adv[0][:9]).any()
+    d = runner.DeviceBatch(wp); d.prepare_gae()
+    d.src_tok_off[3] = 14                                              # sequence 3 would end beyond its buffer
+    d.gae(); torch.cuda.synchronize()
+    assert d.read_status() == binding.DC_ERR_BAD_LAYOUT
+    assert torch.isnan(d.gae_ret[0][12:]).all()
+
 
 def test_empty_batch():
     torch, binding, runner = _gpu()
