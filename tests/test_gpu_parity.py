@@ -285,6 +285,8 @@ def test_group_sizes_and_ddof():
         w.ddof = ddof
         w.reward[:G] = 0.1                                     # identical rewards, inexact value
         check_step(w, label=f"G={G} ddof={ddof}")
+    w.eps = 0.0                                                # identical rewards are +0 by rule: 0 / 0 otherwise
+    check_step(w, label="eps = 0")
 
 
 def test_advantage_ill_conditioned_rewards():

@@ -73,12 +73,13 @@ def test_group_sum_zero_and_identical_groups():
 
 
 def test_identical_rewards_any_group_size():
-    # 0.1 is not exactly representable: r - mean would not cancel for every G
+    # identical rewards give exactly +0 by rule, not by cancellation: with eps = 0 the formula alone is 0 / 0
     for G in (1, 2, 3, 5, 7, 10, 16, 100):
         r = np.full(G, 0.1, np.float32)
         for ddof in (0, 1):
-            a = oracle.group_advantage(r, [0, G], EPS, ddof)
-            assert np.all(a == 0.0) and not np.any(np.signbit(a))
+            for eps in (EPS, 0.0):
+                a = oracle.group_advantage(r, [0, G], eps, ddof)
+                assert np.all(a == 0.0) and not np.any(np.signbit(a))
 
 
 def test_singleton_group_and_empty_group():
