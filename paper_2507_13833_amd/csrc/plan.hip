@@ -186,18 +186,43 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
     }
 
     // ---- 3. micro-batch starts: lane p walks shard p ----
+    // Each hop looks for the last slot that still fits under the budget.  Slots of a shard come in
+    // descending length, so a micro-batch holds about as many slots as the one before it: the
+    // search gallops outwards from that guess and bisects what is left (a few probes of the prefix
+    // instead of log2 N per hop; the hops of a shard are one dependent chain).
     if (tid < P) {
         const int b = L.shard_off[tid + 1];
         int j = L.shard_off[tid];
+        int sz = 1;                                      // slots in the previous micro-batch
         while (j < b) {
             atomicOr(&L.start_bits[j >> 5], 1u << (j & 31));
             const int64_t limit = L.gpre[j] + a.budget;
-            int lo = j + 1, hi = b;                      // largest e in [j+1, b] with gpre[e] <= limit
+            int lo = j + 1, hi = b;                      // largest e in [lo, hi] with gpre[e] <= limit; gpre[lo] may
+                                                         // exceed it: an over-budget slot still advances by one
+            int g = min(j + sz, b);
+            if (g > lo) {
+                if (L.gpre[g] <= limit) {
+                    lo = g;
+                    for (int w = 1; lo < hi; w <<= 1) {  // gallop up
+                        g = min(lo + w, hi);
+                        if (L.gpre[g] <= limit) lo = g; else { hi = g - 1; break; }
+                    }
+                } else {
+                    hi = g - 1;
+                    for (int w = 1; lo < hi; w <<= 1) {  // gallop down
+                        g = max(hi + 1 - w, lo);
+                        if (g == lo) break;
+                        if (L.gpre[g] <= limit) { lo = g; break; }
+                        hi = g - 1;
+                    }
+                }
+            }
             while (lo < hi) {
                 const int mid = (lo + hi + 1) >> 1;
                 if (L.gpre[mid] <= limit) lo = mid; else hi = mid - 1;
             }
-            j = lo;                                      // an over-budget slot still advances by one
+            sz = lo - j;
+            j = lo;
         }
     }
     __syncthreads();
