@@ -127,19 +127,95 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, const int32_t* ke
     // grows by at most G per round.  A check that leaves the smallest below 2^30 therefore keeps every
     // key below 2^30 + (R + 1) G for the next R rounds; R is chosen so that this stays below 2^32
     // with one G to spare.
-    const uint32_t G = (uint32_t)max_len << 6;                    // max_len <= 2^24
+    const uint32_t G = (uint32_t)__builtin_amdgcn_readfirstlane(max_len) << 6;    // max_len <= 2^24
     const uint32_t fit = (3u << 30) / max(G, 1u);                 // >= 3
     const int check_every = (int)min(64u, fit - 2u);
     int until_check = 1;
+    // The kernel is short of scalar registers: keep this pointer in vector registers (or every round
+    // reloads it from the kernel arguments and waits for the load), typed as a global-memory pointer so
+    // that the stores through it stay global stores.
+    typedef __attribute__((address_space(1))) int32_t global_i32;
+    global_i32* worker_of;
+    {
+        uint32_t lo = (uint32_t)reinterpret_cast<uintptr_t>(shard_of_seq);
+        uint32_t hi = (uint32_t)(reinterpret_cast<uintptr_t>(shard_of_seq) >> 32);
+        asm volatile("" : "+v"(lo), "+v"(hi));
+        worker_of = reinterpret_cast<global_i32*>(((uintptr_t)hi << 32) | (uintptr_t)lo);
+    }
     const uint32_t full = KEY_FULL | lane;
-    uint32_t key = ((int)lane < P && C > 0) ? lane : full;
+    const bool mine_exists = (int)lane < P;                       // lane k keeps worker k
+    const uint64_t everyone = P == WAVE ? ~0ull : (1ull << P) - 1ull;
+    uint32_t key = (mine_exists && C > 0) ? lane : full;
     int32_t count = 0;
     int64_t load = 0;
     int pos = 0;
     // the item offered to rank `lane` is fetched one round ahead (two dependent LDS reads), as soon as the
     // accepted prefix is known, so the reads overlap the hand-back of the keys instead of delaying the sort
-    uint32_t s = N > 0 ? (uint32_t)keys[sorted[min((int)lane, N - 1)]] : 0u;
+    uint32_t idx = N > 0 ? (uint32_t)sorted[min((int)lane, N - 1)] : 0u;
+    uint32_t s = N > 0 ? (uint32_t)keys[idx] : 0u;
+    bool all_take = C > 0;                                        // every worker open and the last round placed an item on each
+
     while (pos < N) {
+        // ---- rounds in which every worker takes one item ----
+        // While all P workers are open and whole prefixes are accepted, a worker's count is its count at
+        // entry plus the rounds since, and its load is its key plus a constant.  Nothing has to travel back
+        // to the worker lanes then: the keys stay in rank order from round to round, and the sort of the
+        // updated keys starts before the round's acceptance test has finished (it is only used if the
+        // test passes), which takes the test off the chain of dependent sorts.
+        if (all_take && pos + P <= N) {                           // uniform
+            int32_t cmax = mine_exists ? count : 0;
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) cmax = max(cmax, __shfl_xor(cmax, d, WAVE));
+            const int avail = C - __builtin_amdgcn_readfirstlane(cmax);   // rounds before the first worker is full (>= 1)
+            const int64_t off = load - (int64_t)(key >> 6);       // what the key does not hold of my worker's load
+            int64_t taken = 0;                                    // load taken off the keys by rebasing in here
+            int rounds = 0;
+            uint32_t sk = wave_sort_asc<WIDTH>(key);
+            // items two rounds ahead: nothing a round reads from LDS depends on what the round computes
+            uint32_t idx1 = sorted[min(pos + P + (int)lane, N - 1)];
+            while (rounds < avail && pos + P <= N) {
+                const int t = pos + (int)lane;                    // rank `lane` takes item I[t]
+                const uint32_t id = sk & 63u;
+                const uint32_t s1 = (uint32_t)keys[idx1];
+                const uint32_t idx2 = sorted[min(t + 2 * P, N - 1)];
+                const int32_t before = __builtin_amdgcn_ds_bpermute((int)(id << 2), count) + rounds;   // its count
+                if (--until_check == 0) {                         // uniform
+                    until_check = check_every;
+                    const uint32_t min0 = (uint32_t)__builtin_amdgcn_readlane((int)sk, 0);
+                    if (min0 >= 0x40000000u && min0 < KEY_FULL) {
+                        const uint32_t sub = min0 & ~63u;
+                        if (sk < KEY_FULL) sk -= sub;
+                        taken += (int64_t)(sub >> 6);
+                    }
+                }
+                const uint32_t newk = mine_exists ? sk + (s << 6) : sk;       // absent workers keep their all-ones-ish key
+                const uint32_t sk2 = wave_sort_asc<WIDTH>(newk);              // next round's order, if this round stands
+                const uint32_t pm = wave_excl_scan_umin(mine_exists ? newk : 0xFFFFFFFFu);
+                if (__ballot(mine_exists && sk < pm) != everyone) break;      // not everyone's turn: one general round
+                if (mine_exists) {
+                    step_slot[t] = (uint16_t)before;
+                    worker_of[idx] = (int32_t)id;
+                }
+                pos += P;
+                rounds += 1;
+                sk = sk2;
+                idx = idx1;
+                s = s1;
+                idx1 = idx2;
+            }
+            // back to worker lanes: rank r sends its key to lane (sk & 63); absent workers send theirs to themselves
+            key = (uint32_t)__builtin_amdgcn_ds_permute((int)((sk & 63u) << 2), (int)sk);
+            if (mine_exists) {
+                count += rounds;
+                load = off + taken + (int64_t)(key >> 6);
+                if (count == C) key = full;
+            }
+            until_check = 1;
+            all_take = false;
+            continue;
+        }
+
+        // ---- a general round: the longest accepted prefix of the ranks takes one item each ----
         const int t = pos + (int)lane;
         uint32_t sk = wave_sort_asc<WIDTH>(key);                  // lane r: r-th smallest key
         if (--until_check == 0) {                                 // uniform
@@ -167,15 +243,17 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, const int32_t* ke
             const uint32_t nk = (recv & ~63u) | lane;
             const int mine = pos + (int)(recv & 63u);             // the item I took
             step_slot[mine] = (uint16_t)count;
-            shard_of_seq[sorted[mine]] = (int32_t)lane;
+            worker_of[sorted[mine]] = (int32_t)lane;
             load += (int64_t)((nk - key) >> 6);
             count += 1;
             key = (count == C) ? full : nk;
         }
         pos += m;
+        idx = next_idx;
         s = next_s;
+        all_take = m == P && __ballot(mine_exists && key >= KEY_FULL) == 0ull;
     }
-    if ((int)lane < P) shard_load[lane] = load;
+    if (mine_exists) shard_load[lane] = load;
     worker_count[lane] = count;
     return pos;
 }
