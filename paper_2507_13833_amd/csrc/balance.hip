@@ -72,12 +72,18 @@ __device__ __forceinline__ void counting_pass(BalLds& L, int N, int rounds, Digi
             const bool valid = pos < N;
             uint32_t d = 0;
             if (valid) d = digit(pos) & 0xFFu;
-            uint64_t peers = __ballot(valid);
+            // lanes holding my digit: for every bit, the lanes whose bit equals mine (an invalid lane has d = 0
+            // and is not among the valid ones to begin with)
+            const uint64_t valid_lanes = __builtin_amdgcn_ballot_w64(valid);
+            uint32_t peers_lo = (uint32_t)valid_lanes, peers_hi = (uint32_t)(valid_lanes >> 32);
 #pragma unroll
             for (int b = 0; b < 8; ++b) {
-                const uint64_t bal = __ballot(valid && ((d >> b) & 1u));
-                peers &= ((d >> b) & 1u) ? bal : ~bal;
+                const uint64_t bal = __builtin_amdgcn_ballot_w64(((d >> b) & 1u) != 0u);
+                const uint32_t mine = (uint32_t)__builtin_amdgcn_sbfe((int)d, (unsigned)b, 1u);   // all ones if my bit is set
+                peers_lo &= ~((uint32_t)bal ^ mine);
+                peers_hi &= ~((uint32_t)(bal >> 32) ^ mine);
             }
+            const uint64_t peers = ((uint64_t)peers_hi << 32) | peers_lo;
             const uint64_t lt = (1ull << lane) - 1ull;
             const int before = __popcll(peers & lt);
             const int leader = valid ? (__ffsll((long long)peers) - 1) : lane;
