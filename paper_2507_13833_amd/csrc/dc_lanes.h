@@ -47,8 +47,9 @@ __device__ __forceinline__ uint32_t lane_xor(uint32_t v) {
     if constexpr (J == 1) return dpp_perm<DPP_QUAD_PERM_1032>(v);
     else if constexpr (J == 2) return dpp_perm<DPP_QUAD_PERM_2301>(v);
     else if constexpr (J == 4) {
-        // lanes with bit 2 clear (banks 0, 2) take lane+4, the others lane-4
-        uint32_t t = dpp_mov<DPP_ROW_SHL4, 0xF, 0x5>(v, v);
+        // lanes with bit 2 clear (banks 0, 2) take lane+4, the others lane-4; what the first move leaves in
+        // banks 1, 3 does not matter (the second overwrites it), so it needs no previous value and no copy
+        uint32_t t = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, DPP_ROW_SHL4, 0xF, 0x5, false);
         return dpp_mov<DPP_ROW_SHR4, 0xF, 0xA>(t, v);
     } else if constexpr (J == 8) return dpp_perm<DPP_ROW_ROR8>(v);
     else if constexpr (J == 16) {
