@@ -2,7 +2,8 @@
 """Benchmark of the Data Coordinator reshard path on one MI355X.
 
 A step is one pass of the whole path over one synthetic rollout batch already resident in
-HBM: dc_group_advantage (on a second stream, beside) dc_balance + dc_plan, then dc_gather.
+HBM: dc_balance and dc_group_advantage (one launch: dc_balance_group_advantage), dc_plan,
+dc_gather, all on one stream.
 Prints ONE JSON line: repacked tokens/s for the whole step, the gather kernel's achieved HBM
 bandwidth against the chip's peak (HIP events around every gather launch of the timed region,
 on the stream it is launched on), and the CPU oracle timed on the host as a reported baseline.
@@ -73,7 +74,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: 5, the largest)")
     ap.add_argument("--sets", type=int, default=3, help="rotating buffer sets (defeats cache reuse)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--single-stream", action="store_true", help="issue the four calls on one stream")
+    ap.add_argument("--single-stream", action="store_true", help="issue the four calls one after the other on one stream")
+    ap.add_argument("--two-streams", action="store_true",
+                    help="dc_group_advantage on a second stream beside dc_balance + dc_plan (two cross-stream waits per step)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise copy of known size (1 GiB read + 1 GiB written per "
                          "launch): the yardstick that scales the HBM byte counters of a rocprofv3 --pmc run")
@@ -104,8 +107,10 @@ def main() -> int:
             b.gather()
             if ev is not None:
                 ev[1].record()
-        else:
+        elif args.two_streams:
             b.step_overlapped(ev)
+        else:
+            b.step_fused(ev)
 
     for i in range(args.warmup):
         one_step(sets[i % len(sets)])
@@ -136,6 +141,8 @@ def main() -> int:
     # per-stage device times (events around each call, outside the timed region)
     stage = {}
     for name in ("group_advantage", "balance", "plan", "gather"):
+        getattr(sets[0], name)()                        # a kernel's first launch in a process loads its code
+        torch.cuda.synchronize()
         tot = 0.0
         for i in range(6):
             b = sets[i % len(sets)]
@@ -200,7 +207,9 @@ def main() -> int:
                                f"P={w.n_shards}, token budget {w.token_budget}, {bpt} payload B/token, "
                                f"{w.n_src_shards} rollout shard(s)",
                    "buffer_sets": len(sets),
-                   "streams": 1 if args.single_stream else 2},
+                   "streams": 2 if args.two_streams else 1,
+                   "launches": "separate" if (args.single_stream or args.two_streams)
+                               else "dc_balance_group_advantage, dc_plan, dc_gather"},
         "roofline": {"bound": "hbm", "kernel": "gather_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": gather_bytes, "avg_launch_ms": gather_ms},

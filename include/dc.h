@@ -154,6 +154,18 @@ dc_status dc_group_advantage(const dc_params* prm, const dc_source* src, const i
                              float* const* adv_tok_src_base, int32_t* d_status, void* hip_stream);
 
 /*
+ * dc_balance and dc_group_advantage in ONE launch (same arguments, same results, same device errors):
+ * the two stages are independent, the balance keeps one compute unit busy for its whole run and the
+ * advantage stage streams the tokens meanwhile.  For callers that would otherwise put the two on two
+ * streams: this needs no second stream and no cross-stream wait.
+ */
+dc_status dc_balance_group_advantage(const dc_params* prm, const dc_source* src, const int32_t* d_seq_len,
+                                     int32_t* d_perm, int32_t* d_shard_seq_off, int32_t* d_shard_of_seq,
+                                     int64_t* d_shard_load, const float* d_reward, const int32_t* d_group_off,
+                                     int32_t n_groups, const uint8_t* const* mask_src_base, float* d_adv_seq,
+                                     float* const* adv_tok_src_base, int32_t* d_status, void* hip_stream);
+
+/*
  * Generalized advantage estimation (Schulman et al. 2016, arXiv 1506.02438, eqs. 11-16): the
  * advantage stage of PPO (Sec. 7.1 evaluates PPO with a critic; App. B Table 2 "advantage"), per
  * token, in the rollout layout.  With t_1 < ... < t_m the tokens of sequence i whose mask byte is

@@ -31,7 +31,8 @@ DC_ERR_OVERFLOW = 8
 DC_ERR_BAD_LAYOUT = 9
 
 EXPORTS = ("dc_workspace_bytes", "dc_balance", "dc_group_advantage", "dc_plan", "dc_gather",
-           "dc_repack", "dc_scatter_workspace_bytes", "dc_scatter", "dc_gae", "dc_strerror")
+           "dc_repack", "dc_scatter_workspace_bytes", "dc_scatter", "dc_gae", "dc_balance_group_advantage",
+           "dc_strerror")
 
 
 class dc_params(C.Structure):
@@ -97,6 +98,9 @@ def load() -> C.CDLL:
         lib.dc_gae.argtypes = [C.POINTER(dc_params), C.POINTER(dc_source), vp, vp, C.POINTER(vp), C.POINTER(vp),
                                C.POINTER(vp), C.POINTER(vp), C.c_double, C.c_double, C.c_double,
                                C.POINTER(vp), C.POINTER(vp), vp, vp]
+        lib.dc_balance_group_advantage.restype = C.c_int
+        lib.dc_balance_group_advantage.argtypes = [C.POINTER(dc_params), C.POINTER(dc_source), vp, vp, vp, vp, vp, vp, vp,
+                                                   C.c_int32, C.POINTER(vp), vp, C.POINTER(vp), vp, vp]
         _lib = lib
     return _lib
 
@@ -243,3 +247,16 @@ def dc_gae(prm: dc_params, src: Source, d_seq_len, d_reward, value_src: Sequence
                          keep[2], keep[3], float(gamma), float(lam), float(kl_coef), keep[4], keep[5],
                          _ptr(d_status), _stream(stream)),
            "dc_gae")
+
+
+def dc_balance_group_advantage(prm: dc_params, src: Source, d_seq_len, d_perm, d_shard_seq_off, d_shard_of_seq,
+                               d_shard_load, d_reward, d_group_off, n_groups: int, mask_src: Optional[Sequence],
+                               d_adv_seq, adv_tok_src: Optional[Sequence], d_status, stream=None) -> None:
+    m = _ptr_array(mask_src) if mask_src is not None else None
+    a = _ptr_array(adv_tok_src) if adv_tok_src is not None else None
+    _check(load().dc_balance_group_advantage(
+        C.byref(prm), C.byref(src.struct), _ptr(d_seq_len), _ptr(d_perm), _ptr(d_shard_seq_off), _ptr(d_shard_of_seq),
+        _ptr(d_shard_load), _ptr(d_reward), _ptr(d_group_off), int(n_groups),
+        C.cast(m, C.POINTER(C.c_void_p)) if m is not None else None, _ptr(d_adv_seq),
+        C.cast(a, C.POINTER(C.c_void_p)) if a is not None else None, _ptr(d_status), _stream(stream)),
+        "dc_balance_group_advantage")

@@ -1,6 +1,7 @@
 // C-ABI entry points: host-side validation, argument marshalling, kernel launches.
 // Nothing here allocates, copies or synchronises.
 #include "dc_internal.h"
+#include "advantage_device.h"
 
 namespace dc {
 
@@ -86,21 +87,50 @@ size_t dc_workspace_bytes(const dc_params* prm, int64_t dst_capacity_tokens) {
     return carve_workspace(nullptr, prm->n_seq, dst_capacity_tokens).bytes;
 }
 
-dc_status dc_balance(const dc_params* prm, const int32_t* d_seq_len,
-                     int32_t* d_perm, int32_t* d_shard_seq_off, int32_t* d_shard_of_seq,
-                     int64_t* d_shard_load, int32_t* d_status, void* hip_stream) {
+// Host-side checks of dc_balance's arguments; *cap_eff gets the per-shard item limit.
+static dc_status check_balance(const dc_params* prm, const int32_t* d_seq_len, const int32_t* d_perm,
+                               const int32_t* d_shard_seq_off, const int32_t* d_shard_of_seq,
+                               const int64_t* d_shard_load, int32_t* cap_eff) {
     dc_status rc = check_params(prm);
     if (rc != DC_OK) return rc;
     if (!d_shard_seq_off || !d_shard_load) return DC_ERR_INVALID_ARG;
     if (prm->n_seq > 0 && (!d_seq_len || !d_perm || !d_shard_of_seq)) return DC_ERR_INVALID_ARG;
-    int32_t cap_eff;
     if (prm->cap == 0) {
         if (prm->n_seq % prm->n_shards != 0) return DC_ERR_NOT_DIVISIBLE;     // Algorithm 1: assert N mod K = 0
-        cap_eff = prm->n_seq / prm->n_shards;
+        *cap_eff = prm->n_seq / prm->n_shards;
     } else {
         if ((int64_t)prm->cap * prm->n_shards < prm->n_seq) return DC_ERR_INVALID_ARG;
-        cap_eff = prm->cap;
+        *cap_eff = prm->cap;
     }
+    return DC_OK;
+}
+
+// Host-side checks of dc_group_advantage's arguments (prm already checked); fills *sd.
+static dc_status check_advantage(const dc_params* prm, const dc_source* src, const int32_t* d_seq_len,
+                                 const float* d_reward, const int32_t* d_group_off, int32_t n_groups,
+                                 const uint8_t* const* mask_src_base, const float* d_adv_seq,
+                                 float* const* adv_tok_src_base, SourceDesc* sd) {
+    dc_status rc = check_source(prm, src, sd);
+    if (rc != DC_OK) return rc;
+    if (n_groups < 0 || n_groups > prm->n_seq || !d_group_off) return DC_ERR_INVALID_ARG;
+    if (prm->n_seq > 0 && (!d_seq_len || !d_reward || !d_adv_seq)) return DC_ERR_INVALID_ARG;
+    if (adv_tok_src_base) {
+        if (!mask_src_base) return DC_ERR_INVALID_ARG;
+        for (int s = 0; s < src->n_src_shards; ++s) {
+            if (src->shard_tokens[s] == 0) continue;
+            if (!mask_src_base[s] || !adv_tok_src_base[s]) return DC_ERR_INVALID_ARG;
+            if (!aligned16(mask_src_base[s]) || !aligned16(adv_tok_src_base[s])) return DC_ERR_INVALID_ARG;
+        }
+    }
+    return DC_OK;
+}
+
+dc_status dc_balance(const dc_params* prm, const int32_t* d_seq_len,
+                     int32_t* d_perm, int32_t* d_shard_seq_off, int32_t* d_shard_of_seq,
+                     int64_t* d_shard_load, int32_t* d_status, void* hip_stream) {
+    int32_t cap_eff;
+    dc_status rc = check_balance(prm, d_seq_len, d_perm, d_shard_seq_off, d_shard_of_seq, d_shard_load, &cap_eff);
+    if (rc != DC_OK) return rc;
     hipError_t e = launch_balance(prm->n_seq, prm->n_shards, cap_eff, d_seq_len, d_perm, d_shard_seq_off,
                                   d_shard_of_seq, d_shard_load, d_status, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? DC_OK : DC_ERR_HIP;
@@ -113,21 +143,32 @@ dc_status dc_group_advantage(const dc_params* prm, const dc_source* src, const i
     dc_status rc = check_params(prm);
     if (rc != DC_OK) return rc;
     SourceDesc sd;
-    rc = check_source(prm, src, &sd);
+    rc = check_advantage(prm, src, d_seq_len, d_reward, d_group_off, n_groups, mask_src_base, d_adv_seq,
+                         adv_tok_src_base, &sd);
     if (rc != DC_OK) return rc;
-    if (n_groups < 0 || n_groups > prm->n_seq || !d_group_off) return DC_ERR_INVALID_ARG;
-    if (prm->n_seq > 0 && (!d_seq_len || !d_reward || !d_adv_seq)) return DC_ERR_INVALID_ARG;
-    if (adv_tok_src_base) {
-        if (!mask_src_base) return DC_ERR_INVALID_ARG;
-        for (int s = 0; s < src->n_src_shards; ++s) {
-            if (src->shard_tokens[s] == 0) continue;
-            if (!mask_src_base[s] || !adv_tok_src_base[s]) return DC_ERR_INVALID_ARG;
-            if (!aligned16(mask_src_base[s]) || !aligned16(adv_tok_src_base[s])) return DC_ERR_INVALID_ARG;
-        }
-    }
     hipError_t e = launch_advantage(prm->n_seq, sd, src->d_src_tok_off, d_seq_len, d_reward, d_group_off, n_groups,
                                     prm->eps, prm->ddof, mask_src_base, d_adv_seq, adv_tok_src_base, d_status,
                                     static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? DC_OK : DC_ERR_HIP;
+}
+
+dc_status dc_balance_group_advantage(const dc_params* prm, const dc_source* src, const int32_t* d_seq_len,
+                                     int32_t* d_perm, int32_t* d_shard_seq_off, int32_t* d_shard_of_seq,
+                                     int64_t* d_shard_load, const float* d_reward, const int32_t* d_group_off,
+                                     int32_t n_groups, const uint8_t* const* mask_src_base, float* d_adv_seq,
+                                     float* const* adv_tok_src_base, int32_t* d_status, void* hip_stream) {
+    int32_t cap_eff;
+    dc_status rc = check_balance(prm, d_seq_len, d_perm, d_shard_seq_off, d_shard_of_seq, d_shard_load, &cap_eff);
+    if (rc != DC_OK) return rc;
+    SourceDesc sd;
+    rc = check_advantage(prm, src, d_seq_len, d_reward, d_group_off, n_groups, mask_src_base, d_adv_seq,
+                         adv_tok_src_base, &sd);
+    if (rc != DC_OK) return rc;
+    const AdvArgs adv = make_adv_args(prm->n_seq, sd, src->d_src_tok_off, d_seq_len, d_reward, d_group_off, n_groups,
+                                      prm->eps, prm->ddof, mask_src_base, d_adv_seq, adv_tok_src_base, d_status);
+    hipError_t e = launch_balance_advantage(prm->n_seq, prm->n_shards, cap_eff, d_seq_len, d_perm, d_shard_seq_off,
+                                            d_shard_of_seq, d_shard_load, adv, sd, n_groups, d_status,
+                                            static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? DC_OK : DC_ERR_HIP;
 }
 

@@ -26,7 +26,7 @@
 //   c) a worker that takes an item notes the item's place inside P_k (its item count before) and
 //      its own id; when all items are placed, a scan of the workers' counts gives the start of
 //      every P_k and one pass writes perm: P_0, P_1, ... each in insertion order.
-#include "dc_device.h"
+#include "advantage_device.h"
 #include "dc_lanes.h"
 
 namespace dc {
@@ -348,14 +348,11 @@ __device__ __forceinline__ int lpt_rounds_wide(BalLds& L, int N, int P, int C, c
     return pos;
 }
 
-__global__ __launch_bounds__(BAL_BLOCK) void balance_kernel(int32_t N, int32_t P, int32_t C,
-                                                            const int32_t* __restrict__ seq_len,
-                                                            int32_t* __restrict__ perm,
-                                                            int32_t* __restrict__ shard_seq_off,
-                                                            int32_t* __restrict__ shard_of_seq,
-                                                            int64_t* __restrict__ shard_load,
-                                                            int32_t* status) {
-    __shared__ BalLds L;
+// The whole of Algorithm 1, by one workgroup of BAL_BLOCK threads.
+__device__ __forceinline__ void balance_body(BalLds& L, int32_t N, int32_t P, int32_t C,
+                                             const int32_t* __restrict__ seq_len, int32_t* __restrict__ perm,
+                                             int32_t* __restrict__ shard_seq_off, int32_t* __restrict__ shard_of_seq,
+                                             int64_t* __restrict__ shard_load, int32_t* status) {
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
 
     // ---- load lengths, range ----
@@ -426,11 +423,59 @@ __global__ __launch_bounds__(BAL_BLOCK) void balance_kernel(int32_t N, int32_t P
     }
 }
 
+__global__ __launch_bounds__(BAL_BLOCK) void balance_kernel(int32_t N, int32_t P, int32_t C,
+                                                            const int32_t* __restrict__ seq_len,
+                                                            int32_t* __restrict__ perm,
+                                                            int32_t* __restrict__ shard_seq_off,
+                                                            int32_t* __restrict__ shard_of_seq,
+                                                            int64_t* __restrict__ shard_load,
+                                                            int32_t* status) {
+    __shared__ BalLds L;
+    balance_body(L, N, P, C, seq_len, perm, shard_seq_off, shard_of_seq, shard_load, status);
+}
+
+// Balance and the group-relative advantage in ONE launch: workgroup 0 is the balance workgroup, every
+// other workgroup gives its 16 waves to 16 sequences of the advantage stage.  The two stages are
+// independent and the balance occupies one compute unit for its whole (latency-bound) run, so the
+// advantage stage's HBM traffic hides behind it - without a second stream and the two cross-stream
+// waits per step that go with it (several microseconds each).  The advantage workgroups carry the
+// balance workgroup's LDS allocation, i.e. one of them fits a compute unit: half the waves the
+// stage has as a kernel of its own, still well inside the balance's run time.
+struct BalanceArgs {
+    int32_t N, P, C;
+    const int32_t* seq_len;
+    int32_t* perm;
+    int32_t* shard_seq_off;
+    int32_t* shard_of_seq;
+    int64_t* shard_load;
+    int32_t* status;
+};
+
+__global__ __launch_bounds__(BAL_BLOCK) void balance_advantage_kernel(BalanceArgs b, AdvArgs a, SourceDesc sd) {
+    __shared__ BalLds L;
+    if (blockIdx.x == 0)
+        balance_body(L, b.N, b.P, b.C, b.seq_len, b.perm, b.shard_seq_off, b.shard_of_seq, b.shard_load, b.status);
+    else
+        advantage_wave(a, sd, (int64_t)(blockIdx.x - 1) * BAL_WAVES + threadIdx.x / WAVE);
+}
+
 hipError_t launch_balance(int32_t n_seq, int32_t n_shards, int32_t cap_eff, const int32_t* d_seq_len,
                           int32_t* d_perm, int32_t* d_shard_seq_off, int32_t* d_shard_of_seq,
                           int64_t* d_shard_load, int32_t* d_status, hipStream_t st) {
     hipLaunchKernelGGL(balance_kernel, dim3(1), dim3(BAL_BLOCK), 0, st, n_seq, n_shards, cap_eff, d_seq_len,
                        d_perm, d_shard_seq_off, d_shard_of_seq, d_shard_load, d_status);
+    return hipGetLastError();
+}
+
+hipError_t launch_balance_advantage(int32_t n_seq, int32_t n_shards, int32_t cap_eff, const int32_t* d_seq_len,
+                                    int32_t* d_perm, int32_t* d_shard_seq_off, int32_t* d_shard_of_seq,
+                                    int64_t* d_shard_load, const AdvArgs& adv, const SourceDesc& src,
+                                    int32_t n_groups, int32_t* d_status, hipStream_t st) {
+    BalanceArgs b;
+    b.N = n_seq; b.P = n_shards; b.C = cap_eff; b.seq_len = d_seq_len; b.perm = d_perm;
+    b.shard_seq_off = d_shard_seq_off; b.shard_of_seq = d_shard_of_seq; b.shard_load = d_shard_load; b.status = d_status;
+    const int64_t grid = 1 + (adv_waves(n_seq, n_groups) + BAL_WAVES - 1) / BAL_WAVES;
+    hipLaunchKernelGGL(balance_advantage_kernel, dim3((unsigned)grid), dim3(BAL_BLOCK), 0, st, b, adv, src);
     return hipGetLastError();
 }
 

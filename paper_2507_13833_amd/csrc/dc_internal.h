@@ -76,6 +76,11 @@ hipError_t launch_balance(int32_t n_seq, int32_t n_shards, int32_t cap_eff, cons
                           int32_t* d_perm, int32_t* d_shard_seq_off, int32_t* d_shard_of_seq,
                           int64_t* d_shard_load, int32_t* d_status, hipStream_t st);
 
+struct AdvArgs;
+hipError_t launch_balance_advantage(int32_t n_seq, int32_t n_shards, int32_t cap_eff, const int32_t* d_seq_len,
+                                    int32_t* d_perm, int32_t* d_shard_seq_off, int32_t* d_shard_of_seq,
+                                    int64_t* d_shard_load, const AdvArgs& adv, const SourceDesc& src,
+                                    int32_t n_groups, int32_t* d_status, hipStream_t st);
 hipError_t launch_advantage(int32_t n_seq, const SourceDesc& src, const int64_t* d_src_tok_off,
                             const int32_t* d_seq_len, const float* d_reward, const int32_t* d_group_off,
                             int32_t n_groups, double eps, int32_t ddof,

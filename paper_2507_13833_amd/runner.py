@@ -108,6 +108,24 @@ class DeviceBatch:
         self.plan()
         self.gather()
 
+    def balance_group_advantage(self, per_token: bool = True) -> None:
+        B.dc_balance_group_advantage(self.prm, self.source, self.seq_len, self.perm, self.shard_seq_off,
+                                     self.shard_of_seq, self.shard_load, self.reward, self.group_off, self.w.n_groups,
+                                     self.src_fields["mask"] if per_token else None, self.adv_seq,
+                                     self.adv_tok_src if per_token else None, self.status)
+
+    def step_fused(self, gather_events=None) -> None:
+        """The same pass on ONE stream: balance and the advantage stage share a launch (the advantage
+        workgroups stream the tokens while the balance workgroup runs), then plan, then gather.
+        gather_events: optional (start, end) torch events recorded around the gather launch."""
+        self.balance_group_advantage()
+        self.plan()
+        if gather_events is not None:
+            gather_events[0].record()
+        self.gather()
+        if gather_events is not None:
+            gather_events[1].record()
+
     def step_overlapped(self, gather_events=None) -> None:
         """The same pass with the two independent halves on two HIP streams: the advantage
         kernel (bandwidth-bound, whole chip) runs beside balance + plan (latency-bound, one

@@ -32,13 +32,16 @@ def oracle_step(w, align=1, cap=0):
     return bal, adv, adv_tok, pl
 
 
-def check_step(w, align=1, cap=0, label="", overlapped=False):
+def check_step(w, align=1, cap=0, label="", overlapped=False, fused=False):
     torch, binding, runner = _gpu()
     print(f"[parity] {label or w.name}: N={w.n_seq} P={w.n_shards} T={w.total_tokens} align={align} cap={cap}",
           flush=True)
     d = runner.DeviceBatch(w, align_tokens=align, cap=cap, poison=True)
-    if overlapped:
-        d.step_overlapped()                              # the launch configuration bench.py times: two streams
+    if fused:
+        d.step_fused()                                   # the launch configuration bench.py times: balance and the
+                                                         # advantage stage in one launch
+    elif overlapped:
+        d.step_overlapped()                              # the same on two streams
     else:
         d.step()
     torch.cuda.synchronize()
@@ -105,20 +108,38 @@ def test_full_config(cfg):
     check_step(workloads.make_workload(cfg), label=f"config {cfg}")
 
 
-@pytest.mark.parametrize("cfg", [3, 5])
+@pytest.mark.parametrize("cfg", [3, 4, 5])
 def test_full_config_as_benchmarked(cfg):
-    """Same check on the two-stream step bench.py times (advantage beside balance + plan)."""
-    d = check_step(workloads.make_workload(cfg), label=f"config {cfg}, two streams", overlapped=True)
+    """Same check on the step bench.py times (balance and the advantage stage in one launch, one stream)."""
+    d = check_step(workloads.make_workload(cfg), label=f"config {cfg}, fused launch", fused=True)
     # a second pass over the same buffers must reproduce every output bit for bit
     import torch
     first = {k: v.clone() for k, v in d.dst_fields.items()}
     perm, cu, dst = d.perm.clone(), d.cu_seqlens.clone(), d.dst_tok_off.clone()
-    d.step_overlapped()
+    d.step_fused()
     torch.cuda.synchronize()
     assert d.read_status() == 0
     assert torch.equal(perm, d.perm) and torch.equal(cu, d.cu_seqlens) and torch.equal(dst, d.dst_tok_off)
     for k, v in d.dst_fields.items():
         assert torch.equal(first[k], v), k
+
+
+def test_two_stream_step():
+    """The step with the advantage stage on a second stream beside balance + plan (bench.py --two-streams)."""
+    check_step(workloads.make_workload(3), label="config 3, two streams", overlapped=True)
+
+
+def test_fused_launch_shapes():
+    """Balance + advantage in one launch on small and odd shapes: fewer sequences than one workgroup's waves,
+    more groups than sequences' waves would cover, many shards, an empty batch."""
+    rng = np.random.default_rng(16)
+    check_step(_custom(rng.integers(1, 200, 6), 3, 2, 512), fused=True, label="fused N=6")
+    check_step(_custom(rng.integers(1, 50, 1000), 1, 8, 4096, n_src=2), fused=True, label="fused G=1")
+    check_step(_custom(rng.integers(1, 300, 2048), 8, 128, 2048, n_src=4), fused=True, label="fused P=128")
+    torch, binding, runner = _gpu()
+    d = runner.DeviceBatch(_custom(np.zeros(0, np.int32), 1, 4, 128))
+    d.step_fused(); torch.cuda.synchronize()
+    assert d.read_status() == 0 and int(d.n_mb.item()) == 0
 
 
 def test_padded_rollout_layout():
