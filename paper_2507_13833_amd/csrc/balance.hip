@@ -24,8 +24,9 @@
 //      the accepted prefix comes from a workgroup-wide min-scan, and keys travel between rank
 //      order and worker order through LDS;
 //   c) a worker that takes an item notes the item's place inside P_k (its item count before) and
-//      its own id; when all items are placed, a scan of the workers' counts gives the start of
-//      every P_k and one pass writes perm: P_0, P_1, ... each in insertion order.
+//      its own id (in LDS, where the item's length was); when all items are placed, a scan of the
+//      workers' counts gives the start of every P_k and one pass writes perm (P_0, P_1, ... each in
+//      insertion order) and the worker of every sequence.
 #include "advantage_device.h"
 #include "dc_lanes.h"
 
@@ -122,11 +123,12 @@ __device__ __forceinline__ void counting_pass(BalLds& L, int N, int rounds, Digi
 }
 
 // The assignment rounds (wave 0 only).  WIDTH = 16, 32 or 64 >= P lanes take part in the sort.
-// step_slot[t] = place of item I[t] inside its worker's partition; shard_of_seq gets the worker
-// of every placed sequence; worker_count[k] = |P_k|.  Returns the number of items placed (N).
+// step_slot[t] = place of item I[t] inside its worker's partition; the worker of a placed sequence
+// takes the place of its length in keys[] (an item's length is read for the last time before the item
+// is placed); worker_count[k] = |P_k|.  Returns the number of items placed (N).
 template <int WIDTH>
-__device__ __forceinline__ int lpt_rounds(int N, int P, int C, const int32_t* keys, const uint16_t* sorted,
-                                          int32_t max_len, uint16_t* step_slot, int32_t* __restrict__ shard_of_seq,
+__device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, const uint16_t* sorted,
+                                          int32_t max_len, uint16_t* step_slot,
                                           int32_t* worker_count, int64_t* __restrict__ shard_load) {
     const uint32_t lane = threadIdx.x;
     // Keys of open workers lie within one longest sequence (G, in key units) of the smallest, which
@@ -137,17 +139,6 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, const int32_t* ke
     const uint32_t fit = (3u << 30) / max(G, 1u);                 // >= 3
     const int check_every = (int)min(64u, fit - 2u);
     int until_check = 1;
-    // The kernel is short of scalar registers: keep this pointer in vector registers (or every round
-    // reloads it from the kernel arguments and waits for the load), typed as a global-memory pointer so
-    // that the stores through it stay global stores.
-    typedef __attribute__((address_space(1))) int32_t global_i32;
-    global_i32* worker_of;
-    {
-        uint32_t lo = (uint32_t)reinterpret_cast<uintptr_t>(shard_of_seq);
-        uint32_t hi = (uint32_t)(reinterpret_cast<uintptr_t>(shard_of_seq) >> 32);
-        asm volatile("" : "+v"(lo), "+v"(hi));
-        worker_of = reinterpret_cast<global_i32*>(((uintptr_t)hi << 32) | (uintptr_t)lo);
-    }
     const uint32_t full = KEY_FULL | lane;
     const bool mine_exists = (int)lane < P;                       // lane k keeps worker k
     const uint64_t everyone = P == WAVE ? ~0ull : (1ull << P) - 1ull;
@@ -200,7 +191,7 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, const int32_t* ke
                 if (__ballot(mine_exists && sk < pm) != everyone) break;      // not everyone's turn: one general round
                 if (mine_exists) {
                     step_slot[t] = (uint16_t)before;
-                    worker_of[idx] = (int32_t)id;
+                    keys[idx] = (int32_t)id;                      // the item is placed: its length is not needed again
                 }
                 pos += P;
                 rounds += 1;
@@ -249,7 +240,7 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, const int32_t* ke
             const uint32_t nk = (recv & ~63u) | lane;
             const int mine = pos + (int)(recv & 63u);             // the item I took
             step_slot[mine] = (uint16_t)count;
-            worker_of[sorted[mine]] = (int32_t)lane;
+            keys[sorted[mine]] = (int32_t)lane;               // the item is placed: its length is not needed again
             load += (int64_t)((nk - key) >> 6);
             count += 1;
             key = (count == C) ? full : nk;
@@ -276,8 +267,7 @@ static_assert(DC_MAX_SHARDS <= (1 << WIDE_ID_BITS), "worker id fits the key's lo
 __device__ __forceinline__ uint64_t umin64(uint64_t a, uint64_t b) { return a < b ? a : b; }
 
 __device__ __forceinline__ int lpt_rounds_wide(BalLds& L, int N, int P, int C, const uint16_t* sorted, uint16_t* step_slot,
-                                               int32_t* __restrict__ shard_of_seq, int32_t* __restrict__ shard_seq_off,
-                                               int64_t* __restrict__ shard_load) {
+                                               int32_t* __restrict__ shard_seq_off, int64_t* __restrict__ shard_load) {
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
     uint64_t* kbuf = reinterpret_cast<uint64_t*>(L.cnt);              // keys in worker order; then the keys sent back
     uint64_t* sbuf = kbuf + DC_MAX_SHARDS;                            // keys in rank order
@@ -330,7 +320,7 @@ __device__ __forceinline__ int lpt_rounds_wide(BalLds& L, int N, int P, int C, c
             const uint64_t nk = (recv & ~WIDE_ID_MASK) | (uint64_t)tid;
             const int mine = pos + (int)(recv & WIDE_ID_MASK);        // the item I took
             step_slot[mine] = (uint16_t)count;
-            shard_of_seq[sorted[mine]] = tid;
+            L.keys[sorted[mine]] = tid;                               // placed: its length is not needed again
             load += (int64_t)((nk - key) >> WIDE_ID_BITS);
             count += 1;
             key = (count == C) ? full : nk;
@@ -396,14 +386,14 @@ __device__ __forceinline__ void balance_body(BalLds& L, int32_t N, int32_t P, in
 
     // ---- b) assignment rounds: wave 0 for up to 64 workers, else the whole workgroup ----
     if (P > WAVE) {
-        const int n_placed = lpt_rounds_wide(L, N, P, C, sorted, step_slot, shard_of_seq, shard_seq_off, shard_load);
+        const int n_placed = lpt_rounds_wide(L, N, P, C, sorted, step_slot, shard_seq_off, shard_load);
         if (tid == 0) *placed = n_placed;
     } else if (w == 0) {
         int32_t* worker_count = reinterpret_cast<int32_t*>(L.cnt) + WCOUNT_AT;
         int n_placed;
-        if (P <= 16) n_placed = lpt_rounds<16>(N, P, C, L.keys, sorted, mx, step_slot, shard_of_seq, worker_count, shard_load);
-        else if (P <= 32) n_placed = lpt_rounds<32>(N, P, C, L.keys, sorted, mx, step_slot, shard_of_seq, worker_count, shard_load);
-        else n_placed = lpt_rounds<64>(N, P, C, L.keys, sorted, mx, step_slot, shard_of_seq, worker_count, shard_load);
+        if (P <= 16) n_placed = lpt_rounds<16>(N, P, C, L.keys, sorted, mx, step_slot, worker_count, shard_load);
+        else if (P <= 32) n_placed = lpt_rounds<32>(N, P, C, L.keys, sorted, mx, step_slot, worker_count, shard_load);
+        else n_placed = lpt_rounds<64>(N, P, C, L.keys, sorted, mx, step_slot, worker_count, shard_load);
         // start of every P_k inside perm
         const int32_t c = worker_count[lane];
         const int32_t inc = (int32_t)wave_incl_scan_add_u32((uint32_t)c);
@@ -411,14 +401,14 @@ __device__ __forceinline__ void balance_body(BalLds& L, int32_t N, int32_t P, in
         if (lane < P) shard_seq_off[lane] = inc - c;
         if (lane == 0) { shard_seq_off[P] = N; *placed = n_placed; }
     }
-    __threadfence_block();                                        // shard_of_seq: read back by the whole workgroup below
     __syncthreads();
 
     // ---- c) lay out P_0, P_1, ... each in insertion order ----
     const int n_placed = *placed;
     for (int t = tid; t < n_placed; t += BAL_BLOCK) {
         const int u = sorted[t];
-        const int k = shard_of_seq[u];
+        const int k = L.keys[u];                                  // the worker that took it
+        shard_of_seq[u] = k;
         perm[part_off[k] + step_slot[t]] = u;
     }
 }
