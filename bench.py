@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # out); valid only for the kernel sources with the digest below (profiles/ has the runs).
 TRAFFIC = {
     # config: (fetch bytes + write bytes per gather launch, digest of csrc/gather.hip + csrc/dc_internal.h)
-    5: (1044605600 + 985045400, "f0185b13bfb03abd"),     # profiles/hbm_traffic_config5_pmc.txt
+    5: (1044586100 + 985039100, "1100c7926e5412e2"),     # profiles/hbm_traffic_config5_pmc.txt
 }
 
 
