@@ -125,6 +125,26 @@ def test_group_advantage_host_errors(lib):
     assert e.value.code == B.DC_ERR_INVALID_ARG
 
 
+def test_fused_balance_advantage_host_errors(lib):
+    src = B.Source([0, 8], [64], FAKE)
+    out = (FAKE,) * 4                                         # perm, shard_seq_off, shard_of_seq, shard_load
+    with pytest.raises(B.DcError) as e:                      # the balance half's check
+        B.dc_balance_group_advantage(B.make_params(10, 4, 100), B.Source([0, 10], [64], FAKE), FAKE, *out,
+                                     FAKE, FAKE, 2, None, FAKE, None, FAKE, stream=0)
+    assert e.value.code == B.DC_ERR_NOT_DIVISIBLE
+    prm = B.make_params(8, 4, 100)
+    with pytest.raises(B.DcError) as e:                      # the advantage half's: more groups than sequences
+        B.dc_balance_group_advantage(prm, src, FAKE, *out, FAKE, FAKE, 9, None, FAKE, None, FAKE, stream=0)
+    assert e.value.code == B.DC_ERR_INVALID_ARG
+    with pytest.raises(B.DcError) as e:                      # per-token output without a mask
+        B.dc_balance_group_advantage(prm, src, FAKE, *out, FAKE, FAKE, 2, None, FAKE, [0x4000], FAKE, stream=0)
+    assert e.value.code == B.DC_ERR_INVALID_ARG
+    with pytest.raises(B.DcError) as e:                      # no permutation output
+        B.dc_balance_group_advantage(prm, src, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, 2, None, FAKE, None, FAKE,
+                                     stream=0)
+    assert e.value.code == B.DC_ERR_INVALID_ARG
+
+
 def test_scatter_host_errors(lib):
     prm = B.make_params(8, 4, 100)
     src = B.Source([0, 8], [64], FAKE)
