@@ -107,6 +107,16 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
     const int N = a.n_seq, P = a.n_shards;
     const int nb = (N + PLAN_BLOCK - 1) / PLAN_BLOCK;    // steps of 1024 slots, <= PLAN_IPT
 
+    // the slots' sequences and lengths (validated by slots_kernel): asked for first, so that these loads are in
+    // flight while the shard table is fetched and checked
+    int32_t seq[PLAN_IPT], len[PLAN_IPT];
+#pragma unroll
+    for (int q = 0; q < PLAN_IPT; ++q) {
+        const int j = q * PLAN_BLOCK + tid;
+        seq[q] = j < N ? a.perm[j] : -1;
+        len[q] = j < N ? a.slot_len[j] : 0;
+    }
+
     for (int i = tid; i < PLAN_WORDS; i += PLAN_BLOCK) { L.start_bits[i] = 0; L.seen_bits[i] = 0; }
     if (tid == 0) L.ok = 1;
     __syncthreads();
@@ -124,14 +134,7 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc
         return;
     }
 
-    // ---- 1. slot lengths (validated by slots_kernel), permutation check, dense prefix ----
-    int32_t seq[PLAN_IPT], len[PLAN_IPT];
-#pragma unroll
-    for (int q = 0; q < PLAN_IPT; ++q) {
-        const int j = q * PLAN_BLOCK + tid;
-        seq[q] = j < N ? a.perm[j] : -1;
-        len[q] = j < N ? a.slot_len[j] : 0;
-    }
+    // ---- 1. permutation check, dense prefix of the slot lengths ----
     uint32_t dup = 0;                                    // bit q: perm repeats an earlier entry at my slot of step q
 #pragma unroll
     for (int q = 0; q < PLAN_IPT; ++q) {
