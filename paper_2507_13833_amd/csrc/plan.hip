@@ -101,7 +101,7 @@ __global__ __launch_bounds__(SLOTS_BLOCK) void slots_kernel(PlanArgs a, SourceDe
 
 __device__ __forceinline__ bool start_bit(const PlanLds& L, int j) { return (L.start_bits[j >> 5] >> (j & 31)) & 1u; }
 
-__global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a, SourceDesc sd) {
+__global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a) {
     __shared__ PlanLds L;
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
     const int N = a.n_seq, P = a.n_shards;
@@ -379,7 +379,7 @@ hipError_t launch_plan(const dc_params& prm, const SourceDesc& src, const int64_
         hipError_t e0 = hipGetLastError();
         if (e0 != hipSuccess) return e0;
     }
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(PLAN_BLOCK), 0, st, a, src);
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(PLAN_BLOCK), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_records(prm.n_seq, d_dst_tok_off, ws, st);
