@@ -7,9 +7,10 @@ dc_gather, all on one stream.
 Prints ONE JSON line: repacked tokens/s for the whole step, the gather kernel's achieved HBM
 bandwidth against the chip's peak (HIP events around every gather launch of the timed region,
 on the stream it is launched on), and the CPU oracle timed on the host as a reported baseline.
-Outside the timed region it also times each call of the step on its own, the reverse path
-(dc_scatter) and the PPO advantage stage (dc_gae) on the same batch ("stages", "reverse",
-"ppo_advantage").
+Outside the timed region it also times each call of the step on its own, the step with
+dc_gather_advantage (no rollout-layout copy of the per-token advantages), the reverse path
+(dc_scatter) and the PPO advantage stage (dc_gae) on the same batch ("stages",
+"no_rollout_adv", "reverse", "ppo_advantage").
 """
 from __future__ import annotations
 
@@ -77,6 +78,9 @@ def main() -> int:
     ap.add_argument("--single-stream", action="store_true", help="issue the four calls one after the other on one stream")
     ap.add_argument("--two-streams", action="store_true",
                     help="dc_group_advantage on a second stream beside dc_balance + dc_plan (two cross-stream waits per step)")
+    ap.add_argument("--no-rollout-adv", action="store_true",
+                    help="the step without the rollout-layout copy of the per-token advantages: the fused launch "
+                         "computes adv_seq only, dc_gather_advantage makes the training-layout field from the mask")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise copy of known size (1 GiB read + 1 GiB written per "
                          "launch): the yardstick that scales the HBM byte counters of a rocprofv3 --pmc run")
@@ -98,6 +102,7 @@ def main() -> int:
     sets = [runner.DeviceBatch(w) for _ in range(max(1, args.sets))]
     bpt = sets[0].payload_bytes_per_token             # payload incl. the per-token advantage
     gather_bytes = 2 * bpt * T                         # algorithmic: read once + write once
+    gather_adv_bytes = (2 * bpt - 4) * T               # dc_gather_advantage: the 4-byte advantage is written, not read
 
     def one_step(b, ev=None):
         if args.single_stream:
@@ -109,6 +114,8 @@ def main() -> int:
                 ev[1].record()
         elif args.two_streams:
             b.step_overlapped(ev)
+        elif args.no_rollout_adv:
+            b.step_no_rollout_adv(ev)
         else:
             b.step_fused(ev)
 
@@ -128,7 +135,31 @@ def main() -> int:
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     gather_ms = sum(a.elapsed_time(b) for a, b in ev) / args.steps
+    if args.no_rollout_adv:
+        gather_bytes = gather_adv_bytes
     achieved = gather_bytes / (gather_ms * 1e-3) / 1e9
+
+    # the same step with dc_gather_advantage in place of the per-token advantage pass + dc_gather
+    # (a shorter run of its own, outside the timed region)
+    variant = None
+    if not (args.no_rollout_adv or args.single_stream or args.two_streams):
+        n_var = max(1, min(args.steps, 60))
+        for i in range(3):
+            sets[i % len(sets)].step_no_rollout_adv()
+        evv = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_var)]
+        torch.cuda.synchronize()
+        v0 = time.perf_counter()
+        for i in range(n_var):
+            sets[i % len(sets)].step_no_rollout_adv(evv[i])
+        torch.cuda.synchronize()
+        v_ms = (time.perf_counter() - v0) * 1e3 / n_var
+        vg_ms = sum(a.elapsed_time(b) for a, b in evv) / n_var
+        assert all(s.read_status() == 0 for s in sets)
+        variant = {"calls": "dc_balance_group_advantage (adv_seq only), dc_plan, dc_gather_advantage",
+                   "steps": n_var, "ms_per_step": round(v_ms, 4), "tokens_per_s": T / (v_ms * 1e-3),
+                   "gather_ms": round(vg_ms, 4), "algorithmic_bytes": gather_adv_bytes,
+                   "achieved": gather_adv_bytes / (vg_ms * 1e-3) / 1e9, "unit": "GB/s",
+                   "frac": gather_adv_bytes / (vg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.int32, device="cuda:0")
@@ -192,7 +223,7 @@ def main() -> int:
         ppo = {"call": "dc_gae", **res}
 
     traffic = None
-    if args.config in TRAFFIC and TRAFFIC[args.config][1] == kernel_digest():
+    if not args.no_rollout_adv and args.config in TRAFFIC and TRAFFIC[args.config][1] == kernel_digest():
         traffic = TRAFFIC[args.config][0]
 
     out = {
@@ -209,11 +240,13 @@ def main() -> int:
                    "buffer_sets": len(sets),
                    "streams": 2 if args.two_streams else 1,
                    "launches": "separate" if (args.single_stream or args.two_streams)
-                               else "dc_balance_group_advantage, dc_plan, dc_gather"},
-        "roofline": {"bound": "hbm", "kernel": "gather_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                               else ("dc_balance_group_advantage (adv_seq only), dc_plan, dc_gather_advantage"
+                                     if args.no_rollout_adv else "dc_balance_group_advantage, dc_plan, dc_gather")},
+        "roofline": {"bound": "hbm", "kernel": "gather_adv_kernel" if args.no_rollout_adv else "gather_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": gather_bytes, "avg_launch_ms": gather_ms},
         "stages": stage,
+        "no_rollout_adv": variant,
         "reverse": reverse,
         "ppo_advantage": ppo,
     }

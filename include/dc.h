@@ -17,6 +17,8 @@
  *   dc_gather           segmented copy of every per-token field from the rollout
  *                       layout into the packed training layout.
  *   dc_repack           dc_plan followed by dc_gather.
+ *   dc_gather_advantage dc_gather that makes the per-token advantage field on the way,
+ *                       from the per-sequence advantages and the loss mask.
  *   dc_scatter          the reverse path: per-token fields a training-layout stage
  *                       produced go back from the packed training layout to the
  *                       rollout layout (the collect / concat side of a stage
@@ -211,6 +213,24 @@ dc_status dc_plan(const dc_params* prm, const dc_source* src, const int32_t* d_s
 dc_status dc_gather(const dc_params* prm, const dc_source* src, const dc_field* fields, int32_t n_fields,
                     int64_t dst_capacity_tokens, const int64_t* d_dst_tok_off,
                     const void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream);
+
+/*
+ * dc_gather that also makes the per-token advantage field (Sec. 1 payload list; App. B Table 2
+ * "advantage") directly in the training layout, from the per-sequence advantages:
+ *   d_adv_tok_dst[d_dst_tok_off[j] + t] = m != 0 ? d_adv_seq[d_perm[j]] : +0.0f,
+ * m = the byte of token t of sequence d_perm[j] in fields[mask_field] (elem_bytes 1, the loss mask).
+ * The result is what dc_group_advantage's per-token buffers would give when gathered as one more
+ * float32 field, without those buffers: call dc_group_advantage (or dc_balance_group_advantage) with
+ * adv_tok_src_base = NULL before.  The gather then reads 1 byte per token where it would read 4,
+ * and the advantage stage writes no per-token data.
+ * d_adv_tok_dst: 16-byte aligned float32 arena of dst_capacity_tokens elements (padding elements are
+ * never written).  d_perm[N], d_adv_seq[N]: as dc_balance / dc_group_advantage left them; the plan
+ * in the workspace must come from the same d_perm.  Everything else as for dc_gather.
+ */
+dc_status dc_gather_advantage(const dc_params* prm, const dc_source* src, const dc_field* fields, int32_t n_fields,
+                              int32_t mask_field, const int32_t* d_perm, const float* d_adv_seq, float* d_adv_tok_dst,
+                              int64_t dst_capacity_tokens, const int64_t* d_dst_tok_off,
+                              const void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream);
 
 /* dc_plan then dc_gather. */
 dc_status dc_repack(const dc_params* prm, const dc_source* src, const int32_t* d_seq_len,

@@ -32,7 +32,7 @@ DC_ERR_BAD_LAYOUT = 9
 
 EXPORTS = ("dc_workspace_bytes", "dc_balance", "dc_group_advantage", "dc_plan", "dc_gather",
            "dc_repack", "dc_scatter_workspace_bytes", "dc_scatter", "dc_gae", "dc_balance_group_advantage",
-           "dc_strerror")
+           "dc_gather_advantage", "dc_strerror")
 
 
 class dc_params(C.Structure):
@@ -85,6 +85,9 @@ def load() -> C.CDLL:
         lib.dc_gather.restype = C.c_int
         lib.dc_gather.argtypes = [C.POINTER(dc_params), C.POINTER(dc_source), C.POINTER(dc_field), C.c_int32,
                                   C.c_int64, vp, vp, C.c_size_t, vp, vp]
+        lib.dc_gather_advantage.restype = C.c_int
+        lib.dc_gather_advantage.argtypes = [C.POINTER(dc_params), C.POINTER(dc_source), C.POINTER(dc_field), C.c_int32,
+                                            C.c_int32, vp, vp, vp, C.c_int64, vp, vp, C.c_size_t, vp, vp]
         lib.dc_repack.restype = C.c_int
         lib.dc_repack.argtypes = [C.POINTER(dc_params), C.POINTER(dc_source), vp, vp, vp,
                                   C.POINTER(dc_field), C.c_int32, C.c_int64,
@@ -212,6 +215,16 @@ def dc_gather(prm: dc_params, src: Source, fields: Fields, dst_capacity_tokens: 
     _check(load().dc_gather(C.byref(prm), C.byref(src.struct), fields.array, fields.n, int(dst_capacity_tokens),
                             _ptr(d_dst_tok_off), _ptr(d_ws), int(ws_bytes), _ptr(d_status), _stream(stream)),
            "dc_gather")
+
+
+def dc_gather_advantage(prm: dc_params, src: Source, fields: Fields, mask_field: int, d_perm, d_adv_seq,
+                        d_adv_tok_dst, dst_capacity_tokens: int, d_dst_tok_off, d_ws, ws_bytes: int, d_status,
+                        stream=None) -> None:
+    _check(load().dc_gather_advantage(C.byref(prm), C.byref(src.struct), fields.array, fields.n, int(mask_field),
+                                      _ptr(d_perm), _ptr(d_adv_seq), _ptr(d_adv_tok_dst), int(dst_capacity_tokens),
+                                      _ptr(d_dst_tok_off), _ptr(d_ws), int(ws_bytes), _ptr(d_status),
+                                      _stream(stream)),
+           "dc_gather_advantage")
 
 
 def dc_repack(prm: dc_params, src: Source, d_seq_len, d_perm, d_shard_seq_off, fields: Fields,

@@ -58,7 +58,7 @@ static dc_status fill_field_table(const dc_field* fields, int32_t n_fields, cons
     FieldTable& ft = *out;
     ft.n_fields = n_fields;
     ft.n_src = sd.n_src;
-    for (int f = 0; f < DC_MAX_FIELDS; ++f) {
+    for (int f = 0; f < DC_MAX_FIELDS + 1; ++f) {
         ft.f[f].dst = nullptr; ft.f[f].elem_bytes = 1; ft.f[f].pad = 0;
         for (int s = 0; s < DC_MAX_SRC_SHARDS; ++s) ft.f[f].src[s] = nullptr;
         if (f >= n_fields) continue;
@@ -246,6 +246,34 @@ dc_status dc_gather(const dc_params* prm, const dc_source* src, const dc_field* 
     if (rc != DC_OK) return rc;
     hipError_t e = launch_gather(prm->n_seq, ft, dst_capacity_tokens, d_dst_tok_off, ws,
                                  static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? DC_OK : DC_ERR_HIP;
+}
+
+dc_status dc_gather_advantage(const dc_params* prm, const dc_source* src, const dc_field* fields, int32_t n_fields,
+                              int32_t mask_field, const int32_t* d_perm, const float* d_adv_seq, float* d_adv_tok_dst,
+                              int64_t dst_capacity_tokens, const int64_t* d_dst_tok_off,
+                              const void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream) {
+    (void)d_status;
+    dc_status rc = check_params(prm);
+    if (rc != DC_OK) return rc;
+    SourceDesc sd;
+    rc = check_source(prm, src, &sd);
+    if (rc != DC_OK) return rc;
+    if (n_fields < 0 || dst_capacity_tokens < 0 || !d_dst_tok_off || !d_ws) return DC_ERR_INVALID_ARG;
+    if (n_fields > DC_MAX_FIELDS) return DC_ERR_UNSUPPORTED_SIZE;
+    if (n_fields == 0 || !fields) return DC_ERR_INVALID_ARG;                    // the mask is one of them
+    if (mask_field < 0 || mask_field >= n_fields || fields[mask_field].elem_bytes != 1) return DC_ERR_INVALID_ARG;
+    if (prm->n_seq > 0 && (!d_perm || !d_adv_seq)) return DC_ERR_INVALID_ARG;
+    if (dst_capacity_tokens > 0 && (!d_adv_tok_dst || !aligned16(d_adv_tok_dst))) return DC_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(d_ws) & 255u) return DC_ERR_INVALID_ARG;
+    Workspace ws = carve_workspace(const_cast<void*>(d_ws), prm->n_seq, dst_capacity_tokens);
+    if (ws_bytes < ws.bytes) return DC_ERR_WORKSPACE;
+    if (ws.n_gran > 0x7FFFFFFFLL) return DC_ERR_UNSUPPORTED_SIZE;
+    FieldTable ft;
+    rc = fill_field_table(fields, n_fields, sd, dst_capacity_tokens, &ft);
+    if (rc != DC_OK) return rc;
+    hipError_t e = launch_gather_advantage(prm->n_seq, ft, mask_field, d_perm, d_adv_seq, d_adv_tok_dst,
+                                           dst_capacity_tokens, d_dst_tok_off, ws, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? DC_OK : DC_ERR_HIP;
 }
 

@@ -69,7 +69,7 @@ struct FieldDesc {
 struct FieldTable {                       // by-value kernel argument
     int32_t   n_fields;
     int32_t   n_src;
-    FieldDesc f[DC_MAX_FIELDS];
+    FieldDesc f[DC_MAX_FIELDS + 1];       // one more: the gather that makes the advantage field describes it here
 };
 
 hipError_t launch_balance(int32_t n_seq, int32_t n_shards, int32_t cap_eff, const int32_t* d_seq_len,
@@ -95,6 +95,12 @@ hipError_t launch_plan(const dc_params& prm, const SourceDesc& src, const int64_
 
 hipError_t launch_gather(int32_t n_seq, const FieldTable& ft, int64_t dst_capacity,
                          const int64_t* d_dst_tok_off, const Workspace& ws, hipStream_t st);
+
+// launch_gather plus the float32 advantage arena d_adv_tok_dst, made from field mask_field (1-byte
+// elements) and the per-sequence advantages; the workgroups that make it also move the mask.
+hipError_t launch_gather_advantage(int32_t n_seq, const FieldTable& ft, int mask_field, const int32_t* d_perm,
+                                   const float* d_adv_seq, float* d_adv_tok_dst, int64_t dst_capacity,
+                                   const int64_t* d_dst_tok_off, const Workspace& ws, hipStream_t st);
 
 // Granule tables (ws.gran_first, ws.gran_rec) from slot starts d_dst_tok_off[0..n_seq] and the
 // per-slot descriptors in ws; *ws.plan_ok == 0 makes them empty.

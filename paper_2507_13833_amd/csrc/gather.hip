@@ -369,6 +369,212 @@ __device__ __forceinline__ void move_wave_sparse(const FieldDesc& fd, int n_src,
     }
 }
 
+// ---------------------------------------------------------------- per-token advantage made on the way
+// The advantage field of the training layout without its rollout-layout copy: the value of a
+// token is its sequence's advantage where the sequence's mask byte is non-zero and +0.0f
+// elsewhere (selection, as in the advantage stage), so the gather reads the 1-byte mask where
+// it would read a 4-byte field.  These workgroups also move the mask field itself.
+struct AdvSynth {
+    const int32_t* perm;          // [N] slot -> sequence
+    const float*   adv_seq;       // [N] advantage of every sequence
+    float*         dst;           // float32 arena of the training layout
+};
+// It travels in the field table, in the entry behind the mask's (dst = the arena, src[0] = perm,
+// src[1] = adv_seq), and is read from there by the workgroups that need it: as kernel arguments of
+// their own the pointers would sit in scalar registers of every workgroup.
+__device__ __forceinline__ AdvSynth adv_synth_of(const FieldDesc& fd) {
+    AdvSynth s;
+    s.perm = reinterpret_cast<const int32_t*>(fd.src[0]);
+    s.adv_seq = reinterpret_cast<const float*>(fd.src[1]);
+    s.dst = reinterpret_cast<float*>(fd.dst);
+    return s;
+}
+
+__device__ __forceinline__ uint32_t sload1(const void* p) {
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wold-style-cast"
+    return *(const DC_CONSTANT uint32_t*)p;
+#pragma clang diagnostic pop
+}
+
+// Advantage bits of the output slots first .. first + REC_SLOTS - 1 (indices clamped into the
+// arrays whatever perm holds).  Two batches of scalar loads: one round trip each.
+__device__ __forceinline__ void slot_adv_scalar(const AdvSynth& s, int N, int first, uint32_t (&adv)[REC_SLOTS]) {
+    uint32_t q[REC_SLOTS];
+#pragma unroll
+    for (int k = 0; k < REC_SLOTS; ++k) q[k] = sload1(s.perm + min(first + k, N - 1));
+#pragma unroll
+    for (int k = 0; k < REC_SLOTS; ++k) adv[k] = sload1(s.adv_seq + min(q[k], (uint32_t)(N - 1)));
+}
+
+// The two aligned words that hold the 4 mask bytes at byte address p (any alignment), and the
+// output chunk of those 4 tokens.
+__device__ __forceinline__ void load_mask4(gptr p, uint32_t& w0, uint32_t& w1) {
+    const uintptr_t u = reinterpret_cast<uintptr_t>(p);
+    gptr a4 = reinterpret_cast<gptr>(u & ~uintptr_t(3));
+    w0 = gload4(a4);
+    w1 = (u & 3) ? gload4(a4 + 4) : 0u;
+}
+__device__ __forceinline__ u32x4 select_adv4(uint32_t w0, uint32_t w1, gptr p, uint32_t adv) {
+    const uint32_t m = __builtin_amdgcn_alignbyte(w1, w0, (uint32_t)reinterpret_cast<uintptr_t>(p) & 3u);
+    u32x4 o;
+    o.x = (m & 0x000000FFu) ? adv : 0u;
+    o.y = (m & 0x0000FF00u) ? adv : 0u;
+    o.z = (m & 0x00FF0000u) ? adv : 0u;
+    o.w = (m & 0xFF000000u) ? adv : 0u;
+    return o;
+}
+
+constexpr int ADV_TPC = 4;                    // tokens per 16-byte chunk of the float32 output
+constexpr int ADV_TPI = WAVE * ADV_TPC;       // tokens one wave instruction covers
+
+// The wave's granule of the advantage arena, slots from the granule's record, their advantage
+// bits in adv[].  `mk` is the mask field.
+__device__ __forceinline__ void adv_wave_sparse(const FieldDesc& mk, int n_src, const AdvSynth& s,
+                                                const uint32_t (&adv)[REC_SLOTS], const u32x16& rec, int64_t wave_begin,
+                                                int32_t limit) {
+    const int lane = threadIdx.x & (WAVE - 1);
+    gptr_w dst = reinterpret_cast<gptr_w>(reinterpret_cast<uintptr_t>(s.dst) + (wave_begin << 2));
+
+    const char* base[REC_SLOTS];                           // one batch of scalar loads
+#pragma unroll
+    for (int k = 0; k < REC_SLOTS; ++k)
+        base[k] = n_src > 1 ? mk.src[((int32_t)rec[4 * k + 1] >> LENSH_SHIFT) & (DC_MAX_SRC_SHARDS - 1)] : mk.src[0];
+    SlotS e[REC_SLOTS];                                    // ad: byte address of the granule's token 0 in the mask
+#pragma unroll
+    for (int k = 0; k < REC_SLOTS; ++k) {
+        const int32_t st = (int32_t)rec[4 * k], ls = (int32_t)rec[4 * k + 1];
+        const int64_t so = (int64_t)((uint64_t)rec[4 * k + 2] | ((uint64_t)rec[4 * k + 3] << 32));
+        e[k].st = st;
+        e[k].en = st + (ls & LEN_MASK);
+        e[k].ad = reinterpret_cast<int64_t>(base[k]) + (so - st);
+    }
+
+    constexpr int NU = GATHER_GRAN / ADV_TPI;              // 4 chunks per lane
+    uint32_t in_mask = 0, bnd_mask = 0;
+    gptr from[NU];
+    uint32_t av[NU];
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+        const int32_t lo = u * ADV_TPI;
+        const int32_t c0 = lo + lane * ADV_TPC;
+        int32_t s_en = INT32_MIN;
+        int64_t s_ad = 0;
+        uint32_t s_av = 0;
+#pragma unroll
+        for (int k = 0; k < REC_SLOTS; ++k)
+            if (lo >= e[k].st) { s_en = e[k].en; s_ad = e[k].ad; s_av = adv[k]; }
+        if (s_en >= lo + ADV_TPI && lo + ADV_TPI <= limit) {       // uniform: one slot serves the instruction
+            in_mask |= 1u << u;
+            from[u] = reinterpret_cast<gptr>(s_ad + c0);
+            av[u] = s_av;
+        } else {
+            int32_t e_sel = INT32_MIN;
+            int64_t a_sel = 0;
+            uint32_t v_sel = 0;
+#pragma unroll
+            for (int k = 0; k < REC_SLOTS; ++k)
+                if (c0 >= e[k].st) { e_sel = e[k].en; a_sel = e[k].ad; v_sel = adv[k]; }
+            const bool in = c0 + ADV_TPC <= e_sel && c0 + ADV_TPC <= limit;
+            if (in) in_mask |= 1u << u;
+            else if (c0 < limit) bnd_mask |= 1u << u;
+            from[u] = reinterpret_cast<gptr>(a_sel + c0);
+            av[u] = v_sel;
+        }
+    }
+    uint32_t w0[NU], w1[NU];
+#pragma unroll
+    for (int u = 0; u < NU; ++u)
+        if (in_mask & (1u << u)) load_mask4(from[u], w0[u], w1[u]);
+#pragma unroll
+    for (int u = 0; u < NU; ++u)
+        if (in_mask & (1u << u)) gstore16(dst + (u * WAVE + lane) * 16, select_adv4(w0[u], w1[u], from[u], av[u]));
+    // ---- chunks that touch a slot boundary, padding or the arena end: token by token ----
+    if (__ballot(bnd_mask != 0) == 0ull) return;                             // uniform
+#pragma unroll 1
+    for (int u = 0; u < NU; ++u) {
+        const bool mine = (bnd_mask >> u) & 1u;
+        if (__ballot(mine) == 0ull) continue;                                // uniform
+        const int32_t c0 = u * ADV_TPI + lane * ADV_TPC;
+        uint32_t val[ADV_TPC], sel[ADV_TPC];
+        bool ok[ADV_TPC];
+#pragma unroll
+        for (int r = 0; r < ADV_TPC; ++r) {
+            const int32_t t = c0 + r;
+            int32_t e_sel = INT32_MIN;
+            int64_t a_sel = 0;
+            sel[r] = 0;
+#pragma unroll
+            for (int k = 0; k < REC_SLOTS; ++k)
+                if (t >= e[k].st) { e_sel = e[k].en; a_sel = e[k].ad; sel[r] = adv[k]; }
+            ok[r] = mine && t < e_sel && t < limit;
+            val[r] = 0;
+            if (ok[r]) val[r] = load_elem(0, reinterpret_cast<gptr>(a_sel + t));
+        }
+#pragma unroll
+        for (int r = 0; r < ADV_TPC; ++r)
+            if (ok[r]) store_elem(2, dst + ((int64_t)(c0 + r) << 2), val[r] ? sel[r] : 0u);
+    }
+}
+
+// The same for a tile with many short sequences: slots staged in LDS (whole workgroup).
+__device__ __forceinline__ void adv_tile_dense(const GatherArgs& a, SegLds& sg, uint32_t* sg_adv, const char* const* src,
+                                               const AdvSynth& s, int seg_first, int seg_last, int64_t tile_begin,
+                                               int32_t tile_len) {
+    const int tid = threadIdx.x;
+    const int N = a.n_seq;
+    gptr_w dst = reinterpret_cast<gptr_w>(reinterpret_cast<uintptr_t>(s.dst) + (tile_begin << 2));
+    int seg_base = seg_first;
+    int32_t pass_begin = 0;
+    for (;;) {
+        stage_slots(a, sg, src, 0, seg_base, seg_last, tile_begin);          // addresses in mask bytes
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int k = q * SEG_BATCH + tid;
+            const int j = seg_base + k;
+            if (q == 0 || tid < SEG_AHEAD) {
+                uint32_t v = 0;
+                if (j <= seg_last) {
+                    const uint32_t sq = min((uint32_t)s.perm[j], (uint32_t)(N - 1));
+                    v = __float_as_uint(s.adv_seq[sq]);
+                }
+                sg_adv[k] = v;
+            }
+        }
+        __syncthreads();
+        const int n_left = seg_last - seg_base + 1;
+        const int n_all = min(n_left, NSEG);
+        const bool more = n_left > SEG_BATCH && sg.start[SEG_BATCH] < tile_len;
+        const int32_t pass_end = more ? sg.start[SEG_BATCH] : tile_len;
+#pragma unroll 1
+        for (int u = 0; u < GATHER_TILE_TOKENS / (GATHER_BLOCK * ADV_TPC); ++u) {
+            const int32_t c0 = (tid + u * GATHER_BLOCK) * ADV_TPC;
+            if (c0 < pass_begin || c0 >= pass_end) continue;
+            int k = find_seg(sg.start, n_all, c0);
+            if (k >= 0 && c0 + ADV_TPC <= sg.end[k] && c0 + ADV_TPC <= tile_len) {
+                gptr ad = reinterpret_cast<gptr>(sg.addr[k] + c0);
+                uint32_t w0, w1;
+                load_mask4(ad, w0, w1);
+                gstore16(dst + (tid + u * GATHER_BLOCK) * 16, select_adv4(w0, w1, ad, sg_adv[k]));
+            } else {
+                for (int r = 0; r < ADV_TPC; ++r) {
+                    const int32_t tok = c0 + r;
+                    if (tok >= tile_len) break;
+                    while (k + 1 < n_all && sg.start[k + 1] <= tok) ++k;
+                    if (k >= 0 && tok < sg.end[k]) {
+                        const uint32_t m = load_elem(0, reinterpret_cast<gptr>(sg.addr[k] + tok));
+                        store_elem(2, dst + ((int64_t)tok << 2), m ? sg_adv[k] : 0u);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        if (!more) break;
+        seg_base += SEG_BATCH;
+        pass_begin = pass_end;
+    }
+}
+
 // ---------------------------------------------------------------- the kernel
 // The tile `tile` of carrier field fc.  BACK = false: the forward direction, fields as the
 // table gives them.  BACK = true: the reverse direction, destination = the field's rollout
@@ -427,6 +633,68 @@ __global__ __launch_bounds__(GATHER_BLOCK) void gather_kernel(GatherArgs a, Fiel
     move_tile<false>(a, ft, blockIdx.x % a.tiles, blockIdx.x / a.tiles, 0);
 }
 
+// The tile `tile` of the advantage arena, then the same tile of the mask field.
+__device__ __forceinline__ void adv_tile(const GatherArgs& a, const FieldTable& ft, uint32_t mask_field, uint32_t tile) {
+    __shared__ SegLds sg;
+    __shared__ uint32_t sg_adv[NSEG];
+    __shared__ const char* src[DC_MAX_SRC_SHARDS];
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / WAVE));
+    const int N = a.n_seq;
+    const int64_t tile_begin = (int64_t)tile * GATHER_TILE_TOKENS;
+    const int64_t g0 = (int64_t)tile * GRAN_PER_TILE;
+    const u32x8 F = sload8(a.gran_first + g0);
+    const u32x16 rec = sload16(a.gran_rec + g0 + w);
+    const int first = (int)F[0];
+    if (first < 0 || first >= N) return;
+    bool dense = false;
+#pragma unroll
+    for (int i = 0; i < GRAN_PER_TILE; ++i)
+        dense = dense || ((int)F[i] < N && min((int)F[i + 1], N - 1) - (int)F[i] + 1 > REC_SLOTS);
+    const int32_t limit = (int32_t)min((int64_t)GATHER_TILE_TOKENS, a.capacity - tile_begin);
+    const int32_t wave_limit = min(limit - w * GATHER_GRAN, GATHER_GRAN);
+    const int last = min(max((int)F[GRAN_PER_TILE], first), N - 1);
+    int wave_first = (int)F[0];
+#pragma unroll
+    for (int i = 1; i < GRAN_PER_TILE; ++i)
+        if (w == i) wave_first = (int)F[i];
+
+    const FieldDesc& mk = ft.f[mask_field];
+    const AdvSynth s = adv_synth_of(ft.f[mask_field + 1]);
+    if (!dense) {
+        if (wave_limit > 0) {
+            uint32_t adv[REC_SLOTS];
+            slot_adv_scalar(s, N, wave_first, adv);
+            adv_wave_sparse(mk, ft.n_src, s, adv, rec, tile_begin + w * GATHER_GRAN, wave_limit);
+            // the record once more (a scalar-cache hit) rather than 16 scalar registers held across the part above
+            int w_again = w;
+            asm volatile("" : "+s"(w_again));
+            const u32x16 rec2 = sload16(a.gran_rec + g0 + w_again);
+            move_wave_sparse<false>(mk, ft.n_src, nullptr, nullptr, 0, rec2, tile_begin + w * GATHER_GRAN, wave_limit);
+        }
+    } else {
+        if (threadIdx.x < DC_MAX_SRC_SHARDS) src[threadIdx.x] = mk.src[threadIdx.x];
+        __syncthreads();
+        adv_tile_dense(a, sg, sg_adv, src, s, first, last, tile_begin, limit);
+        move_tile_dense(a, sg, src, 0, mk.dst, first, last, tile_begin, limit);
+    }
+}
+
+// gather_kernel with one more "carrier" behind the others: the advantage arena, made from the mask.
+__global__ __launch_bounds__(GATHER_BLOCK) void gather_adv_kernel(GatherArgs a, FieldTable ft, uint32_t mask_field) {
+    // The advantage tiles write four bytes for every byte they read; a run of them at the end of the
+    // grid would be a pure write stream, which the memory serves more slowly than a mix.  They are
+    // dealt in between the others instead: every (n_carriers + 1)-th workgroup takes one.
+    const uint32_t per = a.n_carriers + 1;
+    const uint32_t round = blockIdx.x / per, r = blockIdx.x % per;
+    if (r == a.n_carriers) {
+        adv_tile(a, ft, mask_field, (uint32_t)__builtin_amdgcn_readfirstlane((int)round));
+    } else {
+        const uint32_t idx = round * a.n_carriers + r;
+        move_tile<false>(a, ft, (uint32_t)__builtin_amdgcn_readfirstlane((int)(idx % a.tiles)),
+                         (uint32_t)__builtin_amdgcn_readfirstlane((int)(idx / a.tiles)), 0);
+    }
+}
+
 // Reverse direction: the same grid over the tiles of all rollout buffers, one behind the other.
 // a.dst_tok_off, a.slot_* and the granule tables arrive as the arrays of all segments; the
 // workgroup narrows them to its segment's part.
@@ -449,21 +717,25 @@ __global__ __launch_bounds__(GATHER_BLOCK) void gather_back_kernel(GatherArgs a,
 }
 
 // Field table with the 4-byte fields first (they carry, the others ride) and the grid's shape.
-static void order_fields(const FieldTable& ft, int64_t tiles, FieldTable* sorted, GatherArgs* a) {
+// skip >= 0: that field goes behind all others and neither carries nor rides (its place is returned).
+static int order_fields(const FieldTable& ft, int64_t tiles, FieldTable* sorted, GatherArgs* a, int skip = -1) {
     *sorted = ft;
     int n = 0, n_wide = 0;
     for (int pass = 0; pass < 2; ++pass)
         for (int f = 0; f < ft.n_fields; ++f)
-            if ((ft.f[f].elem_bytes == 4) == (pass == 0)) {
+            if (f != skip && (ft.f[f].elem_bytes == 4) == (pass == 0)) {
                 sorted->f[n++] = ft.f[f];
                 if (pass == 0) n_wide = n;
             }
+    const int n_moved = n;
+    if (skip >= 0) sorted->f[n] = ft.f[skip];
     // riding pays when the carriers alone give the chip several rounds of workgroups; a small
     // batch needs every workgroup it can get
     const bool ride = n_wide > 0 && tiles * n_wide >= GATHER_RIDE_MIN_WGS;
-    a->n_carriers = (uint32_t)(ride ? n_wide : ft.n_fields);
-    a->n_riders = (uint32_t)ft.n_fields - a->n_carriers;
+    a->n_carriers = (uint32_t)(ride ? n_wide : n_moved);
+    a->n_riders = (uint32_t)n_moved - a->n_carriers;
     a->tiles = (uint32_t)tiles;
+    return n_moved;
 }
 
 hipError_t launch_gather(int32_t n_seq, const FieldTable& ft, int64_t dst_capacity,
@@ -484,6 +756,35 @@ hipError_t launch_gather(int32_t n_seq, const FieldTable& ft, int64_t dst_capaci
     FieldTable sorted;
     order_fields(ft, tiles, &sorted, &a);
     hipLaunchKernelGGL(gather_kernel, dim3((unsigned)(tiles * a.n_carriers)), dim3(GATHER_BLOCK), 0, st, a, sorted);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_advantage(int32_t n_seq, const FieldTable& ft, int mask_field, const int32_t* d_perm,
+                                   const float* d_adv_seq, float* d_adv_tok_dst, int64_t dst_capacity,
+                                   const int64_t* d_dst_tok_off, const Workspace& ws, hipStream_t st) {
+    if (n_seq == 0 || dst_capacity == 0) return hipSuccess;
+    if (mask_field < 0 || mask_field >= ft.n_fields || ft.f[mask_field].elem_bytes != 1) return hipErrorInvalidValue;
+    GatherArgs a;
+    a.n_seq = n_seq;
+    a.capacity = dst_capacity;
+    a.dst_tok_off = d_dst_tok_off;
+    a.slot_src_off = ws.slot_src_off;
+    a.slot_len = ws.slot_len;
+    a.slot_shard = ws.slot_shard;
+    a.gran_first = ws.gran_first;
+    a.gran_rec = ws.gran_rec;
+    const int64_t tiles = (dst_capacity + GATHER_TILE_TOKENS - 1) / GATHER_TILE_TOKENS;
+    if (tiles * (ft.n_fields + 1) > 0x7FFFFFFFLL || tiles * GRAN_PER_TILE + GRAN_PER_TILE + 1 > ws.n_gran)
+        return hipErrorInvalidValue;
+    FieldTable sorted;
+    const int at = order_fields(ft, tiles, &sorted, &a, mask_field);          // the mask's place; behind it:
+    FieldDesc& syn = sorted.f[at + 1];
+    syn.dst = reinterpret_cast<char*>(d_adv_tok_dst);
+    syn.elem_bytes = 4;
+    syn.src[0] = reinterpret_cast<const char*>(d_perm);
+    syn.src[1] = reinterpret_cast<const char*>(d_adv_seq);
+    hipLaunchKernelGGL(gather_adv_kernel, dim3((unsigned)(tiles * (a.n_carriers + 1))), dim3(GATHER_BLOCK), 0, st, a,
+                       sorted, (uint32_t)at);
     return hipGetLastError();
 }
 

@@ -76,6 +76,10 @@ class DeviceBatch:
             (self.adv_tok_src if n == "adv_tok" else self.src_fields[n], self.dst_fields[n], self.elem_bytes[n])
             for n in names])
         self.payload_bytes_per_token = sum(self.elem_bytes.values())
+        # the same without adv_tok: dc_gather_advantage makes that arena from the mask and adv_seq
+        self.moved_names = [n for n in names if n != "adv_tok"]
+        self.moved_fields = B.Fields([(self.src_fields[n], self.dst_fields[n], self.elem_bytes[n])
+                                      for n in self.moved_names])
 
     # ---- the calls of one step ----
     def group_advantage(self, per_token: bool = True, stream=None) -> None:
@@ -95,6 +99,12 @@ class DeviceBatch:
     def gather(self) -> None:
         B.dc_gather(self.prm, self.source, self.fields, self.capacity, self.dst_tok_off, self.ws,
                     self.ws_bytes, self.status)
+
+    def gather_advantage(self) -> None:
+        """dc_gather of every field but adv_tok; the adv_tok arena is made from the mask and adv_seq."""
+        B.dc_gather_advantage(self.prm, self.source, self.moved_fields, self.moved_names.index("mask"), self.perm,
+                              self.adv_seq, self.dst_fields["adv_tok"].view(torch.float32), self.capacity,
+                              self.dst_tok_off, self.ws, self.ws_bytes, self.status)
 
     def repack(self) -> None:
         B.dc_repack(self.prm, self.source, self.seq_len, self.perm, self.shard_seq_off, self.fields,
@@ -123,6 +133,17 @@ class DeviceBatch:
         if gather_events is not None:
             gather_events[0].record()
         self.gather()
+        if gather_events is not None:
+            gather_events[1].record()
+
+    def step_no_rollout_adv(self, gather_events=None) -> None:
+        """The pass without the rollout-layout copy of the per-token advantages: the fused launch
+        computes the per-sequence advantages only, the gather makes the per-token field."""
+        self.balance_group_advantage(per_token=False)
+        self.plan()
+        if gather_events is not None:
+            gather_events[0].record()
+        self.gather_advantage()
         if gather_events is not None:
             gather_events[1].record()
 

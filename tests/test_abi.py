@@ -167,6 +167,34 @@ def test_scatter_host_errors(lib):
     assert B.dc_scatter_workspace_bytes(prm, B.Source([0, 5], [64], FAKE)) == 0
 
 
+def test_gather_advantage_host_errors(lib):
+    prm = B.make_params(8, 4, 100)
+    src = B.Source([0, 8], [64], FAKE)
+    ws = B.dc_workspace_bytes(prm, 64)
+    fields = B.Fields([([0x2000], 0x3000, 4), ([0x4000], 0x5000, 1)])
+    call = lambda f, mask_field, perm=FAKE, adv=FAKE, dst=0x6000, ws_ptr=0x10000, ws_bytes=ws: B.dc_gather_advantage(
+        prm, src, f, mask_field, perm, adv, dst, 64, FAKE, ws_ptr, ws_bytes, FAKE, stream=0)
+    for mask_field in (0, 2, -1):                            # a 4-byte field, beyond the table, negative
+        with pytest.raises(B.DcError) as e:
+            call(fields, mask_field)
+        assert e.value.code == B.DC_ERR_INVALID_ARG
+    with pytest.raises(B.DcError) as e:                      # no fields at all: no mask
+        call(B.Fields([]), 0)
+    assert e.value.code == B.DC_ERR_INVALID_ARG
+    with pytest.raises(B.DcError) as e:                      # no per-sequence advantages
+        call(fields, 1, adv=None)
+    assert e.value.code == B.DC_ERR_INVALID_ARG
+    with pytest.raises(B.DcError) as e:                      # no permutation
+        call(fields, 1, perm=None)
+    assert e.value.code == B.DC_ERR_INVALID_ARG
+    with pytest.raises(B.DcError) as e:                      # advantage arena not 16-byte aligned
+        call(fields, 1, dst=0x6004)
+    assert e.value.code == B.DC_ERR_INVALID_ARG
+    with pytest.raises(B.DcError) as e:                      # workspace too small
+        call(fields, 1, ws_bytes=16)
+    assert e.value.code == B.DC_ERR_WORKSPACE
+
+
 def test_gae_host_errors(lib):
     prm = B.make_params(8, 4, 100)
     src = B.Source([0, 8], [64], FAKE)

@@ -348,6 +348,82 @@ def test_identity_plan_describes_the_rollout_layout_in_place():
     assert np.array_equal(np.diff(sto), w.src_shard_tokens)
 
 
+# ---------------------------------------------------------------- per-token advantages made by the gather
+def check_gather_advantage(w, align=1, cap=0, label="", against_copy=False):
+    """dc_gather_advantage: the training-layout advantage field straight from adv_seq and the mask, against
+    the oracle's definition (broadcast in the rollout layout, then gathered as one more field)."""
+    torch, binding, runner = _gpu()
+    print(f"[parity] gather_advantage {label or w.name}: N={w.n_seq} P={w.n_shards} T={w.total_tokens} "
+          f"align={align} cap={cap}", flush=True)
+    d = runner.DeviceBatch(w, align_tokens=align, cap=cap, poison=True)
+    d.step_no_rollout_adv()
+    torch.cuda.synchronize()
+    assert d.read_status() == 0
+    bal, adv, adv_tok, pl = oracle_step(w, align, cap)
+    assert np.array_equal(d.perm.cpu().numpy(), bal.perm)
+    np.testing.assert_allclose(d.adv_seq.cpu().numpy(), adv, rtol=RTOL, atol=ATOL)
+    assert np.array_equal(d.dst_tok_off.cpu().numpy(), pl.dst_tok_off)
+    for t in d.adv_tok_src:                                   # no per-token data in the rollout layout
+        assert not t.any()
+    arena = d.capacity
+    valid = np.zeros(arena, bool)
+    for k in range(w.n_shards):
+        valid[pl.shard_tok_off[k]: pl.shard_tok_off[k] + bal.shard_load[k]] = True
+    for f in w.fields:                                        # the other fields (the mask among them) as ever
+        want = oracle.gather(w.seq_len, bal.perm, w.src_tok_off, w.src_shard_seq_off, f.shards, pl.dst_tok_off, arena)
+        got = d.dst_fields[f.name].cpu().numpy().view(want.dtype)
+        assert np.array_equal(got[valid], want[valid]), f.name
+        poison = np.frombuffer(bytes([0x5A] * f.elem_bytes), dtype=want.dtype)[0]
+        assert np.all(got[~valid] == poison), f.name
+    want = oracle.gather(w.seq_len, bal.perm, w.src_tok_off, w.src_shard_seq_off, adv_tok, pl.dst_tok_off, arena)
+    got = d.dst_fields["adv_tok"].cpu().numpy().view(np.float32)
+    np.testing.assert_allclose(got[valid], want[valid], rtol=RTOL, atol=ATOL)
+    assert np.all(got[~valid].view(np.uint32) == 0x5A5A5A5A)  # padding and the arena's tail are not written
+    mask_dst = d.dst_fields["mask"].cpu().numpy()
+    assert not got.view(np.uint32)[valid & (mask_dst == 0)].any()       # +0.0 exactly where no loss is taken
+    # every token of a slot carries the bits of ITS sequence's advantage
+    g_adv = d.adv_seq.cpu().numpy().view(np.uint32)
+    for j in np.random.default_rng(2).integers(0, w.n_seq, 64) if w.n_seq else []:
+        i = bal.perm[j]
+        seg = got.view(np.uint32)[pl.dst_tok_off[j]: pl.dst_tok_off[j] + w.seq_len[i]]
+        m = mask_dst[pl.dst_tok_off[j]: pl.dst_tok_off[j] + w.seq_len[i]]
+        assert np.all(seg[m != 0] == g_adv[i])
+    if against_copy:                                          # and the arena equals the copied one bit for bit
+        d2 = runner.DeviceBatch(w, align_tokens=align, cap=cap, poison=True)
+        d2.step_fused()
+        torch.cuda.synchronize()
+        for k in d.dst_fields:
+            assert torch.equal(d.dst_fields[k], d2.dst_fields[k]), k
+    return d
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_gather_advantage_full_config(cfg):
+    check_gather_advantage(workloads.make_workload(cfg), label=f"config {cfg}", against_copy=cfg in (2, 4, 5))
+
+
+def test_gather_advantage_shapes():
+    rng = np.random.default_rng(21)
+    # many slots per tile (slots staged in LDS), several passes per tile, rollout shards, padding between shards
+    check_gather_advantage(_custom(rng.integers(1, 9, 8192), 8, 16, 64, n_src=4), label="lengths 1..8", against_copy=True)
+    check_gather_advantage(_custom(np.ones(4096, np.int32), 4, 64, 7, n_src=2), align=5, label="all length 1")
+    check_gather_advantage(_custom(rng.integers(1, 3000, 1000), 5, 8, 4096, n_src=2), align=3, label="N=1000 align 3")
+    check_gather_advantage(_custom(rng.integers(1, 200, 2), 2, 2, 512), label="N=2")
+    check_gather_advantage(_custom(rng.integers(1, 70000, 63 * 3), 3, 63, 70000), align=4096, label="P=63 align 4096")
+    # records next to LDS-staged tiles, narrow fields riding
+    lens = np.concatenate([rng.integers(3500, 4500, 8192), rng.integers(1, 120, 8192)])
+    rng.shuffle(lens)
+    check_gather_advantage(_custom(lens, 16, 64, 16384, n_src=2), label="8192 long + 8192 short", against_copy=True)
+    # the mask is the only field; mask bytes other than 0 / 1 select like 1
+    w = _custom(rng.integers(1, 900, 512), 8, 4, 4096, fields=())
+    w.fields[0].shards[0][::3] *= 0x80
+    check_gather_advantage(w, label="mask only, bytes 0 / 1 / 0x80")
+    # sequences of 2^24 tokens
+    L = 1 << 24
+    check_gather_advantage(_custom(np.array([L, 5, L - 3, 100], np.int32), 2, 2, 1 << 25, fields=("i32",)),
+                           label="sequences of 2^24 tokens")
+
+
 # ---------------------------------------------------------------- reverse path
 def check_scatter(w, label=""):
     """gather, then scatter the training arenas back: every rollout buffer must equal what the
