@@ -32,7 +32,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # out); valid only for the kernel sources with the digest below (profiles/ has the runs).
 TRAFFIC = {
     # config: (fetch bytes + write bytes per gather launch, digest of csrc/gather.hip + csrc/dc_internal.h)
-    5: (1044586100 + 985039100, "1100c7926e5412e2"),     # profiles/hbm_traffic_config5_pmc.txt
+    5: (1044623400 + 985040700, "8bf74f47e6165089"),     # profiles/hbm_traffic_config5_pmc.txt
+}
+TRAFFIC_ADV = {                                          # the same for dc_gather_advantage's kernel
+    5: (867732400 + 983720700, "8bf74f47e6165089"),
 }
 
 
@@ -223,8 +226,11 @@ def main() -> int:
         ppo = {"call": "dc_gae", **res}
 
     traffic = None
-    if not args.no_rollout_adv and args.config in TRAFFIC and TRAFFIC[args.config][1] == kernel_digest():
-        traffic = TRAFFIC[args.config][0]
+    table = TRAFFIC_ADV if args.no_rollout_adv else TRAFFIC
+    if args.config in table and table[args.config][1] == kernel_digest():
+        traffic = table[args.config][0]
+    if variant is not None and args.config in TRAFFIC_ADV and TRAFFIC_ADV[args.config][1] == kernel_digest():
+        variant["traffic"] = TRAFFIC_ADV[args.config][0]
 
     out = {
         "metric": "repacked tokens/sec and achieved HBM GB/s (fraction of peak), 1 MI355X",

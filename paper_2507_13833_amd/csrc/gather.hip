@@ -100,6 +100,9 @@ __device__ __forceinline__ uint32_t gload4(gptr p) {
 __device__ __forceinline__ void gstore16(gptr_w p, u32x4 v) {
     __builtin_nontemporal_store(v, reinterpret_cast<g_u32x4*>(p));
 }
+__device__ __forceinline__ void gstore4(gptr_w p, uint32_t v) {
+    __builtin_nontemporal_store(v, reinterpret_cast<DC_GLOBAL uint32_t*>(p));
+}
 
 // 16 source bytes starting at byte address a (any alignment): dword loads from the address
 // rounded down to 4, plus the following dword when a is not a multiple of 4; realign()
@@ -373,7 +376,8 @@ __device__ __forceinline__ void move_wave_sparse(const FieldDesc& fd, int n_src,
 // The advantage field of the training layout without its rollout-layout copy: the value of a
 // token is its sequence's advantage where the sequence's mask byte is non-zero and +0.0f
 // elsewhere (selection, as in the advantage stage), so the gather reads the 1-byte mask where
-// it would read a 4-byte field.  These workgroups also move the mask field itself.
+// it would read a 4-byte field.  These workgroups also move the mask field itself, from the
+// bytes they have loaded anyway.
 struct AdvSynth {
     const int32_t* perm;          // [N] slot -> sequence
     const float*   adv_seq;       // [N] advantage of every sequence
@@ -415,8 +419,10 @@ __device__ __forceinline__ void load_mask4(gptr p, uint32_t& w0, uint32_t& w1) {
     w0 = gload4(a4);
     w1 = (u & 3) ? gload4(a4 + 4) : 0u;
 }
-__device__ __forceinline__ u32x4 select_adv4(uint32_t w0, uint32_t w1, gptr p, uint32_t adv) {
-    const uint32_t m = __builtin_amdgcn_alignbyte(w1, w0, (uint32_t)reinterpret_cast<uintptr_t>(p) & 3u);
+__device__ __forceinline__ uint32_t mask4_of(uint32_t w0, uint32_t w1, gptr p) {
+    return __builtin_amdgcn_alignbyte(w1, w0, (uint32_t)reinterpret_cast<uintptr_t>(p) & 3u);
+}
+__device__ __forceinline__ u32x4 select_adv4(uint32_t m, uint32_t adv) {
     u32x4 o;
     o.x = (m & 0x000000FFu) ? adv : 0u;
     o.y = (m & 0x0000FF00u) ? adv : 0u;
@@ -435,6 +441,7 @@ __device__ __forceinline__ void adv_wave_sparse(const FieldDesc& mk, int n_src, 
                                                 int32_t limit) {
     const int lane = threadIdx.x & (WAVE - 1);
     gptr_w dst = reinterpret_cast<gptr_w>(reinterpret_cast<uintptr_t>(s.dst) + (wave_begin << 2));
+    gptr_w mdst = reinterpret_cast<gptr_w>(reinterpret_cast<uintptr_t>(mk.dst) + wave_begin);
 
     const char* base[REC_SLOTS];                           // one batch of scalar loads
 #pragma unroll
@@ -488,7 +495,11 @@ __device__ __forceinline__ void adv_wave_sparse(const FieldDesc& mk, int n_src, 
         if (in_mask & (1u << u)) load_mask4(from[u], w0[u], w1[u]);
 #pragma unroll
     for (int u = 0; u < NU; ++u)
-        if (in_mask & (1u << u)) gstore16(dst + (u * WAVE + lane) * 16, select_adv4(w0[u], w1[u], from[u], av[u]));
+        if (in_mask & (1u << u)) {
+            const uint32_t m = mask4_of(w0[u], w1[u], from[u]);
+            gstore16(dst + (u * WAVE + lane) * 16, select_adv4(m, av[u]));
+            gstore4(mdst + (u * WAVE + lane) * 4, m);      // the mask's own move: the bytes are here already
+        }
     // ---- chunks that touch a slot boundary, padding or the arena end: token by token ----
     if (__ballot(bnd_mask != 0) == 0ull) return;                             // uniform
 #pragma unroll 1
@@ -513,17 +524,21 @@ __device__ __forceinline__ void adv_wave_sparse(const FieldDesc& mk, int n_src, 
         }
 #pragma unroll
         for (int r = 0; r < ADV_TPC; ++r)
-            if (ok[r]) store_elem(2, dst + ((int64_t)(c0 + r) << 2), val[r] ? sel[r] : 0u);
+            if (ok[r]) {
+                store_elem(2, dst + ((int64_t)(c0 + r) << 2), val[r] ? sel[r] : 0u);
+                store_elem(0, mdst + (c0 + r), val[r]);
+            }
     }
 }
 
 // The same for a tile with many short sequences: slots staged in LDS (whole workgroup).
 __device__ __forceinline__ void adv_tile_dense(const GatherArgs& a, SegLds& sg, uint32_t* sg_adv, const char* const* src,
-                                               const AdvSynth& s, int seg_first, int seg_last, int64_t tile_begin,
-                                               int32_t tile_len) {
+                                               const AdvSynth& s, char* mask_dst, int seg_first, int seg_last,
+                                               int64_t tile_begin, int32_t tile_len) {
     const int tid = threadIdx.x;
     const int N = a.n_seq;
     gptr_w dst = reinterpret_cast<gptr_w>(reinterpret_cast<uintptr_t>(s.dst) + (tile_begin << 2));
+    gptr_w mdst = reinterpret_cast<gptr_w>(reinterpret_cast<uintptr_t>(mask_dst) + tile_begin);
     int seg_base = seg_first;
     int32_t pass_begin = 0;
     for (;;) {
@@ -555,7 +570,9 @@ __device__ __forceinline__ void adv_tile_dense(const GatherArgs& a, SegLds& sg, 
                 gptr ad = reinterpret_cast<gptr>(sg.addr[k] + c0);
                 uint32_t w0, w1;
                 load_mask4(ad, w0, w1);
-                gstore16(dst + (tid + u * GATHER_BLOCK) * 16, select_adv4(w0, w1, ad, sg_adv[k]));
+                const uint32_t m = mask4_of(w0, w1, ad);
+                gstore16(dst + (tid + u * GATHER_BLOCK) * 16, select_adv4(m, sg_adv[k]));
+                gstore4(mdst + (tid + u * GATHER_BLOCK) * 4, m);
             } else {
                 for (int r = 0; r < ADV_TPC; ++r) {
                     const int32_t tok = c0 + r;
@@ -564,6 +581,7 @@ __device__ __forceinline__ void adv_tile_dense(const GatherArgs& a, SegLds& sg, 
                     if (k >= 0 && tok < sg.end[k]) {
                         const uint32_t m = load_elem(0, reinterpret_cast<gptr>(sg.addr[k] + tok));
                         store_elem(2, dst + ((int64_t)tok << 2), m ? sg_adv[k] : 0u);
+                        store_elem(0, mdst + tok, m);
                     }
                 }
             }
@@ -633,7 +651,7 @@ __global__ __launch_bounds__(GATHER_BLOCK) void gather_kernel(GatherArgs a, Fiel
     move_tile<false>(a, ft, blockIdx.x % a.tiles, blockIdx.x / a.tiles, 0);
 }
 
-// The tile `tile` of the advantage arena, then the same tile of the mask field.
+// The tile `tile` of the advantage arena and of the mask field.
 __device__ __forceinline__ void adv_tile(const GatherArgs& a, const FieldTable& ft, uint32_t mask_field, uint32_t tile) {
     __shared__ SegLds sg;
     __shared__ uint32_t sg_adv[NSEG];
@@ -665,17 +683,11 @@ __device__ __forceinline__ void adv_tile(const GatherArgs& a, const FieldTable& 
             uint32_t adv[REC_SLOTS];
             slot_adv_scalar(s, N, wave_first, adv);
             adv_wave_sparse(mk, ft.n_src, s, adv, rec, tile_begin + w * GATHER_GRAN, wave_limit);
-            // the record once more (a scalar-cache hit) rather than 16 scalar registers held across the part above
-            int w_again = w;
-            asm volatile("" : "+s"(w_again));
-            const u32x16 rec2 = sload16(a.gran_rec + g0 + w_again);
-            move_wave_sparse<false>(mk, ft.n_src, nullptr, nullptr, 0, rec2, tile_begin + w * GATHER_GRAN, wave_limit);
         }
     } else {
         if (threadIdx.x < DC_MAX_SRC_SHARDS) src[threadIdx.x] = mk.src[threadIdx.x];
         __syncthreads();
-        adv_tile_dense(a, sg, sg_adv, src, s, first, last, tile_begin, limit);
-        move_tile_dense(a, sg, src, 0, mk.dst, first, last, tile_begin, limit);
+        adv_tile_dense(a, sg, sg_adv, src, s, mk.dst, first, last, tile_begin, limit);
     }
 }
 
