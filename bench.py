@@ -138,9 +138,8 @@ def main() -> int:
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     gather_ms = sum(a.elapsed_time(b) for a, b in ev) / args.steps
-    if args.no_rollout_adv:
-        gather_bytes = gather_adv_bytes
-    achieved = gather_bytes / (gather_ms * 1e-3) / 1e9
+    timed_gather_bytes = gather_adv_bytes if args.no_rollout_adv else gather_bytes
+    achieved = timed_gather_bytes / (gather_ms * 1e-3) / 1e9
 
     # the same step with dc_gather_advantage in place of the per-token advantage pass + dc_gather
     # (a shorter run of its own, outside the timed region)
@@ -172,33 +171,30 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    # per-stage device times (events around each call, outside the timed region)
+    def device_ms(call, n=12, warm=3):
+        """Mean device time of call(buffer set), n calls queued back to back between two events (so the
+        host's marshalling of one call overlaps the previous call's kernels), after warm untimed calls."""
+        for i in range(warm):
+            call(sets[i % len(sets)])                   # a kernel's first launch in a process loads its code
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(n):
+            call(sets[i % len(sets)])
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    # per-stage device times, outside the timed region
     stage = {}
     for name in ("group_advantage", "balance", "plan", "gather"):
-        getattr(sets[0], name)()                        # a kernel's first launch in a process loads its code
-        torch.cuda.synchronize()
-        tot = 0.0
-        for i in range(6):
-            b = sets[i % len(sets)]
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(); getattr(b, name)(); e1.record()
-            torch.cuda.synchronize()
-            tot += e0.elapsed_time(e1)
-        stage[name + "_ms"] = round(tot / 6, 4)
+        stage[name + "_ms"] = round(device_ms(lambda b, name=name: getattr(b, name)()), 4)
 
     # the reverse path (training layout -> rollout layout), whole dc_scatter call, outside the timed region
-    tot = 0.0
-    for i in range(6):
-        b = sets[i % len(sets)]
-        if not hasattr(b, "back"):
-            b.prepare_scatter()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(); b.scatter(); e1.record()
-        torch.cuda.synchronize()
-        if i >= 2:
-            tot += e0.elapsed_time(e1)
+    for b in sets:
+        b.prepare_scatter()
+    scatter_ms = device_ms(lambda b: b.scatter())
     assert all(s.read_status() == 0 for s in sets)
-    scatter_ms = tot / 4
     reverse = {"call": "dc_scatter", "ms": round(scatter_ms, 4), "algorithmic_bytes": gather_bytes,
                "achieved": gather_bytes / (scatter_ms * 1e-3) / 1e9, "unit": "GB/s",
                "frac": gather_bytes / (scatter_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
@@ -207,18 +203,10 @@ def main() -> int:
     ppo = None
     if "value" in sets[0].src_fields and sets[0].elem_bytes.get("value") == 4:
         res = {}
+        for b in sets:
+            b.prepare_gae()
         for tag, klc, bpt_gae in (("no_kl", 0.0, 13), ("kl", 0.05, 21)):
-            tot = 0.0
-            for i in range(6):
-                b = sets[i % len(sets)]
-                if not hasattr(b, "gae_adv"):
-                    b.prepare_gae()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record(); b.gae(1.0, 0.95, klc); e1.record()
-                torch.cuda.synchronize()
-                if i >= 2:
-                    tot += e0.elapsed_time(e1)
-            ms = tot / 4
+            ms = device_ms(lambda b, klc=klc: b.gae(1.0, 0.95, klc))
             res[tag] = {"ms": round(ms, 4), "algorithmic_bytes": bpt_gae * T,
                         "achieved": bpt_gae * T / (ms * 1e-3) / 1e9, "unit": "GB/s",
                         "frac": bpt_gae * T / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
@@ -250,7 +238,7 @@ def main() -> int:
                                      if args.no_rollout_adv else "dc_balance_group_advantage, dc_plan, dc_gather")},
         "roofline": {"bound": "hbm", "kernel": "gather_adv_kernel" if args.no_rollout_adv else "gather_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "algorithmic_bytes_per_launch": gather_bytes, "avg_launch_ms": gather_ms},
+                     "algorithmic_bytes_per_launch": timed_gather_bytes, "avg_launch_ms": gather_ms},
         "stages": stage,
         "no_rollout_adv": variant,
         "reverse": reverse,
