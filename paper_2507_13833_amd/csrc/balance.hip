@@ -26,7 +26,9 @@
 //   c) a worker that takes an item notes the item's place inside P_k (its item count before) and
 //      its own id (in LDS, where the item's length was); when all items are placed, a scan of the
 //      workers' counts gives the start of every P_k and one pass writes perm (P_0, P_1, ... each in
-//      insertion order) and the worker of every sequence.
+//      insertion order) and the worker of every sequence.  When N = P * C (the algorithm as printed)
+//      every P_k ends with C items, the items are filed per worker as they are placed, and both
+//      outputs are written in index order.
 #include "advantage_device.h"
 #include "dc_lanes.h"
 
@@ -37,10 +39,17 @@ constexpr int BAL_WAVES = BAL_BLOCK / WAVE;
 constexpr int BAL_ROUNDS = DC_MAX_SEQ / BAL_BLOCK;       // 64-item rounds per wave at the size limit
 constexpr uint32_t KEY_FULL = 0xFFFFFFC0u;               // | worker id: full (or absent) worker
 
+// When every partition ends with exactly C items its place in perm is known beforehand, and wave 0 files
+// the items per worker (worker k's row starts at k * pitch) as it places them; the pitch is C rounded up
+// to 2 mod 4, so that the 64 workers' rows start in 64 different LDS banks.
+constexpr int PLACE_PAD = 4 * WAVE;
+__device__ __forceinline__ int place_pitch(int C) { return C + ((2 - C) & 3); }
+
 struct BalLds {
     int32_t  keys[DC_MAX_SEQ];            // sequence lengths (sanitised)
-    uint16_t idx_a[DC_MAX_SEQ];           // sort ping
-    uint16_t idx_b[DC_MAX_SEQ];           // sort pong; after the sort the free one holds the worker of each step
+    uint16_t idx_a[DC_MAX_SEQ + PLACE_PAD];   // sort ping
+    uint16_t idx_b[DC_MAX_SEQ + PLACE_PAD];   // sort pong; after the sort the free one holds every item's place in its
+                                              // partition, or (all partitions of equal size) the partitions themselves
     alignas(16) uint32_t cnt[256 * BAL_WAVES];   // [digit][wave] counters of the sort passes; afterwards the workers' tables
     int32_t  red[2 * BAL_WAVES];
     uint32_t tmp32[16];
@@ -123,12 +132,14 @@ __device__ __forceinline__ void counting_pass(BalLds& L, int N, int rounds, Digi
 }
 
 // The assignment rounds (wave 0 only).  WIDTH = 16, 32 or 64 >= P lanes take part in the sort.
-// step_slot[t] = place of item I[t] inside its worker's partition; the worker of a placed sequence
-// takes the place of its length in keys[] (an item's length is read for the last time before the item
-// is placed); worker_count[k] = |P_k|.  Returns the number of items placed (N).
+// pitch == 0: step_slot[t] = place of item I[t] inside its worker's partition; pitch > 0 (every
+// partition will hold exactly C items): step_slot[k * pitch + c] = the c-th item of worker k.
+// The worker of a placed sequence takes the place of its length in keys[] (an item's length is
+// read for the last time before the item is placed); worker_count[k] = |P_k|.  Returns the number of
+// items placed (N).
 template <int WIDTH>
 __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, const uint16_t* sorted,
-                                          int32_t max_len, uint16_t* step_slot,
+                                          int32_t max_len, uint16_t* step_slot, int pitch,
                                           int32_t* worker_count, int64_t* __restrict__ shard_load) {
     const uint32_t lane = threadIdx.x;
     // Keys of open workers lie within one longest sequence (G, in key units) of the smallest, which
@@ -190,7 +201,8 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, co
                 const uint32_t pm = wave_excl_scan_umin(mine_exists ? newk : 0xFFFFFFFFu);
                 if (__ballot(mine_exists && sk < pm) != everyone) break;      // not everyone's turn: one general round
                 if (mine_exists) {
-                    step_slot[t] = (uint16_t)before;
+                    if (pitch) step_slot[(int)id * pitch + before] = (uint16_t)idx;
+                    else step_slot[t] = (uint16_t)before;
                     keys[idx] = (int32_t)id;                      // the item is placed: its length is not needed again
                 }
                 pos += P;
@@ -239,8 +251,10 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, co
         if (key <= thr) {                                         // my worker is among the m smallest
             const uint32_t nk = (recv & ~63u) | lane;
             const int mine = pos + (int)(recv & 63u);             // the item I took
-            step_slot[mine] = (uint16_t)count;
-            keys[sorted[mine]] = (int32_t)lane;               // the item is placed: its length is not needed again
+            const uint32_t u_mine = sorted[mine];
+            if (pitch) step_slot[(int)lane * pitch + count] = (uint16_t)u_mine;
+            else step_slot[mine] = (uint16_t)count;
+            keys[u_mine] = (int32_t)lane;                     // the item is placed: its length is not needed again
             load += (int64_t)((nk - key) >> 6);
             count += 1;
             key = (count == C) ? full : nk;
@@ -381,6 +395,8 @@ __device__ __forceinline__ void balance_body(BalLds& L, int32_t N, int32_t P, in
     }
     const uint16_t* sorted = src;                                 // I of Algorithm 1
     uint16_t* step_slot = dst;                                    // place of I[t] inside its worker's partition
+    // every partition ends with exactly C items (Algorithm 1 as printed: C = N / K): rows per worker
+    const int pitch = (P <= WAVE && C > 0 && (int64_t)P * C == N) ? place_pitch(C) : 0;
     int32_t* part_off = reinterpret_cast<int32_t*>(L.cnt) + PART_OFF_AT;
     int32_t* placed = reinterpret_cast<int32_t*>(L.cnt) + PLACED_AT;
 
@@ -391,9 +407,9 @@ __device__ __forceinline__ void balance_body(BalLds& L, int32_t N, int32_t P, in
     } else if (w == 0) {
         int32_t* worker_count = reinterpret_cast<int32_t*>(L.cnt) + WCOUNT_AT;
         int n_placed;
-        if (P <= 16) n_placed = lpt_rounds<16>(N, P, C, L.keys, sorted, mx, step_slot, worker_count, shard_load);
-        else if (P <= 32) n_placed = lpt_rounds<32>(N, P, C, L.keys, sorted, mx, step_slot, worker_count, shard_load);
-        else n_placed = lpt_rounds<64>(N, P, C, L.keys, sorted, mx, step_slot, worker_count, shard_load);
+        if (P <= 16) n_placed = lpt_rounds<16>(N, P, C, L.keys, sorted, mx, step_slot, pitch, worker_count, shard_load);
+        else if (P <= 32) n_placed = lpt_rounds<32>(N, P, C, L.keys, sorted, mx, step_slot, pitch, worker_count, shard_load);
+        else n_placed = lpt_rounds<64>(N, P, C, L.keys, sorted, mx, step_slot, pitch, worker_count, shard_load);
         // start of every P_k inside perm
         const int32_t c = worker_count[lane];
         const int32_t inc = (int32_t)wave_incl_scan_add_u32((uint32_t)c);
@@ -405,6 +421,14 @@ __device__ __forceinline__ void balance_body(BalLds& L, int32_t N, int32_t P, in
 
     // ---- c) lay out P_0, P_1, ... each in insertion order ----
     const int n_placed = *placed;
+    if (pitch) {                                                  // both stores in index order
+        for (int q = tid; q < N; q += BAL_BLOCK) {
+            const int k = q / C;
+            perm[q] = step_slot[k * pitch + (q - k * C)];
+            shard_of_seq[q] = L.keys[q];
+        }
+        return;
+    }
     for (int t = tid; t < n_placed; t += BAL_BLOCK) {
         const int u = sorted[t];
         const int k = L.keys[u];                                  // the worker that took it
