@@ -64,12 +64,24 @@ __device__ __forceinline__ uint32_t lane_xor(uint32_t v) {
 
 template <int K, int J>
 __device__ __forceinline__ uint32_t bitonic_step(uint32_t v) {
-    const uint32_t p = lane_xor<J>(v);
     const uint32_t lane = threadIdx.x & 63u;
     const bool lower = (lane & J) == 0;          // I am the lower lane of the pair
     const bool asc = (lane & K) == 0;            // my block sorts ascending
     // the lower lane of an ascending pair keeps the smaller key, its partner the larger
-    return umed3(v, p, lower == asc ? 0u : 0xFFFFFFFFu);
+    const uint32_t pick = lower == asc ? 0u : 0xFFFFFFFFu;
+    if constexpr (J >= 16) {
+        // a row swap of v with itself leaves {own key, partner's key} in the two results, in an order
+        // that depends on the lane; the median does not care which is which
+        if constexpr (J == 16) {
+            auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+            return umed3(r[0], r[1], pick);
+        } else {
+            auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+            return umed3(r[0], r[1], pick);
+        }
+    } else {
+        return umed3(v, lane_xor<J>(v), pick);
+    }
 }
 
 template <int K, int J>
