@@ -53,6 +53,7 @@ struct BalLds {
     alignas(16) uint32_t cnt[256 * BAL_WAVES];   // [digit][wave] counters of the sort passes; afterwards the workers' tables
     int32_t  red[2 * BAL_WAVES];
     uint32_t tmp32[16];
+    int32_t  spare[2];                    // where lanes without a worker put the stores of a round
     uint64_t tmp64[BAL_WAVES];
 };
 static_assert(sizeof(uint32_t) * 256 * BAL_WAVES >= 2 * sizeof(uint64_t) * DC_MAX_SHARDS, "two key tables fit the counters");
@@ -139,7 +140,7 @@ __device__ __forceinline__ void counting_pass(BalLds& L, int N, int rounds, Digi
 // items placed (N).
 template <int WIDTH>
 __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, const uint16_t* sorted,
-                                          int32_t max_len, uint16_t* step_slot, int pitch,
+                                          int32_t max_len, uint16_t* step_slot, int pitch, int32_t* spare_word,
                                           int32_t* worker_count, int64_t* __restrict__ shard_load) {
     const uint32_t lane = threadIdx.x;
     // Keys of open workers lie within one longest sequence (G, in key units) of the smallest, which
@@ -181,6 +182,9 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, co
             uint32_t sk = wave_sort_asc<WIDTH>(key);
             // items two rounds ahead: nothing a round reads from LDS depends on what the round computes
             uint32_t idx1 = sorted[min(pos + P + (int)lane, N - 1)];
+            // every LDS read issued so far is waited for here, outside the loop: a wait left to the loop's
+            // first use would sit in the loop and also wait, every round, for the stores of the round before
+            asm volatile("" : "+v"(idx1), "+v"(s), "+v"(idx));
             while (rounds < avail && pos + P <= N) {
                 const int t = pos + (int)lane;                    // rank `lane` takes item I[t]
                 const uint32_t id = sk & 63u;
@@ -200,11 +204,12 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, co
                 const uint32_t sk2 = wave_sort_asc<WIDTH>(newk);              // next round's order, if this round stands
                 const uint32_t pm = wave_excl_scan_umin(mine_exists ? newk : 0xFFFFFFFFu);
                 if (__ballot(mine_exists && sk < pm) != everyone) break;      // not everyone's turn: one general round
-                if (mine_exists) {
-                    if (pitch) step_slot[(int)id * pitch + before] = (uint16_t)idx;
-                    else step_slot[t] = (uint16_t)before;
-                    keys[idx] = (int32_t)id;                      // the item is placed: its length is not needed again
-                }
+                // Lanes without a worker store to spare words instead of branching round the stores: after a
+                // branch the compiler's next wait for an LDS read also waits for these stores (LDS operations
+                // retire through one in-order counter), once per round.
+                const int slot_at = pitch ? (int)id * pitch + before : t;
+                step_slot[mine_exists ? slot_at : DC_MAX_SEQ + PLACE_PAD - 1] = (uint16_t)(pitch ? idx : (uint32_t)before);
+                *(mine_exists ? keys + idx : spare_word) = (int32_t)id;   // the item is placed: its length is not needed again
                 pos += P;
                 rounds += 1;
                 sk = sk2;
@@ -406,10 +411,11 @@ __device__ __forceinline__ void balance_body(BalLds& L, int32_t N, int32_t P, in
         if (tid == 0) *placed = n_placed;
     } else if (w == 0) {
         int32_t* worker_count = reinterpret_cast<int32_t*>(L.cnt) + WCOUNT_AT;
+        int32_t* spare = L.spare;
         int n_placed;
-        if (P <= 16) n_placed = lpt_rounds<16>(N, P, C, L.keys, sorted, mx, step_slot, pitch, worker_count, shard_load);
-        else if (P <= 32) n_placed = lpt_rounds<32>(N, P, C, L.keys, sorted, mx, step_slot, pitch, worker_count, shard_load);
-        else n_placed = lpt_rounds<64>(N, P, C, L.keys, sorted, mx, step_slot, pitch, worker_count, shard_load);
+        if (P <= 16) n_placed = lpt_rounds<16>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load);
+        else if (P <= 32) n_placed = lpt_rounds<32>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load);
+        else n_placed = lpt_rounds<64>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load);
         // start of every P_k inside perm
         const int32_t c = worker_count[lane];
         const int32_t inc = (int32_t)wave_incl_scan_add_u32((uint32_t)c);
