@@ -185,12 +185,21 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, co
             // every LDS read issued so far is waited for here, outside the loop: a wait left to the loop's
             // first use would sit in the loop and also wait, every round, for the stores of the round before
             asm volatile("" : "+v"(idx1), "+v"(s), "+v"(idx));
+            // The two LDS stores that record a round's placements are issued at the top of the NEXT round,
+            // behind that round's reads.  LDS operations retire through one in-order counter and the compiler
+            // waits for "everything" at the loop's joins, so a round's first wait also waits for the stores
+            // before it: placed here they have a whole sort to retire, placed at the round's end they
+            // stall the next round.  Lanes without a worker store to spare words (no branch round the stores).
+            uint32_t st_slot = DC_MAX_SEQ + PLACE_PAD - 1, st_val = 0, st_id = 0;      // nothing to record yet
+            int32_t* st_key = spare_word;
             while (rounds < avail && pos + P <= N) {
                 const int t = pos + (int)lane;                    // rank `lane` takes item I[t]
                 const uint32_t id = sk & 63u;
                 const uint32_t s1 = (uint32_t)keys[idx1];
                 const uint32_t idx2 = sorted[min(t + 2 * P, N - 1)];
                 const int32_t before = __builtin_amdgcn_ds_bpermute((int)(id << 2), count) + rounds;   // its count
+                step_slot[st_slot] = (uint16_t)st_val;            // the round before: place inside the partition ...
+                *st_key = (int32_t)st_id;                         // ... and worker (the item's length is not needed again)
                 if (--until_check == 0) {                         // uniform
                     until_check = check_every;
                     const uint32_t min0 = (uint32_t)__builtin_amdgcn_readlane((int)sk, 0);
@@ -204,12 +213,11 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, co
                 const uint32_t sk2 = wave_sort_asc<WIDTH>(newk);              // next round's order, if this round stands
                 const uint32_t pm = wave_excl_scan_umin(mine_exists ? newk : 0xFFFFFFFFu);
                 if (__ballot(mine_exists && sk < pm) != everyone) break;      // not everyone's turn: one general round
-                // Lanes without a worker store to spare words instead of branching round the stores: after a
-                // branch the compiler's next wait for an LDS read also waits for these stores (LDS operations
-                // retire through one in-order counter), once per round.
                 const int slot_at = pitch ? (int)id * pitch + before : t;
-                step_slot[mine_exists ? slot_at : DC_MAX_SEQ + PLACE_PAD - 1] = (uint16_t)(pitch ? idx : (uint32_t)before);
-                *(mine_exists ? keys + idx : spare_word) = (int32_t)id;   // the item is placed: its length is not needed again
+                st_slot = mine_exists ? (uint32_t)slot_at : (uint32_t)(DC_MAX_SEQ + PLACE_PAD - 1);
+                st_val = pitch ? idx : (uint32_t)before;
+                st_key = mine_exists ? keys + idx : spare_word;
+                st_id = id;
                 pos += P;
                 rounds += 1;
                 sk = sk2;
@@ -217,6 +225,9 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, co
                 s = s1;
                 idx1 = idx2;
             }
+            // the last accepted round's record (after a refused round: the same stores once more)
+            step_slot[st_slot] = (uint16_t)st_val;
+            *st_key = (int32_t)st_id;
             // back to worker lanes: rank r sends its key to lane (sk & 63); absent workers send theirs to themselves
             key = (uint32_t)__builtin_amdgcn_ds_permute((int)((sk & 63u) << 2), (int)sk);
             if (mine_exists) {
