@@ -192,7 +192,8 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, co
             // stall the next round.  Lanes without a worker store to spare words (no branch round the stores).
             uint32_t st_slot = DC_MAX_SEQ + PLACE_PAD - 1, st_val = 0, st_id = 0;      // nothing to record yet
             int32_t* st_key = spare_word;
-            while (rounds < avail && pos + P <= N) {
+            const int n_rounds = min(avail, (N - pos) / P);       // >= 1: until a worker is full or the items run out
+            while (rounds < n_rounds) {
                 const int t = pos + (int)lane;                    // rank `lane` takes item I[t]
                 const uint32_t id = sk & 63u;
                 const uint32_t s1 = (uint32_t)keys[idx1];
@@ -200,7 +201,7 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, co
                 const int32_t before = __builtin_amdgcn_ds_bpermute((int)(id << 2), count) + rounds;   // its count
                 step_slot[st_slot] = (uint16_t)st_val;            // the round before: place inside the partition ...
                 *st_key = (int32_t)st_id;                         // ... and worker (the item's length is not needed again)
-                if (--until_check == 0) {                         // uniform
+                if (__builtin_expect(--until_check == 0, 0)) {    // uniform
                     until_check = check_every;
                     const uint32_t min0 = (uint32_t)__builtin_amdgcn_readlane((int)sk, 0);
                     if (min0 >= 0x40000000u && min0 < KEY_FULL) {
@@ -212,7 +213,7 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, co
                 const uint32_t newk = mine_exists ? sk + (s << 6) : sk;       // absent workers keep their all-ones-ish key
                 const uint32_t sk2 = wave_sort_asc<WIDTH>(newk);              // next round's order, if this round stands
                 const uint32_t pm = wave_excl_scan_umin(mine_exists ? newk : 0xFFFFFFFFu);
-                if (__ballot(mine_exists && sk < pm) != everyone) break;      // not everyone's turn: one general round
+                if (__builtin_expect(__ballot(mine_exists && sk < pm) != everyone, 0)) break;   // not everyone's turn: one general round
                 const int slot_at = pitch ? (int)id * pitch + before : t;
                 st_slot = mine_exists ? (uint32_t)slot_at : (uint32_t)(DC_MAX_SEQ + PLACE_PAD - 1);
                 st_val = pitch ? idx : (uint32_t)before;
