@@ -211,9 +211,14 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, co
                     }
                 }
                 const uint32_t newk = mine_exists ? sk + (s << 6) : sk;       // absent workers keep their all-ones-ish key
-                const uint32_t sk2 = wave_sort_asc<WIDTH>(newk);              // next round's order, if this round stands
+                // next round's order, if this round stands; the acceptance test is computed between the steps of
+                // the sort's first levels (the last level is made to wait for its result)
+                const uint32_t half_sorted = wave_sort_front<WIDTH>(newk);
                 const uint32_t pm = wave_excl_scan_umin(mine_exists ? newk : 0xFFFFFFFFu);
-                if (__builtin_expect(__ballot(mine_exists && sk < pm) != everyone, 0)) break;   // not everyone's turn: one general round
+                const uint64_t takers = __builtin_amdgcn_ballot_w64(sk < pm);
+                const bool refused = (takers & everyone) != everyone;
+                const uint32_t sk2 = wave_sort_back<WIDTH>(half_sorted, (uint32_t)refused);
+                if (__builtin_expect(refused, 0)) break;          // not everyone's turn: one general round
                 const int slot_at = pitch ? (int)id * pitch + before : t;
                 st_slot = mine_exists ? (uint32_t)slot_at : (uint32_t)(DC_MAX_SEQ + PLACE_PAD - 1);
                 st_val = pitch ? idx : (uint32_t)before;

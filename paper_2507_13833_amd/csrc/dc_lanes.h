@@ -30,6 +30,10 @@ __device__ __forceinline__ uint32_t dpp_perm(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, CTRL, 0xF, 0xF, false);
 }
 
+// The same with one more (unused) scalar operand: the statement cannot be scheduled before `after`
+// exists, which places whatever computes `after` in front of it (see wave_sort_asc_tied).
+__device__ __forceinline__ uint32_t umed3_after(uint32_t a, uint32_t b, uint32_t c, uint32_t after);
+
 // Median of three unsigned values in one instruction.  med3(a, b, 0) = min(a, b) and
 // med3(a, b, ~0) = max(a, b), so a per-lane constant chooses between the two.  (The compiler
 // treats the statement's output like any vector-ALU result and keeps the idle cycles a DPP
@@ -37,6 +41,12 @@ __device__ __forceinline__ uint32_t dpp_perm(uint32_t v) {
 __device__ __forceinline__ uint32_t umed3(uint32_t a, uint32_t b, uint32_t c) {
     uint32_t r;
     asm("v_med3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+__device__ __forceinline__ uint32_t umed3_after(uint32_t a, uint32_t b, uint32_t c, uint32_t after) {
+    uint32_t r;
+    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c), "s"(after));
     return r;
 }
 
@@ -62,8 +72,8 @@ __device__ __forceinline__ uint32_t lane_xor(uint32_t v) {
     }
 }
 
-template <int K, int J>
-__device__ __forceinline__ uint32_t bitonic_step(uint32_t v) {
+template <int K, int J, bool TIED = false>
+__device__ __forceinline__ uint32_t bitonic_step(uint32_t v, uint32_t after = 0) {
     const uint32_t lane = threadIdx.x & 63u;
     const bool lower = (lane & J) == 0;          // I am the lower lane of the pair
     const bool asc = (lane & K) == 0;            // my block sorts ascending
@@ -74,13 +84,13 @@ __device__ __forceinline__ uint32_t bitonic_step(uint32_t v) {
         // that depends on the lane; the median does not care which is which
         if constexpr (J == 16) {
             auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
-            return umed3(r[0], r[1], pick);
+            return TIED ? umed3_after(r[0], r[1], pick, after) : umed3(r[0], r[1], pick);
         } else {
             auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
-            return umed3(r[0], r[1], pick);
+            return TIED ? umed3_after(r[0], r[1], pick, after) : umed3(r[0], r[1], pick);
         }
     } else {
-        return umed3(v, lane_xor<J>(v), pick);
+        return TIED ? umed3_after(v, lane_xor<J>(v), pick, after) : umed3(v, lane_xor<J>(v), pick);
     }
 }
 
@@ -104,6 +114,21 @@ __device__ __forceinline__ uint32_t bitonic_sort_levels(uint32_t v) {
 template <int WIDTH>
 __device__ __forceinline__ uint32_t wave_sort_asc(uint32_t v) {
     return bitonic_sort_levels<2, WIDTH>(v);
+}
+
+// The two halves of wave_sort_asc: every level but the last, then the last level (the merge of the two
+// sorted halves of a group), whose first step waits for the scalar `after`.  A single wave issues in
+// order and a dependent vector instruction follows its producer only after about 8 cycles, of which the
+// issue takes 4: work that does not depend on the sort runs for free between the sort's steps if
+// it stands between them in the instruction stream, and `after` is how the caller puts it there.
+template <int WIDTH>
+__device__ __forceinline__ uint32_t wave_sort_front(uint32_t v) {
+    return bitonic_sort_levels<2, WIDTH / 2>(v);
+}
+template <int WIDTH>
+__device__ __forceinline__ uint32_t wave_sort_back(uint32_t v, uint32_t after) {
+    v = bitonic_step<WIDTH, WIDTH / 2, true>(v, after);
+    return bitonic_merge<WIDTH, WIDTH / 4>(v);
 }
 
 __device__ __forceinline__ uint32_t umin32(uint32_t a, uint32_t b) { return a < b ? a : b; }
