@@ -194,15 +194,8 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, co
             int32_t* st_key = spare_word;
             const int n_rounds = min(avail, (N - pos) / P);       // >= 1: until a worker is full or the items run out
             while (rounds < n_rounds) {
-                const int t = pos + (int)lane;                    // rank `lane` takes item I[t]
-                const uint32_t id = sk & 63u;
-                const uint32_t s1 = (uint32_t)keys[idx1];
-                const uint32_t idx2 = sorted[min(t + 2 * P, N - 1)];
-                const int32_t before = __builtin_amdgcn_ds_bpermute((int)(id << 2), count) + rounds;   // its count
-                step_slot[st_slot] = (uint16_t)st_val;            // the round before: place inside the partition ...
-                *st_key = (int32_t)st_id;                         // ... and worker (the item's length is not needed again)
-                if (__builtin_expect(--until_check == 0, 0)) {    // uniform
-                    until_check = check_every;
+                if (__builtin_expect(--until_check == 0, 0)) {    // uniform; first, so that the rest of the round is one
+                    until_check = check_every;                    // straight run of instructions for the scheduler
                     const uint32_t min0 = (uint32_t)__builtin_amdgcn_readlane((int)sk, 0);
                     if (min0 >= 0x40000000u && min0 < KEY_FULL) {
                         const uint32_t sub = min0 & ~63u;
@@ -210,6 +203,13 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, co
                         taken += (int64_t)(sub >> 6);
                     }
                 }
+                const int t = pos + (int)lane;                    // rank `lane` takes item I[t]
+                const uint32_t id = sk & 63u;
+                const uint32_t s1 = (uint32_t)keys[idx1];
+                const uint32_t idx2 = sorted[min(t + 2 * P, N - 1)];
+                const int32_t before = __builtin_amdgcn_ds_bpermute((int)(id << 2), count) + rounds;   // its count
+                step_slot[st_slot] = (uint16_t)st_val;            // the round before: place inside the partition ...
+                *st_key = (int32_t)st_id;                         // ... and worker (the item's length is not needed again)
                 const uint32_t newk = mine_exists ? sk + (s << 6) : sk;       // absent workers keep their all-ones-ish key
                 // next round's order, if this round stands; the acceptance test is computed between the steps of
                 // the sort's first levels (the last level is made to wait for its result)
