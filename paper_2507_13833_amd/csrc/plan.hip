@@ -188,12 +188,50 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a) {
         }
     }
 
-    // ---- 3. micro-batch starts: lane p walks shard p ----
+    // ---- 3. micro-batch starts ----
+    // Many shards: lane p walks shard p.
     // Each hop looks for the last slot that still fits under the budget.  Slots of a shard come in
     // descending length, so a micro-batch holds about as many slots as the one before it: the
     // search gallops outwards from that guess and bisects what is left (a few probes of the prefix
     // instead of log2 N per hop; the hops of a shard are one dependent chain).
-    if (tid < P) {
+    if (P <= PLAN_WAVES * 4) {
+        // Few shards: a group of 64, 32 or 16 LANES walks a shard (every wave takes 1, 2 or 4 shards).  A
+        // hop probes the slots behind the micro-batch's start G at a time, one per lane: the prefix sums
+        // do not decrease, so the lanes that still fit are a prefix of the group and a ballot counts them -
+        // one LDS round trip per window where the dependent probes of a search take six to eight.  A
+        // micro-batch of more than two windows finishes with a bisection.
+        const int spw = P <= PLAN_WAVES ? 1 : (P <= 2 * PLAN_WAVES ? 2 : 4);     // shards per wave
+        const int G = WAVE / spw, g = lane / G, gl = lane - g * G;
+        const uint64_t group_mask = (G == WAVE ? ~0ull : (1ull << G) - 1ull);
+        const int p = w * spw + g;
+        if (p < P) {
+            const int b = L.shard_off[p + 1];
+            int j = L.shard_off[p];
+            while (j < b) {                                  // uniform over the group
+                if (gl == 0) atomicOr(&L.start_bits[j >> 5], 1u << (j & 31));
+                const int64_t limit = L.gpre[j] + a.budget;
+                int lo = j + 1, e = j + 1;                   // an over-budget slot still advances by one
+                for (int win = 0;; ++win) {
+                    const int c = lo + gl;
+                    const bool fits = c <= b && L.gpre[min(c, b)] <= limit;
+                    const int cnt = __popcll((__ballot(fits) >> (g * G)) & group_mask);
+                    if (cnt > 0) e = lo + cnt - 1;
+                    if (cnt < G || lo + G > b) break;
+                    lo += G;
+                    if (win == 1) {                          // every lane of the group reads the same words
+                        int l = e, h = b;
+                        while (l < h) {
+                            const int mid = (l + h + 1) >> 1;
+                            if (L.gpre[mid] <= limit) l = mid; else h = mid - 1;
+                        }
+                        e = l;
+                        break;
+                    }
+                }
+                j = e;
+            }
+        }
+    } else if (tid < P) {
         const int b = L.shard_off[tid + 1];
         int j = L.shard_off[tid];
         int sz = 1;                                      // slots in the previous micro-batch
