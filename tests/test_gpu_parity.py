@@ -241,6 +241,33 @@ def test_ragged_sizes():
     check_step(_custom(rng.integers(1, 200, 2), 2, 2, 512), label="N=2")
 
 
+def test_partition_sizes_and_worker_counts():
+    """N = P * C for many (P, C): the items are filed per worker while they are placed (row pitch C rounded up
+    to 2 mod 4), for odd and even C, worker counts that are no power of two, one worker, one item per worker;
+    and the same batches with a limit above C (partitions of unequal size: the other layout pass)."""
+    torch, binding, runner = _gpu()
+    rng = np.random.default_rng(23)
+    for P in (1, 2, 3, 5, 17, 33, 64):
+        for C in (1, 2, 3, 4, 7, 64, 255, 256):
+            N = P * C
+            if N > 16384:
+                continue
+            lens = np.minimum(rng.geometric(0.01, N), 1500).astype(np.int32)
+            if (P + C) % 3 == 0:
+                lens[:] = lens[0]                               # all equal: index order decides everything
+            w = _custom(lens, 1, P, 4096, fields=("i32",))
+            for cap in (0, C + 1):
+                d = runner.DeviceBatch(w, cap=cap)
+                d.balance()
+                torch.cuda.synchronize()
+                assert d.read_status() == 0
+                bal = oracle.balance(w.seq_len, P, cap)
+                assert np.array_equal(d.perm.cpu().numpy(), bal.perm), (P, C, cap)
+                assert np.array_equal(d.shard_seq_off.cpu().numpy(), bal.shard_seq_off), (P, C, cap)
+                assert np.array_equal(d.shard_of_seq.cpu().numpy(), bal.shard_of_seq), (P, C, cap)
+                assert np.array_equal(d.shard_load.cpu().numpy(), bal.shard_load), (P, C, cap)
+
+
 def test_max_sequences():
     rng = np.random.default_rng(10)
     lens = np.minimum(rng.geometric(0.02, 16384), 2000).astype(np.int32)
