@@ -69,6 +69,7 @@ extern "C" {
 #endif
 
 #define DC_MAX_SEQ        16384   /* N: one workgroup sorts and plans in LDS          */
+#define DC_MAX_SEQ_LARGE  1048576 /* N of the calls that say so (dc_balance_ws)      */
 #define DC_MAX_SHARDS     1024    /* P: one lane per shard (one wavefront up to 64,   */
                                   /*    the whole workgroup above)                    */
 #define DC_MAX_FIELDS     8
@@ -137,6 +138,19 @@ size_t dc_workspace_bytes(const dc_params* prm, int64_t dst_capacity_tokens);
 dc_status dc_balance(const dc_params* prm, const int32_t* d_seq_len,
                      int32_t* d_perm, int32_t* d_shard_seq_off, int32_t* d_shard_of_seq,
                      int64_t* d_shard_load, int32_t* d_status, void* hip_stream);
+
+/*
+ * dc_balance for up to DC_MAX_SEQ_LARGE sequences (same results, same errors).  Up to DC_MAX_SEQ
+ * sequences it is dc_balance itself and d_ws may be NULL.  Above, the sort keeps its index arrays in
+ * d_ws (256-byte aligned, dc_balance_workspace_bytes(prm) bytes: 12 bytes per sequence) and the
+ * assignment takes the sorted sequences DC_MAX_SEQ at a time, carrying the workers' loads along; a slower
+ * path (every sort access is a global one).  Limits above DC_MAX_SEQ: n_shards <= 64 and at most 65535
+ * sequences per shard (C of Algorithm 1, or prm->cap), else UNSUPPORTED_SIZE.
+ */
+size_t dc_balance_workspace_bytes(const dc_params* prm);
+dc_status dc_balance_ws(const dc_params* prm, const int32_t* d_seq_len,
+                        int32_t* d_perm, int32_t* d_shard_seq_off, int32_t* d_shard_of_seq,
+                        int64_t* d_shard_load, void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream);
 
 /*
  * Group-relative advantage.  For group g with rewards r_1..r_G (float32):

@@ -15,6 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdc.so")
 
 DC_MAX_SEQ = 16384
+DC_MAX_SEQ_LARGE = 1 << 20
 DC_MAX_SHARDS = 1024
 DC_MAX_FIELDS = 8
 DC_MAX_SRC_SHARDS = 16
@@ -32,7 +33,7 @@ DC_ERR_BAD_LAYOUT = 9
 
 EXPORTS = ("dc_workspace_bytes", "dc_balance", "dc_group_advantage", "dc_plan", "dc_gather",
            "dc_repack", "dc_scatter_workspace_bytes", "dc_scatter", "dc_gae", "dc_balance_group_advantage",
-           "dc_gather_advantage", "dc_strerror")
+           "dc_gather_advantage", "dc_balance_workspace_bytes", "dc_balance_ws", "dc_strerror")
 
 
 class dc_params(C.Structure):
@@ -76,6 +77,10 @@ def load() -> C.CDLL:
         vp = C.c_void_p
         lib.dc_balance.restype = C.c_int
         lib.dc_balance.argtypes = [C.POINTER(dc_params), vp, vp, vp, vp, vp, vp, vp]
+        lib.dc_balance_workspace_bytes.restype = C.c_size_t
+        lib.dc_balance_workspace_bytes.argtypes = [C.POINTER(dc_params)]
+        lib.dc_balance_ws.restype = C.c_int
+        lib.dc_balance_ws.argtypes = [C.POINTER(dc_params), vp, vp, vp, vp, vp, vp, C.c_size_t, vp, vp]
         lib.dc_group_advantage.restype = C.c_int
         lib.dc_group_advantage.argtypes = [C.POINTER(dc_params), C.POINTER(dc_source), vp, vp, vp, C.c_int32,
                                            C.POINTER(vp), vp, C.POINTER(vp), vp, vp]
@@ -184,6 +189,18 @@ def dc_balance(prm: dc_params, d_seq_len, d_perm, d_shard_seq_off, d_shard_of_se
     _check(load().dc_balance(C.byref(prm), _ptr(d_seq_len), _ptr(d_perm), _ptr(d_shard_seq_off),
                              _ptr(d_shard_of_seq), _ptr(d_shard_load), _ptr(d_status), _stream(stream)),
            "dc_balance")
+
+
+def dc_balance_workspace_bytes(prm: dc_params) -> int:
+    return int(load().dc_balance_workspace_bytes(C.byref(prm)))
+
+
+def dc_balance_ws(prm: dc_params, d_seq_len, d_perm, d_shard_seq_off, d_shard_of_seq, d_shard_load,
+                  d_ws, ws_bytes: int, d_status, stream=None) -> None:
+    _check(load().dc_balance_ws(C.byref(prm), _ptr(d_seq_len), _ptr(d_perm), _ptr(d_shard_seq_off),
+                                _ptr(d_shard_of_seq), _ptr(d_shard_load), _ptr(d_ws), int(ws_bytes), _ptr(d_status),
+                                _stream(stream)),
+           "dc_balance_ws")
 
 
 def dc_group_advantage(prm: dc_params, src: Source, d_seq_len, d_reward, d_group_off, n_groups: int,

@@ -25,13 +25,13 @@ Workspace carve_workspace(void* base, int32_t n_seq, int64_t dst_capacity_tokens
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-static dc_status check_params(const dc_params* prm) {
+static dc_status check_params(const dc_params* prm, int32_t max_seq = DC_MAX_SEQ) {
     if (!prm) return DC_ERR_INVALID_ARG;
     if (prm->n_seq < 0 || prm->n_shards < 1 || prm->cap < 0 || prm->align_tokens < 1 || prm->reserved != 0)
         return DC_ERR_INVALID_ARG;
     if (prm->token_budget < 1 || prm->token_budget > 0x7FFFFFFFLL) return DC_ERR_INVALID_ARG;
     if (prm->ddof < 0 || !(prm->eps >= 0.0)) return DC_ERR_INVALID_ARG;
-    if (prm->n_seq > DC_MAX_SEQ || prm->n_shards > DC_MAX_SHARDS) return DC_ERR_UNSUPPORTED_SIZE;
+    if (prm->n_seq > max_seq || prm->n_shards > DC_MAX_SHARDS) return DC_ERR_UNSUPPORTED_SIZE;
     return DC_OK;
 }
 
@@ -90,8 +90,8 @@ size_t dc_workspace_bytes(const dc_params* prm, int64_t dst_capacity_tokens) {
 // Host-side checks of dc_balance's arguments; *cap_eff gets the per-shard item limit.
 static dc_status check_balance(const dc_params* prm, const int32_t* d_seq_len, const int32_t* d_perm,
                                const int32_t* d_shard_seq_off, const int32_t* d_shard_of_seq,
-                               const int64_t* d_shard_load, int32_t* cap_eff) {
-    dc_status rc = check_params(prm);
+                               const int64_t* d_shard_load, int32_t* cap_eff, int32_t max_seq = DC_MAX_SEQ) {
+    dc_status rc = check_params(prm, max_seq);
     if (rc != DC_OK) return rc;
     if (!d_shard_seq_off || !d_shard_load) return DC_ERR_INVALID_ARG;
     if (prm->n_seq > 0 && (!d_seq_len || !d_perm || !d_shard_of_seq)) return DC_ERR_INVALID_ARG;
@@ -133,6 +133,36 @@ dc_status dc_balance(const dc_params* prm, const int32_t* d_seq_len,
     if (rc != DC_OK) return rc;
     hipError_t e = launch_balance(prm->n_seq, prm->n_shards, cap_eff, d_seq_len, d_perm, d_shard_seq_off,
                                   d_shard_of_seq, d_shard_load, d_status, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? DC_OK : DC_ERR_HIP;
+}
+
+// Workspace of the balance beyond DC_MAX_SEQ sequences: two index arrays and one word per sorted item.
+static size_t balance_ws_bytes(int32_t n_seq) {
+    if (n_seq <= DC_MAX_SEQ) return 0;
+    return 3 * (((size_t)n_seq + 63) & ~(size_t)63) * sizeof(int32_t) + 256;
+}
+
+size_t dc_balance_workspace_bytes(const dc_params* prm) {
+    if (!prm || prm->n_seq < 0 || prm->n_seq > DC_MAX_SEQ_LARGE) return 0;
+    return balance_ws_bytes(prm->n_seq);
+}
+
+dc_status dc_balance_ws(const dc_params* prm, const int32_t* d_seq_len,
+                        int32_t* d_perm, int32_t* d_shard_seq_off, int32_t* d_shard_of_seq,
+                        int64_t* d_shard_load, void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream) {
+    int32_t cap_eff;
+    dc_status rc = check_balance(prm, d_seq_len, d_perm, d_shard_seq_off, d_shard_of_seq, d_shard_load, &cap_eff,
+                                 DC_MAX_SEQ_LARGE);
+    if (rc != DC_OK) return rc;
+    if (prm->n_seq <= DC_MAX_SEQ)
+        return dc_balance(prm, d_seq_len, d_perm, d_shard_seq_off, d_shard_of_seq, d_shard_load, d_status, hip_stream);
+    // the portions of the assignment run on one wavefront, and a place inside a partition is kept in 16 bits
+    if (prm->n_shards > 64 || cap_eff > 65535) return DC_ERR_UNSUPPORTED_SIZE;
+    if (!d_ws || (reinterpret_cast<uintptr_t>(d_ws) & 255u)) return DC_ERR_INVALID_ARG;
+    if (ws_bytes < balance_ws_bytes(prm->n_seq)) return DC_ERR_WORKSPACE;
+    hipError_t e = launch_balance_large(prm->n_seq, prm->n_shards, cap_eff, d_seq_len, d_perm, d_shard_seq_off,
+                                        d_shard_of_seq, d_shard_load, d_ws, d_status,
+                                        static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? DC_OK : DC_ERR_HIP;
 }
 

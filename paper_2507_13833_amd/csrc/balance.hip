@@ -29,436 +29,9 @@
 //      insertion order) and the worker of every sequence.  When N = P * C (the algorithm as printed)
 //      every P_k ends with C items, the items are filed per worker as they are placed, and both
 //      outputs are written in index order.
-#include "advantage_device.h"
-#include "dc_lanes.h"
+#include "balance_device.h"
 
 namespace dc {
-
-constexpr int BAL_BLOCK = 1024;
-constexpr int BAL_WAVES = BAL_BLOCK / WAVE;
-constexpr int BAL_ROUNDS = DC_MAX_SEQ / BAL_BLOCK;       // 64-item rounds per wave at the size limit
-constexpr uint32_t KEY_FULL = 0xFFFFFFC0u;               // | worker id: full (or absent) worker
-
-// When every partition ends with exactly C items its place in perm is known beforehand, and wave 0 files
-// the items per worker (worker k's row starts at k * pitch) as it places them; the pitch is C rounded up
-// to 2 mod 4, so that the 64 workers' rows start in 64 different LDS banks.
-constexpr int PLACE_PAD = 4 * WAVE;
-__device__ __forceinline__ int place_pitch(int C) { return C + ((2 - C) & 3); }
-
-struct BalLds {
-    int32_t  keys[DC_MAX_SEQ];            // sequence lengths (sanitised)
-    uint16_t idx_a[DC_MAX_SEQ + PLACE_PAD];   // sort ping
-    uint16_t idx_b[DC_MAX_SEQ + PLACE_PAD];   // sort pong; after the sort the free one holds every item's place in its
-                                              // partition, or (all partitions of equal size) the partitions themselves
-    alignas(16) uint32_t cnt[256 * BAL_WAVES];   // [digit][wave] counters of the sort passes; afterwards the workers' tables
-    int32_t  red[2 * BAL_WAVES];
-    uint32_t tmp32[16];
-    int32_t  spare[2];                    // where lanes without a worker put the stores of a round
-    uint64_t tmp64[BAL_WAVES];
-};
-static_assert(sizeof(uint32_t) * 256 * BAL_WAVES >= 2 * sizeof(uint64_t) * DC_MAX_SHARDS, "two key tables fit the counters");
-static_assert(DC_MAX_SHARDS <= BAL_BLOCK, "one thread per worker");
-
-// Where the tables of the assignment live inside BalLds::cnt once the sort is done.
-constexpr int PART_OFF_AT = 0;                         // int32 [P + 1]: start of every P_k inside perm
-constexpr int PLACED_AT = DC_MAX_SHARDS + 8;           // int32: items placed
-constexpr int WCOUNT_AT = DC_MAX_SHARDS + 16;          // int32 [64]: |P_k| of the one-wave path
-
-// One stable counting pass over positions [0, N): position pos carries digit(pos) in
-// [0, 256); emit(pos, out) receives its output position.  Wave w owns the contiguous
-// positions [w*rounds*64, (w+1)*rounds*64), so (digit, wave, rank-in-wave) is the
-// stable order.  Every lane of the workgroup must call it.
-template <typename DigitFn, typename EmitFn>
-__device__ __forceinline__ void counting_pass(BalLds& L, int N, int rounds, DigitFn digit, EmitFn emit) {
-    const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
-    const int wave_base = w * rounds * WAVE;
-    for (int i = tid; i < 256 * BAL_WAVES; i += BAL_BLOCK) L.cnt[i] = 0;
-    __syncthreads();
-    uint32_t packed[BAL_ROUNDS];                                  // digit << 16 | rank before me in my wave
-#pragma unroll
-    for (int r = 0; r < BAL_ROUNDS; ++r) {
-        packed[r] = 0;
-        if (r < rounds) {                                         // uniform
-            const int pos = wave_base + r * WAVE + lane;
-            const bool valid = pos < N;
-            uint32_t d = 0;
-            if (valid) d = digit(pos) & 0xFFu;
-            // lanes holding my digit: for every bit, the lanes whose bit equals mine (an invalid lane has d = 0
-            // and is not among the valid ones to begin with)
-            const uint64_t valid_lanes = __builtin_amdgcn_ballot_w64(valid);
-            uint32_t peers_lo = (uint32_t)valid_lanes, peers_hi = (uint32_t)(valid_lanes >> 32);
-#pragma unroll
-            for (int b = 0; b < 8; ++b) {
-                const uint64_t bal = __builtin_amdgcn_ballot_w64(((d >> b) & 1u) != 0u);
-                const uint32_t mine = (uint32_t)__builtin_amdgcn_sbfe((int)d, (unsigned)b, 1u);   // all ones if my bit is set
-                peers_lo &= ~((uint32_t)bal ^ mine);
-                peers_hi &= ~((uint32_t)(bal >> 32) ^ mine);
-            }
-            const uint64_t peers = ((uint64_t)peers_hi << 32) | peers_lo;
-            const uint64_t lt = (1ull << lane) - 1ull;
-            const int before = __popcll(peers & lt);
-            const int leader = valid ? (__ffsll((long long)peers) - 1) : lane;
-            uint32_t old = 0;
-            if (valid && lane == leader) {                        // one lane per distinct digit
-                uint32_t* c = &L.cnt[d * BAL_WAVES + w];
-                old = *c;
-                *c = old + (uint32_t)__popcll(peers);
-            }
-            old = (uint32_t)__shfl((int)old, leader, WAVE);
-            packed[r] = (d << 16) | (old + (uint32_t)before);
-        }
-    }
-    __syncthreads();
-    {   // exclusive scan of the 4096 counters in (digit, wave) order
-        uint32_t c4[4], s = 0;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) { c4[q] = L.cnt[tid * 4 + q]; s += c4[q]; }
-        uint32_t tot;
-        uint32_t run = block_excl_scan_add<uint32_t>(s, L.tmp32, &tot);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) { L.cnt[tid * 4 + q] = run; run += c4[q]; }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int r = 0; r < BAL_ROUNDS; ++r) {
-        if (r < rounds) {
-            const int pos = wave_base + r * WAVE + lane;
-            if (pos < N) {
-                const uint32_t d = packed[r] >> 16, rk = packed[r] & 0xFFFFu;
-                emit(pos, (int)(L.cnt[d * BAL_WAVES + w] + rk));
-            }
-        }
-    }
-    __syncthreads();
-}
-
-// The assignment rounds (wave 0 only).  WIDTH = 16, 32 or 64 >= P lanes take part in the sort.
-// pitch == 0: step_slot[t] = place of item I[t] inside its worker's partition; pitch > 0 (every
-// partition will hold exactly C items): step_slot[k * pitch + c] = the c-th item of worker k.
-// The worker of a placed sequence takes the place of its length in keys[] (an item's length is
-// read for the last time before the item is placed); worker_count[k] = |P_k|.  Returns the number of
-// items placed (N).
-template <int WIDTH>
-__device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, const uint16_t* sorted,
-                                          int32_t max_len, uint16_t* step_slot, int pitch, int32_t* spare_word,
-                                          int32_t* worker_count, int64_t* __restrict__ shard_load) {
-    const uint32_t lane = threadIdx.x;
-    // Keys of open workers lie within one longest sequence (G, in key units) of the smallest, which
-    // grows by at most G per round.  A check that leaves the smallest below 2^30 therefore keeps every
-    // key below 2^30 + (R + 1) G for the next R rounds; R is chosen so that this stays below 2^32
-    // with one G to spare.
-    const uint32_t G = (uint32_t)__builtin_amdgcn_readfirstlane(max_len) << 6;    // max_len <= 2^24
-    const uint32_t fit = (3u << 30) / max(G, 1u);                 // >= 3
-    const int check_every = (int)min(64u, fit - 2u);
-    int until_check = 1;
-    const uint32_t full = KEY_FULL | lane;
-    const bool mine_exists = (int)lane < P;                       // lane k keeps worker k
-    const uint64_t everyone = P == WAVE ? ~0ull : (1ull << P) - 1ull;
-    uint32_t key = (mine_exists && C > 0) ? lane : full;
-    int32_t count = 0;
-    int64_t load = 0;
-    int pos = 0;
-    // the item offered to rank `lane` is fetched one round ahead (two dependent LDS reads), as soon as the
-    // accepted prefix is known, so the reads overlap the hand-back of the keys instead of delaying the sort
-    uint32_t idx = N > 0 ? (uint32_t)sorted[min((int)lane, N - 1)] : 0u;
-    uint32_t s = N > 0 ? (uint32_t)keys[idx] : 0u;
-    bool all_take = C > 0;                                        // every worker open and the last round placed an item on each
-
-    while (pos < N) {
-        // ---- rounds in which every worker takes one item ----
-        // While all P workers are open and whole prefixes are accepted, a worker's count is its count at
-        // entry plus the rounds since, and its load is its key plus a constant.  Nothing has to travel back
-        // to the worker lanes then: the keys stay in rank order from round to round, and the sort of the
-        // updated keys starts before the round's acceptance test has finished (it is only used if the
-        // test passes), which takes the test off the chain of dependent sorts.
-        if (all_take && pos + P <= N) {                           // uniform
-            int32_t cmax = mine_exists ? count : 0;
-#pragma unroll
-            for (int d = 32; d >= 1; d >>= 1) cmax = max(cmax, __shfl_xor(cmax, d, WAVE));
-            const int avail = C - __builtin_amdgcn_readfirstlane(cmax);   // rounds before the first worker is full (>= 1)
-            const int64_t off = load - (int64_t)(key >> 6);       // what the key does not hold of my worker's load
-            int64_t taken = 0;                                    // load taken off the keys by rebasing in here
-            int rounds = 0;
-            uint32_t sk = wave_sort_asc<WIDTH>(key);
-            // items two rounds ahead: nothing a round reads from LDS depends on what the round computes
-            uint32_t idx1 = sorted[min(pos + P + (int)lane, N - 1)];
-            // every LDS read issued so far is waited for here, outside the loop: a wait left to the loop's
-            // first use would sit in the loop and also wait, every round, for the stores of the round before
-            asm volatile("" : "+v"(idx1), "+v"(s), "+v"(idx));
-            // The two LDS stores that record a round's placements are issued at the top of the NEXT round,
-            // behind that round's reads.  LDS operations retire through one in-order counter and the compiler
-            // waits for "everything" at the loop's joins, so a round's first wait also waits for the stores
-            // before it: placed here they have a whole sort to retire, placed at the round's end they
-            // stall the next round.  Lanes without a worker store to spare words (no branch round the stores).
-            uint32_t st_slot = DC_MAX_SEQ + PLACE_PAD - 1, st_val = 0, st_id = 0;      // nothing to record yet
-            int32_t* st_key = spare_word;
-            const int n_rounds = min(avail, (N - pos) / P);       // >= 1: until a worker is full or the items run out
-            while (rounds < n_rounds) {
-                if (__builtin_expect(--until_check == 0, 0)) {    // uniform; first, so that the rest of the round is one
-                    until_check = check_every;                    // straight run of instructions for the scheduler
-                    const uint32_t min0 = (uint32_t)__builtin_amdgcn_readlane((int)sk, 0);
-                    if (min0 >= 0x40000000u && min0 < KEY_FULL) {
-                        const uint32_t sub = min0 & ~63u;
-                        if (sk < KEY_FULL) sk -= sub;
-                        taken += (int64_t)(sub >> 6);
-                    }
-                }
-                const int t = pos + (int)lane;                    // rank `lane` takes item I[t]
-                const uint32_t id = sk & 63u;
-                const uint32_t s1 = (uint32_t)keys[idx1];
-                const uint32_t idx2 = sorted[min(t + 2 * P, N - 1)];
-                const int32_t before = __builtin_amdgcn_ds_bpermute((int)(id << 2), count) + rounds;   // its count
-                step_slot[st_slot] = (uint16_t)st_val;            // the round before: place inside the partition ...
-                *st_key = (int32_t)st_id;                         // ... and worker (the item's length is not needed again)
-                const uint32_t newk = mine_exists ? sk + (s << 6) : sk;       // absent workers keep their all-ones-ish key
-                // next round's order, if this round stands; the acceptance test is computed between the steps of
-                // the sort's first levels (the last level is made to wait for its result)
-                const uint32_t half_sorted = wave_sort_front<WIDTH>(newk);
-                const uint32_t pm = wave_excl_scan_umin(mine_exists ? newk : 0xFFFFFFFFu);
-                const uint64_t takers = __builtin_amdgcn_ballot_w64(sk < pm);
-                const bool refused = (takers & everyone) != everyone;
-                const uint32_t sk2 = wave_sort_back<WIDTH>(half_sorted, (uint32_t)refused);
-                if (__builtin_expect(refused, 0)) break;          // not everyone's turn: one general round
-                const int slot_at = pitch ? (int)id * pitch + before : t;
-                st_slot = mine_exists ? (uint32_t)slot_at : (uint32_t)(DC_MAX_SEQ + PLACE_PAD - 1);
-                st_val = pitch ? idx : (uint32_t)before;
-                st_key = mine_exists ? keys + idx : spare_word;
-                st_id = id;
-                pos += P;
-                rounds += 1;
-                sk = sk2;
-                idx = idx1;
-                s = s1;
-                idx1 = idx2;
-            }
-            // the last accepted round's record (after a refused round: the same stores once more)
-            step_slot[st_slot] = (uint16_t)st_val;
-            *st_key = (int32_t)st_id;
-            // back to worker lanes: rank r sends its key to lane (sk & 63); absent workers send theirs to themselves
-            key = (uint32_t)__builtin_amdgcn_ds_permute((int)((sk & 63u) << 2), (int)sk);
-            if (mine_exists) {
-                count += rounds;
-                load = off + taken + (int64_t)(key >> 6);
-                if (count == C) key = full;
-            }
-            until_check = 1;
-            all_take = false;
-            continue;
-        }
-
-        // ---- a general round: the longest accepted prefix of the ranks takes one item each ----
-        const int t = pos + (int)lane;
-        uint32_t sk = wave_sort_asc<WIDTH>(key);                  // lane r: r-th smallest key
-        if (--until_check == 0) {                                 // uniform
-            until_check = check_every;
-            const uint32_t min0 = (uint32_t)__builtin_amdgcn_readlane((int)sk, 0);
-            if (min0 >= 0x40000000u && min0 < KEY_FULL) {         // rebase: subtract the minimum load
-                const uint32_t sub = min0 & ~63u;
-                if (key < KEY_FULL) key -= sub;
-                if (sk < KEY_FULL) sk -= sub;
-            }
-        }
-        const bool valid = sk < KEY_FULL && t < N;
-        const uint32_t newk = valid ? sk + (s << 6) : 0xFFFFFFFFu;
-        const uint32_t pm = wave_excl_scan_umin(newk);            // smallest updated key among ranks below mine
-        const uint64_t acc = __ballot(valid && sk < pm);
-        const int m = (~acc == 0ull) ? WAVE : (__ffsll((long long)~acc) - 1);   // accepted prefix
-        if (m == 0) break;                                        // cannot happen: cap * P >= N
-        const uint32_t next_idx = sorted[min(t + m, N - 1)];      // next round's item: first read
-        // back to worker lanes: rank r sends its updated key, its own rank in place of the worker id,
-        // to lane (sk & 63)
-        const uint32_t recv = (uint32_t)__builtin_amdgcn_ds_permute((int)((sk & 63u) << 2), (int)((newk & ~63u) | lane));
-        const uint32_t thr = (uint32_t)__builtin_amdgcn_readlane((int)sk, m - 1);
-        const uint32_t next_s = (uint32_t)keys[next_idx];         // second read
-        if (key <= thr) {                                         // my worker is among the m smallest
-            const uint32_t nk = (recv & ~63u) | lane;
-            const int mine = pos + (int)(recv & 63u);             // the item I took
-            const uint32_t u_mine = sorted[mine];
-            if (pitch) step_slot[(int)lane * pitch + count] = (uint16_t)u_mine;
-            else step_slot[mine] = (uint16_t)count;
-            keys[u_mine] = (int32_t)lane;                     // the item is placed: its length is not needed again
-            load += (int64_t)((nk - key) >> 6);
-            count += 1;
-            key = (count == C) ? full : nk;
-        }
-        pos += m;
-        idx = next_idx;
-        s = next_s;
-        all_take = m == P && __ballot(mine_exists && key >= KEY_FULL) == 0ull;
-    }
-    if (mine_exists) shard_load[lane] = load;
-    worker_count[lane] = count;
-    return pos;
-}
-
-// The same rounds for 64 < P <= DC_MAX_SHARDS workers, run by the whole workgroup: thread k keeps
-// worker k (64-bit key load << 10 | k, all-ones-ish when full or absent), thread r also plays
-// rank r of the sorted order.  Every thread of the workgroup must call it (barriers inside).
-// Returns the number of items placed; part_off[0..P] gets the start of every P_k.
-constexpr int WIDE_ID_BITS = 10;
-constexpr uint64_t WIDE_ID_MASK = (1ull << WIDE_ID_BITS) - 1ull;
-constexpr uint64_t WIDE_FULL = ~WIDE_ID_MASK;          // | worker id: full (or absent) worker
-static_assert(DC_MAX_SHARDS <= (1 << WIDE_ID_BITS), "worker id fits the key's low bits");
-
-__device__ __forceinline__ uint64_t umin64(uint64_t a, uint64_t b) { return a < b ? a : b; }
-
-__device__ __forceinline__ int lpt_rounds_wide(BalLds& L, int N, int P, int C, const uint16_t* sorted, uint16_t* step_slot,
-                                               int32_t* __restrict__ shard_seq_off, int64_t* __restrict__ shard_load) {
-    const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
-    uint64_t* kbuf = reinterpret_cast<uint64_t*>(L.cnt);              // keys in worker order; then the keys sent back
-    uint64_t* sbuf = kbuf + DC_MAX_SHARDS;                            // keys in rank order
-    const uint64_t full = WIDE_FULL | (uint64_t)tid;
-    uint64_t key = (tid < P && C > 0) ? (uint64_t)tid : full;
-    int32_t count = 0;
-    int64_t load = 0;
-    int pos = 0;
-    while (pos < N) {                                                 // pos is the same in every thread
-        kbuf[tid] = key;
-        __syncthreads();
-        // my rank = keys below mine (keys are distinct: the worker id sits in the low bits)
-        if (tid < P) {
-            int rank = 0;
-            for (int j = 0; j < P; ++j) rank += kbuf[j] < key ? 1 : 0;
-            sbuf[rank] = key;
-        }
-        __syncthreads();
-        // ---- rank view: thread r offers item I[pos + r] to the worker with the r-th smallest key ----
-        const uint64_t sk = tid < P ? sbuf[tid] : ~0ull;
-        const int t = pos + tid;
-        const bool valid = tid < P && sk < WIDE_FULL && t < N;
-        const uint64_t s = valid ? (uint64_t)(uint32_t)L.keys[sorted[t]] : 0ull;
-        const uint64_t newk = valid ? sk + (s << WIDE_ID_BITS) : ~0ull;
-        // smallest updated key among the ranks below mine
-        uint64_t inc = newk;
-#pragma unroll
-        for (int d = 1; d < WAVE; d <<= 1) {
-            const uint64_t o = __shfl_up(inc, d, WAVE);
-            if (lane >= d) inc = umin64(inc, o);
-        }
-        uint64_t pm = __shfl_up(inc, 1, WAVE);
-        if (lane == 0) pm = ~0ull;
-        if (lane == WAVE - 1) L.tmp64[w] = inc;
-        __syncthreads();
-        for (int q = 0; q < w; ++q) pm = umin64(pm, L.tmp64[q]);
-        // accepted prefix: ranks below the first one whose worker is no longer the minimum
-        const uint64_t fail = __ballot(!(valid && sk < pm));
-        if (lane == 0) L.red[w] = fail ? w * WAVE + (__ffsll((long long)fail) - 1) : BAL_BLOCK;
-        __syncthreads();
-        int m = BAL_BLOCK;
-        for (int q = 0; q < BAL_WAVES; ++q) m = min(m, L.red[q]);
-        if (m == 0) break;                                            // cannot happen: cap * P >= N (uniform)
-        // back to the workers: rank r sends its updated key, its own rank in place of the worker id
-        if (tid < m) kbuf[sk & WIDE_ID_MASK] = (newk & ~WIDE_ID_MASK) | (uint64_t)tid;
-        const uint64_t thr = sbuf[m - 1];
-        __syncthreads();
-        if (tid < P && key <= thr) {                                  // my worker is among the m smallest
-            const uint64_t recv = kbuf[tid];
-            const uint64_t nk = (recv & ~WIDE_ID_MASK) | (uint64_t)tid;
-            const int mine = pos + (int)(recv & WIDE_ID_MASK);        // the item I took
-            step_slot[mine] = (uint16_t)count;
-            L.keys[sorted[mine]] = tid;                               // placed: its length is not needed again
-            load += (int64_t)((nk - key) >> WIDE_ID_BITS);
-            count += 1;
-            key = (count == C) ? full : nk;
-        }
-        pos += m;
-        // the next round's first barrier separates these reads of kbuf from its rewriting by other threads:
-        // a thread only overwrites its own entry before that barrier
-    }
-    __syncthreads();                                                  // kbuf / sbuf are done with: the tables take their place
-    int32_t total;
-    const int32_t off = block_excl_scan_add<int32_t>(count, reinterpret_cast<int32_t*>(L.tmp32), &total);
-    int32_t* part_off = reinterpret_cast<int32_t*>(L.cnt) + PART_OFF_AT;
-    if (tid < P) { part_off[tid] = off; shard_seq_off[tid] = off; shard_load[tid] = load; }
-    if (tid == 0) { part_off[P] = total; shard_seq_off[P] = N; }
-    return pos;
-}
-
-// The whole of Algorithm 1, by one workgroup of BAL_BLOCK threads.
-__device__ __forceinline__ void balance_body(BalLds& L, int32_t N, int32_t P, int32_t C,
-                                             const int32_t* __restrict__ seq_len, int32_t* __restrict__ perm,
-                                             int32_t* __restrict__ shard_seq_off, int32_t* __restrict__ shard_of_seq,
-                                             int64_t* __restrict__ shard_load, int32_t* status) {
-    const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
-
-    // ---- load lengths, range ----
-    int32_t mx = 0, mn = INT32_MAX;
-    for (int i = tid; i < N; i += BAL_BLOCK) {
-        int32_t s = seq_len[i];
-        if (s <= 0 || s > DC_MAX_SEQ_LEN) { set_status(status, DC_ERR_ZERO_LENGTH_SEQ); s = 1; }
-        L.keys[i] = s;
-        mx = max(mx, s);
-        mn = min(mn, s);
-    }
-    for (int d = 32; d >= 1; d >>= 1) {
-        mx = max(mx, __shfl_xor(mx, d, WAVE));
-        mn = min(mn, __shfl_xor(mn, d, WAVE));
-    }
-    if (lane == 0) { L.red[w] = mx; L.red[BAL_WAVES + w] = mn; }
-    __syncthreads();
-    mx = 0; mn = INT32_MAX;
-    for (int i = 0; i < BAL_WAVES; ++i) { mx = max(mx, L.red[i]); mn = min(mn, L.red[BAL_WAVES + i]); }
-    const uint32_t range = N > 0 ? (uint32_t)(mx - mn) : 0u;
-    const int nbits = 32 - __clz(range | 1u);
-    const int passes = range == 0 ? 0 : (nbits + 7) / 8;
-
-    // ---- a) radix sort of indices by (mx - len) ascending, stable ----
-    const int rounds = (N + BAL_BLOCK - 1) / BAL_BLOCK;           // <= BAL_ROUNDS
-    for (int i = tid; i < N; i += BAL_BLOCK) L.idx_a[i] = (uint16_t)i;
-    uint16_t* src = L.idx_a;
-    uint16_t* dst = L.idx_b;
-    __syncthreads();
-    for (int pass = 0; pass < passes; ++pass) {
-        const int shift = pass * 8;
-        counting_pass(L, N, rounds,
-                      [&](int pos) { return ((uint32_t)(mx - L.keys[src[pos]])) >> shift; },
-                      [&](int pos, int out) { dst[out] = src[pos]; });
-        uint16_t* t = src; src = dst; dst = t;
-    }
-    const uint16_t* sorted = src;                                 // I of Algorithm 1
-    uint16_t* step_slot = dst;                                    // place of I[t] inside its worker's partition
-    // every partition ends with exactly C items (Algorithm 1 as printed: C = N / K): rows per worker
-    const int pitch = (P <= WAVE && C > 0 && (int64_t)P * C == N) ? place_pitch(C) : 0;
-    int32_t* part_off = reinterpret_cast<int32_t*>(L.cnt) + PART_OFF_AT;
-    int32_t* placed = reinterpret_cast<int32_t*>(L.cnt) + PLACED_AT;
-
-    // ---- b) assignment rounds: wave 0 for up to 64 workers, else the whole workgroup ----
-    if (P > WAVE) {
-        const int n_placed = lpt_rounds_wide(L, N, P, C, sorted, step_slot, shard_seq_off, shard_load);
-        if (tid == 0) *placed = n_placed;
-    } else if (w == 0) {
-        int32_t* worker_count = reinterpret_cast<int32_t*>(L.cnt) + WCOUNT_AT;
-        int32_t* spare = L.spare;
-        int n_placed;
-        if (P <= 16) n_placed = lpt_rounds<16>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load);
-        else if (P <= 32) n_placed = lpt_rounds<32>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load);
-        else n_placed = lpt_rounds<64>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load);
-        // start of every P_k inside perm
-        const int32_t c = worker_count[lane];
-        const int32_t inc = (int32_t)wave_incl_scan_add_u32((uint32_t)c);
-        part_off[lane] = inc - c;
-        if (lane < P) shard_seq_off[lane] = inc - c;
-        if (lane == 0) { shard_seq_off[P] = N; *placed = n_placed; }
-    }
-    __syncthreads();
-
-    // ---- c) lay out P_0, P_1, ... each in insertion order ----
-    const int n_placed = *placed;
-    if (pitch) {                                                  // both stores in index order
-        for (int q = tid; q < N; q += BAL_BLOCK) {
-            const int k = q / C;
-            perm[q] = step_slot[k * pitch + (q - k * C)];
-            shard_of_seq[q] = L.keys[q];
-        }
-        return;
-    }
-    for (int t = tid; t < n_placed; t += BAL_BLOCK) {
-        const int u = sorted[t];
-        const int k = L.keys[u];                                  // the worker that took it
-        shard_of_seq[u] = k;
-        perm[part_off[k] + step_slot[t]] = u;
-    }
-}
 
 __global__ __launch_bounds__(BAL_BLOCK) void balance_kernel(int32_t N, int32_t P, int32_t C,
                                                             const int32_t* __restrict__ seq_len,

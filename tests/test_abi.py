@@ -37,7 +37,7 @@ def test_struct_layouts_match_header():
     assert B.dc_params.token_budget.offset == 16 and B.dc_params.eps.offset == 24
     assert C.sizeof(B.dc_source) == 32 and C.sizeof(B.dc_field) == 24
     text = open(os.path.join(ROOT, "include", "dc.h")).read()
-    for name, val in (("DC_MAX_SEQ", B.DC_MAX_SEQ), ("DC_MAX_SHARDS", B.DC_MAX_SHARDS),
+    for name, val in (("DC_MAX_SEQ", B.DC_MAX_SEQ), ("DC_MAX_SEQ_LARGE", B.DC_MAX_SEQ_LARGE), ("DC_MAX_SHARDS", B.DC_MAX_SHARDS),
                       ("DC_MAX_FIELDS", B.DC_MAX_FIELDS), ("DC_MAX_SRC_SHARDS", B.DC_MAX_SRC_SHARDS)):
         assert re.search(rf"#define\s+{name}\s+{val}\b", text)
     codes = dict(re.findall(r"(DC_(?:OK|ERR_[A-Z_]+))\s*=\s*(\d+)", text))
@@ -71,6 +71,39 @@ def test_balance_host_errors(lib):
     with pytest.raises(B.DcError) as e:
         B.dc_balance(B.make_params(8, 4, 100), None, FAKE, FAKE, FAKE, FAKE, FAKE, stream=0)
     assert e.value.code == B.DC_ERR_INVALID_ARG
+
+
+def test_balance_ws_host_errors(lib):
+    big = B.DC_MAX_SEQ * 4
+    assert B.dc_balance_workspace_bytes(B.make_params(B.DC_MAX_SEQ, 64, 100)) == 0
+    assert B.dc_balance_workspace_bytes(B.make_params(B.DC_MAX_SEQ_LARGE + 64, 64, 100)) == 0
+    ws = B.dc_balance_workspace_bytes(B.make_params(big, 64, 100))
+    assert ws >= 12 * big
+    out = (FAKE,) * 5                                         # seq_len, perm, shard_seq_off, shard_of_seq, shard_load
+    with pytest.raises(B.DcError) as e:                      # workspace too small
+        B.dc_balance_ws(B.make_params(big, 64, 100), *out, 0x10000, ws - 1, FAKE, stream=0)
+    assert e.value.code == B.DC_ERR_WORKSPACE
+    with pytest.raises(B.DcError) as e:                      # no workspace
+        B.dc_balance_ws(B.make_params(big, 64, 100), *out, None, ws, FAKE, stream=0)
+    assert e.value.code == B.DC_ERR_INVALID_ARG
+    with pytest.raises(B.DcError) as e:                      # workspace misaligned
+        B.dc_balance_ws(B.make_params(big, 64, 100), *out, 0x10010, ws, FAKE, stream=0)
+    assert e.value.code == B.DC_ERR_INVALID_ARG
+    with pytest.raises(B.DcError) as e:                      # more than 64 shards above DC_MAX_SEQ
+        B.dc_balance_ws(B.make_params(big, 128, 100), *out, 0x10000, ws, FAKE, stream=0)
+    assert e.value.code == B.DC_ERR_UNSUPPORTED_SIZE
+    with pytest.raises(B.DcError) as e:                      # more than 65535 sequences per shard
+        B.dc_balance_ws(B.make_params(1 << 18, 2, 100), *out, 0x10000, 1 << 24, FAKE, stream=0)
+    assert e.value.code == B.DC_ERR_UNSUPPORTED_SIZE
+    with pytest.raises(B.DcError) as e:                      # beyond DC_MAX_SEQ_LARGE
+        B.dc_balance_ws(B.make_params(B.DC_MAX_SEQ_LARGE + 64, 64, 100), *out, 0x10000, 1 << 26, FAKE, stream=0)
+    assert e.value.code == B.DC_ERR_UNSUPPORTED_SIZE
+    with pytest.raises(B.DcError) as e:                      # Algorithm 1's assertion
+        B.dc_balance_ws(B.make_params(big + 1, 64, 100), *out, 0x10000, 1 << 24, FAKE, stream=0)
+    assert e.value.code == B.DC_ERR_NOT_DIVISIBLE
+    with pytest.raises(B.DcError) as e:                      # dc_balance itself keeps its limit
+        B.dc_balance(B.make_params(big, 64, 100), *out, FAKE, stream=0)
+    assert e.value.code == B.DC_ERR_UNSUPPORTED_SIZE
 
 
 def test_plan_and_gather_host_errors(lib):

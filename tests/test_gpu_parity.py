@@ -322,6 +322,48 @@ def test_more_than_64_shards():
     check_step(_custom(rng.integers(1, 300, 200), 2, 200, 512), label="N=P=200")
 
 
+def _check_balance_ws(lens, P, cap=0, label=""):
+    torch, binding, runner = _gpu()
+    lens = np.asarray(lens, np.int32)
+    N = len(lens)
+    print(f"[parity] balance_ws {label}: N={N} P={P} cap={cap}", flush=True)
+    prm = binding.make_params(N, P, 1 << 20, 1e-6, 1, cap, 1)
+    dev = torch.device("cuda:0")
+    seq_len = torch.from_numpy(lens).to(dev)
+    perm = torch.full((N,), -1, dtype=torch.int32, device=dev)
+    shard_seq_off = torch.full((P + 1,), -1, dtype=torch.int32, device=dev)
+    shard_of_seq = torch.full((N,), -1, dtype=torch.int32, device=dev)
+    shard_load = torch.full((P,), -1, dtype=torch.int64, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    nb = binding.dc_balance_workspace_bytes(prm)
+    assert (nb > 0) == (N > binding.DC_MAX_SEQ)
+    ws = torch.empty(max(nb, 256), dtype=torch.uint8, device=dev) if nb else None
+    binding.dc_balance_ws(prm, seq_len, perm, shard_seq_off, shard_of_seq, shard_load, ws, nb, status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    bal = oracle.balance(lens, P, cap)
+    assert np.array_equal(perm.cpu().numpy(), bal.perm)
+    assert np.array_equal(shard_seq_off.cpu().numpy(), bal.shard_seq_off)
+    assert np.array_equal(shard_of_seq.cpu().numpy(), bal.shard_of_seq)
+    assert np.array_equal(shard_load.cpu().numpy(), bal.shard_load)
+
+
+def test_balance_beyond_the_lds():
+    """dc_balance_ws above DC_MAX_SEQ sequences: index arrays in a workspace, the assignment in portions."""
+    rng = np.random.default_rng(31)
+    heavy = lambda n: np.minimum(64 * (1.0 - rng.random(n)) ** (-1 / 1.3), 32768).astype(np.int32) + rng.integers(512, 4096, n)
+    _check_balance_ws(heavy(16384 + 64), 64, label="one round more than the LDS holds")
+    _check_balance_ws(heavy(32768), 64, label="two portions, long tail")
+    _check_balance_ws(np.minimum(rng.geometric(0.002, 49152), 9000), 16, label="three portions, P=16")
+    _check_balance_ws(rng.integers(1, 300, 100000), 8, label="N=100000, many equal lengths")
+    _check_balance_ws(rng.integers(1, 5000, 40000), 7, cap=6000, label="partitions of unequal size")
+    _check_balance_ws(rng.integers(1, 5000, 40003), 7, cap=40003 // 7 + 1, label="N no multiple of P")
+    _check_balance_ws(np.full(20000, 77), 4, label="all equal")
+    _check_balance_ws(rng.integers(1, 100, 30000), 1, label="one worker")
+    _check_balance_ws(heavy(63 * 785), 63, label="P=63, portions that end inside a round")
+    _check_balance_ws(heavy(8192), 32, label="below the limit: dc_balance itself, no workspace")
+
+
 def test_longest_sequence_and_most_fields():
     # two sequences of DC_MAX_SEQ_LEN tokens next to tiny ones (LPT keys, 32-bit offsets inside a tile, int64 outside)
     L = 1 << 24
