@@ -7,7 +7,8 @@
  * the one DP-layout change of a GRPO step):
  *
  *   dc_balance          Algorithm 1, Constrained LPT Load Balancing: N sequence
- *                       lengths -> P shards of (by default) exactly N/P sequences.
+ *                       lengths -> P shards of (by default) exactly N/P sequences
+ *                       (dc_balance_ws: the same for more than DC_MAX_SEQ sequences).
  *   dc_group_advantage  the "advantage" stage of GRPO (Sec. 1 payload list,
  *                       App. B Table 2): each response's reward normalised by
  *                       its prompt group's mean and std, then broadcast over the
@@ -68,8 +69,11 @@
 extern "C" {
 #endif
 
-#define DC_MAX_SEQ        16384   /* N: one workgroup sorts and plans in LDS          */
-#define DC_MAX_SEQ_LARGE  1048576 /* N of the calls that say so (dc_balance_ws)      */
+#define DC_MAX_SEQ        16384   /* N of dc_balance, dc_balance_group_advantage: one   */
+                                  /*    workgroup sorts and assigns in LDS            */
+#define DC_MAX_SEQ_LARGE  1048576 /* N of every other call (dc_balance_ws among them); */
+                                  /*    above DC_MAX_SEQ the balance and the plan take  */
+                                  /*    slower paths through workspace memory          */
 #define DC_MAX_SHARDS     1024    /* P: one lane per shard (one wavefront up to 64,   */
                                   /*    the whole workgroup above)                    */
 #define DC_MAX_FIELDS     8
@@ -122,7 +126,8 @@ typedef struct dc_field {
 } dc_field;
 
 /* Bytes of device workspace dc_plan / dc_gather / dc_repack need for these sizes
- * (about 70 bytes per 1024 tokens of capacity plus 16 bytes per sequence). */
+ * (about 70 bytes per 1024 tokens of capacity plus 16 bytes per sequence; above DC_MAX_SEQ
+ * sequences 8.25 bytes per sequence more). */
 size_t dc_workspace_bytes(const dc_params* prm, int64_t dst_capacity_tokens);
 
 /*

@@ -19,13 +19,22 @@ Workspace carve_workspace(void* base, int32_t n_seq, int64_t dst_capacity_tokens
     w.gran_first = reinterpret_cast<int32_t*>(p + off);   off += round_up((size_t)w.n_gran * sizeof(int32_t), 256);
     w.gran_rec = reinterpret_cast<GranRec*>(p + off);     off += round_up((size_t)w.n_gran * sizeof(GranRec), 256);
     w.plan_ok = reinterpret_cast<int32_t*>(p + off);      off += 256;
+    w.gpre = nullptr; w.word_starts = nullptr; w.word_last = nullptr;
+    if (n_seq > DC_MAX_SEQ) {
+        const size_t words = n / 32 + 2;
+        w.gpre = reinterpret_cast<int64_t*>(p + off);        off += round_up((n + 1) * sizeof(int64_t), 256);
+        w.word_starts = reinterpret_cast<int32_t*>(p + off); off += round_up(words * sizeof(int32_t), 256);
+        w.word_last = reinterpret_cast<int32_t*>(p + off);   off += round_up(words * sizeof(int32_t), 256);
+    }
     w.bytes = off + 256;
     return w;
 }
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-static dc_status check_params(const dc_params* prm, int32_t max_seq = DC_MAX_SEQ) {
+// max_seq: DC_MAX_SEQ for the calls whose kernels keep all sequences in one workgroup's LDS (dc_balance,
+// dc_balance_group_advantage), DC_MAX_SEQ_LARGE for the others.
+static dc_status check_params(const dc_params* prm, int32_t max_seq = DC_MAX_SEQ_LARGE) {
     if (!prm) return DC_ERR_INVALID_ARG;
     if (prm->n_seq < 0 || prm->n_shards < 1 || prm->cap < 0 || prm->align_tokens < 1 || prm->reserved != 0)
         return DC_ERR_INVALID_ARG;

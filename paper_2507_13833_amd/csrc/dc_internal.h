@@ -49,6 +49,9 @@ struct Workspace {
     int32_t* gran_first;     // [n_gran] first slot j with end(j) > g * GATHER_GRAN (N if none); non-decreasing
     GranRec* gran_rec;       // [n_gran]
     int32_t* plan_ok;        // [1] 0 if the plan kernel found the shard table unusable and planned nothing
+    int64_t* gpre;           // [N + 1]  } only above DC_MAX_SEQ slots (else null): what plan_kernel keeps in LDS
+    int32_t* word_starts;    // [N / 32 + 2]
+    int32_t* word_last;      // [N / 32 + 2]
     int64_t  n_gran;         // ceil(capacity / GATHER_GRAN) + GRAN_TABLE_PAD; entries past the arena hold N / no slot
     size_t   bytes;
 };
@@ -92,6 +95,36 @@ hipError_t launch_advantage(int32_t n_seq, const SourceDesc& src, const int64_t*
                             int32_t n_groups, double eps, int32_t ddof,
                             const uint8_t* const* mask_base, float* d_adv_seq, float* const* adv_tok_base,
                             int32_t* d_status, hipStream_t st);
+
+// Arguments of the plan kernels.
+struct PlanArgs {
+    int32_t n_seq, n_shards, align;
+    int64_t budget, capacity;
+    const int64_t* src_tok_off;
+    const int32_t* seq_len;
+    const int32_t* perm;
+    const int32_t* shard_seq_off;
+    int64_t* dst_tok_off;
+    int64_t* shard_tok_off;
+    int32_t* shard_mb_off;
+    int32_t* mb_seq_off;
+    int32_t* cu_seqlens;
+    int32_t* n_mb;
+    int64_t* slot_src_off;
+    int32_t* slot_len;
+    int32_t* slot_shard;
+    int32_t* plan_ok;
+    int32_t* status;
+    // more than DC_MAX_SEQ slots only (workspace): dense prefix of the slot lengths, and per word of 32 slots
+    // the micro-batch starts before it / the last start before it
+    int64_t* gpre;
+    int32_t* word_starts;
+    int32_t* word_last;
+};
+
+// plan_kernel's work for DC_MAX_SEQ < n_seq <= DC_MAX_SEQ_LARGE: one workgroup, the prefix and the per-word
+// tables in the workspace instead of the LDS.
+hipError_t launch_plan_large(const PlanArgs& a, hipStream_t st);
 
 hipError_t launch_plan(const dc_params& prm, const SourceDesc& src, const int64_t* d_src_tok_off,
                        const int32_t* d_seq_len, const int32_t* d_perm, const int32_t* d_shard_seq_off,

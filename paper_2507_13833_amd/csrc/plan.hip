@@ -29,25 +29,6 @@ constexpr int PLAN_WAVES = PLAN_BLOCK / WAVE;
 constexpr int PLAN_IPT = DC_MAX_SEQ / PLAN_BLOCK;        // slots per lane at the size limit
 constexpr int PLAN_WORDS = DC_MAX_SEQ / 32;
 
-struct PlanArgs {
-    int32_t n_seq, n_shards, align;
-    int64_t budget, capacity;
-    const int64_t* src_tok_off;
-    const int32_t* seq_len;
-    const int32_t* perm;
-    const int32_t* shard_seq_off;
-    int64_t* dst_tok_off;
-    int64_t* shard_tok_off;
-    int32_t* shard_mb_off;
-    int32_t* mb_seq_off;
-    int32_t* cu_seqlens;
-    int32_t* n_mb;
-    int64_t* slot_src_off;
-    int32_t* slot_len;
-    int32_t* slot_shard;
-    int32_t* plan_ok;
-    int32_t* status;
-};
 
 struct PlanLds {
     int64_t  gpre[DC_MAX_SEQ + 1];          // dense exclusive prefix of slot lengths
@@ -411,14 +392,21 @@ hipError_t launch_plan(const dc_params& prm, const SourceDesc& src, const int64_
     a.mb_seq_off = d_mb_seq_off; a.cu_seqlens = d_cu_seqlens; a.n_mb = d_n_mb;
     a.slot_src_off = ws.slot_src_off; a.slot_len = ws.slot_len; a.slot_shard = ws.slot_shard;
     a.plan_ok = ws.plan_ok; a.status = d_status;
+    a.gpre = ws.gpre; a.word_starts = ws.word_starts; a.word_last = ws.word_last;
     if (prm.n_seq > 0) {
         hipLaunchKernelGGL(slots_kernel, dim3((unsigned)((prm.n_seq + SLOTS_BLOCK - 1) / SLOTS_BLOCK)), dim3(SLOTS_BLOCK),
                            0, st, a, src);
         hipError_t e0 = hipGetLastError();
         if (e0 != hipSuccess) return e0;
     }
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(PLAN_BLOCK), 0, st, a);
-    hipError_t e = hipGetLastError();
+    hipError_t e;
+    if (prm.n_seq > DC_MAX_SEQ) {
+        if (!ws.gpre) return hipErrorInvalidValue;
+        e = launch_plan_large(a, st);
+    } else {
+        hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(PLAN_BLOCK), 0, st, a);
+        e = hipGetLastError();
+    }
     if (e != hipSuccess) return e;
     return launch_records(prm.n_seq, d_dst_tok_off, ws, st);
 }

@@ -63,6 +63,10 @@ class DeviceBatch:
         self.n_mb = torch.zeros(1, dtype=torch.int32, device=dev)
         self.ws_bytes = B.dc_workspace_bytes(self.prm, self.capacity)
         self.ws = torch.zeros(self.ws_bytes, dtype=torch.uint8, device=dev)
+        # more sequences than dc_balance takes: dc_balance_ws and its workspace
+        self.large = N > B.DC_MAX_SEQ
+        self.bal_ws_bytes = B.dc_balance_workspace_bytes(self.prm)
+        self.bal_ws = torch.zeros(self.bal_ws_bytes, dtype=torch.uint8, device=dev) if self.bal_ws_bytes else None
 
         self.dst_fields: Dict[str, torch.Tensor] = {}
         for name, eb in self.elem_bytes.items():
@@ -88,6 +92,10 @@ class DeviceBatch:
                              self.adv_tok_src if per_token else None, self.status, stream)
 
     def balance(self) -> None:
+        if self.large:
+            B.dc_balance_ws(self.prm, self.seq_len, self.perm, self.shard_seq_off, self.shard_of_seq,
+                            self.shard_load, self.bal_ws, self.bal_ws_bytes, self.status)
+            return
         B.dc_balance(self.prm, self.seq_len, self.perm, self.shard_seq_off, self.shard_of_seq,
                      self.shard_load, self.status)
 
@@ -119,6 +127,10 @@ class DeviceBatch:
         self.gather()
 
     def balance_group_advantage(self, per_token: bool = True) -> None:
+        if self.large:                                   # the one-launch form keeps dc_balance's size limit
+            self.group_advantage(per_token)
+            self.balance()
+            return
         B.dc_balance_group_advantage(self.prm, self.source, self.seq_len, self.perm, self.shard_seq_off,
                                      self.shard_of_seq, self.shard_load, self.reward, self.group_off, self.w.n_groups,
                                      self.src_fields["mask"] if per_token else None, self.adv_seq,

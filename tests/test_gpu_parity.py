@@ -364,6 +364,46 @@ def test_balance_beyond_the_lds():
     _check_balance_ws(heavy(8192), 32, label="below the limit: dc_balance itself, no workspace")
 
 
+def test_more_sequences_than_the_lds_holds():
+    """The whole path above DC_MAX_SEQ sequences: dc_balance_ws, the plan through workspace memory, and the
+    kernels that never cared (advantage, gather, scatter, GAE)."""
+    rng = np.random.default_rng(33)
+    lens = np.minimum(rng.geometric(0.006, 32768), 2500).astype(np.int32)
+    w = _custom(lens, 16, 64, 8192, n_src=4)
+    check_step(w, label="N=32768 P=64")
+    check_step(w, align=16, label="N=32768 P=64 align 16")
+    check_gather_advantage(w, label="N=32768 P=64")
+    check_scatter(w, label="N=32768 P=64")
+    lens = rng.integers(1, 400, 50000).astype(np.int32)
+    w = _custom(lens, 5, 8, 3000, n_src=2)
+    check_step(w, label="N=50000 P=8, ~20 slots per micro-batch")
+    check_step(w, cap=50000 // 8 + 7, label="N=50000 P=8 cap=C+7")
+    w = _with_ppo_fields(_custom(np.minimum(rng.geometric(0.01, 20480), 1500).astype(np.int32), 4, 16, 100000, n_src=2))
+    check_step(w, label="N=20480 P=16, ~60 slots per micro-batch... and more than two windows")
+    check_gae(w, 0.99, 0.95, 0.0, label="N=20480")
+    # many shards above the limit: the plan's one-lane-per-shard walk (dc_balance_ws stops at 64 shards, so the
+    # partition comes from the oracle here)
+    torch, binding, runner = _gpu()
+    lens = rng.integers(1, 300, 128 * 200).astype(np.int32)
+    w = _custom(lens, 8, 128, 2048, n_src=2)
+    d = runner.DeviceBatch(w, poison=True)
+    bal = oracle.balance(w.seq_len, 128)
+    d.perm.copy_(torch.from_numpy(bal.perm)); d.shard_seq_off.copy_(torch.from_numpy(bal.shard_seq_off))
+    d.plan(); d.gather()
+    torch.cuda.synchronize()
+    assert d.read_status() == 0
+    pl = oracle.plan(w.seq_len, bal.perm, bal.shard_seq_off, w.token_budget, 1)
+    M = int(d.n_mb.item())
+    assert M == pl.n_mb
+    assert np.array_equal(d.dst_tok_off.cpu().numpy(), pl.dst_tok_off)
+    assert np.array_equal(d.shard_mb_off.cpu().numpy(), pl.shard_mb_off)
+    assert np.array_equal(d.mb_seq_off.cpu().numpy()[:M + 1], pl.mb_seq_off)
+    assert np.array_equal(d.cu_seqlens.cpu().numpy()[:w.n_seq + M], pl.cu_seqlens)
+    f = w.fields[0]
+    want = oracle.gather(w.seq_len, bal.perm, w.src_tok_off, w.src_shard_seq_off, f.shards, pl.dst_tok_off, d.capacity)
+    assert np.array_equal(d.dst_fields[f.name].cpu().numpy().view(want.dtype), want)
+
+
 def test_longest_sequence_and_most_fields():
     # two sequences of DC_MAX_SEQ_LEN tokens next to tiny ones (LPT keys, 32-bit offsets inside a tile, int64 outside)
     L = 1 << 24
@@ -717,6 +757,42 @@ def test_device_status_codes():
     d.gae(); torch.cuda.synchronize()
     assert d.read_status() == binding.DC_ERR_BAD_LAYOUT
     assert torch.isnan(d.gae_ret[0][12:]).all()
+
+
+def test_device_status_codes_above_the_lds_limit():
+    """The same refusals on the paths for more than DC_MAX_SEQ sequences."""
+    torch, binding, runner = _gpu()
+    rng = np.random.default_rng(35)
+    lens = rng.integers(1, 200, 20480).astype(np.int32)
+    w = _custom(lens, 4, 16, 4096, n_src=2, fields=("i32",))
+
+    d = runner.DeviceBatch(w)
+    d.seq_len[12345] = 0                                               # zero-length sequence
+    d.balance(); torch.cuda.synchronize()
+    assert d.read_status() == binding.DC_ERR_ZERO_LENGTH_SEQ
+
+    d = runner.DeviceBatch(w)
+    d.capacity -= 1                                                    # arena one token short
+    d.balance(); d.plan(); d.gather(); torch.cuda.synchronize()
+    assert d.read_status() == binding.DC_ERR_OVERFLOW
+
+    d = runner.DeviceBatch(w, poison=True)
+    d.balance(); torch.cuda.synchronize()
+    d.perm[20000] = d.perm[3]                                          # not a permutation: the repeat moves nothing
+    d.plan(); d.gather(); torch.cuda.synchronize()
+    assert d.read_status() == binding.DC_ERR_BAD_LAYOUT
+
+    d = runner.DeviceBatch(w)
+    d.balance(); torch.cuda.synchronize()
+    d.shard_seq_off[5] = d.shard_seq_off[4] - 1                        # shard table not monotone: nothing is planned
+    d.plan(); d.gather(); torch.cuda.synchronize()
+    assert d.read_status() == binding.DC_ERR_BAD_LAYOUT
+    assert int(d.n_mb.item()) == 0
+
+    w2 = _custom(np.concatenate([lens, [5000] * 16]).astype(np.int32), 4, 16, 4096, n_src=2, fields=("i32",))
+    d = runner.DeviceBatch(w2)
+    d.step(); torch.cuda.synchronize()                                 # 5000 > budget 4096
+    assert d.read_status() == binding.DC_ERR_SEQ_EXCEEDS_BUDGET
 
 
 def test_empty_batch():
