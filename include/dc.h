@@ -149,8 +149,8 @@ dc_status dc_balance(const dc_params* prm, const int32_t* d_seq_len,
  * sequences it is dc_balance itself and d_ws may be NULL.  Above, the sort keeps its index arrays in
  * d_ws (256-byte aligned, dc_balance_workspace_bytes(prm) bytes: 12 bytes per sequence) and the
  * assignment takes the sorted sequences DC_MAX_SEQ at a time, carrying the workers' loads along; a slower
- * path (every sort access is a global one).  Limits above DC_MAX_SEQ: n_shards <= 64 and at most 65535
- * sequences per shard (C of Algorithm 1, or prm->cap), else UNSUPPORTED_SIZE.
+ * path (every sort access is a global one).  Limit above DC_MAX_SEQ: at most 65535 sequences per
+ * shard (C of Algorithm 1, or prm->cap), else UNSUPPORTED_SIZE.
  */
 size_t dc_balance_workspace_bytes(const dc_params* prm);
 dc_status dc_balance_ws(const dc_params* prm, const int32_t* d_seq_len,

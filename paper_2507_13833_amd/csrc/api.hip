@@ -165,8 +165,7 @@ dc_status dc_balance_ws(const dc_params* prm, const int32_t* d_seq_len,
     if (rc != DC_OK) return rc;
     if (prm->n_seq <= DC_MAX_SEQ)
         return dc_balance(prm, d_seq_len, d_perm, d_shard_seq_off, d_shard_of_seq, d_shard_load, d_status, hip_stream);
-    // the portions of the assignment run on one wavefront, and a place inside a partition is kept in 16 bits
-    if (prm->n_shards > 64 || cap_eff > 65535) return DC_ERR_UNSUPPORTED_SIZE;
+    if (cap_eff > 65535) return DC_ERR_UNSUPPORTED_SIZE;            // a place inside a partition is kept in 16 bits
     if (!d_ws || (reinterpret_cast<uintptr_t>(d_ws) & 255u)) return DC_ERR_INVALID_ARG;
     if (ws_bytes < balance_ws_bytes(prm->n_seq)) return DC_ERR_WORKSPACE;
     hipError_t e = launch_balance_large(prm->n_seq, prm->n_shards, cap_eff, d_seq_len, d_perm, d_shard_seq_off,

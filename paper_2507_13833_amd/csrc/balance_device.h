@@ -295,15 +295,31 @@ static_assert(DC_MAX_SHARDS <= (1 << WIDE_ID_BITS), "worker id fits the key's lo
 
 __device__ __forceinline__ uint64_t umin64(uint64_t a, uint64_t b) { return a < b ? a : b; }
 
-__device__ __forceinline__ int lpt_rounds_wide(BalLds& L, int N, int P, int C, const uint16_t* sorted, uint16_t* step_slot,
-                                               int32_t* __restrict__ shard_seq_off, int64_t* __restrict__ shard_load) {
+// What thread k keeps of worker k between two portions of the items (see LptCarry).
+struct WideCarry {
+    uint64_t key;
+    int32_t  count;
+    int64_t  load;
+};
+__device__ __forceinline__ WideCarry wide_fresh(int P, int C) {
+    const int tid = threadIdx.x;
+    WideCarry c;
+    c.key = (tid < P && C > 0) ? (uint64_t)tid : (WIDE_FULL | (uint64_t)tid);
+    c.count = 0;
+    c.load = 0;
+    return c;
+}
+
+// The rounds over the N items of one portion.  Returns the number of items placed.
+__device__ __forceinline__ int lpt_rounds_wide_portion(BalLds& L, int N, int P, int C, const uint16_t* sorted,
+                                                       uint16_t* step_slot, WideCarry& carry) {
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
     uint64_t* kbuf = reinterpret_cast<uint64_t*>(L.cnt);              // keys in worker order; then the keys sent back
     uint64_t* sbuf = kbuf + DC_MAX_SHARDS;                            // keys in rank order
     const uint64_t full = WIDE_FULL | (uint64_t)tid;
-    uint64_t key = (tid < P && C > 0) ? (uint64_t)tid : full;
-    int32_t count = 0;
-    int64_t load = 0;
+    uint64_t key = carry.key;
+    int32_t count = carry.count;
+    int64_t load = carry.load;
     int pos = 0;
     while (pos < N) {                                                 // pos is the same in every thread
         kbuf[tid] = key;
@@ -358,13 +374,28 @@ __device__ __forceinline__ int lpt_rounds_wide(BalLds& L, int N, int P, int C, c
         // the next round's first barrier separates these reads of kbuf from its rewriting by other threads:
         // a thread only overwrites its own entry before that barrier
     }
+    carry.key = key; carry.count = count; carry.load = load;
+    return pos;
+}
+
+// After the last portion: part_off[0..P] gets the start of every P_k, the outputs their tables (N: all items).
+__device__ __forceinline__ void lpt_wide_finish(BalLds& L, int N, int P, const WideCarry& carry,
+                                                int32_t* __restrict__ shard_seq_off, int64_t* __restrict__ shard_load) {
+    const int tid = threadIdx.x;
     __syncthreads();                                                  // kbuf / sbuf are done with: the tables take their place
     int32_t total;
-    const int32_t off = block_excl_scan_add<int32_t>(count, reinterpret_cast<int32_t*>(L.tmp32), &total);
+    const int32_t off = block_excl_scan_add<int32_t>(carry.count, reinterpret_cast<int32_t*>(L.tmp32), &total);
     int32_t* part_off = reinterpret_cast<int32_t*>(L.cnt) + PART_OFF_AT;
-    if (tid < P) { part_off[tid] = off; shard_seq_off[tid] = off; shard_load[tid] = load; }
+    if (tid < P) { part_off[tid] = off; shard_seq_off[tid] = off; shard_load[tid] = carry.load; }
     if (tid == 0) { part_off[P] = total; shard_seq_off[P] = N; }
-    return pos;
+}
+
+__device__ __forceinline__ int lpt_rounds_wide(BalLds& L, int N, int P, int C, const uint16_t* sorted, uint16_t* step_slot,
+                                               int32_t* __restrict__ shard_seq_off, int64_t* __restrict__ shard_load) {
+    WideCarry carry = wide_fresh(P, C);
+    const int placed = lpt_rounds_wide_portion(L, N, P, C, sorted, step_slot, carry);
+    lpt_wide_finish(L, N, P, carry, shard_seq_off, shard_load);
+    return placed;
 }
 
 // The whole of Algorithm 1, by one workgroup of BAL_BLOCK threads.

@@ -3,15 +3,15 @@
 
 namespace dc {
 
-// N > DC_MAX_SEQ (up to DC_MAX_SEQ_LARGE), P <= 64: the same algorithm by one workgroup, with the
+// N > DC_MAX_SEQ (up to DC_MAX_SEQ_LARGE): the same algorithm by one workgroup, with the
 // index arrays of the sort in a caller-supplied workspace and the assignment fed in portions of
-// DC_MAX_SEQ sorted items, staged into the LDS arrays the rounds read (lpt_rounds as it is; the
+// DC_MAX_SEQ sorted items, staged into the LDS arrays the rounds read (lpt_rounds / lpt_rounds_wide as they are; the
 // workers' keys, counts and loads are carried from portion to portion).  A slow path next to
 // balance.hip's: every access to the index arrays is a global one.
 struct BalanceLargeWs {
     int32_t* idx_a;        // [N] sort ping
     int32_t* idx_b;        // [N] sort pong
-    int32_t* place;        // [N] by sorted position: worker << 24 | place inside its partition
+    int32_t* place;        // [N] by sorted position: worker << 16 | place inside its partition
 };
 
 // counting_pass with positions, digits and outputs outside the LDS.  Wave w owns the contiguous positions
@@ -118,7 +118,8 @@ __global__ __launch_bounds__(BAL_BLOCK) void balance_large_kernel(int32_t N, int
     // ---- b) the assignment, DC_MAX_SEQ sorted items at a time ----
     int32_t* worker_count = reinterpret_cast<int32_t*>(L.cnt) + WCOUNT_AT;
     int32_t* part_off = reinterpret_cast<int32_t*>(L.cnt) + PART_OFF_AT;
-    LptCarry carry = lpt_fresh(P, C);                             // wave 0's lanes keep the workers
+    LptCarry carry = lpt_fresh(P, C);                             // up to 64 workers: wave 0's lanes keep them
+    WideCarry wide = wide_fresh(P, C);                            // more: thread k keeps worker k
     for (int c0 = 0; c0 < N; c0 += DC_MAX_SEQ) {
         const int n = min(DC_MAX_SEQ, N - c0);
         for (int t = tid; t < n; t += BAL_BLOCK) {
@@ -126,17 +127,21 @@ __global__ __launch_bounds__(BAL_BLOCK) void balance_large_kernel(int32_t N, int
             L.idx_a[t] = (uint16_t)t;                             // the portion is in order already
         }
         __syncthreads();
-        if (w == 0) {
+        if (P > WAVE) {
+            lpt_rounds_wide_portion(L, n, P, C, L.idx_a, L.idx_b, wide);
+        } else if (w == 0) {
             if (P <= 16) lpt_rounds<16>(n, P, C, L.keys, L.idx_a, mx, L.idx_b, 0, L.spare, worker_count, shard_load, carry);
             else if (P <= 32) lpt_rounds<32>(n, P, C, L.keys, L.idx_a, mx, L.idx_b, 0, L.spare, worker_count, shard_load, carry);
             else lpt_rounds<64>(n, P, C, L.keys, L.idx_a, mx, L.idx_b, 0, L.spare, worker_count, shard_load, carry);
         }
         __syncthreads();
         for (int t = tid; t < n; t += BAL_BLOCK)                  // keys[t]: the worker that took item t of the portion
-            ws.place[c0 + t] = (L.keys[t] << 24) | (int32_t)L.idx_b[t];
+            ws.place[c0 + t] = (L.keys[t] << 16) | (int32_t)L.idx_b[t];
         __syncthreads();
     }
-    if (w == 0) {                                                 // start of every P_k inside perm
+    if (P > WAVE) {
+        lpt_wide_finish(L, N, P, wide, shard_seq_off, shard_load);
+    } else if (w == 0) {                                          // start of every P_k inside perm
         const int32_t c = worker_count[lane];
         const int32_t inc = (int32_t)wave_incl_scan_add_u32((uint32_t)c);
         part_off[lane] = inc - c;
@@ -150,9 +155,9 @@ __global__ __launch_bounds__(BAL_BLOCK) void balance_large_kernel(int32_t N, int
     for (int t = tid; t < N; t += BAL_BLOCK) {
         const int u = sorted[t];
         const int32_t pl = ws.place[t];
-        const int k = (pl >> 24) & (WAVE - 1);                    // (every item is placed: P * C >= N; no index leaves
+        const int k = min((int)((uint32_t)pl >> 16), P - 1);      // (every item is placed: P * C >= N; no index leaves
         shard_of_seq[u] = k;                                      //  the arrays whatever the words hold)
-        perm[min(part_off[k] + (pl & 0xFFFFFF), N - 1)] = u;
+        perm[min(part_off[k] + (pl & 0xFFFF), N - 1)] = u;
     }
 }
 

@@ -89,9 +89,6 @@ def test_balance_ws_host_errors(lib):
     with pytest.raises(B.DcError) as e:                      # workspace misaligned
         B.dc_balance_ws(B.make_params(big, 64, 100), *out, 0x10010, ws, FAKE, stream=0)
     assert e.value.code == B.DC_ERR_INVALID_ARG
-    with pytest.raises(B.DcError) as e:                      # more than 64 shards above DC_MAX_SEQ
-        B.dc_balance_ws(B.make_params(big, 128, 100), *out, 0x10000, ws, FAKE, stream=0)
-    assert e.value.code == B.DC_ERR_UNSUPPORTED_SIZE
     with pytest.raises(B.DcError) as e:                      # more than 65535 sequences per shard
         B.dc_balance_ws(B.make_params(1 << 18, 2, 100), *out, 0x10000, 1 << 24, FAKE, stream=0)
     assert e.value.code == B.DC_ERR_UNSUPPORTED_SIZE

@@ -362,6 +362,9 @@ def test_balance_beyond_the_lds():
     _check_balance_ws(rng.integers(1, 100, 30000), 1, label="one worker")
     _check_balance_ws(heavy(63 * 785), 63, label="P=63, portions that end inside a round")
     _check_balance_ws(heavy(8192), 32, label="below the limit: dc_balance itself, no workspace")
+    _check_balance_ws(heavy(128 * 300), 128, label="128 workers")
+    _check_balance_ws(rng.integers(1, 2000, 1000 * 40), 1000, label="1000 workers, lengths with many ties")
+    _check_balance_ws(heavy(65 * 600), 65, cap=640, label="65 workers, partitions of unequal size")
 
 
 def test_more_sequences_than_the_lds_holds():
@@ -381,27 +384,9 @@ def test_more_sequences_than_the_lds_holds():
     w = _with_ppo_fields(_custom(np.minimum(rng.geometric(0.01, 20480), 1500).astype(np.int32), 4, 16, 100000, n_src=2))
     check_step(w, label="N=20480 P=16, ~60 slots per micro-batch... and more than two windows")
     check_gae(w, 0.99, 0.95, 0.0, label="N=20480")
-    # many shards above the limit: the plan's one-lane-per-shard walk (dc_balance_ws stops at 64 shards, so the
-    # partition comes from the oracle here)
-    torch, binding, runner = _gpu()
+    # many shards above the limit: the whole workgroup assigns, one lane per shard walks the micro-batches
     lens = rng.integers(1, 300, 128 * 200).astype(np.int32)
-    w = _custom(lens, 8, 128, 2048, n_src=2)
-    d = runner.DeviceBatch(w, poison=True)
-    bal = oracle.balance(w.seq_len, 128)
-    d.perm.copy_(torch.from_numpy(bal.perm)); d.shard_seq_off.copy_(torch.from_numpy(bal.shard_seq_off))
-    d.plan(); d.gather()
-    torch.cuda.synchronize()
-    assert d.read_status() == 0
-    pl = oracle.plan(w.seq_len, bal.perm, bal.shard_seq_off, w.token_budget, 1)
-    M = int(d.n_mb.item())
-    assert M == pl.n_mb
-    assert np.array_equal(d.dst_tok_off.cpu().numpy(), pl.dst_tok_off)
-    assert np.array_equal(d.shard_mb_off.cpu().numpy(), pl.shard_mb_off)
-    assert np.array_equal(d.mb_seq_off.cpu().numpy()[:M + 1], pl.mb_seq_off)
-    assert np.array_equal(d.cu_seqlens.cpu().numpy()[:w.n_seq + M], pl.cu_seqlens)
-    f = w.fields[0]
-    want = oracle.gather(w.seq_len, bal.perm, w.src_tok_off, w.src_shard_seq_off, f.shards, pl.dst_tok_off, d.capacity)
-    assert np.array_equal(d.dst_fields[f.name].cpu().numpy().view(want.dtype), want)
+    check_step(_custom(lens, 8, 128, 2048, n_src=2), label="N=25600 P=128")
 
 
 def test_longest_sequence_and_most_fields():
