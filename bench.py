@@ -32,10 +32,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # out); valid only for the kernel sources with the digest below (profiles/ has the runs).
 TRAFFIC = {
     # config: (fetch bytes + write bytes per gather launch, digest of csrc/gather.hip + csrc/dc_internal.h)
-    5: (1044623400 + 985040700, "8bf74f47e6165089"),     # profiles/hbm_traffic_config5_pmc.txt
+    5: (1044536900 + 985038600, "053e77118e55f191"),     # profiles/hbm_traffic_config5_pmc.txt
 }
 TRAFFIC_ADV = {                                          # the same for dc_gather_advantage's kernel
-    5: (867732400 + 983720700, "8bf74f47e6165089"),
+    5: (867835400 + 983742500, "053e77118e55f191"),
 }
 
 
