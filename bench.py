@@ -9,8 +9,9 @@ bandwidth against the chip's peak (HIP events around every gather launch of the 
 on the stream it is launched on), and the CPU oracle timed on the host as a reported baseline.
 Outside the timed region it also times each call of the step on its own, the step with
 dc_gather_advantage (no rollout-layout copy of the per-token advantages), the reverse path
-(dc_scatter) and the PPO advantage stage (dc_gae) on the same batch ("stages",
-"no_rollout_adv", "reverse", "ppo_advantage").
+(dc_scatter) and the PPO advantage stage (dc_gae) on the same batch, and a plain copy of the
+gather's byte count as the box's ceiling ("stages", "no_rollout_adv", "reverse", "ppo_advantage",
+"copy_ceiling").
 """
 from __future__ import annotations
 
@@ -213,6 +214,25 @@ def main() -> int:
         assert all(s.read_status() == 0 for s in sets)
         ppo = {"call": "dc_gae", **res}
 
+    # the achievable ceiling on this machine: a plain elementwise copy (one torch kernel) of the gather's byte count,
+    # 3 rotating buffer pairs, measured the same way
+    n_words = gather_bytes // 2 // 4
+    pairs = [(torch.ones(n_words, dtype=torch.int32, device="cuda:0"), torch.empty(n_words, dtype=torch.int32, device="cuda:0"))
+             for _ in range(3)]
+    for i in range(3):
+        torch.add(pairs[i][0], 1, out=pairs[i][1])
+    torch.cuda.synchronize()
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for i in range(12):
+        torch.add(pairs[i % 3][0], 1, out=pairs[i % 3][1])
+    c1.record()
+    torch.cuda.synchronize()
+    copy_ms = c0.elapsed_time(c1) / 12
+    ceiling = {"what": "plain elementwise copy (one torch kernel) of the gather's byte count, same box",
+               "ms": round(copy_ms, 4), "achieved": 2 * n_words * 4 / (copy_ms * 1e-3) / 1e9, "unit": "GB/s"}
+    del pairs
+
     traffic = None
     table = TRAFFIC_ADV if args.no_rollout_adv else TRAFFIC
     if args.config in table and table[args.config][1] == kernel_digest():
@@ -239,6 +259,7 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": "gather_adv_kernel" if args.no_rollout_adv else "gather_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes_per_launch": timed_gather_bytes, "avg_launch_ms": gather_ms},
+        "copy_ceiling": ceiling,
         "stages": stage,
         "no_rollout_adv": variant,
         "reverse": reverse,
