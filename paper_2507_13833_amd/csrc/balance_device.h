@@ -130,7 +130,9 @@ __device__ __forceinline__ LptCarry lpt_fresh(int P, int C) {
     return c;
 }
 
-template <int WIDTH>
+// TIGHT: P == WIDTH and pitch > 0 (the printed algorithm on 16, 32 or 64 workers): the rounds in which every
+// worker takes an item drop the selects that the general case needs.
+template <int WIDTH, bool TIGHT = false>
 __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, const uint16_t* sorted,
                                           int32_t max_len, uint16_t* step_slot, int pitch, int32_t* spare_word,
                                           int32_t* worker_count, int64_t* __restrict__ shard_load, LptCarry& carry) {
@@ -202,19 +204,22 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, co
                 const int32_t before = __builtin_amdgcn_ds_bpermute((int)(id << 2), count) + rounds;   // its count
                 step_slot[st_slot] = (uint16_t)st_val;            // the round before: place inside the partition ...
                 *st_key = (int32_t)st_id;                         // ... and worker (the item's length is not needed again)
-                const uint32_t newk = mine_exists ? sk + (s << 6) : sk;       // absent workers keep their all-ones-ish key
+                // absent workers keep their all-ones-ish key; with WIDTH workers the lanes beyond them sort among
+                // themselves and come behind them in the scan: what they hold does not matter
+                const uint32_t newk = (TIGHT || mine_exists) ? sk + (s << 6) : sk;
                 // next round's order, if this round stands; the acceptance test is computed between the steps of
                 // the sort's first levels (the last level is made to wait for its result)
                 const uint32_t half_sorted = wave_sort_front<WIDTH>(newk);
-                const uint32_t pm = wave_excl_scan_umin(mine_exists ? newk : 0xFFFFFFFFu);
+                const uint32_t pm = wave_excl_scan_umin((TIGHT || mine_exists) ? newk : 0xFFFFFFFFu);
                 const uint64_t takers = __builtin_amdgcn_ballot_w64(sk < pm);
                 const bool refused = (takers & everyone) != everyone;
                 const uint32_t sk2 = wave_sort_back<WIDTH>(half_sorted, (uint32_t)refused);
                 if (__builtin_expect(refused, 0)) break;          // not everyone's turn: one general round
-                const int slot_at = pitch ? (int)id * pitch + before : t;
-                st_slot = mine_exists ? (uint32_t)slot_at : (uint32_t)(DC_MAX_SEQ + PLACE_PAD - 1);
-                st_val = pitch ? idx : (uint32_t)before;
-                st_key = mine_exists ? keys + idx : spare_word;
+                constexpr bool EVERY_LANE = TIGHT && WIDTH == WAVE;           // every lane keeps a worker
+                const int slot_at = (TIGHT || pitch) ? (int)id * pitch + before : t;
+                st_slot = (EVERY_LANE || mine_exists) ? (uint32_t)slot_at : (uint32_t)(DC_MAX_SEQ + PLACE_PAD - 1);
+                st_val = (TIGHT || pitch) ? idx : (uint32_t)before;
+                st_key = (EVERY_LANE || mine_exists) ? keys + idx : spare_word;
                 st_id = id;
                 pos += P;
                 rounds += 1;
@@ -227,6 +232,7 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, co
             step_slot[st_slot] = (uint16_t)st_val;
             *st_key = (int32_t)st_id;
             // back to worker lanes: rank r sends its key to lane (sk & 63); absent workers send theirs to themselves
+            if (TIGHT && !mine_exists) sk = full;                 // (whatever the rounds left in their lanes)
             key = (uint32_t)__builtin_amdgcn_ds_permute((int)((sk & 63u) << 2), (int)sk);
             if (mine_exists) {
                 count += rounds;
@@ -455,7 +461,11 @@ __device__ __forceinline__ void balance_body(BalLds& L, int32_t N, int32_t P, in
         int32_t* spare = L.spare;
         LptCarry fresh = lpt_fresh(P, C);
         int n_placed;
-        if (P <= 16) n_placed = lpt_rounds<16>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
+        const bool tight = pitch != 0 && (P == 16 || P == 32 || P == 64);
+        if (tight && P == 16) n_placed = lpt_rounds<16, true>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
+        else if (tight && P == 32) n_placed = lpt_rounds<32, true>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
+        else if (tight) n_placed = lpt_rounds<64, true>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
+        else if (P <= 16) n_placed = lpt_rounds<16>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
         else if (P <= 32) n_placed = lpt_rounds<32>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
         else n_placed = lpt_rounds<64>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
         // start of every P_k inside perm
