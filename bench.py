@@ -214,6 +214,48 @@ def main() -> int:
         assert all(s.read_status() == 0 for s in sets)
         ppo = {"call": "dc_gae", **res}
 
+    # Double buffer (Sec. 6.5): the step that fills one buffer set beside a consumer that still reads the set
+    # filled before it (stand-in consumer: one reduction over each 4-byte arena of that set), on two streams of
+    # the default priority, against the same two pieces of work issued one after the other; outside the timed region
+    double_buffer = None
+    if len(sets) >= 2:
+        def consume(b):
+            for n, v in b.dst_fields.items():
+                if b.elem_bytes.get(n, 4) == 4:
+                    v.view(torch.float32).sum()          # the bits read as floats: only the traffic matters
+        main_s, side_s = torch.cuda.current_stream(), torch.cuda.Stream()
+        ev_step, ev_cons = torch.cuda.Event(), torch.cuda.Event()
+
+        def both(i, overlap):
+            cur, prev = sets[i % len(sets)], sets[(i - 1) % len(sets)]
+            if overlap:
+                ev_step.record(main_s)                   # prev is complete, and so is the consumer's earlier pass
+                side_s.wait_event(ev_step)
+                with torch.cuda.stream(side_s):
+                    consume(prev)
+                    ev_cons.record(side_s)
+                cur.step_fused()
+                main_s.wait_event(ev_cons)
+            else:
+                consume(prev)
+                cur.step_fused()
+
+        res = {}
+        for tag, overlap in (("serial_ms", False), ("overlapped_ms", True)):
+            for i in range(3):
+                both(i, overlap)
+            torch.cuda.synchronize()
+            d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            d0.record()
+            for i in range(12):
+                both(i, overlap)
+            d1.record()
+            torch.cuda.synchronize()
+            res[tag] = round(d0.elapsed_time(d1) / 12, 4)
+        assert all(s.read_status() == 0 for s in sets)
+        double_buffer = {"what": "one step into buffer set i beside a reduction over the 4-byte arenas of set i-1 "
+                                 "(two streams) vs one after the other", **res}
+
     # the achievable ceiling on this machine: a plain elementwise copy (one torch kernel) of the gather's byte count,
     # 3 rotating buffer pairs, measured the same way
     n_words = gather_bytes // 2 // 4
@@ -264,6 +306,7 @@ def main() -> int:
         "no_rollout_adv": variant,
         "reverse": reverse,
         "ppo_advantage": ppo,
+        "double_buffer": double_buffer,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)

@@ -26,8 +26,8 @@
  *                        next-fit micro-batches under a token budget,
  *                        per-micro-batch cu_seqlens.  (Sec. 6 "Distributed
  *                        Databuffer": redistribution between stages whose DP
- *                        sizes differ; the packing itself is this build's
- *                        reading, the paper pads.)
+ *                        sizes differ; the packing itself is a reading of
+ *                        that passage, the paper's own batches are padded.)
  *   dco_gather           per-sequence copy rollout layout -> training layout.
  *   dco_scatter          the same copy backwards (training layout -> rollout
  *                        layout), for fields a training-layout stage produced

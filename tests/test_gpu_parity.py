@@ -45,6 +45,12 @@ def check_step(w, align=1, cap=0, label="", overlapped=False, fused=False):
     else:
         d.step()
     torch.cuda.synchronize()
+    compare_step(d, w, align, cap)
+    return d
+
+
+def compare_step(d, w, align=1, cap=0):
+    """Every output of one finished step on DeviceBatch d against the oracle's."""
     assert d.read_status() == 0
 
     bal, adv, adv_tok, pl = oracle_step(w, align, cap)
@@ -99,7 +105,6 @@ def check_step(w, align=1, cap=0, label="", overlapped=False, fused=False):
         seg_src = src_adv[shard_of[i]][w.src_tok_off[i]: w.src_tok_off[i] + w.seq_len[i]]
         seg_dst = got[pl.dst_tok_off[j]: pl.dst_tok_off[j] + w.seq_len[i]]
         assert np.array_equal(seg_src.view(np.uint32), seg_dst.view(np.uint32))
-    return d
 
 
 # ---------------------------------------------------------------- the five configs, full size
@@ -153,6 +158,35 @@ def test_step_replayed_from_a_hip_graph():
             for a, b in zip(want_small, got_small):
                 assert torch.equal(a, b), rep
         del g
+
+
+def test_double_buffered_steps_on_two_streams():
+    """Sec. 6.5 (double buffer) on one GPU: the library keeps no state and every call takes its arenas and its
+    workspace as arguments, so the step that fills one buffer set may run on a second stream while a consumer
+    still reads the other set.  Two sets with different batches, each on a stream of its own (default
+    priority), three alternations issued without a host synchronisation in between, a reduction over the
+    set's arenas behind every step as the consumer: both sets match the oracle and the consumer reads the
+    same bits every time."""
+    torch, binding, runner = _gpu()
+    rng = np.random.default_rng(65)
+    ws = [workloads.make_workload(2), _custom(rng.integers(1, 3000, 3072), 8, 24, 8192, n_src=2)]
+    ds = [runner.DeviceBatch(w, poison=True) for w in ws]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for s in streams:
+        s.wait_stream(torch.cuda.current_stream())
+    sums = [[], []]
+    for rep in range(3):
+        for k in (0, 1):
+            with torch.cuda.stream(streams[k]):
+                ds[k].step_fused()
+                sums[k].append(torch.stack([v.view(torch.uint8).sum(dtype=torch.int64) for v in ds[k].dst_fields.values()]))
+    for s in streams:
+        s.synchronize()
+    torch.cuda.synchronize()
+    for k in (0, 1):
+        print(f"[parity] double buffer, set {k}: N={ws[k].n_seq} P={ws[k].n_shards}", flush=True)
+        compare_step(ds[k], ws[k])
+        assert all(torch.equal(sums[k][0], x) for x in sums[k][1:])
 
 
 def test_two_stream_step():
