@@ -85,6 +85,9 @@ def main() -> int:
     ap.add_argument("--no-rollout-adv", action="store_true",
                     help="the step without the rollout-layout copy of the per-token advantages: the fused launch "
                          "computes adv_seq only, dc_gather_advantage makes the training-layout field from the mask")
+    ap.add_argument("--no-double-buffer", action="store_true",
+                    help="skip the double_buffer side measurement (its steps run beside another kernel, which "
+                         "would enter a profiler's per-kernel averages)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise copy of known size (1 GiB read + 1 GiB written per "
                          "launch): the yardstick that scales the HBM byte counters of a rocprofv3 --pmc run")
@@ -218,7 +221,7 @@ def main() -> int:
     # filled before it (stand-in consumer: one reduction over each 4-byte arena of that set), on two streams of
     # the default priority, against the same two pieces of work issued one after the other; outside the timed region
     double_buffer = None
-    if len(sets) >= 2:
+    if len(sets) >= 2 and not args.no_double_buffer:
         def consume(b):
             for n, v in b.dst_fields.items():
                 if b.elem_bytes.get(n, 4) == 4:

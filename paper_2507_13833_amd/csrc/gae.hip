@@ -17,14 +17,20 @@
 //     tokens from the state entering it;
 //   * a wave whose 512 tokens all bear loss (the inside of a response) never looks at a mask
 //     again; a wave without any loss-bearing token (a prompt) only writes zeros.
+//   * the outputs leave through a transpose in LDS, so that a store instruction writes 64
+//     consecutive 16-byte chunks (a lane's own 8 tokens are 32 bytes: two instructions that
+//     each write every other 16 bytes, which streaming stores handle at a third of the rate).
 // All arithmetic is float64 (the kernel is bound by HBM, not by the vector unit: 13 B per token,
 // 21 with the KL penalty); outputs are rounded once to float32.
 // Measured rationale: one wave per sequence left the longest sequence (36 K tokens, 141 dependent
-// blocks) running alone for 160 us; anything derived from a loaded mask word at load time makes
+// blocks) running alone for 160 us; with two waves it is still 36 dependent iterations, which
+// run on alone when the sequence's workgroup starts late, so the first workgroups of the grid
+// look for long sequences and start those; anything derived from a loaded mask word at load time makes
 // the wave wait for the loads it has just issued (the prefetch ring keeps the raw words);
 // with the arrays resident in the last-level cache, plain loads with streaming stores beat both
 // all-plain and all-streaming accesses by a third (every line of the value array is touched by
 // two load instructions, 32 bytes apart per lane); from HBM the three are equal.
+#include <algorithm>
 #include "dc_device.h"
 #include "dc_internal.h"
 #include "dc_lanes.h"
@@ -36,6 +42,7 @@ constexpr int GAE_WAVES = 2;                 // waves that share one sequence
 struct GaeArgs {
     int32_t        n_seq, use_kl;
     double         gamma, decay, kl_coef;            // decay = gamma * lambda
+    int32_t        n_early, long_len;                // workgroups that start long sequences early; what counts as long
     const int64_t* src_tok_off;
     const int32_t* seq_len;
     const float*   reward;
@@ -131,6 +138,24 @@ __device__ __forceinline__ double readlane_f64(double v, int src) {
     return __longlong_as_double((long long)((uint64_t)lo | ((uint64_t)hi << 32)));
 }
 
+constexpr int GAE_SET = 32;                  // sequences among which one may be started early
+__device__ __forceinline__ bool gae_is_long(int32_t ln, int32_t long_len) { return ln >= long_len && ln <= DC_MAX_SEQ_LEN; }
+// The longest long sequence among set, set + n_early, set + 2 n_early, ... (GAE_SET of them; ties: the lowest
+// index), or -1; every wave that asks gets the same answer.
+__device__ __forceinline__ int gae_longest_of_set(const GaeArgs& a, int set, int lane) {
+    const int k = lane & (GAE_SET - 1);
+    const int64_t idx = (int64_t)set + (int64_t)k * a.n_early;
+    int32_t ln = 0;
+    if (idx < a.n_seq) ln = a.seq_len[idx];
+    long long key = gae_is_long(ln, a.long_len) ? (((long long)ln << 8) | (long long)(GAE_SET - 1 - k)) : -1ll;
+#pragma unroll
+    for (int d = GAE_SET / 2; d >= 1; d >>= 1) {
+        const long long o = __shfl_xor(key, d, WAVE);
+        key = o > key ? o : key;
+    }
+    return key < 0 ? -1 : set + (GAE_SET - 1 - (int)(key & 0xFF)) * a.n_early;
+}
+
 // Iterations whose loads are in flight ahead of the one worked on.
 template <bool KL> constexpr int GAE_AHEAD = 2;
 
@@ -147,9 +172,20 @@ __global__ __launch_bounds__(NW * WAVE) void gae_kernel(GaeArgs a, SourceDesc sd
     constexpr int T = GAE_TPL;
     __shared__ double s_u[NW], s_P[NW], s_B[NW];
     __shared__ int32_t s_has[NW];
+    __shared__ __attribute__((aligned(16))) float s_stage[NW][2 * WAVE * GAE_TPL];   // a wave's outputs on their way out
     const int lane = threadIdx.x & (WAVE - 1);
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / WAVE));
-    const int i = blockIdx.x;                                      // one workgroup per sequence
+    // One workgroup per sequence, in index order, behind n_early workgroups that each start the longest
+    // sequence of a set of GAE_SET (every n_early-th sequence from their own index on) if it is a long one:
+    // a 36 K-token sequence is 36 dependent iterations, and started late it runs on alone after the rest.
+    int i = (int)blockIdx.x - a.n_early;
+    const bool early = i < 0;
+    if (early || gae_is_long(a.seq_len[i], a.long_len)) {          // uniform over the workgroup
+        const int set = early ? (int)blockIdx.x : i % a.n_early;
+        const int longest = gae_longest_of_set(a, set, lane);
+        if (early ? longest < 0 : longest == i) return;            // nothing to start early / started early
+        if (early) i = __builtin_amdgcn_readfirstlane(longest);
+    }
     int s = 0;
     while (s + 1 < sd.n_src && i >= sd.seq_off[s + 1]) ++s;
     const int64_t so = a.src_tok_off[i];
@@ -198,7 +234,6 @@ __global__ __launch_bounds__(NW * WAVE) void gae_kernel(GaeArgs a, SourceDesc sd
         } else {
             load_lane<KL>(V, M, LP, RF, q * T, q >= q_lo, so, end, cur);
         }
-        const int64_t x0 = q * T;
         const uint32_t loss = nonzero_bytes(cur.m[0]) | (nonzero_bytes(cur.m[1]) << 4);   // bit t: token t bears loss
         const uint64_t holders = __ballot(loss != 0);              // lanes of my wave with a loss-bearing token
         const bool any = holders != 0ull;                          // uniform over the wave
@@ -281,35 +316,21 @@ __global__ __launch_bounds__(NW * WAVE) void gae_kernel(GaeArgs a, SourceDesc sd
         }
 
         // ---- outputs: replay my tokens from the state entering my lane ----
-        if (solid) {
+        float oa[T], orr[T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) { oa[t] = 0.0f; orr[t] = 0.0f; }
+        if (any) {
             // the maps of all lanes before mine (identity for lane 0), applied to the state entering the wave
             const double Pe = dpp_mov_f64<DPP_WAVE_SHR1>(1.0, Pi), Be = dpp_mov_f64<DPP_WAVE_SHR1>(0.0, Bi);
             double A = __builtin_fma(Pe, A_w, Be);
-            float oa[T], orr[T];
+            if (solid) {
 #pragma unroll
-            for (int t = T - 1; t >= 0; --t) {
-                A = __builtin_fma(decay, A, r[t]);
-                oa[t] = (float)A;
-                orr[t] = (float)(A + (double)cur.v[t]);
-            }
-            if (cur.inside != 0u) {                                // a solid lane inside the sequence holds all 8 tokens
-                f32x4 o;
-                o.x = oa[0]; o.y = oa[1]; o.z = oa[2]; o.w = oa[3];
-                __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(ADV + x0));
-                o.x = oa[4]; o.y = oa[5]; o.z = oa[6]; o.w = oa[7];
-                __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(ADV + x0 + 4));
-                o.x = orr[0]; o.y = orr[1]; o.z = orr[2]; o.w = orr[3];
-                __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(RET + x0));
-                o.x = orr[4]; o.y = orr[5]; o.z = orr[6]; o.w = orr[7];
-                __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(RET + x0 + 4));
-            }
-        } else {
-            float oa[T], orr[T];
-#pragma unroll
-            for (int t = 0; t < T; ++t) { oa[t] = 0.0f; orr[t] = 0.0f; }
-            if (any) {
-                const double Pe = dpp_mov_f64<DPP_WAVE_SHR1>(1.0, Pi), Be = dpp_mov_f64<DPP_WAVE_SHR1>(0.0, Bi);
-                double A = __builtin_fma(Pe, A_w, Be);
+                for (int t = T - 1; t >= 0; --t) {
+                    A = __builtin_fma(decay, A, r[t]);
+                    oa[t] = (float)A;
+                    orr[t] = (float)(A + (double)cur.v[t]);
+                }
+            } else {
 #pragma unroll
                 for (int t = T - 1; t >= 0; --t)
                     if (loss & (1u << t)) {
@@ -318,20 +339,39 @@ __global__ __launch_bounds__(NW * WAVE) void gae_kernel(GaeArgs a, SourceDesc sd
                         orr[t] = (float)(A + (double)cur.v[t]);
                     }
             }
-            if (cur.inside == 0xFFu) {
-                f32x4 o;
-                o.x = oa[0]; o.y = oa[1]; o.z = oa[2]; o.w = oa[3];
-                __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(ADV + x0));
-                o.x = oa[4]; o.y = oa[5]; o.z = oa[6]; o.w = oa[7];
-                __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(ADV + x0 + 4));
-                o.x = orr[0]; o.y = orr[1]; o.z = orr[2]; o.w = orr[3];
-                __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(RET + x0));
-                o.x = orr[4]; o.y = orr[5]; o.z = orr[6]; o.w = orr[7];
-                __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(RET + x0 + 4));
-            } else if (cur.inside != 0u) {
+        }
+        // ---- stores, through a transpose in LDS: a lane's 8 tokens are 32 bytes, and 16 bytes per lane at a
+        // 32-byte stride, the other halves in a second instruction, is a pattern that streaming stores write at
+        // a third of the rate of 64 consecutive 16-byte chunks (2.3 against 6.3 TB/s, write-only probe).
+        // Memory order runs against lane order; the wave's window starts at lane 63's first token.
+        if (__ballot(cur.inside != 0u) != 0ull) {                  // uniform: some token of the window lies inside
+            float* st_a = s_stage[w];
+            float* st_r = st_a + WAVE * T;
+            const int mine = (WAVE - 1 - lane) * T;
+            f32x4 o;
+            o.x = oa[0]; o.y = oa[1]; o.z = oa[2]; o.w = oa[3];
+            *reinterpret_cast<f32x4*>(st_a + mine) = o;
+            o.x = oa[4]; o.y = oa[5]; o.z = oa[6]; o.w = oa[7];
+            *reinterpret_cast<f32x4*>(st_a + mine + 4) = o;
+            o.x = orr[0]; o.y = orr[1]; o.z = orr[2]; o.w = orr[3];
+            *reinterpret_cast<f32x4*>(st_r + mine) = o;
+            o.x = orr[4]; o.y = orr[5]; o.z = orr[6]; o.w = orr[7];
+            *reinterpret_cast<f32x4*>(st_r + mine + 4) = o;
+            const int64_t base = (top - (int64_t)w * WAVE - (WAVE - 1)) * T;
 #pragma unroll
-                for (int t = 0; t < T; ++t)
-                    if (cur.inside & (1u << t)) { ADV[x0 + t] = oa[t]; RET[x0 + t] = orr[t]; }
+            for (int u = 0; u < 2; ++u) {
+                const int c = (u * WAVE + lane) * 4;               // my chunk of 4 tokens in this instruction
+                const int64_t t0 = base + c;
+                const f32x4 va = *reinterpret_cast<const f32x4*>(st_a + c);
+                const f32x4 vr = *reinterpret_cast<const f32x4*>(st_r + c);
+                if (t0 >= so && t0 + 4 <= end) {
+                    __builtin_nontemporal_store(va, reinterpret_cast<f32x4*>(ADV + t0));
+                    __builtin_nontemporal_store(vr, reinterpret_cast<f32x4*>(RET + t0));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (t0 + e >= so && t0 + e < end) { ADV[t0 + e] = va[e]; RET[t0 + e] = vr[e]; }
+                }
             }
         }
         A_carry = A_next;
@@ -349,6 +389,13 @@ hipError_t launch_gae(int32_t n_seq, const SourceDesc& src, const int64_t* d_src
     a.n_seq = n_seq; a.use_kl = kl_coef != 0.0 ? 1 : 0;
     a.gamma = gamma; a.decay = gamma * lambda; a.kl_coef = kl_coef;
     a.src_tok_off = d_src_tok_off; a.seq_len = d_seq_len; a.reward = d_reward; a.status = d_status;
+    // long: at least twice the mean (the buffers' sizes bound the lengths' sum) and at least 4 iterations
+    int64_t tokens = 0;
+    for (int s = 0; s < src.n_src; ++s) tokens += src.tokens[s];
+    const int64_t twice_mean = 2 * (tokens / n_seq);
+    a.long_len = (int32_t)std::min<int64_t>(std::max<int64_t>(twice_mean, 4 * GAE_WAVES * WAVE * GAE_TPL), INT32_MAX);
+    a.n_early = (n_seq + GAE_SET - 1) / GAE_SET;
+    const unsigned grid = (unsigned)(n_seq + a.n_early);
     for (int s = 0; s < DC_MAX_SRC_SHARDS; ++s) {
         const bool on = s < src.n_src;
         a.value[s] = on ? value_base[s] : nullptr;
@@ -359,9 +406,9 @@ hipError_t launch_gae(int32_t n_seq, const SourceDesc& src, const int64_t* d_src
         a.ret[s] = on ? ret_base[s] : nullptr;
     }
     if (a.use_kl)
-        hipLaunchKernelGGL((gae_kernel<GAE_WAVES, true>), dim3((unsigned)n_seq), dim3(GAE_WAVES * WAVE), 0, st, a, src);
+        hipLaunchKernelGGL((gae_kernel<GAE_WAVES, true>), dim3(grid), dim3(GAE_WAVES * WAVE), 0, st, a, src);
     else
-        hipLaunchKernelGGL((gae_kernel<GAE_WAVES, false>), dim3((unsigned)n_seq), dim3(GAE_WAVES * WAVE), 0, st, a, src);
+        hipLaunchKernelGGL((gae_kernel<GAE_WAVES, false>), dim3(grid), dim3(GAE_WAVES * WAVE), 0, st, a, src);
     return hipGetLastError();
 }
 
