@@ -719,6 +719,13 @@ def test_gae_shapes_and_special_cases():
     mk[:300] = 0
     mk[300:600] = 0; mk[700:1000] = 0
     check_gae(w, 0.99, 0.95, 0.0, label="fully and partly masked sequences")
+    # long sequences are started by the grid's first workgroups, one per set of every (N/32)-th sequence: three
+    # long ones in one set (two of equal length), one alone in its set, one in each rollout shard's tail
+    lens = rng.integers(100, 600, 96)
+    lens[[5, 8, 11, 0, 95]] = [9000, 12000, 12000, 5000, 4096]
+    w = _with_ppo_fields(_custom(lens, 8, 8, 16384, n_src=2))
+    check_gae(w, 0.99, 0.95, 0.03, label="long sequences among short ones")
+    check_gae(_with_ppo_fields(_custom(np.array([20000, 30, 17000]), 1, 1, 65536)), 1.0, 0.9, 0.0, label="N=3, two long")
 
 
 def test_gae_padded_rows():
