@@ -16,7 +16,7 @@
 //     composed by a 6-step DPP scan, the waves' maps through LDS, and each lane then replays its
 //     tokens from the state entering it;
 //   * a wave whose 512 tokens all bear loss (the inside of a response) never looks at a mask
-//     again; a wave without any loss-bearing token (a prompt) only writes zeros.
+//     again; a wave without any loss-bearing token (a prompt) only writes zeros;
 //   * the outputs leave through a transpose in LDS, so that a store instruction writes 64
 //     consecutive 16-byte chunks (a lane's own 8 tokens are 32 bytes: two instructions that
 //     each write every other 16 bytes, which streaming stores handle at a third of the rate).
@@ -27,9 +27,8 @@
 // run on alone when the sequence's workgroup starts late, so the first workgroups of the grid
 // look for long sequences and start those; anything derived from a loaded mask word at load time makes
 // the wave wait for the loads it has just issued (the prefetch ring keeps the raw words);
-// with the arrays resident in the last-level cache, plain loads with streaming stores beat both
-// all-plain and all-streaming accesses by a third (every line of the value array is touched by
-// two load instructions, 32 bytes apart per lane); from HBM the three are equal.
+// plain loads with streaming stores beat both all-plain and all-streaming accesses (every line
+// of the value array is touched by two load instructions, 32 bytes apart per lane).
 #include <algorithm>
 #include "dc_device.h"
 #include "dc_internal.h"
