@@ -16,7 +16,7 @@ constexpr int ADV_BLOCK = 256;
 constexpr int ADV_WAVES = ADV_BLOCK / WAVE;
 
 __global__ __launch_bounds__(ADV_BLOCK) void advantage_kernel(AdvArgs a, SourceDesc sd) {
-    advantage_wave(a, sd, (int64_t)blockIdx.x * ADV_WAVES + threadIdx.x / WAVE);   // one wave per sequence
+    advantage_wave(a, sd, (int64_t)blockIdx.x * ADV_WAVES + __builtin_amdgcn_readfirstlane((int)(threadIdx.x / WAVE)));   // one wave per sequence
 }
 
 AdvArgs make_adv_args(int32_t n_seq, const SourceDesc& src, const int64_t* d_src_tok_off, const int32_t* d_seq_len,

@@ -66,7 +66,7 @@ __global__ __launch_bounds__(BAL_BLOCK) void balance_advantage_kernel(BalanceArg
     if (blockIdx.x == 0)
         balance_body(L, b.N, b.P, b.C, b.seq_len, b.perm, b.shard_seq_off, b.shard_of_seq, b.shard_load, b.status);
     else
-        advantage_wave(a, sd, (int64_t)(blockIdx.x - 1) * BAL_WAVES + threadIdx.x / WAVE);
+        advantage_wave(a, sd, (int64_t)(blockIdx.x - 1) * BAL_WAVES + __builtin_amdgcn_readfirstlane((int)(threadIdx.x / WAVE)));
 }
 
 hipError_t launch_balance(int32_t n_seq, int32_t n_shards, int32_t cap_eff, const int32_t* d_seq_len,
