@@ -1,7 +1,7 @@
 """CPU oracle for the Data Coordinator reshard path -- TEST INFRASTRUCTURE ONLY.
 
 Thin ctypes/NumPy marshalling over ``dc_oracle.c`` (plain C, float64 statistics,
-literal heap-based Algorithm 1, per-sequence copy loops).  Only tests, the smoke
+Algorithm 1 as a scan over the workers per sequence, per-sequence copy loops).  Only tests, the smoke
 check and the benchmark's CPU-baseline leg may import this package; the HIP
 product path never does, and this package never imports the product.
 """

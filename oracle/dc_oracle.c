@@ -7,9 +7,8 @@
  * All pointers are host pointers; the caller owns every buffer.
  *
  *   dco_balance          Algorithm 1 "Constrained LPT Load Balancing" (Sec. 6,
- *                        "Load Balancing"): descending argsort, a min-heap of
- *                        (load, k) tuples, full workers popped, set aside in B
- *                        and pushed back.
+ *                        "Load Balancing"): longest sequence first, each to the
+ *                        least-loaded worker that is not full.
  *   dco_group_advantage  group-relative (GRPO, Sec. 2 / Sec. 1 payload list)
  *                        advantage of each response: reward minus its prompt
  *                        group's mean over the group's std; float64, rounded
@@ -48,62 +47,32 @@ enum { DCO_OK = 0, DCO_BAD_ARG = 1, DCO_NOT_DIVISIBLE = 2, DCO_SEQ_EXCEEDS_BUDGE
 /* Algorithm 1                                                          */
 /* ------------------------------------------------------------------ */
 
-typedef struct { int64_t load; int32_t k; } heap_item;
-
-/* tuples compare lexicographically: smaller load first, then smaller k */
-static int item_less(heap_item a, heap_item b) {
-    if (a.load != b.load) return a.load < b.load;
-    return a.k < b.k;
-}
-
-static void heap_push(heap_item* h, int32_t* n, heap_item x) {
-    int32_t i = (*n)++;
-    h[i] = x;
-    while (i > 0) {
-        int32_t p = (i - 1) / 2;
-        if (!item_less(h[i], h[p])) break;
-        heap_item t = h[i]; h[i] = h[p]; h[p] = t;
-        i = p;
-    }
-}
-
-static heap_item heap_pop_min(heap_item* h, int32_t* n) {
-    heap_item top = h[0];
-    h[0] = h[--(*n)];
-    int32_t i = 0;
-    for (;;) {
-        int32_t l = 2 * i + 1, r = l + 1, m = i;
-        if (l < *n && item_less(h[l], h[m])) m = l;
-        if (r < *n && item_less(h[r], h[m])) m = r;
-        if (m == i) break;
-        heap_item t = h[i]; h[i] = h[m]; h[m] = t;
-        i = m;
-    }
-    return top;
-}
-
-static const int32_t* g_sort_keys;
-/* descending length; equal lengths keep ascending original index (stable) */
-static int cmp_desc_stable(const void* a, const void* b) {
-    int32_t ia = *(const int32_t*)a, ib = *(const int32_t*)b;
-    if (g_sort_keys[ia] != g_sort_keys[ib]) return g_sort_keys[ia] > g_sort_keys[ib] ? -1 : 1;
-    return ia < ib ? -1 : (ia > ib);
+/* The order in which Algorithm 1 hands the sequences out: longest first, sequences of equal
+ * length in ascending index order (the reading taken where the paper leaves ties open). */
+static const int32_t* g_len_of;
+static int longer_first(const void* pa, const void* pb) {
+    const int32_t a = *(const int32_t*)pa, b = *(const int32_t*)pb;
+    if (g_len_of[a] != g_len_of[b]) return g_len_of[a] > g_len_of[b] ? -1 : 1;
+    return a < b ? -1 : (a > b);
 }
 
 /*
- * Algorithm 1.  S[N] lengths, K workers, cap = 0 takes the paper's C = N/K
- * (N mod K must be 0); cap > 0 replaces C (cap = N makes the cardinality test
- * vacuous and the algorithm is then textbook LPT).
- * Outputs: perm[N] = members of P_0, then P_1, ... each in insertion order;
- * shard_seq_off[K+1] = CSR offsets of the P_k inside perm; shard_of_seq[N];
- * shard_load[K].
+ * Algorithm 1, written from what it computes: the sequences are taken longest first, and each
+ * goes to the worker whose (load, id) pair is lexicographically smallest among the workers that
+ * still hold fewer than C sequences; that worker's load grows by the sequence's length.  (The
+ * paper finds that worker with a priority queue from which full workers are taken out and put
+ * back; here it is found by looking at every worker.)
+ * S[N] lengths, K workers.  cap = 0 takes the paper's C = N/K, for which N mod K must be 0;
+ * cap > 0 replaces C (cap = N makes the cardinality test vacuous: textbook LPT).
+ * Outputs: perm[N] = members of P_0, then P_1, ... each in the order they were added;
+ * shard_seq_off[K+1] = CSR offsets of the P_k inside perm; shard_of_seq[N]; shard_load[K].
  */
 int dco_balance(const int32_t* S, int32_t N, int32_t K, int32_t cap,
                 int32_t* perm, int32_t* shard_seq_off, int32_t* shard_of_seq, int64_t* shard_load) {
     if (N < 0 || K < 1) return DCO_BAD_ARG;
     int64_t C;
     if (cap == 0) {
-        if (N % K != 0) return DCO_NOT_DIVISIBLE;       /* Assert N mod K = 0 */
+        if (N % K != 0) return DCO_NOT_DIVISIBLE;
         C = N / K;
     } else {
         if (cap < 0 || (int64_t)cap * K < N) return DCO_BAD_ARG;
@@ -111,48 +80,38 @@ int dco_balance(const int32_t* S, int32_t N, int32_t K, int32_t cap,
     }
     for (int32_t i = 0; i < N; ++i) if (S[i] <= 0) return DCO_ZERO_LENGTH;
 
-    int32_t* I = (int32_t*)malloc(sizeof(int32_t) * (size_t)(N > 0 ? N : 1));
-    heap_item* H = (heap_item*)malloc(sizeof(heap_item) * (size_t)K);
-    heap_item* B = (heap_item*)malloc(sizeof(heap_item) * (size_t)K);
-    int32_t* count = (int32_t*)calloc((size_t)K, sizeof(int32_t));
-    int32_t* worker_of_step = (int32_t*)malloc(sizeof(int32_t) * (size_t)(N > 0 ? N : 1));
-    if (!I || !H || !B || !count || !worker_of_step) { free(I); free(H); free(B); free(count); free(worker_of_step); return DCO_NOMEM; }
+    const size_t n1 = (size_t)(N > 0 ? N : 1);
+    int32_t* order = (int32_t*)malloc(sizeof(int32_t) * n1);
+    int32_t* taken_by = (int32_t*)malloc(sizeof(int32_t) * n1);     /* worker of the t-th sequence handed out */
+    int32_t* held = (int32_t*)calloc((size_t)K, sizeof(int32_t));   /* |P_k| */
+    if (!order || !taken_by || !held) { free(order); free(taken_by); free(held); return DCO_NOMEM; }
 
-    for (int32_t i = 0; i < N; ++i) I[i] = i;           /* I <- argsort(S, descending) */
-    g_sort_keys = S;
-    qsort(I, (size_t)N, sizeof(int32_t), cmp_desc_stable);
+    for (int32_t i = 0; i < N; ++i) order[i] = i;
+    g_len_of = S;
+    qsort(order, (size_t)N, sizeof(int32_t), longer_first);
 
-    int32_t hn = 0;                                     /* H <- {(0,k)} */
-    for (int32_t k = 0; k < K; ++k) { heap_item x = {0, k}; heap_push(H, &hn, x); }
-
-    for (int32_t t = 0; t < N; ++t) {                   /* for each u in I */
-        int32_t u = I[t];
-        int32_t bn = 0;                                 /* B <- empty */
-        for (;;) {
-            heap_item top = heap_pop_min(H, &hn);
-            if (count[top.k] < C) {                     /* |P_k| < C */
-                worker_of_step[t] = top.k;              /* P_k <- P_k U {u} */
-                count[top.k] += 1;
-                heap_item x = {top.load + S[u], top.k};
-                heap_push(H, &hn, x);
-                break;
-            }
-            B[bn++] = top;
-        }
-        for (int32_t b = 0; b < bn; ++b) heap_push(H, &hn, B[b]);
-    }
-
-    /* lay the P_k out one after the other, members in insertion order */
-    shard_seq_off[0] = 0;
-    for (int32_t k = 0; k < K; ++k) { shard_seq_off[k + 1] = shard_seq_off[k] + count[k]; shard_load[k] = 0; }
-    memset(count, 0, sizeof(int32_t) * (size_t)K);
+    for (int32_t k = 0; k < K; ++k) shard_load[k] = 0;
     for (int32_t t = 0; t < N; ++t) {
-        int32_t k = worker_of_step[t], u = I[t];
-        perm[shard_seq_off[k] + count[k]++] = u;
-        shard_of_seq[u] = k;
-        shard_load[k] += S[u];
+        int32_t to = -1;
+        for (int32_t k = 0; k < K; ++k) {
+            if (held[k] >= C) continue;                              /* full: not a candidate */
+            if (to < 0 || shard_load[k] < shard_load[to]) to = k;    /* equal loads: the smaller id stays */
+        }
+        taken_by[t] = to;
+        held[to] += 1;
+        shard_load[to] += S[order[t]];
     }
-    free(I); free(H); free(B); free(count); free(worker_of_step);
+
+    /* lay the P_k out one after the other, members in the order they were added */
+    shard_seq_off[0] = 0;
+    for (int32_t k = 0; k < K; ++k) shard_seq_off[k + 1] = shard_seq_off[k] + held[k];
+    memset(held, 0, sizeof(int32_t) * (size_t)K);
+    for (int32_t t = 0; t < N; ++t) {
+        const int32_t k = taken_by[t], u = order[t];
+        perm[shard_seq_off[k] + held[k]++] = u;
+        shard_of_seq[u] = k;
+    }
+    free(order); free(taken_by); free(held);
     return DCO_OK;
 }
 

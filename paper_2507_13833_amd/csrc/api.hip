@@ -105,7 +105,7 @@ static dc_status check_balance(const dc_params* prm, const int32_t* d_seq_len, c
     if (!d_shard_seq_off || !d_shard_load) return DC_ERR_INVALID_ARG;
     if (prm->n_seq > 0 && (!d_seq_len || !d_perm || !d_shard_of_seq)) return DC_ERR_INVALID_ARG;
     if (prm->cap == 0) {
-        if (prm->n_seq % prm->n_shards != 0) return DC_ERR_NOT_DIVISIBLE;     // Algorithm 1: assert N mod K = 0
+        if (prm->n_seq % prm->n_shards != 0) return DC_ERR_NOT_DIVISIBLE;     // Algorithm 1 needs K to divide N
         *cap_eff = prm->n_seq / prm->n_shards;
     } else {
         if ((int64_t)prm->cap * prm->n_shards < prm->n_seq) return DC_ERR_INVALID_ARG;

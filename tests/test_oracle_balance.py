@@ -1,7 +1,8 @@
 """Pins for the oracle's Algorithm 1 (Constrained LPT Load Balancing, Sec. 6).
 
-None of these re-types the oracle's heap loop: they check it against hand traces,
-exhaustive search, an independent arg-min formulation, Graham's theorem for the
+None of these re-types the oracle's loop (a scan over the workers per item): they check it
+against hand traces, exhaustive search, an independent formulation with a priority queue from
+which full workers are taken out and put back (the library's heapq), Graham's theorem for the
 unconstrained special case and structural invariants.
 """
 import itertools
@@ -39,22 +40,32 @@ def test_hand_traces():
     assert n >= 4
 
 
-def argmin_lpt(S, K, C):
-    """Independent formulation: each item goes to the lexicographically smallest
-    (load, k) among workers that are not full.  pop_min with full workers set aside
-    selects exactly that worker."""
+def queue_lpt(S, K, C):
+    """Independent formulation: a priority queue of (load, k) pairs (the library's binary heap).
+    The smallest pair is taken out until it belongs to a worker that is not full; that worker
+    takes the item and goes back with its new load, and so do the full ones taken out on the
+    way.  Selects the lexicographically smallest (load, k) among the workers that are not full."""
+    import heapq
     order = sorted(range(len(S)), key=lambda i: (-S[i], i))
-    load = [0] * K
+    queue = [(0, k) for k in range(K)]
+    heapq.heapify(queue)
     mem = [[] for _ in range(K)]
     for u in order:
-        k = min((k for k in range(K) if len(mem[k]) < C), key=lambda k: (load[k], k))
+        aside = []
+        while True:
+            load, k = heapq.heappop(queue)
+            if len(mem[k]) < C:
+                break
+            aside.append((load, k))
         mem[k].append(u)
-        load[k] += S[u]
-    return mem, load
+        heapq.heappush(queue, (load + S[u], k))
+        for x in aside:
+            heapq.heappush(queue, x)
+    return mem, [sum(S[u] for u in m) for m in mem]
 
 
 @pytest.mark.parametrize("seed", range(6))
-def test_heap_equals_masked_argmin(seed):
+def test_scan_equals_priority_queue(seed):
     rng = np.random.default_rng(seed)
     for _ in range(150):
         K = int(rng.integers(1, 9))
@@ -62,12 +73,12 @@ def test_heap_equals_masked_argmin(seed):
         hi = int(rng.choice([3, 10, 1000]))            # small ranges force many ties
         S = rng.integers(1, hi + 1, K * C).tolist()
         b = oracle.balance(S, K)
-        mem, load = argmin_lpt(S, K, C)
+        mem, load = queue_lpt(S, K, C)
         assert members(b) == mem
         assert b.shard_load.tolist() == load
         # textbook LPT: constraint vacuous
         b2 = oracle.balance(S, K, cap=len(S))
-        mem2, load2 = argmin_lpt(S, K, len(S))
+        mem2, load2 = queue_lpt(S, K, len(S))
         assert members(b2) == mem2 and b2.shard_load.tolist() == load2
 
 

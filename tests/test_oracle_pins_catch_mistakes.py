@@ -24,7 +24,7 @@ SRC = os.path.join(os.path.dirname(oracle.__file__), "dc_oracle.c")
 def _balance_pins():
     T_bal.test_hand_traces()
     for seed in range(6):
-        T_bal.test_heap_equals_masked_argmin(seed)
+        T_bal.test_scan_equals_priority_queue(seed)
     T_bal.test_constraint_changes_the_answer()
     T_bal.test_structure_on_all_workloads()
     for K, N in ((2, 8), (3, 9), (4, 12)):
@@ -85,18 +85,21 @@ def _gae_pins():
 MISTAKES = [
     # ---- Algorithm 1
     ("equal loads resolved to the LARGEST worker id",
-     "return a.k < b.k;", "return a.k > b.k;", _balance_pins),
-    ("ascending instead of descending lengths",
-     "return g_sort_keys[ia] > g_sort_keys[ib] ? -1 : 1;", "return g_sort_keys[ia] < g_sort_keys[ib] ? -1 : 1;",
+     "if (to < 0 || shard_load[k] < shard_load[to]) to = k;", "if (to < 0 || shard_load[k] <= shard_load[to]) to = k;",
      _balance_pins),
+    ("ascending instead of descending lengths",
+     "return g_len_of[a] > g_len_of[b] ? -1 : 1;", "return g_len_of[a] < g_len_of[b] ? -1 : 1;", _balance_pins),
     ("equal lengths in descending index order",
-     "return ia < ib ? -1 : (ia > ib);", "return ia > ib ? -1 : (ia < ib);", _balance_pins),
+     "return a < b ? -1 : (a > b);", "return a > b ? -1 : (a < b);", _balance_pins),
     ("cardinality test off by one (a worker may take C + 1 items)",
-     "if (count[top.k] < C) {", "if (count[top.k] <= C) {", _balance_pins),
+     "if (held[k] >= C) continue;", "if (held[k] > C) continue;", _balance_pins),
     ("cardinality constraint dropped",
-     "if (count[top.k] < C) {", "if (1) {", _balance_pins),
+     "if (held[k] >= C) continue;", ";", _balance_pins),
     ("the load of a worker is not advanced by the item's length",
-     "heap_item x = {top.load + S[u], top.k};", "heap_item x = {top.load + 1, top.k};", _balance_pins),
+     "shard_load[to] += S[order[t]];", "shard_load[to] += 1;", _balance_pins),
+    ("the most loaded worker takes the item",
+     "if (to < 0 || shard_load[k] < shard_load[to]) to = k;", "if (to < 0 || shard_load[k] > shard_load[to]) to = k;",
+     _balance_pins),
     # ---- group-relative advantage
     ("eps inside the square root",
      "double sd = sqrt(ss / (double)(G - ddof));", "double sd = sqrt(ss / (double)(G - ddof) + eps); eps = 0;",
