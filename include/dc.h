@@ -79,6 +79,7 @@ extern "C" {
 #define DC_MAX_FIELDS     8
 #define DC_MAX_SRC_SHARDS 16
 #define DC_MAX_SEQ_LEN    (1 << 24)
+#define DC_REPACK_NOALLOC_WS_BYTES (8u << 20)   /* the device array dc_repack_noalloc plans in */
 
 typedef enum dc_status {
     DC_OK = 0,
@@ -258,6 +259,27 @@ dc_status dc_repack(const dc_params* prm, const dc_source* src, const int32_t* d
                     int64_t* d_dst_tok_off, int64_t* d_shard_tok_off, int32_t* d_shard_mb_off,
                     int32_t* d_mb_seq_off, int32_t* d_cu_seqlens, int32_t* d_n_mb,
                     void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream);
+
+/*
+ * dc_repack without a workspace argument, for callers that cannot allocate device memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The plan's
+ * workspace is a device array of DC_REPACK_NOALLOC_WS_BYTES (8 MiB) inside the library; each GPU the
+ * library runs on holds its own copy until the process ends.  The call allocates and frees
+ * nothing.  Arguments, results, host and device errors are dc_repack's; the device that owns the
+ * buffers and the stream must be the current HIP device.
+ * Limit: dc_workspace_bytes(prm, dst_capacity_tokens) must not exceed DC_REPACK_NOALLOC_WS_BYTES
+ * (about 120 M tokens of capacity with 16 384 sequences), else UNSUPPORTED_SIZE and nothing is
+ * enqueued.
+ * All calls on one GPU share that GPU's array: two calls whose kernels may overlap there (two
+ * streams, two threads) race; calls on one stream do not.  A dc_gather / dc_scatter that is to
+ * reuse the plan later needs dc_repack with a workspace of the caller's.
+ */
+dc_status dc_repack_noalloc(const dc_params* prm, const dc_source* src, const int32_t* d_seq_len,
+                            const int32_t* d_perm, const int32_t* d_shard_seq_off,
+                            const dc_field* fields, int32_t n_fields, int64_t dst_capacity_tokens,
+                            int64_t* d_dst_tok_off, int64_t* d_shard_tok_off, int32_t* d_shard_mb_off,
+                            int32_t* d_mb_seq_off, int32_t* d_cu_seqlens, int32_t* d_n_mb,
+                            int32_t* d_status, void* hip_stream);
 
 /* Bytes of device workspace dc_scatter needs (256-byte aligned, like dc_plan's). */
 size_t dc_scatter_workspace_bytes(const dc_params* prm, const dc_source* src);

@@ -19,6 +19,7 @@ DC_MAX_SEQ_LARGE = 1 << 20
 DC_MAX_SHARDS = 1024
 DC_MAX_FIELDS = 8
 DC_MAX_SRC_SHARDS = 16
+DC_REPACK_NOALLOC_WS_BYTES = 8 << 20
 
 DC_OK = 0
 DC_ERR_INVALID_ARG = 1
@@ -33,7 +34,7 @@ DC_ERR_BAD_LAYOUT = 9
 
 EXPORTS = ("dc_workspace_bytes", "dc_balance", "dc_group_advantage", "dc_plan", "dc_gather",
            "dc_repack", "dc_scatter_workspace_bytes", "dc_scatter", "dc_gae", "dc_balance_group_advantage",
-           "dc_gather_advantage", "dc_balance_workspace_bytes", "dc_balance_ws", "dc_strerror")
+           "dc_gather_advantage", "dc_balance_workspace_bytes", "dc_balance_ws", "dc_repack_noalloc", "dc_strerror")
 
 
 class dc_params(C.Structure):
@@ -97,6 +98,10 @@ def load() -> C.CDLL:
         lib.dc_repack.argtypes = [C.POINTER(dc_params), C.POINTER(dc_source), vp, vp, vp,
                                   C.POINTER(dc_field), C.c_int32, C.c_int64,
                                   vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp, vp]
+        lib.dc_repack_noalloc.restype = C.c_int
+        lib.dc_repack_noalloc.argtypes = [C.POINTER(dc_params), C.POINTER(dc_source), vp, vp, vp,
+                                          C.POINTER(dc_field), C.c_int32, C.c_int64,
+                                          vp, vp, vp, vp, vp, vp, vp, vp]
         lib.dc_scatter_workspace_bytes.restype = C.c_size_t
         lib.dc_scatter_workspace_bytes.argtypes = [C.POINTER(dc_params), C.POINTER(dc_source)]
         lib.dc_scatter.restype = C.c_int
@@ -252,6 +257,17 @@ def dc_repack(prm: dc_params, src: Source, d_seq_len, d_perm, d_shard_seq_off, f
                             _ptr(d_shard_tok_off), _ptr(d_shard_mb_off), _ptr(d_mb_seq_off), _ptr(d_cu_seqlens),
                             _ptr(d_n_mb), _ptr(d_ws), int(ws_bytes), _ptr(d_status), _stream(stream)),
            "dc_repack")
+
+
+def dc_repack_noalloc(prm: dc_params, src: Source, d_seq_len, d_perm, d_shard_seq_off, fields: Fields,
+                      dst_capacity_tokens: int, d_dst_tok_off, d_shard_tok_off, d_shard_mb_off, d_mb_seq_off,
+                      d_cu_seqlens, d_n_mb, d_status, stream=None) -> None:
+    _check(load().dc_repack_noalloc(C.byref(prm), C.byref(src.struct), _ptr(d_seq_len), _ptr(d_perm),
+                                    _ptr(d_shard_seq_off), fields.array, fields.n, int(dst_capacity_tokens),
+                                    _ptr(d_dst_tok_off), _ptr(d_shard_tok_off), _ptr(d_shard_mb_off),
+                                    _ptr(d_mb_seq_off), _ptr(d_cu_seqlens), _ptr(d_n_mb), _ptr(d_status),
+                                    _stream(stream)),
+           "dc_repack_noalloc")
 
 
 def dc_scatter_workspace_bytes(prm: dc_params, src: Source) -> int:

@@ -119,6 +119,12 @@ class DeviceBatch:
                     self.capacity, self.dst_tok_off, self.shard_tok_off, self.shard_mb_off, self.mb_seq_off,
                     self.cu_seqlens, self.n_mb, self.ws, self.ws_bytes, self.status)
 
+    def repack_noalloc(self) -> None:
+        """dc_repack planning in the library's own device array (no workspace argument)."""
+        B.dc_repack_noalloc(self.prm, self.source, self.seq_len, self.perm, self.shard_seq_off, self.fields,
+                            self.capacity, self.dst_tok_off, self.shard_tok_off, self.shard_mb_off, self.mb_seq_off,
+                            self.cu_seqlens, self.n_mb, self.status)
+
     def step(self) -> None:
         """One pass of the whole path: advantage, balance, plan, gather."""
         self.group_advantage()
