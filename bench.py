@@ -4,9 +4,12 @@
 A step is one pass of the whole path over one synthetic rollout batch already resident in
 HBM: dc_balance and dc_group_advantage (one launch: dc_balance_group_advantage), dc_plan,
 dc_gather, all on one stream.
-Prints ONE JSON line: repacked tokens/s for the whole step, the gather kernel's achieved HBM
-bandwidth against the chip's peak (HIP events around every gather launch of the timed region,
-on the stream it is launched on), and the CPU oracle timed on the host as a reported baseline.
+Prints ONE JSON line.  Its headline is workload config 5 (the largest): repacked tokens/s for the
+whole step, the gather kernel's achieved HBM bandwidth against the chip's peak (HIP events around
+every gather launch of the timed region, on the stream it is launched on; mean, median and
+minimum), and the CPU oracle timed on the host as a reported baseline.  "other_configs" carries
+the same step figures for configs 3 and 4, measured the same way in the same process, so that one
+run covers every configuration the bandwidth target names.
 Outside the timed region it also times each call of the step on its own, the step with
 dc_gather_advantage (no rollout-layout copy of the per-token advantages), the reverse path
 (dc_scatter) and the PPO advantage stage (dc_gae) on the same batch, and a plain copy of the
@@ -19,6 +22,7 @@ import argparse
 import hashlib
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -31,9 +35,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per gather launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch), each
 # scaled by what the same counter reads for the plain copy of --calibrate-copy (2^30 B in, 2^30 B
 # out); valid only for the kernel sources with the digest below (profiles/ has the runs).
+TRAFFIC_SOURCE = "profiles/hbm_traffic_config5_pmc.txt"
 TRAFFIC = {
     # config: (fetch bytes + write bytes per gather launch, digest of csrc/gather.hip + csrc/dc_internal.h)
-    5: (1044536900 + 985038600, "053e77118e55f191"),     # profiles/hbm_traffic_config5_pmc.txt
+    5: (1044536900 + 985038600, "053e77118e55f191"),
 }
 TRAFFIC_ADV = {                                          # the same for dc_gather_advantage's kernel
     5: (867835400 + 983742500, "053e77118e55f191"),
@@ -48,10 +53,35 @@ def kernel_digest() -> str:
     return h.hexdigest()[:16]
 
 
-def cpu_baseline(w, budget_s: float = 12.0):
-    """Time the oracle (as it stands, single thread) on the same workload: whole oracle steps
-    repeated until about budget_s seconds of CPU work are done."""
+def host_description():
+    """Cores this process may run on, and the CPU's model string."""
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count() or 1
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if line.lower().startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return cores, model
+
+
+def cpu_baseline(w, budget_s: float = 12.0, gather_budget_s: float = 6.0):
+    """Time the oracle (as it stands) on the same workload.  value: whole oracle steps on ONE thread,
+    repeated until about budget_s seconds of CPU work are done.  gather_all_cores: the oracle's gather
+    alone (one copy per sequence: independent pieces of work), the slots cut into one contiguous
+    range per host core, each range one call of the same oracle function from a thread of its own."""
+    import concurrent.futures
+
+    import numpy as np
+
     import oracle
+    host_cores, cpu_model = host_description()
     mask = w.field_by_name("mask").shards
     reps, spent = 0, 0.0
     while reps == 0 or (spent < budget_s and reps < 1000):
@@ -66,9 +96,42 @@ def cpu_baseline(w, budget_s: float = 12.0):
         oracle.gather(w.seq_len, bal.perm, w.src_tok_off, w.src_shard_seq_off, adv_tok, pl.dst_tok_off, arena)
         spent += time.perf_counter() - t0
         reps += 1
+
+    # the gather on every core: slot ranges of about equal token counts, destination arenas allocated
+    # and touched beforehand (the single-thread figure above includes allocating them)
+    n_thr = max(1, host_cores)
+    cuts = np.searchsorted(pl.dst_tok_off, np.linspace(0, arena, n_thr + 1)).astype(int)
+    cuts[0], cuts[-1] = 0, w.n_seq
+    shards_of = [f.shards for f in w.fields] + [adv_tok]
+    arenas = [np.zeros(arena, s[0].dtype) for s in shards_of]
+
+    def part(t):
+        for shards, dst in zip(shards_of, arenas):
+            oracle.gather_slots(w.seq_len, bal.perm, w.src_tok_off, w.src_shard_seq_off, shards, pl.dst_tok_off,
+                                dst, int(cuts[t]), int(cuts[t + 1]))
+
+    g_reps, g_spent = 0, 0.0
+    with concurrent.futures.ThreadPoolExecutor(n_thr) as pool:
+        list(pool.map(part, range(n_thr)))                       # untimed: threads started, pages mapped
+        while g_reps == 0 or (g_spent < gather_budget_s and g_reps < 1000):
+            t0 = time.perf_counter()
+            list(pool.map(part, range(n_thr)))                   # ctypes releases the interpreter lock during a call
+            g_spent += time.perf_counter() - t0
+            g_reps += 1
+    payload = sum(a.dtype.itemsize for a in arenas)
     return {"value": w.total_tokens * reps / spent, "unit": "tokens/s", "cores": 1, "kind": "oracle",
             "sample": f"whole workload ({w.total_tokens} tokens per step), {reps} full oracle steps "
-                      f"(balance, advantage, plan, gather of every field), {spent:.1f} s, one thread"}
+                      f"(balance, advantage, plan, gather of every field), {spent:.1f} s, one thread",
+            "host_cores": host_cores, "cpu_model": cpu_model,
+            "gather_all_cores": {"value": w.total_tokens * g_reps / g_spent, "unit": "tokens/s", "cores": n_thr,
+                                 "GB_per_s": 2 * payload * w.total_tokens * g_reps / g_spent / 1e9,
+                                 "sample": f"the oracle's gather alone, every field of the whole workload, {g_reps} "
+                                           f"passes, {g_spent:.1f} s, {n_thr} threads over disjoint slot ranges, "
+                                           f"arenas allocated beforehand"}}
+
+
+def stats_ms(xs):
+    return {"mean": statistics.fmean(xs), "median": statistics.median(xs), "min": min(xs)}
 
 
 def main() -> int:
@@ -76,9 +139,13 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: 5, the largest)")
+    ap.add_argument("--config", type=int, default=5, help="headline workload 1..5 (default: 5, the largest)")
+    ap.add_argument("--other-configs", type=str, default=None,
+                    help="comma-separated workloads measured beside the headline one, step figures only "
+                         "(default: 3,4 when the headline is config 5, else none; 'none' for none)")
     ap.add_argument("--sets", type=int, default=3, help="rotating buffer sets (defeats cache reuse)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sides", action="store_true", help="skip every side measurement (profiling runs)")
     ap.add_argument("--single-stream", action="store_true", help="issue the four calls one after the other on one stream")
     ap.add_argument("--two-streams", action="store_true",
                     help="dc_group_advantage on a second stream beside dc_balance + dc_plan (two cross-stream waits per step)")
@@ -104,13 +171,6 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
 
-    w = workloads.make_workload(args.config)
-    T = w.total_tokens
-    sets = [runner.DeviceBatch(w) for _ in range(max(1, args.sets))]
-    bpt = sets[0].payload_bytes_per_token             # payload incl. the per-token advantage
-    gather_bytes = 2 * bpt * T                         # algorithmic: read once + write once
-    gather_adv_bytes = (2 * bpt - 4) * T               # dc_gather_advantage: the 4-byte advantage is written, not read
-
     def one_step(b, ev=None):
         if args.single_stream:
             b.group_advantage(); b.balance(); b.plan()
@@ -126,30 +186,97 @@ def main() -> int:
         else:
             b.step_fused(ev)
 
-    for i in range(args.warmup):
-        one_step(sets[i % len(sets)])
-    torch.cuda.synchronize()
-    assert all(s.read_status() == 0 for s in sets)
+    def timed_steps(w, sets, steps, warmup):
+        """warmup untimed steps, then `steps` steps between two synchronisations.  Returns wall ms per
+        step, the gather launches' durations (HIP events round each) and the steps' own durations
+        (end of one step's gather to the end of the next one's: the steps are queued back to back)."""
+        for i in range(warmup):
+            one_step(sets[i % len(sets)])
+        torch.cuda.synchronize()
+        assert all(s.read_status() == 0 for s in sets)
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            one_step(sets[i % len(sets)], ev[i])
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        assert all(s.read_status() == 0 for s in sets)
+        gather_ms = [a.elapsed_time(b) for a, b in ev]
+        step_ms = [ev[i - 1][1].elapsed_time(ev[i][1]) for i in range(1, steps)]
+        return (t1 - t0) * 1e3 / steps, gather_ms, step_ms
 
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        one_step(sets[i % len(sets)], ev[i])
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    assert all(s.read_status() == 0 for s in sets)
+    def step_record(w, sets, steps, warmup):
+        T = w.total_tokens
+        bpt = sets[0].payload_bytes_per_token          # payload incl. the per-token advantage
+        nbytes = (2 * bpt - 4) * T if args.no_rollout_adv else 2 * bpt * T
+        ms, g_ms, s_ms = timed_steps(w, sets, steps, warmup)
+        g = stats_ms(g_ms)
+        return {"workload": f"config {w.cfg} ({w.name}): {w.n_seq} sequences, {T} tokens, P={w.n_shards}, "
+                            f"token budget {w.token_budget}, {bpt} payload B/token, {w.n_src_shards} rollout shard(s)",
+                "tokens": T, "tokens_per_s": T / (ms * 1e-3), "ms_per_step": ms,
+                "step_ms_device": stats_ms(s_ms) if s_ms else None,
+                "gather": {"algorithmic_bytes_per_launch": nbytes, "launch_ms": g,
+                           "achieved": nbytes / (g["mean"] * 1e-3) / 1e9, "unit": "GB/s",
+                           "frac": nbytes / (g["mean"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                           "frac_median": nbytes / (g["median"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                           "frac_best": nbytes / (g["min"] * 1e-3) / 1e9 / HBM_PEAK_GBS}}
 
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    gather_ms = sum(a.elapsed_time(b) for a, b in ev) / args.steps
-    timed_gather_bytes = gather_adv_bytes if args.no_rollout_adv else gather_bytes
-    achieved = timed_gather_bytes / (gather_ms * 1e-3) / 1e9
+    # ---- the other configurations first (their buffers are released before the headline run) ----
+    if args.other_configs is None:
+        others = [3, 4] if args.config == 5 and not (args.single_stream or args.two_streams) else []
+    elif args.other_configs.strip().lower() in ("", "none"):
+        others = []
+    else:
+        others = [int(x) for x in args.other_configs.split(",")]
+    other_configs = {}
+    for cfg in others:
+        wo = workloads.make_workload(cfg)
+        so = [runner.DeviceBatch(wo) for _ in range(max(1, args.sets))]
+        other_configs[str(cfg)] = step_record(wo, so, args.steps, args.warmup)
+        del so, wo
+        torch.cuda.empty_cache()
+
+    # ---- the headline configuration ----
+    w = workloads.make_workload(args.config)
+    T = w.total_tokens
+    sets = [runner.DeviceBatch(w) for _ in range(max(1, args.sets))]
+    bpt = sets[0].payload_bytes_per_token
+    gather_bytes = 2 * bpt * T                         # algorithmic: read once + write once
+    gather_adv_bytes = (2 * bpt - 4) * T               # dc_gather_advantage: the 4-byte advantage is written, not read
+    head = step_record(w, sets, args.steps, args.warmup)
+    ms_per_step = head["ms_per_step"]
+    gather_ms = head["gather"]["launch_ms"]["mean"]
+    timed_gather_bytes = head["gather"]["algorithmic_bytes_per_launch"]
+    achieved = head["gather"]["achieved"]
+
+    def device_ms(call, n=50, warm=3):
+        """Device time of call(buffer set): n calls queued back to back with an event between each two (so the
+        host's marshalling of one call overlaps the previous call's kernels), after warm untimed calls.
+        Returns {"mean", "median", "min"} in ms."""
+        for i in range(warm):
+            call(sets[i % len(sets)])                   # a kernel's first launch in a process loads its code
+        torch.cuda.synchronize()
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+        marks[0].record()
+        for i in range(n):
+            call(sets[i % len(sets)])
+            marks[i + 1].record()
+        torch.cuda.synchronize()
+        return stats_ms([marks[i].elapsed_time(marks[i + 1]) for i in range(n)])
+
+    def bw(nbytes, st):
+        return {"ms": round(st["median"], 4), "ms_mean": round(st["mean"], 4), "ms_min": round(st["min"], 4),
+                "algorithmic_bytes": nbytes, "achieved": nbytes / (st["median"] * 1e-3) / 1e9, "unit": "GB/s",
+                "frac": nbytes / (st["median"] * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+    variant = stage = reverse = ppo = double_buffer = ceiling = None
+    sides = not args.no_sides
 
     # the same step with dc_gather_advantage in place of the per-token advantage pass + dc_gather
     # (a shorter run of its own, outside the timed region)
-    variant = None
-    if not (args.no_rollout_adv or args.single_stream or args.two_streams):
-        n_var = max(1, min(args.steps, 60))
+    if sides and not (args.no_rollout_adv or args.single_stream or args.two_streams):
+        n_var = max(2, min(args.steps, 60))
         for i in range(3):
             sets[i % len(sets)].step_no_rollout_adv()
         evv = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_var)]
@@ -159,13 +286,14 @@ def main() -> int:
             sets[i % len(sets)].step_no_rollout_adv(evv[i])
         torch.cuda.synchronize()
         v_ms = (time.perf_counter() - v0) * 1e3 / n_var
-        vg_ms = sum(a.elapsed_time(b) for a, b in evv) / n_var
+        vg = stats_ms([a.elapsed_time(b) for a, b in evv])
         assert all(s.read_status() == 0 for s in sets)
         variant = {"calls": "dc_balance_group_advantage (adv_seq only), dc_plan, dc_gather_advantage",
                    "steps": n_var, "ms_per_step": round(v_ms, 4), "tokens_per_s": T / (v_ms * 1e-3),
-                   "gather_ms": round(vg_ms, 4), "algorithmic_bytes": gather_adv_bytes,
-                   "achieved": gather_adv_bytes / (vg_ms * 1e-3) / 1e9, "unit": "GB/s",
-                   "frac": gather_adv_bytes / (vg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+                   "gather_ms": round(vg["mean"], 4), "gather_ms_median": round(vg["median"], 4),
+                   "gather_ms_min": round(vg["min"], 4), "algorithmic_bytes": gather_adv_bytes,
+                   "achieved": gather_adv_bytes / (vg["mean"] * 1e-3) / 1e9, "unit": "GB/s",
+                   "frac": gather_adv_bytes / (vg["mean"] * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.int32, device="cuda:0")
@@ -175,53 +303,40 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    def device_ms(call, n=12, warm=3):
-        """Mean device time of call(buffer set), n calls queued back to back between two events (so the
-        host's marshalling of one call overlaps the previous call's kernels), after warm untimed calls."""
-        for i in range(warm):
-            call(sets[i % len(sets)])                   # a kernel's first launch in a process loads its code
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for i in range(n):
-            call(sets[i % len(sets)])
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / n
+    if sides:
+        # per-stage device times (median of 50 calls), outside the timed region
+        stage = {}
+        for name in ("group_advantage", "balance", "plan", "gather"):
+            st = device_ms(lambda b, name=name: getattr(b, name)())
+            stage[name + "_ms"] = round(st["median"], 4)
+            stage[name + "_ms_min"] = round(st["min"], 4)
+        st = device_ms(lambda b: b.balance_group_advantage())
+        stage["balance_group_advantage_ms"] = round(st["median"], 4)
+        stage["balance_group_advantage_ms_min"] = round(st["min"], 4)
+        stage["group_advantage_algorithmic_bytes"] = 5 * T       # 1 B mask read + 4 B advantage written per token
 
-    # per-stage device times, outside the timed region
-    stage = {}
-    for name in ("group_advantage", "balance", "plan", "gather"):
-        stage[name + "_ms"] = round(device_ms(lambda b, name=name: getattr(b, name)()), 4)
-
-    # the reverse path (training layout -> rollout layout), whole dc_scatter call, outside the timed region
-    for b in sets:
-        b.prepare_scatter()
-    scatter_ms = device_ms(lambda b: b.scatter())
-    assert all(s.read_status() == 0 for s in sets)
-    reverse = {"call": "dc_scatter", "ms": round(scatter_ms, 4), "algorithmic_bytes": gather_bytes,
-               "achieved": gather_bytes / (scatter_ms * 1e-3) / 1e9, "unit": "GB/s",
-               "frac": gather_bytes / (scatter_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
-
-    # PPO advantage stage (dc_gae) on the same batch, where the workload has a value field; outside the timed region
-    ppo = None
-    if "value" in sets[0].src_fields and sets[0].elem_bytes.get("value") == 4:
-        res = {}
+        # the reverse path (training layout -> rollout layout), whole dc_scatter call
         for b in sets:
-            b.prepare_gae()
-        for tag, klc, bpt_gae in (("no_kl", 0.0, 13), ("kl", 0.05, 21)):
-            ms = device_ms(lambda b, klc=klc: b.gae(1.0, 0.95, klc))
-            res[tag] = {"ms": round(ms, 4), "algorithmic_bytes": bpt_gae * T,
-                        "achieved": bpt_gae * T / (ms * 1e-3) / 1e9, "unit": "GB/s",
-                        "frac": bpt_gae * T / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+            b.prepare_scatter()
+        reverse = {"call": "dc_scatter", **bw(gather_bytes, device_ms(lambda b: b.scatter()))}
         assert all(s.read_status() == 0 for s in sets)
-        ppo = {"call": "dc_gae", **res}
+        for b in sets:
+            b.release_scatter()
+
+        # PPO advantage stage (dc_gae) on the same batch, where the workload has a value field
+        if "value" in sets[0].src_fields and sets[0].elem_bytes.get("value") == 4:
+            res = {}
+            for b in sets:
+                b.prepare_gae()
+            for tag, klc, bpt_gae in (("no_kl", 0.0, 13), ("kl", 0.05, 21)):
+                res[tag] = bw(bpt_gae * T, device_ms(lambda b, klc=klc: b.gae(1.0, 0.95, klc)))
+            assert all(s.read_status() == 0 for s in sets)
+            ppo = {"call": "dc_gae", **res}
 
     # Double buffer (Sec. 6.5): the step that fills one buffer set beside a consumer that still reads the set
     # filled before it (stand-in consumer: one reduction over each 4-byte arena of that set), on two streams of
     # the default priority, against the same two pieces of work issued one after the other; outside the timed region
-    double_buffer = None
-    if len(sets) >= 2 and not args.no_double_buffer:
+    if sides and len(sets) >= 2 and not args.no_double_buffer:
         def consume(b):
             for n, v in b.dst_fields.items():
                 if b.elem_bytes.get(n, 4) == 4:
@@ -250,33 +365,35 @@ def main() -> int:
             torch.cuda.synchronize()
             d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             d0.record()
-            for i in range(12):
+            for i in range(24):
                 both(i, overlap)
             d1.record()
             torch.cuda.synchronize()
-            res[tag] = round(d0.elapsed_time(d1) / 12, 4)
+            res[tag] = round(d0.elapsed_time(d1) / 24, 4)
         assert all(s.read_status() == 0 for s in sets)
         double_buffer = {"what": "one step into buffer set i beside a reduction over the 4-byte arenas of set i-1 "
                                  "(two streams) vs one after the other", **res}
 
     # the achievable ceiling on this machine: a plain elementwise copy (one torch kernel) of the gather's byte count,
     # 3 rotating buffer pairs, measured the same way
-    n_words = gather_bytes // 2 // 4
-    pairs = [(torch.ones(n_words, dtype=torch.int32, device="cuda:0"), torch.empty(n_words, dtype=torch.int32, device="cuda:0"))
-             for _ in range(3)]
-    for i in range(3):
-        torch.add(pairs[i][0], 1, out=pairs[i][1])
-    torch.cuda.synchronize()
-    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    c0.record()
-    for i in range(12):
-        torch.add(pairs[i % 3][0], 1, out=pairs[i % 3][1])
-    c1.record()
-    torch.cuda.synchronize()
-    copy_ms = c0.elapsed_time(c1) / 12
-    ceiling = {"what": "plain elementwise copy (one torch kernel) of the gather's byte count, same box",
-               "ms": round(copy_ms, 4), "achieved": 2 * n_words * 4 / (copy_ms * 1e-3) / 1e9, "unit": "GB/s"}
-    del pairs
+    if sides:
+        n_words = gather_bytes // 2 // 4
+        pairs = [(torch.ones(n_words, dtype=torch.int32, device="cuda:0"), torch.empty(n_words, dtype=torch.int32, device="cuda:0"))
+                 for _ in range(3)]
+        for i in range(3):
+            torch.add(pairs[i][0], 1, out=pairs[i][1])
+        torch.cuda.synchronize()
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(31)]
+        marks[0].record()
+        for i in range(30):
+            torch.add(pairs[i % 3][0], 1, out=pairs[i % 3][1])
+            marks[i + 1].record()
+        torch.cuda.synchronize()
+        cst = stats_ms([marks[i].elapsed_time(marks[i + 1]) for i in range(30)])
+        ceiling = {"what": "plain elementwise copy (one torch kernel) of the gather's byte count, same box",
+                   "ms": round(cst["median"], 4), "ms_min": round(cst["min"], 4),
+                   "achieved": 2 * n_words * 4 / (cst["median"] * 1e-3) / 1e9, "unit": "GB/s"}
+        del pairs
 
     traffic = None
     table = TRAFFIC_ADV if args.no_rollout_adv else TRAFFIC
@@ -285,25 +402,31 @@ def main() -> int:
     if variant is not None and args.config in TRAFFIC_ADV and TRAFFIC_ADV[args.config][1] == kernel_digest():
         variant["traffic"] = TRAFFIC_ADV[args.config][0]
 
+    g = head["gather"]
     out = {
         "metric": "repacked tokens/sec and achieved HBM GB/s (fraction of peak), 1 MI355X",
         "value": T / (ms_per_step * 1e-3),
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
+        "ms_per_step_device": head["step_ms_device"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"config {args.config} ({w.name}): {w.n_seq} sequences, {T} tokens, "
-                               f"P={w.n_shards}, token budget {w.token_budget}, {bpt} payload B/token, "
-                               f"{w.n_src_shards} rollout shard(s)",
+        "config": {"workload": head["workload"],
                    "buffer_sets": len(sets),
                    "streams": 2 if args.two_streams else 1,
                    "launches": "separate" if (args.single_stream or args.two_streams)
                                else ("dc_balance_group_advantage (adv_seq only), dc_plan, dc_gather_advantage"
                                      if args.no_rollout_adv else "dc_balance_group_advantage, dc_plan, dc_gather")},
-        "roofline": {"bound": "hbm", "kernel": "gather_adv_kernel" if args.no_rollout_adv else "gather_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "gather_adv_kernel" if args.no_rollout_adv else "gather_kernel",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "algorithmic_bytes_per_launch": timed_gather_bytes, "avg_launch_ms": gather_ms},
+                     "traffic_source": (TRAFFIC_SOURCE + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, taken earlier on "
+                                        "these kernel sources; not measured in this run)") if traffic else None,
+                     "algorithmic_bytes_per_launch": timed_gather_bytes, "avg_launch_ms": gather_ms,
+                     "median_launch_ms": g["launch_ms"]["median"], "min_launch_ms": g["launch_ms"]["min"],
+                     "frac_median": g["frac_median"], "frac_best": g["frac_best"]},
+        "other_configs": other_configs,
         "copy_ceiling": ceiling,
         "stages": stage,
         "no_rollout_adv": variant,

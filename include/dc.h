@@ -128,7 +128,11 @@ typedef struct dc_field {
 
 /* Bytes of device workspace dc_plan / dc_gather / dc_repack need for these sizes
  * (about 70 bytes per 1024 tokens of capacity plus 16 bytes per sequence; above DC_MAX_SEQ
- * sequences 8.25 bytes per sequence more). */
+ * sequences 8.25 bytes per sequence more).  The workspace is where the re-partitioning of
+ * Sec. 6 "Distributed Databuffer" keeps its routing tables between dc_plan and dc_gather: which
+ * sequence of which rollout shard each piece of the training layout comes from.  It is the
+ * caller's, like every buffer (the paper's Databuffer owns its storage; here nothing is owned).
+ * Returns 0 for a null prm. */
 size_t dc_workspace_bytes(const dc_params* prm, int64_t dst_capacity_tokens);
 
 /*
@@ -211,7 +215,19 @@ dc_status dc_gae(const dc_params* prm, const dc_source* src, const int32_t* d_se
                  int32_t* d_status, void* hip_stream);
 
 /*
- * Plan of the packed training layout (see "Layouts").  Outputs (device):
+ * Plan of the packed training layout (see "Layouts"): where the Databuffer of Sec. 6 ("Distributed
+ * Databuffer": redistribution between two stages whose DP sizes differ) puts every sequence once
+ * Algorithm 1 has said which worker takes it.  The paper pads its batches (Sec. 7.1); the packed
+ * form, the token-budget micro-batches and cu_seqlens follow the statement of the task this library
+ * serves, as read under "Layouts" above.
+ * d_perm / d_shard_seq_off: as dc_balance wrote them, or any permutation and shard table.
+ * d_perm == NULL: no re-partitioning, slot j holds sequence j.  d_shard_seq_off == NULL (then d_perm
+ * must be NULL and prm->n_shards == src->n_src_shards, else INVALID_ARG): the training shards ARE the
+ * rollout shards.  That is the case of Sec. 6 "Local Cache" - the DP size does not change between the
+ * two stages, so the data stays where it is: with packed rollout buffers the plan then describes them
+ * in place (d_dst_tok_off[j] - d_shard_tok_off[shard of j] == d_src_tok_off[j]), the next stage reads
+ * them through it and no dc_gather is needed.
+ * Outputs (device):
  * d_dst_tok_off[N+1] (last = d_shard_tok_off[P]), d_shard_tok_off[P+1], d_shard_mb_off[P+1],
  * d_mb_seq_off[N+1] (first M+1 entries valid), d_cu_seqlens[2N] (first N+M valid), d_n_mb[1] = M.
  * Also fills the workspace with what dc_gather needs.  dst_capacity_tokens is the
@@ -225,7 +241,9 @@ dc_status dc_plan(const dc_params* prm, const dc_source* src, const int32_t* d_s
                   void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream);
 
 /*
- * Segmented gather: for every slot j and field f copy seq_len[perm[j]] elements from
+ * Segmented gather: the data movement of the Databuffer's re-partitioning (Sec. 6 "Distributed
+ * Databuffer"; App. B Table 2 counts it as put / get), for the payload fields of Sec. 1 (token ids,
+ * masks, log-probs, values, advantages).  For every slot j and field f copy seq_len[perm[j]] elements from
  * the sequence's place in the rollout layout to element d_dst_tok_off[j] of f.d_dst,
  * as raw bytes.  Must follow a dc_plan on the same stream with the same prm, src,
  * dst_capacity_tokens, d_dst_tok_off and workspace.
@@ -252,7 +270,10 @@ dc_status dc_gather_advantage(const dc_params* prm, const dc_source* src, const 
                               int64_t dst_capacity_tokens, const int64_t* d_dst_tok_off,
                               const void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream);
 
-/* dc_plan then dc_gather. */
+/* dc_plan then dc_gather: the whole re-partitioning of Sec. 6 "Distributed Databuffer" for one
+ * batch, once dc_balance (Sec. 6 "Load Balancing") has assigned the sequences.  Arguments, errors
+ * and NULL conventions are those of the two calls; the gather's arguments are checked before the
+ * plan is enqueued. */
 dc_status dc_repack(const dc_params* prm, const dc_source* src, const int32_t* d_seq_len,
                     const int32_t* d_perm, const int32_t* d_shard_seq_off,
                     const dc_field* fields, int32_t n_fields, int64_t dst_capacity_tokens,
@@ -292,7 +313,8 @@ size_t dc_scatter_workspace_bytes(const dc_params* prm, const dc_source* src);
  * rollout buffers (WRITTEN, 16-byte aligned).  Elements of a rollout buffer that belong to no sequence
  * (padding between rows) are left untouched.  d_dst_tok_off: as dc_plan wrote it for the same prm,
  * src and d_perm.  Sequences must not overlap in the rollout layout.
- * Device errors: BAD_LAYOUT (perm entry or offsets out of range, overlapping sequences),
+ * Device errors: BAD_LAYOUT (perm entry or offsets out of range, a sequence named twice by perm,
+ * overlapping sequences),
  * ZERO_LENGTH_SEQ, OVERFLOW (a slot reaches beyond dst_capacity_tokens); a slot that fails a check
  * moves nothing.
  */

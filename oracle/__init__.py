@@ -180,6 +180,24 @@ def gather(seq_len, perm, src_tok_off, src_shard_seq_off, src_shards: Sequence[n
     return dst
 
 
+def gather_slots(seq_len, perm, src_tok_off, src_shard_seq_off, src_shards: Sequence[np.ndarray],
+                 dst_tok_off, dst: np.ndarray, j0: int, j1: int) -> None:
+    """The same copy for the output slots [j0, j1) only, into a destination arena the caller made:
+    dco_gather called on that part of perm / dst_tok_off.  Calls on disjoint slot ranges write
+    disjoint elements, so they may run in threads of their own (ctypes releases the interpreter lock)."""
+    S = _i32(seq_len)
+    pm = _i32(perm)
+    sto = np.ascontiguousarray(src_tok_off, dtype=np.int64)
+    sso = _i32(src_shard_seq_off)
+    dto = np.ascontiguousarray(dst_tok_off, dtype=np.int64)
+    srcs = [np.ascontiguousarray(x) for x in src_shards]
+    assert dst.flags.c_contiguous and dst.dtype == srcs[0].dtype and 0 <= j0 <= j1 <= len(pm)
+    ptrs = (C.c_void_p * len(srcs))(*[x.ctypes.data for x in srcs])
+    _chk(_load().dco_gather(_p(S), C.c_int32(j1 - j0), C.c_void_p(pm.ctypes.data + 4 * j0), _p(sto), _p(sso),
+                            C.c_int32(len(srcs)), ptrs, _p(dst), C.c_int32(dst.dtype.itemsize),
+                            C.c_void_p(dto.ctypes.data + 8 * j0)))
+
+
 def scatter(seq_len, perm, src_tok_off, src_shard_seq_off, arena: np.ndarray, dst_tok_off,
             rollout_shards: Sequence[np.ndarray]) -> List[np.ndarray]:
     """Reverse of gather for one field: training arena -> copies of the given rollout buffers

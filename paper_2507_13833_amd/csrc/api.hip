@@ -18,7 +18,9 @@ Workspace carve_workspace(void* base, int32_t n_seq, int64_t dst_capacity_tokens
     w.slot_shard = reinterpret_cast<int32_t*>(p + off);   off += round_up(n * sizeof(int32_t), 256);
     w.gran_first = reinterpret_cast<int32_t*>(p + off);   off += round_up((size_t)w.n_gran * sizeof(int32_t), 256);
     w.gran_rec = reinterpret_cast<GranRec*>(p + off);     off += round_up((size_t)w.n_gran * sizeof(GranRec), 256);
-    w.plan_ok = reinterpret_cast<int32_t*>(p + off);      off += 256;
+    w.plan_ok = reinterpret_cast<int32_t*>(p + off);      off += 256;     // plan_ok, then own_shard_off, in one block
+    w.own_shard_off = w.plan_ok + 16;
+    static_assert((16 + DC_MAX_SRC_SHARDS + 1) * sizeof(int32_t) <= 256, "both fit the block");
     w.gpre = nullptr; w.word_starts = nullptr; w.word_last = nullptr;
     if (n_seq > DC_MAX_SEQ) {
         const size_t words = n / 32 + 2;
@@ -250,9 +252,11 @@ dc_status dc_plan(const dc_params* prm, const dc_source* src, const int32_t* d_s
     rc = check_source(prm, src, &sd);
     if (rc != DC_OK) return rc;
     if (dst_capacity_tokens < 0) return DC_ERR_INVALID_ARG;
-    if (!d_shard_seq_off || !d_dst_tok_off || !d_shard_tok_off || !d_shard_mb_off || !d_mb_seq_off || !d_n_mb || !d_ws)
+    if (!d_dst_tok_off || !d_shard_tok_off || !d_shard_mb_off || !d_mb_seq_off || !d_n_mb || !d_ws)
         return DC_ERR_INVALID_ARG;
-    if (prm->n_seq > 0 && (!d_seq_len || !d_perm || !d_cu_seqlens)) return DC_ERR_INVALID_ARG;
+    if (prm->n_seq > 0 && (!d_seq_len || !d_cu_seqlens)) return DC_ERR_INVALID_ARG;
+    // no shard table: the layout is kept, shard for shard (needs no permutation either)
+    if (!d_shard_seq_off && (d_perm || prm->n_shards != src->n_src_shards)) return DC_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(d_ws) & 255u) return DC_ERR_INVALID_ARG;
     Workspace ws = carve_workspace(d_ws, prm->n_seq, dst_capacity_tokens);
     if (ws_bytes < ws.bytes) return DC_ERR_WORKSPACE;

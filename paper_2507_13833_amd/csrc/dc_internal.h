@@ -20,7 +20,8 @@ constexpr int GATHER_TILE_TOKENS = GRAN_PER_TILE * GATHER_GRAN;
 constexpr int REC_SLOTS = 4;
 constexpr int32_t REL_FAR = 1 << 30;            // "no slot" / "beyond this granule" in relative tokens
 constexpr int LENSH_SHIFT = 26;                 // length | rollout shard << 26
-constexpr uint32_t DENSE_FLAG = 0x80000000u;    // in entry 0's lensh: more slots start inside the granule than the record holds
+static_assert(DC_MAX_SEQ_LEN < (1 << LENSH_SHIFT) && DC_MAX_SRC_SHARDS <= (1 << (31 - LENSH_SHIFT)),
+              "a length and a rollout shard share one non-negative 32-bit word");
 
 // The first REC_SLOTS slots that reach into a granule, relative to the granule's first
 // token.  Unused entries have start = REL_FAR.  64 bytes: one 16-dword scalar load.
@@ -49,6 +50,7 @@ struct Workspace {
     int32_t* gran_first;     // [n_gran] first slot j with end(j) > g * GATHER_GRAN (N if none); non-decreasing
     GranRec* gran_rec;       // [n_gran]
     int32_t* plan_ok;        // [1] 0 if the plan kernel found the shard table unusable and planned nothing
+    int32_t* own_shard_off;  // [DC_MAX_SRC_SHARDS + 1] the rollout shards' sequence offsets, for a plan that keeps them
     int64_t* gpre;           // [N + 1]  } only above DC_MAX_SEQ slots (else null): what plan_kernel keeps in LDS
     int32_t* word_starts;    // [N / 32 + 2]
     int32_t* word_last;      // [N / 32 + 2]
@@ -104,6 +106,8 @@ struct PlanArgs {
     const int32_t* seq_len;
     const int32_t* perm;
     const int32_t* shard_seq_off;
+    int32_t* own_shard_off;         // not null: the caller gave no shard table; slots_kernel writes the rollout shards'
+                                    // one here and shard_seq_off points at it
     int64_t* dst_tok_off;
     int64_t* shard_tok_off;
     int32_t* shard_mb_off;

@@ -53,8 +53,9 @@ constexpr int SLOTS_BLOCK = 256;
 __global__ __launch_bounds__(SLOTS_BLOCK) void slots_kernel(PlanArgs a, SourceDesc sd) {
     const int j = blockIdx.x * SLOTS_BLOCK + threadIdx.x;
     const int N = a.n_seq;
+    if (a.own_shard_off && j <= sd.n_src) a.own_shard_off[j] = sd.seq_off[j];     // the plan keeps the rollout shards
     if (j >= N) return;
-    const int32_t i = a.perm[j];
+    const int32_t i = a.perm ? a.perm[j] : j;                                     // no permutation: slot j holds sequence j
     const bool placed = i >= 0 && i < N;
     int32_t ln = placed ? a.seq_len[i] : 0;
     const int64_t so = placed ? a.src_tok_off[i] : 0;
@@ -94,7 +95,7 @@ __global__ __launch_bounds__(PLAN_BLOCK) void plan_kernel(PlanArgs a) {
 #pragma unroll
     for (int q = 0; q < PLAN_IPT; ++q) {
         const int j = q * PLAN_BLOCK + tid;
-        seq[q] = j < N ? a.perm[j] : -1;
+        seq[q] = j < N ? (a.perm ? a.perm[j] : j) : -1;
         len[q] = j < N ? a.slot_len[j] : 0;
     }
 
@@ -345,9 +346,6 @@ __device__ __forceinline__ void build_record(int N, bool usable, const int64_t* 
             }
         }
     }
-    // a further slot that starts inside the granule: the record does not hold them all
-    if (first + REC_SLOTS < N && starts[first + REC_SLOTS] - begin < GATHER_GRAN)
-        rec.e[0].lensh |= (int32_t)DENSE_FLAG;
     *first_out = first;
     u32x4* out = reinterpret_cast<u32x4*>(rec_out);
     const u32x4* in = reinterpret_cast<const u32x4*>(&rec);
@@ -393,9 +391,11 @@ hipError_t launch_plan(const dc_params& prm, const SourceDesc& src, const int64_
     a.slot_src_off = ws.slot_src_off; a.slot_len = ws.slot_len; a.slot_shard = ws.slot_shard;
     a.plan_ok = ws.plan_ok; a.status = d_status;
     a.gpre = ws.gpre; a.word_starts = ws.word_starts; a.word_last = ws.word_last;
-    if (prm.n_seq > 0) {
-        hipLaunchKernelGGL(slots_kernel, dim3((unsigned)((prm.n_seq + SLOTS_BLOCK - 1) / SLOTS_BLOCK)), dim3(SLOTS_BLOCK),
-                           0, st, a, src);
+    a.own_shard_off = nullptr;
+    if (!d_shard_seq_off) { a.own_shard_off = ws.own_shard_off; a.shard_seq_off = ws.own_shard_off; }
+    if (prm.n_seq > 0 || a.own_shard_off) {
+        hipLaunchKernelGGL(slots_kernel, dim3((unsigned)max(1, (prm.n_seq + SLOTS_BLOCK - 1) / SLOTS_BLOCK)),
+                           dim3(SLOTS_BLOCK), 0, st, a, src);
         hipError_t e0 = hipGetLastError();
         if (e0 != hipSuccess) return e0;
     }

@@ -66,7 +66,7 @@ __global__ __launch_bounds__(PLANL_BLOCK) void plan_large_kernel(PlanArgs a) {
     // ---- 1. permutation check (a repeat moves nothing), dense prefix of the slot lengths ----
     bool dup = false;
     for (int j = tid; j < N; j += PLANL_BLOCK) {
-        const int32_t i = a.perm[j];                     // out-of-range entries were emptied by slots_kernel
+        const int32_t i = a.perm ? a.perm[j] : j;        // out-of-range entries were emptied by slots_kernel
         if (i >= 0 && i < N && ((atomicOr(&L.bits[i >> 5], 1u << (i & 31)) >> (i & 31)) & 1u)) {
             dup = true;
             a.slot_len[j] = 0;

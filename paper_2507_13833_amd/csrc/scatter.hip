@@ -78,8 +78,11 @@ __global__ __launch_bounds__(SCAT_BLOCK) void scatter_slots_kernel(ScatArgs a, S
     const int64_t next = last_in_shard ? shard_tokens(sd, sh) : a.src_tok_off[i + 1];
     if (so < 0 || so + ln > shard_tokens(sd, sh) || so + ln > next) { set_status(a.status, DC_ERR_BAD_LAYOUT); return; }
     if (from < 0 || from + ln > a.capacity) { set_status(a.status, DC_ERR_OVERFLOW); return; }
+    // the first slot that claims a sequence places it; a second one means perm is not a permutation (and, N
+    // entries being in range, that some sequence is placed by none).  One of the claimants' offsets is used:
+    // outputs are unspecified once the status is set, but every access stays inside the buffers.
+    if (atomicCAS(a.r_len + i, 0, ln) != 0) { set_status(a.status, DC_ERR_BAD_LAYOUT); return; }
     a.r_src_off[i] = from;
-    a.r_len[i] = ln;
 }
 
 BackSegs make_back_segs(const SourceDesc& src) {

@@ -202,6 +202,12 @@ class DeviceBatch:
         self.sws_bytes = B.dc_scatter_workspace_bytes(self.prm, self.source)
         self.sws = torch.zeros(self.sws_bytes, dtype=torch.uint8, device=self.dev)
 
+    def release_scatter(self) -> None:
+        """Drop the buffers prepare_scatter made."""
+        self.back_fields = {}
+        self.back = None
+        self.sws = None
+
     def scatter(self) -> None:
         """Reverse path: training arenas -> rollout buffers (after plan / gather of the same step)."""
         B.dc_scatter(self.prm, self.source, self.seq_len, self.perm, self.back, self.capacity, self.dst_tok_off,

@@ -92,6 +92,9 @@ def test_balance_ws_host_errors(lib):
     with pytest.raises(B.DcError) as e:                      # more than 65535 sequences per shard
         B.dc_balance_ws(B.make_params(1 << 18, 2, 100), *out, 0x10000, 1 << 24, FAKE, stream=0)
     assert e.value.code == B.DC_ERR_UNSUPPORTED_SIZE
+    with pytest.raises(B.DcError) as e:                      # exactly one more than a shard may hold
+        B.dc_balance_ws(B.make_params(2 * 65536, 2, 100), *out, 0x10000, 1 << 24, FAKE, stream=0)
+    assert e.value.code == B.DC_ERR_UNSUPPORTED_SIZE
     with pytest.raises(B.DcError) as e:                      # beyond DC_MAX_SEQ_LARGE
         B.dc_balance_ws(B.make_params(B.DC_MAX_SEQ_LARGE + 64, 64, 100), *out, 0x10000, 1 << 26, FAKE, stream=0)
     assert e.value.code == B.DC_ERR_UNSUPPORTED_SIZE

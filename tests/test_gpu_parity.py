@@ -399,6 +399,8 @@ def test_balance_beyond_the_lds():
     _check_balance_ws(heavy(128 * 300), 128, label="128 workers")
     _check_balance_ws(rng.integers(1, 2000, 1000 * 40), 1000, label="1000 workers, lengths with many ties")
     _check_balance_ws(heavy(65 * 600), 65, cap=640, label="65 workers, partitions of unequal size")
+    # the most a shard may hold above DC_MAX_SEQ sequences: a place inside a partition is a 16-bit number
+    _check_balance_ws(rng.integers(1, 60, 2 * 65535), 2, label="65535 sequences per shard")
 
 
 def test_more_sequences_than_the_lds_holds():
@@ -505,6 +507,82 @@ def test_identity_plan_describes_the_rollout_layout_in_place():
     shard_of = np.repeat(np.arange(P), np.diff(w.src_shard_seq_off))
     assert np.array_equal(d.dst_tok_off.cpu().numpy()[:-1] - sto[shard_of], w.src_tok_off)
     assert np.array_equal(np.diff(sto), w.src_shard_tokens)
+
+
+def test_plan_without_permutation_and_shard_table_keeps_the_rollout_shards():
+    """The same case with nothing materialised on the device: d_perm = NULL (slot j holds sequence j) and
+    d_shard_seq_off = NULL (the training shards are the rollout shards, Sec. 6 "Local Cache").  Every plan
+    output against the oracle's plan of the identity permutation; then dc_repack with d_perm = NULL and an
+    explicit shard table moves every field unpermuted."""
+    torch, binding, runner = _gpu()
+    for cfg in (4, 2):                                               # 8 rollout shards; one rollout shard
+        w = workloads.make_workload(cfg)
+        d = runner.DeviceBatch(w, poison=True)
+        P = w.n_src_shards
+        prm = binding.make_params(w.n_seq, P, w.token_budget)
+        shard_tok_off = torch.zeros(P + 1, dtype=torch.int64, device=d.dev)
+        shard_mb_off = torch.zeros(P + 1, dtype=torch.int32, device=d.dev)
+        ws_bytes = binding.dc_workspace_bytes(prm, d.capacity)
+        ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=d.dev)
+        binding.dc_plan(prm, d.source, d.seq_len, None, None, d.capacity, d.dst_tok_off, shard_tok_off, shard_mb_off,
+                        d.mb_seq_off, d.cu_seqlens, d.n_mb, ws, ws_bytes, d.status)
+        torch.cuda.synchronize()
+        assert d.read_status() == 0
+        ident = np.arange(w.n_seq, dtype=np.int32)
+        pl = oracle.plan(w.seq_len, ident, w.src_shard_seq_off, w.token_budget)
+        M = int(d.n_mb.item())
+        assert M == pl.n_mb
+        assert np.array_equal(d.dst_tok_off.cpu().numpy(), pl.dst_tok_off)
+        assert np.array_equal(shard_tok_off.cpu().numpy(), pl.shard_tok_off)
+        assert np.array_equal(shard_mb_off.cpu().numpy(), pl.shard_mb_off)
+        assert np.array_equal(d.mb_seq_off.cpu().numpy()[:M + 1], pl.mb_seq_off)
+        assert np.array_equal(d.cu_seqlens.cpu().numpy()[: w.n_seq + M], pl.cu_seqlens)
+        shard_of = np.repeat(np.arange(P), np.diff(w.src_shard_seq_off))
+        assert np.array_equal(d.dst_tok_off.cpu().numpy()[:-1] - pl.shard_tok_off[shard_of], w.src_tok_off)
+        # a shard table without a permutation: 4 training shards of N/4 consecutive sequences, fields moved as they lie
+        prm4 = binding.make_params(w.n_seq, 4, w.token_budget)
+        sso4 = torch.arange(5, dtype=torch.int32, device=d.dev) * (w.n_seq // 4)
+        st4 = torch.zeros(5, dtype=torch.int64, device=d.dev)
+        sm4 = torch.zeros(5, dtype=torch.int32, device=d.dev)
+        binding.dc_repack(prm4, d.source, d.seq_len, None, sso4, d.moved_fields, d.capacity, d.dst_tok_off, st4, sm4,
+                          d.mb_seq_off, d.cu_seqlens, d.n_mb, ws, ws_bytes, d.status)
+        torch.cuda.synchronize()
+        assert d.read_status() == 0
+        pl4 = oracle.plan(w.seq_len, ident, sso4.cpu().numpy(), w.token_budget)
+        assert np.array_equal(d.dst_tok_off.cpu().numpy(), pl4.dst_tok_off)
+        arena = int(pl4.shard_tok_off[-1])
+        for f in w.fields:
+            want = oracle.gather(w.seq_len, ident, w.src_tok_off, w.src_shard_seq_off, f.shards, pl4.dst_tok_off, arena)
+            assert np.array_equal(d.dst_fields[f.name].cpu().numpy().view(want.dtype)[:arena], want), f.name
+    # host errors: a shard table may only be left out together with the permutation, and P must then be the
+    # number of rollout shards
+    with pytest.raises(binding.DcError) as e:
+        binding.dc_plan(prm, d.source, d.seq_len, d.perm, None, d.capacity, d.dst_tok_off, shard_tok_off, shard_mb_off,
+                        d.mb_seq_off, d.cu_seqlens, d.n_mb, ws, ws_bytes, d.status)
+    assert e.value.code == binding.DC_ERR_INVALID_ARG
+    with pytest.raises(binding.DcError) as e:
+        binding.dc_plan(prm4, d.source, d.seq_len, None, None, d.capacity, d.dst_tok_off, st4, sm4,
+                        d.mb_seq_off, d.cu_seqlens, d.n_mb, ws, ws_bytes, d.status)
+    assert e.value.code == binding.DC_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("cfg", [3, 4, 5])
+def test_repack_full_config(cfg):
+    """dc_repack itself (one call: plan, then gather) on the large configurations, every output against the oracle
+    and bit-equal to dc_plan followed by dc_gather."""
+    torch, binding, runner = _gpu()
+    w = workloads.make_workload(cfg)
+    print(f"[parity] dc_repack config {cfg}: N={w.n_seq} T={w.total_tokens}", flush=True)
+    d = runner.DeviceBatch(w, poison=True)
+    d.group_advantage(); d.balance(); d.repack()
+    torch.cuda.synchronize()
+    compare_step(d, w)
+    two = runner.DeviceBatch(w, poison=True)
+    two.step()
+    torch.cuda.synchronize()
+    assert torch.equal(d.cu_seqlens, two.cu_seqlens) and torch.equal(d.dst_tok_off, two.dst_tok_off)
+    for k, v in d.dst_fields.items():
+        assert torch.equal(v, two.dst_fields[k]), k
 
 
 # ---------------------------------------------------------------- per-token advantages made by the gather
@@ -615,7 +693,7 @@ def check_scatter(w, label=""):
     return d
 
 
-@pytest.mark.parametrize("cfg", [1, 2, 4, 5])
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
 def test_scatter_full_config(cfg):
     check_scatter(workloads.make_workload(cfg), label=f"config {cfg}")
 
@@ -654,6 +732,12 @@ def test_scatter_padded_rows_and_errors():
     d.dst_tok_off[3] = d.capacity
     d.scatter(); torch.cuda.synchronize()
     assert d.read_status() == binding.DC_ERR_OVERFLOW
+    # perm that names a sequence twice (and so another one never) is refused
+    d = runner.DeviceBatch(w)
+    d.step(); d.prepare_scatter(); torch.cuda.synchronize()
+    d.perm[5] = d.perm[9]
+    d.scatter(); torch.cuda.synchronize()
+    assert d.read_status() == binding.DC_ERR_BAD_LAYOUT
 
 
 # ---------------------------------------------------------------- PPO advantage stage (GAE)

@@ -222,3 +222,20 @@ def test_scatter_hand_example():
     arena = np.array([10, 11, 12, 20, 21], np.int32)
     out = oracle.scatter(S, [1, 0], [1, 4], [0, 2], arena, [0, 3, 5], [np.zeros(8, np.int32)])[0]
     assert out.tolist() == [0, 20, 21, 0, 10, 11, 12, 0]
+
+
+def test_gather_by_slot_ranges_equals_gather():
+    """gather_slots over disjoint slot ranges (what the benchmark's threaded CPU leg calls) fills
+    the same arena as one gather call."""
+    w = workloads.make_workload(1)
+    bal = oracle.balance(w.seq_len, w.n_shards)
+    pl = oracle.plan(w.seq_len, bal.perm, bal.shard_seq_off, w.token_budget)
+    arena = int(pl.shard_tok_off[-1])
+    for f in w.fields:
+        want = oracle.gather(w.seq_len, bal.perm, w.src_tok_off, w.src_shard_seq_off, f.shards, pl.dst_tok_off, arena)
+        got = np.zeros(arena, want.dtype)
+        cuts = [0, 1, 7, w.n_seq // 2, w.n_seq]
+        for a, b in zip(cuts[:-1], cuts[1:]):
+            oracle.gather_slots(w.seq_len, bal.perm, w.src_tok_off, w.src_shard_seq_off, f.shards, pl.dst_tok_off,
+                                got, a, b)
+        assert np.array_equal(got, want), f.name
