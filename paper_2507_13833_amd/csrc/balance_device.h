@@ -2,6 +2,7 @@
 // balance_large.hip: more sequences than the LDS holds): the workgroup's LDS layout, the stable counting
 // pass of the radix sort, and the assignment rounds.
 #pragma once
+#include <cstddef>
 #include "advantage_device.h"
 #include "dc_lanes.h"
 
@@ -19,7 +20,7 @@ constexpr int PLACE_PAD = 4 * WAVE;
 __device__ __forceinline__ int place_pitch(int C) { return C + ((2 - C) & 3); }
 
 struct BalLds {
-    int32_t  keys[DC_MAX_SEQ];            // sequence lengths (sanitised)
+    int32_t  keys[DC_MAX_SEQ + PLACE_PAD];    // sequence lengths (sanitised); packed path: the sorted items, see lpt_rounds_packed
     uint16_t idx_a[DC_MAX_SEQ + PLACE_PAD];   // sort ping
     uint16_t idx_b[DC_MAX_SEQ + PLACE_PAD];   // sort pong; after the sort the free one holds every item's place in its
                                               // partition, or (all partitions of equal size) the partitions themselves
@@ -290,6 +291,245 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, co
     return pos;
 }
 
+// ---------------------------------------------------------------------------------------------------
+// The rounds once more for the printed algorithm on 16, 32 or 64 workers (P == WIDTH, N == P * C) with
+// lengths below 2^16: the common case, and the one in which the rounds are most of the kernel's time.
+//
+// A round of one wave is the sort of the 64 updated keys, a chain of dependent instructions with idle
+// issue cycles between them, plus whatever else the round does.  Measured on the chip, vector
+// instructions placed into those idle cycles are nearly free, but every LDS instruction costs the wave
+// about 20 cycles, a scalar branch on a vector result 50 to 60 (the scalar unit waits for the vector
+// pipeline), and the loop's own branch about 40.  So this path
+//   - keeps the sorted items as ONE array of 32-bit words, length << 16 | sequence, in sorted order
+//     (items[]; built by the whole workgroup after the sort): a round reads one word per lane at an address
+//     that does not depend on anything it computes, instead of an index and then a length;
+//   - files that whole word in its worker's row (rows[k * pitch + c] = the c-th item of worker k), so that no
+//     second store per round records the worker of a sequence; the layout pass derives it from the row;
+//   - takes the worker's count from a cross-lane read only when the workers' counts differ at the phase's
+//     start (they do not unless rounds with fewer takers came before);
+//   - runs FAST_BATCH rounds as one straight piece of code without a test when a bound says that all of
+//     them will stand, and one round at a time with the exact test otherwise.
+// The bound: keys come in ascending order and items in descending order.  With D = largest - smallest key,
+// a round stands if D < its smallest item (the largest key is then below every updated key), and it leaves
+// D' <= max(D, its largest - its smallest item).  So a run of rounds stands if D < L and F - L < L, where
+// F = the first item of the run and L = its last one.  One look at 64 items (the last ones of the next 64
+// batches, one per lane) says how many batches that covers: up to 256 rounds per look.
+constexpr int FAST_BATCH = 4;
+constexpr uint32_t PACKED_MAX_LEN = 0xFFFFu;             // lengths up to this take the packed path
+
+__device__ __forceinline__ int row_pitch(int C) { return C | 1; }      // odd: the workers' rows start in different banks
+
+template <int WIDTH>
+__device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint32_t* items, int32_t max_len,
+                                                 uint32_t* rows, int pitch, uint32_t* spare_word,
+                                                 int32_t* worker_count, int64_t* __restrict__ shard_load) {
+    const uint32_t lane = threadIdx.x;
+    const uint32_t G = (uint32_t)__builtin_amdgcn_readfirstlane(max_len) << 6;    // see lpt_rounds for the rebasing
+    const uint32_t fit = (3u << 30) / max(G, 1u);
+    const int check_every = (int)min(64u, fit - 2u);
+    int until_check = 1;
+    const uint32_t full = KEY_FULL | lane;
+    const bool mine_exists = (int)lane < P;                       // lane k keeps worker k (P == WIDTH)
+    const uint64_t everyone = P == WAVE ? ~0ull : (1ull << P) - 1ull;
+    constexpr bool EVERY_LANE = WIDTH == WAVE;
+    constexpr int NS = net_steps(WIDTH);
+    constexpr uint32_t NONE = 0xFFFFFFFFu;
+    uint32_t key = (mine_exists && C > 0) ? lane : full;
+    int32_t count = 0;
+    int64_t load = 0;
+    int pos = 0;
+    uint32_t e = items[lane];                                     // the item offered to rank `lane` (the array is padded)
+    bool all_take = C > 0;
+    const uint32_t pitch4 = (uint32_t)pitch * 4u;
+    int no_look = 0, look_wait = 0;                               // tested rounds before the bound is looked at again
+    char* const rows_b = reinterpret_cast<char*>(rows);
+    char* const spare_b = reinterpret_cast<char*>(spare_word);
+
+    while (pos < N) {
+        if (all_take && pos + P <= N) {                           // uniform: every worker is open
+            int32_t cmax = mine_exists ? count : 0, cmin = mine_exists ? count : INT32_MAX;
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) {
+                cmax = max(cmax, __shfl_xor(cmax, d, WAVE));
+                cmin = min(cmin, __shfl_xor(cmin, d, WAVE));
+            }
+            const int c_hi = __builtin_amdgcn_readfirstlane(cmax), c_lo = __builtin_amdgcn_readfirstlane(cmin);
+            const bool level = c_hi == c_lo;                      // every worker holds the same number of items
+            const int64_t off = load - (int64_t)(key >> 6);       // what the key does not hold of my worker's load
+            int64_t taken = 0;                                    // load taken off the keys by rebasing in here
+            int rounds = 0;
+            uint32_t sk = wave_sort_asc<WIDTH>(key);
+            const int n_rounds = min(C - c_hi, (N - pos) / P);    // >= 1: until a worker is full or the items run out
+            const uint32_t* next_item = items + pos + P + (int)lane;       // the item of the next round for this rank
+            const int32_t count4 = count * 4;
+
+            // One round that is known to stand; r = rounds done before it in this phase.  LEVEL: all counts are c_lo.
+            auto sure_round = [&](int r, auto level_c) {
+                constexpr bool LEVEL = decltype(level_c)::value;
+                uint32_t v = sk + ((e >> 16) << 6);               // the keys after this round
+                const uint32_t id = sk & 63u;                     // the worker rank `lane` belongs to
+                uint32_t e1 = 0;
+                int32_t before4 = 0;
+                const uint32_t row_at = 4u * (uint32_t)(LEVEL ? c_lo + r : r);
+                v = wave_sort_steps<WIDTH, 0, NS>(v, [&](auto slot) {
+                    constexpr int S = decltype(slot)::value;
+                    if constexpr (S == 0) e1 = *next_item;
+                    if constexpr (S == 1 && !LEVEL) before4 = __builtin_amdgcn_ds_bpermute((int)(id << 2), count4);
+                    if constexpr (S == 3) next_item += P;
+                    if constexpr (S == 8) {
+                        char* at = rows_b + (__umul24(id, pitch4) + (uint32_t)before4 + row_at);
+                        if constexpr (!EVERY_LANE) at = mine_exists ? at : spare_b;
+                        *reinterpret_cast<uint32_t*>(at) = e;      // filed with its worker
+                    }
+                    if constexpr (S == 12) e = e1;
+                });
+                sk = v;
+            };
+            // One round with the exact test (every rank's key below the smallest updated key of the ranks before
+            // it); false, and nothing changed, if it does not stand.  The row entry is written before the outcome
+            // is known: after a refusal the general round files the worker's next item in the same place.
+            auto tested_round = [&](int r) -> bool {
+                const uint32_t sk_in = sk, e_in = e;
+                uint32_t v = sk + ((e >> 16) << 6);
+                uint32_t m = v;                                   // becomes the running minimum of the updated keys
+                const uint32_t id = sk & 63u;
+                uint32_t e1 = 0;
+                int32_t before4 = 0;
+                v = wave_sort_steps<WIDTH, 0, NS>(v, [&](auto slot) {
+                    constexpr int S = decltype(slot)::value;
+                    if constexpr (S == 0) e1 = *next_item;
+                    if constexpr (S == 1) before4 = __builtin_amdgcn_ds_bpermute((int)(id << 2), count4);
+                    if constexpr (S == 3) m = umin32(m, dpp_mov<DPP_ROW_SHR1>(NONE, m));
+                    if constexpr (S == 5) m = umin32(m, dpp_mov<DPP_ROW_SHR2>(NONE, m));
+                    if constexpr (S == 6) m = umin32(m, dpp_mov<DPP_ROW_SHR4>(NONE, m));
+                    if constexpr (S == 7) m = umin32(m, dpp_mov<DPP_ROW_SHR8>(NONE, m));
+                    if constexpr (S == 8) m = umin32(m, dpp_mov<DPP_ROW_BCAST15, 0xA>(NONE, m));
+                    if constexpr (S == 9) m = umin32(m, dpp_mov<DPP_ROW_BCAST31, 0xC>(NONE, m));
+                    if constexpr (S == 10) {
+                        char* at = rows_b + (__umul24(id, pitch4) + (uint32_t)before4 + 4u * (uint32_t)r);
+                        if constexpr (!EVERY_LANE) at = mine_exists ? at : spare_b;
+                        *reinterpret_cast<uint32_t*>(at) = e;
+                    }
+                    if constexpr (S == 11) m = dpp_mov<DPP_WAVE_SHR1>(NONE, m);
+                    if constexpr (S == 13) e = e1;
+                });
+                if (__builtin_expect((__ballot(sk_in < m) & everyone) != everyone, 0)) { e = e_in; return false; }
+                next_item += P;
+                sk = v;
+                return true;
+            };
+
+            while (rounds < n_rounds) {
+                if (--until_check <= 0) {                         // uniform; every check_every rounds or so
+                    until_check = check_every;
+                    const uint32_t min0 = (uint32_t)__builtin_amdgcn_readlane((int)sk, 0);
+                    if (min0 >= 0x40000000u && min0 < KEY_FULL) { // rebase: subtract the minimum load
+                        const uint32_t sub = min0 & ~63u;
+                        if (sk < KEY_FULL) sk -= sub;
+                        taken += (int64_t)(sub >> 6);
+                    }
+                }
+                // How many batches does the bound cover?  It asks for L > max(D / 64, F / 2) (D in key units); lane i
+                // looks at the last item of the (i + 1)-th batch from here, and the items only get shorter.
+                int sure = 0;
+                const int may = min(n_rounds - rounds, until_check) / FAST_BATCH;      // batches before the phase ends / the next check
+                if (may > 0 && --no_look < 0) {
+                    const uint32_t k_lo = (uint32_t)__builtin_amdgcn_readlane((int)sk, 0);
+                    const uint32_t k_hi = (uint32_t)__builtin_amdgcn_readlane((int)sk, WIDTH - 1);
+                    const uint32_t first = (uint32_t)__builtin_amdgcn_readlane((int)e, 0) >> 16;
+                    const uint32_t need = max((k_hi - k_lo) >> 6, first >> 1);
+                    const uint32_t probe = items[min(pos + ((int)lane + 1) * (FAST_BATCH * P) - 1, N - 1)] >> 16;
+                    const uint64_t good = __ballot((int)lane < may && probe > need);
+                    sure = (~good == 0ull) ? WAVE : (__ffsll((long long)~good) - 1);
+                    // a look costs about half a round: where the bound does not hold (one worker far above the
+                    // others, as after a very long sequence) the next look waits, longer every time
+                    look_wait = sure > 0 ? 0 : min(2 * look_wait + 2, 32);
+                    no_look = look_wait;
+                }
+                if (sure > 0) {
+                    if (level) {
+                        for (int b = 0; b < sure; ++b) {
+#pragma unroll
+                            for (int u = 0; u < FAST_BATCH; ++u) sure_round(rounds + u, std::true_type{});
+                            rounds += FAST_BATCH;
+                        }
+                    } else {
+                        for (int b = 0; b < sure; ++b) {
+#pragma unroll
+                            for (int u = 0; u < FAST_BATCH; ++u) sure_round(rounds + u, std::false_type{});
+                            rounds += FAST_BATCH;
+                        }
+                    }
+                    until_check -= sure * FAST_BATCH - 1;
+                    pos += sure * FAST_BATCH * P;
+                } else {
+                    // rounds with the exact test, in a loop of their own, until the next look or check
+                    int burst = max(1, min(min(n_rounds - rounds, until_check), no_look + 1));
+                    const int want = burst;
+                    bool stands = true;
+                    do {
+                        stands = tested_round(rounds);
+                        if (!stands) break;
+                        pos += P;
+                        rounds += 1;
+                    } while (--burst > 0);
+                    until_check -= (want - burst) - 1;            // (one was taken off at the loop's top)
+                    no_look -= want - burst;
+                    if (!stands) break;
+                }
+            }
+            // back to worker lanes: rank r sends its key to lane (sk & 63); lanes without a worker send theirs to themselves
+            if (!mine_exists) sk = full;                          // (whatever the rounds left in their lanes)
+            key = (uint32_t)__builtin_amdgcn_ds_permute((int)((sk & 63u) << 2), (int)sk);
+            if (mine_exists) {
+                count += rounds;
+                load = off + taken + (int64_t)(key >> 6);
+                if (count == C) key = full;
+            }
+            until_check = 1;
+            all_take = false;
+            if (rounds > 0) continue;                             // else: the general round below decides exactly
+        }
+
+        // ---- a general round: the longest accepted prefix of the ranks takes one item each ----
+        const int t = pos + (int)lane;
+        uint32_t sk = wave_sort_asc<WIDTH>(key);                  // lane r: r-th smallest key
+        if (--until_check <= 0) {                                 // uniform
+            until_check = check_every;
+            const uint32_t min0 = (uint32_t)__builtin_amdgcn_readlane((int)sk, 0);
+            if (min0 >= 0x40000000u && min0 < KEY_FULL) {         // rebase: subtract the minimum load
+                const uint32_t sub = min0 & ~63u;
+                if (key < KEY_FULL) key -= sub;
+                if (sk < KEY_FULL) sk -= sub;
+            }
+        }
+        const bool valid = sk < KEY_FULL && t < N;
+        const uint32_t newk = valid ? sk + ((e >> 16) << 6) : 0xFFFFFFFFu;
+        const uint32_t pm = wave_excl_scan_umin(newk);            // smallest updated key among ranks below mine
+        const uint64_t acc = __ballot(valid && sk < pm);
+        const int m = (~acc == 0ull) ? WAVE : (__ffsll((long long)~acc) - 1);   // accepted prefix
+        if (m == 0) break;                                        // cannot happen: C * P == N
+        // back to worker lanes: rank r sends its updated key, its own rank in place of the worker id,
+        // to lane (sk & 63)
+        const uint32_t recv = (uint32_t)__builtin_amdgcn_ds_permute((int)((sk & 63u) << 2), (int)((newk & ~63u) | lane));
+        const uint32_t thr = (uint32_t)__builtin_amdgcn_readlane((int)sk, m - 1);
+        const uint32_t next_e = items[t + m];                     // next round's item (padded array)
+        if (key <= thr) {                                         // my worker is among the m smallest
+            const uint32_t nk = (recv & ~63u) | lane;
+            rows[(int)lane * pitch + count] = items[pos + (int)(recv & 63u)];     // the item I took
+            load += (int64_t)((nk - key) >> 6);
+            count += 1;
+            key = (count == C) ? full : nk;
+        }
+        pos += m;
+        e = next_e;
+        all_take = __ballot(mine_exists && key >= KEY_FULL) == 0ull;      // every worker is open: the next round is tried above
+    }
+    if (mine_exists) shard_load[lane] = load;
+    worker_count[lane] = count;
+    return pos;
+}
+
 // The same rounds for 64 < P <= DC_MAX_SHARDS workers, run by the whole workgroup: thread k keeps
 // worker k (64-bit key load << 10 | k, all-ones-ish when full or absent), thread r also plays
 // rank r of the sorted order.  Every thread of the workgroup must call it (barriers inside).
@@ -413,12 +653,18 @@ __device__ __forceinline__ void balance_body(BalLds& L, int32_t N, int32_t P, in
 
     // ---- load lengths, range ----
     int32_t mx = 0, mn = INT32_MAX;
-    for (int i = tid; i < N; i += BAL_BLOCK) {
-        int32_t s = seq_len[i];
-        if (s <= 0 || s > DC_MAX_SEQ_LEN) { set_status(status, DC_ERR_ZERO_LENGTH_SEQ); s = 1; }
-        L.keys[i] = s;
-        mx = max(mx, s);
-        mn = min(mn, s);
+    int32_t mine_len[BAL_ROUNDS];
+#pragma unroll
+    for (int q = 0; q < BAL_ROUNDS; ++q) {
+        const int i = q * BAL_BLOCK + tid;
+        mine_len[q] = 1;
+        if (i < N) {
+            int32_t s = seq_len[i];
+            if (s <= 0 || s > DC_MAX_SEQ_LEN) { set_status(status, DC_ERR_ZERO_LENGTH_SEQ); s = 1; }
+            mine_len[q] = s;
+            mx = max(mx, s);
+            mn = min(mn, s);
+        }
     }
     for (int d = 32; d >= 1; d >>= 1) {
         mx = max(mx, __shfl_xor(mx, d, WAVE));
@@ -431,9 +677,75 @@ __device__ __forceinline__ void balance_body(BalLds& L, int32_t N, int32_t P, in
     const uint32_t range = N > 0 ? (uint32_t)(mx - mn) : 0u;
     const int nbits = 32 - __clz(range | 1u);
     const int passes = range == 0 ? 0 : (nbits + 7) / 8;
-
-    // ---- a) radix sort of indices by (mx - len) ascending, stable ----
     const int rounds = (N + BAL_BLOCK - 1) / BAL_BLOCK;           // <= BAL_ROUNDS
+    // every partition ends with exactly C items (Algorithm 1 as printed: C = N / K): rows per worker
+    const int pitch = (P <= WAVE && C > 0 && (int64_t)P * C == N) ? place_pitch(C) : 0;
+    int32_t* part_off = reinterpret_cast<int32_t*>(L.cnt) + PART_OFF_AT;
+    int32_t* placed = reinterpret_cast<int32_t*>(L.cnt) + PLACED_AT;
+    const bool tight = pitch != 0 && (P == 16 || P == 32 || P == 64);
+
+    // ---- the printed algorithm on 16, 32 or 64 workers with lengths below 2^16 (lpt_rounds_packed) ----
+    // One word per sequence, length << 16 | index, is all that is kept: the sort moves those words between
+    // the two halves of the LDS (a pass takes its digit from the word it moves, not from a table of lengths),
+    // the rounds read them in sorted order, and the half the sort ends in leaves the other one to the workers'
+    // rows.
+    if (tight && (uint32_t)mx <= PACKED_MAX_LEN) {                // (uniform)
+        static_assert(offsetof(BalLds, idx_b) == offsetof(BalLds, idx_a) + sizeof(uint16_t) * (DC_MAX_SEQ + PLACE_PAD) &&
+                      offsetof(BalLds, idx_a) % 4 == 0, "the two index arrays are one run of words");
+        uint32_t* src = reinterpret_cast<uint32_t*>(L.keys);      // DC_MAX_SEQ + PLACE_PAD words each
+        uint32_t* dst = reinterpret_cast<uint32_t*>(L.idx_a);
+#pragma unroll
+        for (int q = 0; q < BAL_ROUNDS; ++q) {
+            const int i = q * BAL_BLOCK + tid;
+            if (i < N) src[i] = ((uint32_t)mine_len[q] << 16) | (uint32_t)i;
+        }
+        __syncthreads();
+        for (int pass = 0; pass < passes; ++pass) {
+            const int shift = pass * 8;
+            counting_pass(L, N, rounds,
+                          [&](int pos) { return ((uint32_t)mx - (src[pos] >> 16)) >> shift; },
+                          [&](int pos, int out) { dst[out] = src[pos]; });
+            uint32_t* t = src; src = dst; dst = t;
+        }
+        uint32_t* const items = src;                              // I of Algorithm 1, each entry with its length
+        uint32_t* const rows = dst;
+        if (tid < PLACE_PAD) items[N + tid] = 0;                  // the rounds read a little beyond the last item
+        __syncthreads();
+        const int rpitch = row_pitch(C);
+        if (w == 0) {
+            int32_t* worker_count = reinterpret_cast<int32_t*>(L.cnt) + WCOUNT_AT;
+            uint32_t* spare = reinterpret_cast<uint32_t*>(L.spare);
+            int n_placed;
+            if (P == 16) n_placed = lpt_rounds_packed<16>(N, P, C, items, mx, rows, rpitch, spare, worker_count, shard_load);
+            else if (P == 32) n_placed = lpt_rounds_packed<32>(N, P, C, items, mx, rows, rpitch, spare, worker_count, shard_load);
+            else n_placed = lpt_rounds_packed<64>(N, P, C, items, mx, rows, rpitch, spare, worker_count, shard_load);
+            const int32_t c = worker_count[lane];
+            const int32_t inc = (int32_t)wave_incl_scan_add_u32((uint32_t)c);
+            if (lane < P) shard_seq_off[lane] = inc - c;
+            if (lane == 0) { shard_seq_off[P] = N; *placed = n_placed; }
+        }
+        __syncthreads();
+        // ---- P_0, P_1, ... are the rows; the worker of a sequence is the row it stands in ----
+        // (gathered by sequence in the LDS, where the sorted items were, so that both outputs leave in index
+        // order: 16 384 scattered 4-byte stores take longer to drain than the rounds save)
+        uint32_t* const worker_of = items;
+        for (int q = tid; q < N; q += BAL_BLOCK) {
+            const int k = q / C;
+            const uint32_t u = min(rows[k * rpitch + (q - k * C)] & 0xFFFFu, (uint32_t)(N - 1));   // (no index leaves the
+            perm[q] = (int32_t)u;                                                                  //  arrays whatever a word holds)
+            worker_of[u] = (uint32_t)k;
+        }
+        __syncthreads();
+        for (int i = tid; i < N; i += BAL_BLOCK) shard_of_seq[i] = (int32_t)worker_of[i];
+        return;
+    }
+
+#pragma unroll
+    for (int q = 0; q < BAL_ROUNDS; ++q) {
+        const int i = q * BAL_BLOCK + tid;
+        if (i < N) L.keys[i] = mine_len[q];
+    }
+    // ---- a) radix sort of indices by (mx - len) ascending, stable ----
     for (int i = tid; i < N; i += BAL_BLOCK) L.idx_a[i] = (uint16_t)i;
     uint16_t* src = L.idx_a;
     uint16_t* dst = L.idx_b;
@@ -447,11 +759,6 @@ __device__ __forceinline__ void balance_body(BalLds& L, int32_t N, int32_t P, in
     }
     const uint16_t* sorted = src;                                 // I of Algorithm 1
     uint16_t* step_slot = dst;                                    // place of I[t] inside its worker's partition
-    // every partition ends with exactly C items (Algorithm 1 as printed: C = N / K): rows per worker
-    const int pitch = (P <= WAVE && C > 0 && (int64_t)P * C == N) ? place_pitch(C) : 0;
-    int32_t* part_off = reinterpret_cast<int32_t*>(L.cnt) + PART_OFF_AT;
-    int32_t* placed = reinterpret_cast<int32_t*>(L.cnt) + PLACED_AT;
-
     // ---- b) assignment rounds: wave 0 for up to 64 workers, else the whole workgroup ----
     if (P > WAVE) {
         const int n_placed = lpt_rounds_wide(L, N, P, C, sorted, step_slot, shard_seq_off, shard_load);
@@ -461,7 +768,6 @@ __device__ __forceinline__ void balance_body(BalLds& L, int32_t N, int32_t P, in
         int32_t* spare = L.spare;
         LptCarry fresh = lpt_fresh(P, C);
         int n_placed;
-        const bool tight = pitch != 0 && (P == 16 || P == 32 || P == 64);
         if (tight && P == 16) n_placed = lpt_rounds<16, true>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
         else if (tight && P == 32) n_placed = lpt_rounds<32, true>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
         else if (tight) n_placed = lpt_rounds<64, true>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);

@@ -4,6 +4,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace dc {
 
@@ -129,6 +130,70 @@ template <int WIDTH>
 __device__ __forceinline__ uint32_t wave_sort_back(uint32_t v, uint32_t after) {
     v = bitonic_step<WIDTH, WIDTH / 2, true>(v, after);
     return bitonic_merge<WIDTH, WIDTH / 4>(v);
+}
+
+// The same network one compare-exchange at a time, so that a caller can place other work between the
+// steps.  Step i of the sort of WIDTH lanes is (net_k(i), net_j(i)): merge size and partner distance.
+constexpr int net_steps(int width) {
+    int n = 0;
+    for (int k = 2; k <= width; k <<= 1)
+        for (int j = k >> 1; j >= 1; j >>= 1) ++n;
+    return n;
+}
+constexpr int net_k(int i) {
+    for (int k = 2;; k <<= 1)
+        for (int j = k >> 1; j >= 1; j >>= 1)
+            if (i-- == 0) return k;
+}
+constexpr int net_j(int i) {
+    for (int k = 2;; k <<= 1)
+        for (int j = k >> 1; j >= 1; j >>= 1)
+            if (i-- == 0) return j;
+}
+struct XchgPair { uint32_t a, b; };       // a lane's key and its partner's, in either order
+// First half of a step: fetch the partner's key (the cross-lane move).
+template <int J>
+__device__ __forceinline__ XchgPair xchg_fetch(uint32_t v) {
+    XchgPair x;
+    if constexpr (J == 16) {
+        auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+        x.a = r[0]; x.b = r[1];
+    } else if constexpr (J == 32) {
+        auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+        x.a = r[0]; x.b = r[1];
+    } else {
+        x.a = v; x.b = lane_xor<J>(v);
+    }
+    return x;
+}
+// Second half: keep the smaller or the larger of the two (see bitonic_step).
+template <int K, int J>
+__device__ __forceinline__ uint32_t xchg_keep(XchgPair x) {
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t pick = ((lane & J) == 0) == ((lane & K) == 0) ? 0u : 0xFFFFFFFFu;
+    return umed3(x.a, x.b, pick);
+}
+
+// Steps [FROM, TO) of the sort of WIDTH lanes.  side(slot) is called twice per step, with the compile-time
+// slot numbers 2 i (between the fetch and the keep of step i) and 2 i + 1 (behind the keep); what it does
+// there is issued in the idle cycles between the step's two dependent instructions and must not depend
+// on the sort.  The scheduler is told to leave that order alone.
+template <int WIDTH, int FROM, int TO, typename Side>
+__device__ __forceinline__ uint32_t wave_sort_steps(uint32_t v, Side&& side) {
+    if constexpr (FROM < TO) {
+        constexpr int K = net_k(FROM), J = net_j(FROM);
+        const XchgPair x = xchg_fetch<J>(v);
+        __builtin_amdgcn_sched_barrier(0);
+        side(std::integral_constant<int, 2 * FROM>{});
+        __builtin_amdgcn_sched_barrier(0);
+        v = xchg_keep<K, J>(x);
+        __builtin_amdgcn_sched_barrier(0);
+        side(std::integral_constant<int, 2 * FROM + 1>{});
+        __builtin_amdgcn_sched_barrier(0);
+        return wave_sort_steps<WIDTH, FROM + 1, TO>(v, side);
+    } else {
+        return v;
+    }
 }
 
 __device__ __forceinline__ uint32_t umin32(uint32_t a, uint32_t b) { return a < b ? a : b; }
