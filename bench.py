@@ -2,8 +2,8 @@
 """Benchmark of the Data Coordinator reshard path on one MI355X.
 
 A step is one pass of the whole path over one synthetic rollout batch already resident in
-HBM: dc_balance and dc_group_advantage (one launch: dc_balance_group_advantage), dc_plan,
-dc_gather, all on one stream.
+HBM, on one stream: dc_balance_plan_group_advantage (Algorithm 1, the advantage stage and the plan:
+two launches), then dc_gather.  (--three-calls: dc_balance_group_advantage, dc_plan, dc_gather.)
 Prints ONE JSON line.  Its headline is workload config 5 (the largest): repacked tokens/s for the
 whole step, the gather kernel's achieved HBM bandwidth against the chip's peak (HIP events around
 every gather launch of the timed region, on the stream it is launched on; mean, median and
@@ -146,6 +146,9 @@ def main() -> int:
     ap.add_argument("--sets", type=int, default=3, help="rotating buffer sets (defeats cache reuse)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sides", action="store_true", help="skip every side measurement (profiling runs)")
+    ap.add_argument("--three-calls", action="store_true",
+                    help="dc_balance_group_advantage, dc_plan, dc_gather (five launches) in place of "
+                         "dc_balance_plan_group_advantage, dc_gather (three)")
     ap.add_argument("--single-stream", action="store_true", help="issue the four calls one after the other on one stream")
     ap.add_argument("--two-streams", action="store_true",
                     help="dc_group_advantage on a second stream beside dc_balance + dc_plan (two cross-stream waits per step)")
@@ -181,10 +184,13 @@ def main() -> int:
                 ev[1].record()
         elif args.two_streams:
             b.step_overlapped(ev)
-        elif args.no_rollout_adv:
-            b.step_no_rollout_adv(ev)
+        elif args.three_calls:
+            if args.no_rollout_adv:
+                b.step_no_rollout_adv(ev)
+            else:
+                b.step_fused(ev)
         else:
-            b.step_fused(ev)
+            b.step_two_calls(ev, per_token=not args.no_rollout_adv)
 
     def timed_steps(w, sets, steps, warmup):
         """warmup untimed steps, then `steps` steps between two synchronisations.  Returns wall ms per
@@ -224,7 +230,7 @@ def main() -> int:
 
     # ---- the other configurations first (their buffers are released before the headline run) ----
     if args.other_configs is None:
-        others = [3, 4] if args.config == 5 and not (args.single_stream or args.two_streams) else []
+        others = [3, 4] if args.config == 5 and not (args.single_stream or args.two_streams or args.three_calls) else []
     elif args.other_configs.strip().lower() in ("", "none"):
         others = []
     else:
@@ -277,18 +283,21 @@ def main() -> int:
     # (a shorter run of its own, outside the timed region)
     if sides and not (args.no_rollout_adv or args.single_stream or args.two_streams):
         n_var = max(2, min(args.steps, 60))
+        var_step = (lambda b, ev=None: b.step_no_rollout_adv(ev)) if args.three_calls else \
+                   (lambda b, ev=None: b.step_two_calls(ev, per_token=False))
         for i in range(3):
-            sets[i % len(sets)].step_no_rollout_adv()
+            var_step(sets[i % len(sets)])
         evv = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_var)]
         torch.cuda.synchronize()
         v0 = time.perf_counter()
         for i in range(n_var):
-            sets[i % len(sets)].step_no_rollout_adv(evv[i])
+            var_step(sets[i % len(sets)], evv[i])
         torch.cuda.synchronize()
         v_ms = (time.perf_counter() - v0) * 1e3 / n_var
         vg = stats_ms([a.elapsed_time(b) for a, b in evv])
         assert all(s.read_status() == 0 for s in sets)
-        variant = {"calls": "dc_balance_group_advantage (adv_seq only), dc_plan, dc_gather_advantage",
+        variant = {"calls": ("dc_balance_group_advantage (adv_seq only), dc_plan, dc_gather_advantage" if args.three_calls
+                             else "dc_balance_plan_group_advantage (adv_seq only), dc_gather_advantage"),
                    "steps": n_var, "ms_per_step": round(v_ms, 4), "tokens_per_s": T / (v_ms * 1e-3),
                    "gather_ms": round(vg["mean"], 4), "gather_ms_median": round(vg["median"], 4),
                    "gather_ms_min": round(vg["min"], 4), "algorithmic_bytes": gather_adv_bytes,
@@ -313,6 +322,9 @@ def main() -> int:
         st = device_ms(lambda b: b.balance_group_advantage())
         stage["balance_group_advantage_ms"] = round(st["median"], 4)
         stage["balance_group_advantage_ms_min"] = round(st["min"], 4)
+        st = device_ms(lambda b: b.balance_plan_group_advantage())
+        stage["balance_plan_group_advantage_ms"] = round(st["median"], 4)
+        stage["balance_plan_group_advantage_ms_min"] = round(st["min"], 4)
         stage["group_advantage_algorithmic_bytes"] = 5 * T       # 1 B mask read + 4 B advantage written per token
 
         # the reverse path (training layout -> rollout layout), whole dc_scatter call
@@ -352,11 +364,11 @@ def main() -> int:
                 with torch.cuda.stream(side_s):
                     consume(prev)
                     ev_cons.record(side_s)
-                cur.step_fused()
+                cur.step_two_calls()
                 main_s.wait_event(ev_cons)
             else:
                 consume(prev)
-                cur.step_fused()
+                cur.step_two_calls()
 
         res = {}
         for tag, overlap in (("serial_ms", False), ("overlapped_ms", True)):
@@ -416,8 +428,11 @@ def main() -> int:
                    "buffer_sets": len(sets),
                    "streams": 2 if args.two_streams else 1,
                    "launches": "separate" if (args.single_stream or args.two_streams)
-                               else ("dc_balance_group_advantage (adv_seq only), dc_plan, dc_gather_advantage"
-                                     if args.no_rollout_adv else "dc_balance_group_advantage, dc_plan, dc_gather")},
+                               else (("dc_balance_group_advantage (adv_seq only), dc_plan, dc_gather_advantage"
+                                      if args.no_rollout_adv else "dc_balance_group_advantage, dc_plan, dc_gather")
+                                     if args.three_calls else
+                                     ("dc_balance_plan_group_advantage (adv_seq only), dc_gather_advantage"
+                                      if args.no_rollout_adv else "dc_balance_plan_group_advantage, dc_gather"))},
         "roofline": {"bound": "hbm", "kernel": "gather_adv_kernel" if args.no_rollout_adv else "gather_kernel",
                      "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

@@ -192,6 +192,26 @@ dc_status dc_balance_group_advantage(const dc_params* prm, const dc_source* src,
                                      float* const* adv_tok_src_base, int32_t* d_status, void* hip_stream);
 
 /*
+ * dc_balance_group_advantage followed by dc_plan, with fewer launches (same arguments as the two calls,
+ * same results, same device errors, every argument checked before anything is enqueued): the three
+ * steps that come before the data movement in the re-partitioning of Sec. 6 - Algorithm 1 ("Load
+ * Balancing"), the advantage stage, and the layout the "Distributed Databuffer" redistributes into.
+ * With Algorithm 1 as printed (cap = 0 or cap * P = N) on 16, 32 or 64 shards and up to DC_MAX_SEQ
+ * sequences, the plan runs as the tail of the workgroup that balances: that workgroup holds every output
+ * slot's sequence and length when it is done, which is all the plan reads.  Two launches instead of
+ * five; dc_gather (or dc_gather_advantage) follows as after dc_plan.  Other shapes: the two calls one after
+ * the other.
+ */
+dc_status dc_balance_plan_group_advantage(const dc_params* prm, const dc_source* src, const int32_t* d_seq_len,
+                                          int32_t* d_perm, int32_t* d_shard_seq_off, int32_t* d_shard_of_seq,
+                                          int64_t* d_shard_load, const float* d_reward, const int32_t* d_group_off,
+                                          int32_t n_groups, const uint8_t* const* mask_src_base, float* d_adv_seq,
+                                          float* const* adv_tok_src_base, int64_t dst_capacity_tokens,
+                                          int64_t* d_dst_tok_off, int64_t* d_shard_tok_off, int32_t* d_shard_mb_off,
+                                          int32_t* d_mb_seq_off, int32_t* d_cu_seqlens, int32_t* d_n_mb,
+                                          void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream);
+
+/*
  * Generalized advantage estimation (Schulman et al. 2016, arXiv 1506.02438, eqs. 11-16): the
  * advantage stage of PPO (Sec. 7.1 evaluates PPO with a critic; App. B Table 2 "advantage"), per
  * token, in the rollout layout.  With t_1 < ... < t_m the tokens of sequence i whose mask byte is

@@ -34,7 +34,7 @@ DC_ERR_BAD_LAYOUT = 9
 
 EXPORTS = ("dc_workspace_bytes", "dc_balance", "dc_group_advantage", "dc_plan", "dc_gather",
            "dc_repack", "dc_scatter_workspace_bytes", "dc_scatter", "dc_gae", "dc_balance_group_advantage",
-           "dc_gather_advantage", "dc_balance_workspace_bytes", "dc_balance_ws", "dc_repack_noalloc", "dc_strerror")
+           "dc_gather_advantage", "dc_balance_workspace_bytes", "dc_balance_ws", "dc_repack_noalloc", "dc_balance_plan_group_advantage", "dc_strerror")
 
 
 class dc_params(C.Structure):
@@ -114,6 +114,10 @@ def load() -> C.CDLL:
         lib.dc_balance_group_advantage.restype = C.c_int
         lib.dc_balance_group_advantage.argtypes = [C.POINTER(dc_params), C.POINTER(dc_source), vp, vp, vp, vp, vp, vp, vp,
                                                    C.c_int32, C.POINTER(vp), vp, C.POINTER(vp), vp, vp]
+        lib.dc_balance_plan_group_advantage.restype = C.c_int
+        lib.dc_balance_plan_group_advantage.argtypes = [C.POINTER(dc_params), C.POINTER(dc_source), vp, vp, vp, vp, vp, vp, vp,
+                                                        C.c_int32, C.POINTER(vp), vp, C.POINTER(vp), C.c_int64,
+                                                        vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp, vp]
         _lib = lib
     return _lib
 
@@ -306,3 +310,20 @@ def dc_balance_group_advantage(prm: dc_params, src: Source, d_seq_len, d_perm, d
         C.cast(m, C.POINTER(C.c_void_p)) if m is not None else None, _ptr(d_adv_seq),
         C.cast(a, C.POINTER(C.c_void_p)) if a is not None else None, _ptr(d_status), _stream(stream)),
         "dc_balance_group_advantage")
+
+
+def dc_balance_plan_group_advantage(prm: dc_params, src: Source, d_seq_len, d_perm, d_shard_seq_off, d_shard_of_seq,
+                                    d_shard_load, d_reward, d_group_off, n_groups: int, mask_src: Optional[Sequence],
+                                    d_adv_seq, adv_tok_src: Optional[Sequence], dst_capacity_tokens: int, d_dst_tok_off,
+                                    d_shard_tok_off, d_shard_mb_off, d_mb_seq_off, d_cu_seqlens, d_n_mb, d_ws,
+                                    ws_bytes: int, d_status, stream=None) -> None:
+    m = _ptr_array(mask_src) if mask_src is not None else None
+    a = _ptr_array(adv_tok_src) if adv_tok_src is not None else None
+    _check(load().dc_balance_plan_group_advantage(
+        C.byref(prm), C.byref(src.struct), _ptr(d_seq_len), _ptr(d_perm), _ptr(d_shard_seq_off), _ptr(d_shard_of_seq),
+        _ptr(d_shard_load), _ptr(d_reward), _ptr(d_group_off), int(n_groups),
+        C.cast(m, C.POINTER(C.c_void_p)) if m is not None else None, _ptr(d_adv_seq),
+        C.cast(a, C.POINTER(C.c_void_p)) if a is not None else None, int(dst_capacity_tokens), _ptr(d_dst_tok_off),
+        _ptr(d_shard_tok_off), _ptr(d_shard_mb_off), _ptr(d_mb_seq_off), _ptr(d_cu_seqlens), _ptr(d_n_mb),
+        _ptr(d_ws), int(ws_bytes), _ptr(d_status), _stream(stream)),
+        "dc_balance_plan_group_advantage")

@@ -212,6 +212,52 @@ dc_status dc_balance_group_advantage(const dc_params* prm, const dc_source* src,
     return e == hipSuccess ? DC_OK : DC_ERR_HIP;
 }
 
+dc_status dc_balance_plan_group_advantage(const dc_params* prm, const dc_source* src, const int32_t* d_seq_len,
+                                          int32_t* d_perm, int32_t* d_shard_seq_off, int32_t* d_shard_of_seq,
+                                          int64_t* d_shard_load, const float* d_reward, const int32_t* d_group_off,
+                                          int32_t n_groups, const uint8_t* const* mask_src_base, float* d_adv_seq,
+                                          float* const* adv_tok_src_base, int64_t dst_capacity_tokens,
+                                          int64_t* d_dst_tok_off, int64_t* d_shard_tok_off, int32_t* d_shard_mb_off,
+                                          int32_t* d_mb_seq_off, int32_t* d_cu_seqlens, int32_t* d_n_mb,
+                                          void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream) {
+    // every argument is checked before anything is enqueued
+    int32_t cap_eff;
+    dc_status rc = check_balance(prm, d_seq_len, d_perm, d_shard_seq_off, d_shard_of_seq, d_shard_load, &cap_eff);
+    if (rc != DC_OK) return rc;
+    SourceDesc sd;
+    rc = check_advantage(prm, src, d_seq_len, d_reward, d_group_off, n_groups, mask_src_base, d_adv_seq,
+                         adv_tok_src_base, &sd);
+    if (rc != DC_OK) return rc;
+    if (dst_capacity_tokens < 0) return DC_ERR_INVALID_ARG;
+    if (!d_dst_tok_off || !d_shard_tok_off || !d_shard_mb_off || !d_mb_seq_off || !d_n_mb || !d_ws) return DC_ERR_INVALID_ARG;
+    if (prm->n_seq > 0 && !d_cu_seqlens) return DC_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(d_ws) & 255u) return DC_ERR_INVALID_ARG;
+    Workspace ws = carve_workspace(d_ws, prm->n_seq, dst_capacity_tokens);
+    if (ws_bytes < ws.bytes) return DC_ERR_WORKSPACE;
+    if (ws.n_gran > 0x7FFFFFFFLL) return DC_ERR_UNSUPPORTED_SIZE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    // the printed algorithm on 16, 32 or 64 workers: the plan runs as the tail of the balance workgroup
+    const bool one_launch = prm->n_seq > 0 && (prm->n_shards == 16 || prm->n_shards == 32 || prm->n_shards == 64) &&
+                            (int64_t)cap_eff * prm->n_shards == prm->n_seq;
+    if (!one_launch) {
+        rc = dc_balance_group_advantage(prm, src, d_seq_len, d_perm, d_shard_seq_off, d_shard_of_seq, d_shard_load, d_reward,
+                                        d_group_off, n_groups, mask_src_base, d_adv_seq, adv_tok_src_base, d_status, hip_stream);
+        if (rc != DC_OK) return rc;
+        return dc_plan(prm, src, d_seq_len, d_perm, d_shard_seq_off, dst_capacity_tokens, d_dst_tok_off, d_shard_tok_off,
+                       d_shard_mb_off, d_mb_seq_off, d_cu_seqlens, d_n_mb, d_ws, ws_bytes, d_status, hip_stream);
+    }
+    const AdvArgs adv = make_adv_args(prm->n_seq, sd, src->d_src_tok_off, d_seq_len, d_reward, d_group_off, n_groups,
+                                      prm->eps, prm->ddof, mask_src_base, d_adv_seq, adv_tok_src_base, d_status);
+    const PlanArgs plan = make_plan_args(*prm, src->d_src_tok_off, d_seq_len, d_perm, d_shard_seq_off, dst_capacity_tokens,
+                                         d_dst_tok_off, d_shard_tok_off, d_shard_mb_off, d_mb_seq_off, d_cu_seqlens, d_n_mb,
+                                         ws, d_status);
+    hipError_t e = launch_balance_plan_advantage(prm->n_seq, prm->n_shards, cap_eff, d_seq_len, d_perm, d_shard_seq_off,
+                                                 d_shard_of_seq, d_shard_load, plan, adv, sd, n_groups, d_status, st);
+    if (e != hipSuccess) return DC_ERR_HIP;
+    e = launch_records_slots(plan, sd, ws, st);
+    return e == hipSuccess ? DC_OK : DC_ERR_HIP;
+}
+
 dc_status dc_gae(const dc_params* prm, const dc_source* src, const int32_t* d_seq_len, const float* d_reward,
                  const float* const* value_src_base, const uint8_t* const* mask_src_base,
                  const float* const* logp_src_base, const float* const* ref_logp_src_base,

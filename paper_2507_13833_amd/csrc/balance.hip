@@ -30,6 +30,7 @@
 //      every P_k ends with C items, the items are filed per worker as they are placed, and both
 //      outputs are written in index order.
 #include "balance_device.h"
+#include "plan_device.h"
 
 namespace dc {
 
@@ -69,6 +70,31 @@ __global__ __launch_bounds__(BAL_BLOCK) void balance_advantage_kernel(BalanceArg
         advantage_wave(a, sd, (int64_t)(blockIdx.x - 1) * BAL_WAVES + __builtin_amdgcn_readfirstlane((int)(threadIdx.x / WAVE)));
 }
 
+// The same launch with the plan of the packed training layout as the tail of the balance workgroup: when
+// Algorithm 1 is done the workgroup holds every output slot's sequence and length, which is all the plan
+// reads, so the plan's own launch, the gathers of lengths through perm in front of it (slots_kernel) and
+// its permutation check fall away.  The LDS is Algorithm 1's first and the plan's afterwards.
+static_assert(BAL_BLOCK == PLAN_BLOCK && BAL_ROUNDS == PLAN_IPT, "one lane handles the same slots in both");
+constexpr size_t BAL_PLAN_LDS = sizeof(BalLds) > sizeof(PlanLds) ? sizeof(BalLds) : sizeof(PlanLds);
+
+__global__ __launch_bounds__(BAL_BLOCK) void balance_plan_advantage_kernel(BalanceArgs b, PlanArgs p, AdvArgs a, SourceDesc sd) {
+    __shared__ __align__(16) unsigned char lds[BAL_PLAN_LDS];
+    if (blockIdx.x != 0) {
+        advantage_wave(a, sd, (int64_t)(blockIdx.x - 1) * BAL_WAVES + __builtin_amdgcn_readfirstlane((int)(threadIdx.x / WAVE)));
+        return;
+    }
+    SlotRegs s;
+    balance_body(*reinterpret_cast<BalLds*>(lds), b.N, b.P, b.C, b.seq_len, b.perm, b.shard_seq_off, b.shard_of_seq,
+                 b.shard_load, b.status, &s);
+#pragma unroll
+    for (int q = 0; q < PLAN_IPT; ++q) {                          // the slots' lengths, for the launch that builds the granule tables
+        const int j = q * PLAN_BLOCK + (int)threadIdx.x;
+        if (j < b.N) p.slot_len[j] = s.len[q];
+    }
+    __syncthreads();                                              // Algorithm 1's tables have been read for the last time
+    plan_body(*reinterpret_cast<PlanLds*>(lds), p, s.seq, s.len, false, b.C);
+}
+
 hipError_t launch_balance(int32_t n_seq, int32_t n_shards, int32_t cap_eff, const int32_t* d_seq_len,
                           int32_t* d_perm, int32_t* d_shard_seq_off, int32_t* d_shard_of_seq,
                           int64_t* d_shard_load, int32_t* d_status, hipStream_t st) {
@@ -86,6 +112,20 @@ hipError_t launch_balance_advantage(int32_t n_seq, int32_t n_shards, int32_t cap
     b.shard_seq_off = d_shard_seq_off; b.shard_of_seq = d_shard_of_seq; b.shard_load = d_shard_load; b.status = d_status;
     const int64_t grid = 1 + (adv_waves(n_seq, n_groups) + BAL_WAVES - 1) / BAL_WAVES;
     hipLaunchKernelGGL(balance_advantage_kernel, dim3((unsigned)grid), dim3(BAL_BLOCK), 0, st, b, adv, src);
+    return hipGetLastError();
+}
+
+hipError_t launch_balance_plan_advantage(int32_t n_seq, int32_t n_shards, int32_t cap_eff, const int32_t* d_seq_len,
+                                         int32_t* d_perm, int32_t* d_shard_seq_off, int32_t* d_shard_of_seq,
+                                         int64_t* d_shard_load, const PlanArgs& plan, const AdvArgs& adv,
+                                         const SourceDesc& src, int32_t n_groups, int32_t* d_status, hipStream_t st) {
+    if (!(n_shards == 16 || n_shards == 32 || n_shards == 64) || (int64_t)cap_eff * n_shards != n_seq || n_seq > DC_MAX_SEQ)
+        return hipErrorInvalidValue;
+    BalanceArgs b;
+    b.N = n_seq; b.P = n_shards; b.C = cap_eff; b.seq_len = d_seq_len; b.perm = d_perm;
+    b.shard_seq_off = d_shard_seq_off; b.shard_of_seq = d_shard_of_seq; b.shard_load = d_shard_load; b.status = d_status;
+    const int64_t grid = 1 + (adv_waves(n_seq, n_groups) + BAL_WAVES - 1) / BAL_WAVES;
+    hipLaunchKernelGGL(balance_plan_advantage_kernel, dim3((unsigned)grid), dim3(BAL_BLOCK), 0, st, b, plan, adv, src);
     return hipGetLastError();
 }
 

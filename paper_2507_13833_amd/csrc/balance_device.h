@@ -645,10 +645,18 @@ __device__ __forceinline__ int lpt_rounds_wide(BalLds& L, int N, int P, int C, c
 }
 
 // The whole of Algorithm 1, by one workgroup of BAL_BLOCK threads.
+// What a lane hands to the plan when that runs as the tail of this workgroup: the sequence and the length of
+// output slots tid, tid + BAL_BLOCK, ... (seq = -1, len = 0 beyond N).
+struct SlotRegs {
+    int32_t seq[BAL_ROUNDS];
+    int32_t len[BAL_ROUNDS];
+};
+
+// slots != nullptr (only with P in {16, 32, 64} and P * C == N): also fill *slots.
 __device__ __forceinline__ void balance_body(BalLds& L, int32_t N, int32_t P, int32_t C,
                                              const int32_t* __restrict__ seq_len, int32_t* __restrict__ perm,
                                              int32_t* __restrict__ shard_seq_off, int32_t* __restrict__ shard_of_seq,
-                                             int64_t* __restrict__ shard_load, int32_t* status) {
+                                             int64_t* __restrict__ shard_load, int32_t* status, SlotRegs* slots = nullptr) {
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
 
     // ---- load lengths, range ----
@@ -729,11 +737,18 @@ __device__ __forceinline__ void balance_body(BalLds& L, int32_t N, int32_t P, in
         // (gathered by sequence in the LDS, where the sorted items were, so that both outputs leave in index
         // order: 16 384 scattered 4-byte stores take longer to drain than the rounds save)
         uint32_t* const worker_of = items;
-        for (int q = tid; q < N; q += BAL_BLOCK) {
-            const int k = q / C;
-            const uint32_t u = min(rows[k * rpitch + (q - k * C)] & 0xFFFFu, (uint32_t)(N - 1));   // (no index leaves the
-            perm[q] = (int32_t)u;                                                                  //  arrays whatever a word holds)
-            worker_of[u] = (uint32_t)k;
+#pragma unroll
+        for (int qq = 0; qq < BAL_ROUNDS; ++qq) {
+            const int q = qq * BAL_BLOCK + tid;
+            if (slots) { slots->seq[qq] = -1; slots->len[qq] = 0; }
+            if (q < N) {
+                const int k = q / C;
+                const uint32_t e = rows[k * rpitch + (q - k * C)];
+                const uint32_t u = min(e & 0xFFFFu, (uint32_t)(N - 1));      // (no index leaves the arrays whatever a word holds)
+                perm[q] = (int32_t)u;
+                worker_of[u] = (uint32_t)k;
+                if (slots) { slots->seq[qq] = (int32_t)u; slots->len[qq] = (int32_t)(e >> 16); }
+            }
         }
         __syncthreads();
         for (int i = tid; i < N; i += BAL_BLOCK) shard_of_seq[i] = (int32_t)worker_of[i];
@@ -786,10 +801,21 @@ __device__ __forceinline__ void balance_body(BalLds& L, int32_t N, int32_t P, in
     // ---- c) lay out P_0, P_1, ... each in insertion order ----
     const int n_placed = *placed;
     if (pitch) {                                                  // both stores in index order
-        for (int q = tid; q < N; q += BAL_BLOCK) {
-            const int k = q / C;
-            perm[q] = step_slot[k * pitch + (q - k * C)];
-            shard_of_seq[q] = L.keys[q];
+#pragma unroll
+        for (int qq = 0; qq < BAL_ROUNDS; ++qq) {
+            const int q = qq * BAL_BLOCK + tid;
+            if (slots) { slots->seq[qq] = -1; slots->len[qq] = 0; }
+            if (q < N) {
+                const int k = q / C;
+                const int u = min((int)step_slot[k * pitch + (q - k * C)], N - 1);
+                perm[q] = u;
+                shard_of_seq[q] = L.keys[q];
+                if (slots) {                                      // (lengths of 2^16 and more: they are in global memory only)
+                    const int32_t s = seq_len[u];
+                    slots->seq[qq] = u;
+                    slots->len[qq] = (s <= 0 || s > DC_MAX_SEQ_LEN) ? 1 : s;
+                }
+            }
         }
         return;
     }

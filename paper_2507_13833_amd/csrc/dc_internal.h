@@ -126,6 +126,23 @@ struct PlanArgs {
     int32_t* word_last;
 };
 
+PlanArgs make_plan_args(const dc_params& prm, const int64_t* d_src_tok_off, const int32_t* d_seq_len,
+                        const int32_t* d_perm, const int32_t* d_shard_seq_off, int64_t dst_capacity,
+                        int64_t* d_dst_tok_off, int64_t* d_shard_tok_off, int32_t* d_shard_mb_off,
+                        int32_t* d_mb_seq_off, int32_t* d_cu_seqlens, int32_t* d_n_mb, const Workspace& ws,
+                        int32_t* d_status);
+
+// Granule tables and per-slot source descriptors behind a plan that ran as the balance workgroup's tail
+// (p.slot_len holds the slots' lengths, nothing else of the per-slot arrays is filled yet).
+hipError_t launch_records_slots(const PlanArgs& p, const SourceDesc& src, const Workspace& ws, hipStream_t st);
+
+// Balance, group advantage and the plan in one launch (workgroup 0: Algorithm 1, then the plan as its tail;
+// the other workgroups: the advantage stage).  Needs n_shards in {16, 32, 64}, cap_eff * n_shards == n_seq.
+hipError_t launch_balance_plan_advantage(int32_t n_seq, int32_t n_shards, int32_t cap_eff, const int32_t* d_seq_len,
+                                         int32_t* d_perm, int32_t* d_shard_seq_off, int32_t* d_shard_of_seq,
+                                         int64_t* d_shard_load, const PlanArgs& plan, const AdvArgs& adv,
+                                         const SourceDesc& src, int32_t n_groups, int32_t* d_status, hipStream_t st);
+
 // plan_kernel's work for DC_MAX_SEQ < n_seq <= DC_MAX_SEQ_LARGE: one workgroup, the prefix and the per-word
 // tables in the workspace instead of the LDS.
 hipError_t launch_plan_large(const PlanArgs& a, hipStream_t st);

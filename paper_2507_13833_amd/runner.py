@@ -142,6 +142,33 @@ class DeviceBatch:
                                      self.src_fields["mask"] if per_token else None, self.adv_seq,
                                      self.adv_tok_src if per_token else None, self.status)
 
+    def balance_plan_group_advantage(self, per_token: bool = True) -> None:
+        if self.large:                                   # the call keeps dc_balance's size limit
+            self.group_advantage(per_token)
+            self.balance()
+            self.plan()
+            return
+        B.dc_balance_plan_group_advantage(self.prm, self.source, self.seq_len, self.perm, self.shard_seq_off,
+                                          self.shard_of_seq, self.shard_load, self.reward, self.group_off,
+                                          self.w.n_groups, self.src_fields["mask"] if per_token else None, self.adv_seq,
+                                          self.adv_tok_src if per_token else None, self.capacity, self.dst_tok_off,
+                                          self.shard_tok_off, self.shard_mb_off, self.mb_seq_off, self.cu_seqlens,
+                                          self.n_mb, self.ws, self.ws_bytes, self.status)
+
+    def step_two_calls(self, gather_events=None, per_token: bool = True) -> None:
+        """The whole pass as two calls: dc_balance_plan_group_advantage (balance, advantage stage and plan: two
+        launches where the shape allows it), then the gather.  gather_events: optional (start, end) torch events
+        recorded around the gather launch."""
+        self.balance_plan_group_advantage(per_token)
+        if gather_events is not None:
+            gather_events[0].record()
+        if per_token:
+            self.gather()
+        else:
+            self.gather_advantage()
+        if gather_events is not None:
+            gather_events[1].record()
+
     def step_fused(self, gather_events=None) -> None:
         """The same pass on ONE stream: balance and the advantage stage share a launch (the advantage
         workgroups stream the tokens while the balance workgroup runs), then plan, then gather.

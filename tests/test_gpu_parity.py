@@ -32,12 +32,14 @@ def oracle_step(w, align=1, cap=0):
     return bal, adv, adv_tok, pl
 
 
-def check_step(w, align=1, cap=0, label="", overlapped=False, fused=False):
+def check_step(w, align=1, cap=0, label="", overlapped=False, fused=False, two_calls=False):
     torch, binding, runner = _gpu()
     print(f"[parity] {label or w.name}: N={w.n_seq} P={w.n_shards} T={w.total_tokens} align={align} cap={cap}",
           flush=True)
     d = runner.DeviceBatch(w, align_tokens=align, cap=cap, poison=True)
-    if fused:
+    if two_calls:
+        d.step_two_calls()                               # balance, advantage stage and plan in one call, then the gather
+    elif fused:
         d.step_fused()                                   # the launch configuration bench.py times: balance and the
                                                          # advantage stage in one launch
     elif overlapped:
@@ -127,6 +129,90 @@ def test_full_config_as_benchmarked(cfg):
     assert torch.equal(perm, d.perm) and torch.equal(cu, d.cu_seqlens) and torch.equal(dst, d.dst_tok_off)
     for k, v in d.dst_fields.items():
         assert torch.equal(first[k], v), k
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_full_config_balance_and_plan_in_one_call(cfg):
+    """dc_balance_plan_group_advantage + dc_gather (what bench.py times): on configs 3-5 the plan runs as the tail
+    of the balance workgroup, on configs 1 and 2 (4 and 8 shards) the call issues the separate kernels."""
+    import torch
+    d = check_step(workloads.make_workload(cfg), label=f"config {cfg}, balance + plan in one call", two_calls=True)
+    first = {k: v.clone() for k, v in d.dst_fields.items()}
+    perm, cu, dst = d.perm.clone(), d.cu_seqlens.clone(), d.dst_tok_off.clone()
+    d.step_two_calls()                                   # a second pass reproduces every output bit for bit
+    torch.cuda.synchronize()
+    assert d.read_status() == 0
+    assert torch.equal(perm, d.perm) and torch.equal(cu, d.cu_seqlens) and torch.equal(dst, d.dst_tok_off)
+    for k, v in d.dst_fields.items():
+        assert torch.equal(first[k], v), k
+
+
+def test_balance_and_plan_in_one_call_shapes():
+    rng = np.random.default_rng(51)
+    for P, N in ((16, 16), (32, 32 * 3), (64, 64 * 17), (64, 4096), (16, 16 * 1024), (32, 32 * 512)):
+        lens = np.minimum(rng.geometric(0.004, N), 6000).astype(np.int32)
+        check_step(_custom(lens, 1 if N < 64 else 4, P, 16384, n_src=2 if N >= 64 else 1), label=f"P={P} N={N}", two_calls=True)
+    # tiny sequences: many slots per gather tile, hundreds per micro-batch
+    check_step(_custom(rng.integers(1, 9, 8192), 8, 16, 64, n_src=4), label="lengths 1..8", two_calls=True)
+    # shard starts aligned; a budget that one slot fills exactly
+    lens = rng.integers(1, 700, 64 * 40).astype(np.int32)
+    lens[5] = 4096
+    for align in (3, 64):
+        check_step(_custom(lens, 8, 64, 4096, n_src=2), align=align, label=f"align {align}", two_calls=True)
+    # lengths of 2^16 and more leave the packed path (one word per sequence) for the general one, plan still in the call
+    lens = rng.integers(1, 3000, 32 * 16).astype(np.int32)
+    lens[7] = 70000; lens[100] = 65536; lens[101] = 65535
+    check_step(_custom(lens, 4, 32, 1 << 17, fields=("i32",)), label="a sequence of 70000 tokens", two_calls=True)
+    # all lengths equal (no sort pass), and a long tail that keeps one worker far above the others
+    check_step(_custom(np.full(64 * 30, 77), 8, 64, 1024), label="all equal", two_calls=True)
+    heavy = np.minimum(64 * (1.0 - rng.random(64 * 64)) ** (-1 / 1.3), 32768).astype(np.int32) + rng.integers(512, 4096, 64 * 64)
+    check_step(_custom(heavy, 16, 64, 65536, fields=("i32",)), label="long tail", two_calls=True)
+    # shapes the call hands to the separate kernels: partitions of unequal size, 8 shards, 128 shards
+    check_step(_custom(rng.integers(1, 500, 1000), 5, 16, 4096), cap=70, label="cap 70", two_calls=True)
+    check_step(_custom(rng.integers(1, 500, 1024), 8, 8, 4096), label="P=8", two_calls=True)
+    check_step(_custom(rng.integers(1, 300, 128 * 20), 8, 128, 2048, n_src=2), label="P=128", two_calls=True)
+    # and the training-layout advantage field made by the gather behind it
+    w = workloads.make_workload(2, n_shards=16)
+    torch, binding, runner = _gpu()
+    a, b = runner.DeviceBatch(w, poison=True), runner.DeviceBatch(w, poison=True)
+    a.step_two_calls(per_token=False); b.step_no_rollout_adv()
+    torch.cuda.synchronize()
+    assert a.read_status() == 0 and b.read_status() == 0
+    for k in a.dst_fields:
+        assert torch.equal(a.dst_fields[k], b.dst_fields[k]), k
+
+
+def test_balance_and_plan_in_one_call_status_codes():
+    torch, binding, runner = _gpu()
+    lens = np.random.default_rng(52).integers(1, 60, 64).astype(np.int32)
+    lens[9] = 200
+    w = _custom(lens, 4, 16, 100)                                      # 200 > budget 100
+    d = runner.DeviceBatch(w)
+    d.step_two_calls(); torch.cuda.synchronize()
+    assert d.read_status() == binding.DC_ERR_SEQ_EXCEEDS_BUDGET
+    w = _custom(lens, 4, 16, 4096)
+    d = runner.DeviceBatch(w)
+    d.seq_len[1] = 0                                                   # zero-length sequence
+    d.step_two_calls(); torch.cuda.synchronize()
+    assert d.read_status() == binding.DC_ERR_ZERO_LENGTH_SEQ
+    d = runner.DeviceBatch(w)
+    d.capacity -= 1                                                    # arena one token short
+    d.step_two_calls(); torch.cuda.synchronize()
+    assert d.read_status() == binding.DC_ERR_OVERFLOW
+    d = runner.DeviceBatch(w, poison=True)
+    d.src_tok_off[3] = w.total_tokens                                  # a sequence that would start beyond its buffer
+    d.step_two_calls(); torch.cuda.synchronize()
+    assert d.read_status() == binding.DC_ERR_BAD_LAYOUT
+    # host errors come before anything is enqueued
+    d = runner.DeviceBatch(w)
+    with pytest.raises(binding.DcError) as e:
+        binding.dc_balance_plan_group_advantage(d.prm, d.source, d.seq_len, d.perm, d.shard_seq_off, d.shard_of_seq,
+                                                d.shard_load, d.reward, d.group_off, w.n_groups, d.src_fields["mask"],
+                                                d.adv_seq, d.adv_tok_src, d.capacity, d.dst_tok_off, d.shard_tok_off,
+                                                d.shard_mb_off, d.mb_seq_off, d.cu_seqlens, d.n_mb, d.ws, 16, d.status)
+    assert e.value.code == binding.DC_ERR_WORKSPACE
+    torch.cuda.synchronize()
+    assert not d.perm.any()                                            # nothing ran
 
 
 def test_step_replayed_from_a_hip_graph():
