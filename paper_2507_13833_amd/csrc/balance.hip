@@ -84,8 +84,8 @@ __global__ __launch_bounds__(BAL_BLOCK) void balance_plan_advantage_kernel(Balan
         return;
     }
     SlotRegs s;
-    balance_body(*reinterpret_cast<BalLds*>(lds), b.N, b.P, b.C, b.seq_len, b.perm, b.shard_seq_off, b.shard_of_seq,
-                 b.shard_load, b.status, &s);
+    balance_body_t<true>(*reinterpret_cast<BalLds*>(lds), b.N, b.P, b.C, b.seq_len, b.perm, b.shard_seq_off, b.shard_of_seq,
+                         b.shard_load, b.status, s);
 #pragma unroll
     for (int q = 0; q < PLAN_IPT; ++q) {                          // the slots' lengths, for the launch that builds the granule tables
         const int j = q * PLAN_BLOCK + (int)threadIdx.x;

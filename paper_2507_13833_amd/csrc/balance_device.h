@@ -652,11 +652,12 @@ struct SlotRegs {
     int32_t len[BAL_ROUNDS];
 };
 
-// slots != nullptr (only with P in {16, 32, 64} and P * C == N): also fill *slots.
-__device__ __forceinline__ void balance_body(BalLds& L, int32_t N, int32_t P, int32_t C,
-                                             const int32_t* __restrict__ seq_len, int32_t* __restrict__ perm,
-                                             int32_t* __restrict__ shard_seq_off, int32_t* __restrict__ shard_of_seq,
-                                             int64_t* __restrict__ shard_load, int32_t* status, SlotRegs* slots = nullptr) {
+// FILL (only with P in {16, 32, 64} and P * C == N): also fill slots.
+template <bool FILL>
+__device__ __forceinline__ void balance_body_t(BalLds& L, int32_t N, int32_t P, int32_t C,
+                                               const int32_t* __restrict__ seq_len, int32_t* __restrict__ perm,
+                                               int32_t* __restrict__ shard_seq_off, int32_t* __restrict__ shard_of_seq,
+                                               int64_t* __restrict__ shard_load, int32_t* status, SlotRegs& slots) {
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
 
     // ---- load lengths, range ----
@@ -740,14 +741,14 @@ __device__ __forceinline__ void balance_body(BalLds& L, int32_t N, int32_t P, in
 #pragma unroll
         for (int qq = 0; qq < BAL_ROUNDS; ++qq) {
             const int q = qq * BAL_BLOCK + tid;
-            if (slots) { slots->seq[qq] = -1; slots->len[qq] = 0; }
+            if constexpr (FILL) { slots.seq[qq] = -1; slots.len[qq] = 0; }
             if (q < N) {
                 const int k = q / C;
                 const uint32_t e = rows[k * rpitch + (q - k * C)];
                 const uint32_t u = min(e & 0xFFFFu, (uint32_t)(N - 1));      // (no index leaves the arrays whatever a word holds)
                 perm[q] = (int32_t)u;
                 worker_of[u] = (uint32_t)k;
-                if (slots) { slots->seq[qq] = (int32_t)u; slots->len[qq] = (int32_t)(e >> 16); }
+                if constexpr (FILL) { slots.seq[qq] = (int32_t)u; slots.len[qq] = (int32_t)(e >> 16); }
             }
         }
         __syncthreads();
@@ -804,16 +805,16 @@ __device__ __forceinline__ void balance_body(BalLds& L, int32_t N, int32_t P, in
 #pragma unroll
         for (int qq = 0; qq < BAL_ROUNDS; ++qq) {
             const int q = qq * BAL_BLOCK + tid;
-            if (slots) { slots->seq[qq] = -1; slots->len[qq] = 0; }
+            if constexpr (FILL) { slots.seq[qq] = -1; slots.len[qq] = 0; }
             if (q < N) {
                 const int k = q / C;
                 const int u = min((int)step_slot[k * pitch + (q - k * C)], N - 1);
                 perm[q] = u;
                 shard_of_seq[q] = L.keys[q];
-                if (slots) {                                      // (lengths of 2^16 and more: they are in global memory only)
+                if constexpr (FILL) {                             // (lengths of 2^16 and more: they are in global memory only)
                     const int32_t s = seq_len[u];
-                    slots->seq[qq] = u;
-                    slots->len[qq] = (s <= 0 || s > DC_MAX_SEQ_LEN) ? 1 : s;
+                    slots.seq[qq] = u;
+                    slots.len[qq] = (s <= 0 || s > DC_MAX_SEQ_LEN) ? 1 : s;
                 }
             }
         }
@@ -825,6 +826,14 @@ __device__ __forceinline__ void balance_body(BalLds& L, int32_t N, int32_t P, in
         shard_of_seq[u] = k;
         perm[part_off[k] + step_slot[t]] = u;
     }
+}
+
+__device__ __forceinline__ void balance_body(BalLds& L, int32_t N, int32_t P, int32_t C,
+                                             const int32_t* __restrict__ seq_len, int32_t* __restrict__ perm,
+                                             int32_t* __restrict__ shard_seq_off, int32_t* __restrict__ shard_of_seq,
+                                             int64_t* __restrict__ shard_load, int32_t* status) {
+    SlotRegs unused;
+    balance_body_t<false>(L, N, P, C, seq_len, perm, shard_seq_off, shard_of_seq, shard_load, status, unused);
 }
 
 }  // namespace dc
