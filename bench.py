@@ -345,6 +345,31 @@ def main() -> int:
             assert all(s.read_status() == 0 for s in sets)
             ppo = {"call": "dc_gae", **res}
 
+    # Algorithm 1 beyond what one workgroup's LDS holds (dc_balance_ws): 65 536 sequences of this workload's
+    # length distribution over 64 shards
+    beyond_lds = None
+    if sides:
+        import numpy as np
+        from paper_2507_13833_amd import binding, workloads
+        n_big, p_big = 65536, 64
+        lens = workloads.sequence_lengths(args.config, n_big)
+        prm = binding.make_params(n_big, p_big, 1 << 20, 1e-6, 1, 0, 1)
+        dev = torch.device("cuda:0")
+        d_len = torch.from_numpy(lens).to(dev)
+        d_perm = torch.empty(n_big, dtype=torch.int32, device=dev)
+        d_off = torch.empty(p_big + 1, dtype=torch.int32, device=dev)
+        d_of = torch.empty(n_big, dtype=torch.int32, device=dev)
+        d_load = torch.empty(p_big, dtype=torch.int64, device=dev)
+        d_st = torch.zeros(1, dtype=torch.int32, device=dev)
+        nb = binding.dc_balance_workspace_bytes(prm)
+        d_ws = torch.empty(nb, dtype=torch.uint8, device=dev)
+        st = device_ms(lambda b: binding.dc_balance_ws(prm, d_len, d_perm, d_off, d_of, d_load, d_ws, nb, d_st))
+        assert int(d_st.item()) == 0 and int(d_load.sum().item()) == int(lens.astype(np.int64).sum())
+        beyond_lds = {"call": "dc_balance_ws", "n_seq": n_big, "n_shards": p_big,
+                      "lengths": f"the length recipe of config {args.config}", "workspace_bytes": nb,
+                      "ms": round(st["median"], 4), "ms_min": round(st["min"], 4)}
+        del d_len, d_perm, d_off, d_of, d_load, d_ws
+
     # Double buffer (Sec. 6.5): the step that fills one buffer set beside a consumer that still reads the set
     # filled before it (stand-in consumer: one reduction over each 4-byte arena of that set), on two streams of
     # the default priority, against the same two pieces of work issued one after the other; outside the timed region
@@ -448,6 +473,7 @@ def main() -> int:
         "reverse": reverse,
         "ppo_advantage": ppo,
         "double_buffer": double_buffer,
+        "balance_beyond_lds": beyond_lds,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)

@@ -151,11 +151,13 @@ dc_status dc_balance(const dc_params* prm, const int32_t* d_seq_len,
 
 /*
  * dc_balance for up to DC_MAX_SEQ_LARGE sequences (same results, same errors).  Up to DC_MAX_SEQ
- * sequences it is dc_balance itself and d_ws may be NULL.  Above, the sort keeps its index arrays in
- * d_ws (256-byte aligned, dc_balance_workspace_bytes(prm) bytes: 12 bytes per sequence) and the
- * assignment takes the sorted sequences DC_MAX_SEQ at a time, carrying the workers' loads along; a slower
- * path (every sort access is a global one).  Limit above DC_MAX_SEQ: at most 65535 sequences per
- * shard (C of Algorithm 1, or prm->cap), else UNSUPPORTED_SIZE.
+ * sequences it is dc_balance itself and d_ws may be NULL.  Above, it is a chain of launches on the stream:
+ * the sort of Algorithm 1's first statement runs over many workgroups and keeps its index arrays, the sorted
+ * lengths and its digit counts in d_ws (256-byte aligned, dc_balance_workspace_bytes(prm) bytes: about 13 bytes
+ * per sequence); the assignment is one workgroup that takes the sorted sequences DC_MAX_SEQ at a time,
+ * carrying the workers' loads along; a last launch writes d_perm and d_shard_of_seq.  d_ws holds nothing the
+ * caller needs afterwards.  Limit above DC_MAX_SEQ: at most 65535 sequences per shard (C of Algorithm 1, or
+ * prm->cap), else UNSUPPORTED_SIZE.
  */
 size_t dc_balance_workspace_bytes(const dc_params* prm);
 dc_status dc_balance_ws(const dc_params* prm, const int32_t* d_seq_len,

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdc.so")
-SOURCES = ["api.hip", "balance.hip", "balance_large.hip", "advantage.hip", "plan.hip", "plan_large.hip", "gather.hip", "scatter.hip", "gae.hip", "noalloc.hip"]
+SOURCES = ["api.hip", "balance.hip", "balance_large.hip", "sort_large.hip", "advantage.hip", "plan.hip", "plan_large.hip", "gather.hip", "scatter.hip", "gae.hip", "noalloc.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-result"]

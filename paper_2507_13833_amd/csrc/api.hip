@@ -147,10 +147,11 @@ dc_status dc_balance(const dc_params* prm, const int32_t* d_seq_len,
     return e == hipSuccess ? DC_OK : DC_ERR_HIP;
 }
 
-// Workspace of the balance beyond DC_MAX_SEQ sequences: two index arrays and one word per sorted item.
+// Workspace of the balance beyond DC_MAX_SEQ sequences: the sort's two index arrays (one of them holds a word per
+// sorted item afterwards), the sorted lengths, and the sort's table of digit counts.
 static size_t balance_ws_bytes(int32_t n_seq) {
     if (n_seq <= DC_MAX_SEQ) return 0;
-    return 3 * (((size_t)n_seq + 63) & ~(size_t)63) * sizeof(int32_t) + 256;
+    return 3 * (((size_t)n_seq + 63) & ~(size_t)63) * sizeof(int32_t) + dc::sort_large_table_bytes(n_seq) + 256;
 }
 
 size_t dc_balance_workspace_bytes(const dc_params* prm) {

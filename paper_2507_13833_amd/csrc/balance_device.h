@@ -314,15 +314,36 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, co
 // D' <= max(D, its largest - its smallest item).  So a run of rounds stands if D < L and F - L < L, where
 // F = the first item of the run and L = its last one.  One look at 64 items (the last ones of the next 64
 // batches, one per lane) says how many batches that covers: up to 256 rounds per look.
+//
+// PORTION: the N items are one portion of a longer sorted list (more sequences than the LDS holds).  The workers'
+// keys, counts and loads come from, and go back to, *carry; the item words carry their index inside the portion;
+// the rows start empty with every call and hold row_cap items each, and the call returns, before all N items are
+// placed, as soon as one row is full (the caller empties the rows and offers the rest again).
 constexpr int FAST_BATCH = 4;
 constexpr uint32_t PACKED_MAX_LEN = 0xFFFFu;             // lengths up to this take the packed path
 
 __device__ __forceinline__ int row_pitch(int C) { return C | 1; }      // odd: the workers' rows start in different banks
 
-template <int WIDTH>
+// What lane k keeps of worker k between two portions.
+struct PackedCarry {
+    uint32_t key;
+    int32_t  count;
+    int64_t  load;
+};
+__device__ __forceinline__ PackedCarry packed_fresh(int P, int C) {
+    const uint32_t lane = threadIdx.x & (WAVE - 1);
+    PackedCarry c;
+    c.key = ((int)lane < P && C > 0) ? lane : (KEY_FULL | lane);
+    c.count = 0;
+    c.load = 0;
+    return c;
+}
+
+template <int WIDTH, bool PORTION = false>
 __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint32_t* items, int32_t max_len,
                                                  uint32_t* rows, int pitch, uint32_t* spare_word,
-                                                 int32_t* worker_count, int64_t* __restrict__ shard_load) {
+                                                 int32_t* worker_count, int64_t* __restrict__ shard_load,
+                                                 PackedCarry* carry = nullptr, int row_cap = 0) {
     const uint32_t lane = threadIdx.x;
     const uint32_t G = (uint32_t)__builtin_amdgcn_readfirstlane(max_len) << 6;    // see lpt_rounds for the rebasing
     const uint32_t fit = (3u << 30) / max(G, 1u);
@@ -337,31 +358,43 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
     uint32_t key = (mine_exists && C > 0) ? lane : full;
     int32_t count = 0;
     int64_t load = 0;
+    if constexpr (PORTION) { key = carry->key; count = carry->count; load = carry->load; }
+    const int32_t row_base = count;                               // PORTION: my row's first entry is my item number row_base
     int pos = 0;
     uint32_t e = items[lane];                                     // the item offered to rank `lane` (the array is padded)
     bool all_take = C > 0;
+    if constexpr (PORTION) all_take = __ballot(mine_exists && key >= KEY_FULL) == 0ull;
     const uint32_t pitch4 = (uint32_t)pitch * 4u;
     int no_look = 0, look_wait = 0;                               // tested rounds before the bound is looked at again
     char* const rows_b = reinterpret_cast<char*>(rows);
     char* const spare_b = reinterpret_cast<char*>(spare_word);
 
     while (pos < N) {
+        if constexpr (PORTION) {                                  // a full row ends the portion
+            if (__ballot(mine_exists && count - row_base >= row_cap) != 0ull) break;
+        }
         if (all_take && pos + P <= N) {                           // uniform: every worker is open
-            int32_t cmax = mine_exists ? count : 0, cmin = mine_exists ? count : INT32_MAX;
+            // (counts as the rows see them: PORTION counts from the call's start)
+            const int32_t in_row = PORTION ? count - row_base : count;
+            int32_t cmax = mine_exists ? in_row : 0, cmin = mine_exists ? in_row : INT32_MAX;
+            int32_t gmax = mine_exists ? count : 0;
 #pragma unroll
             for (int d = 32; d >= 1; d >>= 1) {
                 cmax = max(cmax, __shfl_xor(cmax, d, WAVE));
                 cmin = min(cmin, __shfl_xor(cmin, d, WAVE));
+                if constexpr (PORTION) gmax = max(gmax, __shfl_xor(gmax, d, WAVE));
             }
             const int c_hi = __builtin_amdgcn_readfirstlane(cmax), c_lo = __builtin_amdgcn_readfirstlane(cmin);
-            const bool level = c_hi == c_lo;                      // every worker holds the same number of items
+            const bool level = c_hi == c_lo;                      // every row holds the same number of items
             const int64_t off = load - (int64_t)(key >> 6);       // what the key does not hold of my worker's load
             int64_t taken = 0;                                    // load taken off the keys by rebasing in here
             int rounds = 0;
             uint32_t sk = wave_sort_asc<WIDTH>(key);
-            const int n_rounds = min(C - c_hi, (N - pos) / P);    // >= 1: until a worker is full or the items run out
+            // >= 1: until a worker (PORTION: or a row) is full or the items run out
+            const int n_rounds = PORTION ? min(min(C - __builtin_amdgcn_readfirstlane(gmax), row_cap - c_hi), (N - pos) / P)
+                                         : min(C - c_hi, (N - pos) / P);
             const uint32_t* next_item = items + pos + P + (int)lane;       // the item of the next round for this rank
-            const int32_t count4 = count * 4;
+            const int32_t count4 = in_row * 4;
 
             // One round that is known to stand; r = rounds done before it in this phase.  LEVEL: all counts are c_lo.
             auto sure_round = [&](int r, auto level_c) {
@@ -516,7 +549,7 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
         const uint32_t next_e = items[t + m];                     // next round's item (padded array)
         if (key <= thr) {                                         // my worker is among the m smallest
             const uint32_t nk = (recv & ~63u) | lane;
-            rows[(int)lane * pitch + count] = items[pos + (int)(recv & 63u)];     // the item I took
+            rows[(int)lane * pitch + (PORTION ? count - row_base : count)] = items[pos + (int)(recv & 63u)];     // the item I took
             load += (int64_t)((nk - key) >> 6);
             count += 1;
             key = (count == C) ? full : nk;
@@ -527,6 +560,7 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
     }
     if (mine_exists) shard_load[lane] = load;
     worker_count[lane] = count;
+    if constexpr (PORTION) { carry->key = key; carry->count = count; carry->load = load; }
     return pos;
 }
 

@@ -81,11 +81,16 @@ hipError_t launch_balance(int32_t n_seq, int32_t n_shards, int32_t cap_eff, cons
                           int32_t* d_perm, int32_t* d_shard_seq_off, int32_t* d_shard_of_seq,
                           int64_t* d_shard_load, int32_t* d_status, hipStream_t st);
 
-// The same for DC_MAX_SEQ < n_seq <= DC_MAX_SEQ_LARGE, n_shards <= 64, cap_eff < 2^16; d_ws: 3 * roundup(n_seq, 64)
-// int32 words, 256-byte aligned.
+// The same for DC_MAX_SEQ < n_seq <= DC_MAX_SEQ_LARGE, cap_eff < 2^16; d_ws: 3 * roundup(n_seq, 64) int32 words and
+// then sort_large_table_bytes(n_seq) bytes, 256-byte aligned.
 hipError_t launch_balance_large(int32_t n_seq, int32_t n_shards, int32_t cap_eff, const int32_t* d_seq_len,
                                 int32_t* d_perm, int32_t* d_shard_seq_off, int32_t* d_shard_of_seq,
                                 int64_t* d_shard_load, void* d_ws, int32_t* d_status, hipStream_t st);
+
+// Indices by descending length (stable), by many workgroups (sort_large.hip).
+size_t sort_large_table_bytes(int32_t n_seq);
+hipError_t launch_sort_large(int32_t n_seq, const int32_t* d_seq_len, int32_t* d_idx_a, int32_t* d_idx_b,
+                             int32_t* d_sorted_len, uint32_t* d_counts, int32_t* d_status, hipStream_t st);
 
 struct AdvArgs;
 hipError_t launch_balance_advantage(int32_t n_seq, int32_t n_shards, int32_t cap_eff, const int32_t* d_seq_len,

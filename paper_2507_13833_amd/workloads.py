@@ -162,6 +162,18 @@ def _multiturn_mask(rng: np.random.Generator, prompt_len, seq_len, tok_off, tota
     return m
 
 
+def sequence_lengths(cfg: int, n_seq: int, seed: int | None = None) -> np.ndarray:
+    """Only the sequence lengths of workload ``cfg`` with ``n_seq`` sequences, a multiple of its group size (the
+    first two draws of make_workload): for measurements of the balance alone at sizes whose payload is not needed."""
+    sh = _SHAPES[cfg]
+    if n_seq % sh["G"]:
+        raise ValueError("sequence count must be a multiple of the group size")
+    prompts = n_seq // sh["G"]
+    rng = np.random.default_rng(1000 + cfg if seed is None else seed)
+    p_len = np.repeat(rng.integers(sh["plo"], sh["phi"] + 1, prompts), sh["G"]).astype(np.int32)
+    return (p_len + _response_len(cfg, rng, prompts * sh["G"])).astype(np.int32)
+
+
 def make_workload(cfg: int, prompts: int | None = None, n_shards: int | None = None,
                   seed: int | None = None) -> Workload:
     """Draw workload ``cfg`` (1..5).  ``prompts`` shrinks the batch for quick tests

@@ -487,6 +487,13 @@ def test_balance_beyond_the_lds():
     _check_balance_ws(heavy(65 * 600), 65, cap=640, label="65 workers, partitions of unequal size")
     # the most a shard may hold above DC_MAX_SEQ sequences: a place inside a partition is a 16-bit number
     _check_balance_ws(rng.integers(1, 60, 2 * 65535), 2, label="65535 sequences per shard")
+    # 16, 32 or 64 workers, all partitions of equal size, lengths below 2^16: the packed rounds, portion by portion
+    _check_balance_ws(rng.integers(200, 6000, 65536), 32, label="packed rounds, four portions of 512 rounds")
+    one_long = np.concatenate([[60000], rng.integers(1, 40, 16 * 2048 - 1)])
+    _check_balance_ws(one_long, 16, label="packed rounds, a worker's row fills before the portion ends")
+    _check_balance_ws(np.concatenate([[65535], heavy(64 * 300 - 1)]), 64, label="packed rounds, longest length 65535")
+    _check_balance_ws(np.concatenate([[65536], heavy(64 * 300 - 1)]), 64, label="one length above the packed words")
+    _check_balance_ws(heavy(64 * 1001), 64, label="packed rounds, a short last portion")
 
 
 def test_more_sequences_than_the_lds_holds():
