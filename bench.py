@@ -411,6 +411,34 @@ def main() -> int:
         double_buffer = {"what": "one step into buffer set i beside a reduction over the 4-byte arenas of set i-1 "
                                  "(two streams) vs one after the other", **res}
 
+        # two independent batches in flight: the step of buffer set i on stream i mod 2 (default priority), so the
+        # latency-bound balance + plan of one batch runs beside the other batch's gather; whole steps, none skipped
+        lanes = [torch.cuda.Stream(), torch.cuda.Stream()]
+        for q in lanes:
+            q.wait_stream(main_s)
+
+        def in_flight(n):
+            for i in range(n):
+                with torch.cuda.stream(lanes[i % 2]):
+                    sets[i % 2].step_two_calls()
+            for q in lanes:
+                main_s.wait_stream(q)
+        in_flight(4)
+        torch.cuda.synchronize()
+        d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n_fl = 40
+        d0.record()
+        for q in lanes:
+            q.wait_stream(main_s)
+        in_flight(n_fl)
+        d1.record()
+        torch.cuda.synchronize()
+        assert all(s.read_status() == 0 for s in sets)
+        fl_ms = d0.elapsed_time(d1) / n_fl
+        double_buffer["two_batches_in_flight"] = {
+            "what": "steps of two buffer sets alternating on two streams, each step complete; ms per step",
+            "steps": n_fl, "ms_per_step": round(fl_ms, 4), "tokens_per_s": T / (fl_ms * 1e-3)}
+
     # the achievable ceiling on this machine: a plain elementwise copy (one torch kernel) of the gather's byte count,
     # 3 rotating buffer pairs, measured the same way
     if sides:
@@ -431,6 +459,37 @@ def main() -> int:
                    "ms": round(cst["median"], 4), "ms_min": round(cst["min"], 4),
                    "achieved": 2 * n_words * 4 / (cst["median"] * 1e-3) / 1e9, "unit": "GB/s"}
         del pairs
+
+        # the same for the write-heavy stages: plain torch kernels with their mix of bytes read and written per
+        # token, over T elements (three rotating buffer sets, median of 30 launches)
+        def plain_ms(make, run):
+            bufs = [make() for _ in range(3)]
+            for i in range(3):
+                run(bufs[i])
+            torch.cuda.synchronize()
+            mk = [torch.cuda.Event(enable_timing=True) for _ in range(31)]
+            mk[0].record()
+            for i in range(30):
+                run(bufs[i % 3])
+                mk[i + 1].record()
+            torch.cuda.synchronize()
+            return stats_ms([mk[i].elapsed_time(mk[i + 1]) for i in range(30)])
+
+        def probe(what, nbytes, st):
+            return {"what": what, "ms": round(st["median"], 4), "ms_min": round(st["min"], 4),
+                    "achieved": nbytes / (st["median"] * 1e-3) / 1e9, "unit": "GB/s",
+                    "frac": nbytes / (st["median"] * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        dev0 = torch.device("cuda:0")
+        ceiling["write_only"] = probe(
+            "fill of T float32 (0 B read, 4 B written per token: the advantage stage reads 1 B and writes 4 B)", 4 * T,
+            plain_ms(lambda: torch.empty(T, dtype=torch.float32, device=dev0), lambda o: o.fill_(1.0)))
+        ceiling["read4_write8"] = probe(
+            "torch.frexp of T float32 (one kernel, 4 B read, 8 B written per token: dc_gae reads 5 B and writes 8 B)",
+            12 * T,
+            plain_ms(lambda: (torch.ones(T, dtype=torch.float32, device=dev0),
+                              torch.empty(T, dtype=torch.float32, device=dev0),
+                              torch.empty(T, dtype=torch.int32, device=dev0)),
+                     lambda b: torch.frexp(b[0], out=(b[1], b[2]))))
 
     traffic = None
     table = TRAFFIC_ADV if args.no_rollout_adv else TRAFFIC
