@@ -38,10 +38,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 TRAFFIC_SOURCE = "profiles/hbm_traffic_config5_pmc.txt"
 TRAFFIC = {
     # config: (fetch bytes + write bytes per gather launch, digest of csrc/gather.hip + csrc/dc_internal.h)
-    5: (1044536900 + 985038600, "053e77118e55f191"),
+    5: (1044678400 + 985062200, "0212e81ab9ea787e"),
 }
 TRAFFIC_ADV = {                                          # the same for dc_gather_advantage's kernel
-    5: (867835400 + 983742500, "053e77118e55f191"),
+    5: (867787700 + 983746300, "0212e81ab9ea787e"),
 }
 
 
