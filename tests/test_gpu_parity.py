@@ -494,6 +494,9 @@ def test_balance_beyond_the_lds():
     _check_balance_ws(np.concatenate([[65535], heavy(64 * 300 - 1)]), 64, label="packed rounds, longest length 65535")
     _check_balance_ws(np.concatenate([[65536], heavy(64 * 300 - 1)]), 64, label="one length above the packed words")
     _check_balance_ws(heavy(64 * 1001), 64, label="packed rounds, a short last portion")
+    # the most sequences the call takes
+    _check_balance_ws(heavy(1 << 20), 64, label="2^20 sequences, packed rounds in 64 portions")
+    _check_balance_ws(rng.integers(1, 2000, 1 << 20), 1024, label="2^20 sequences on 1024 workers")
 
 
 def test_more_sequences_than_the_lds_holds():
