@@ -167,10 +167,9 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, co
         // updated keys starts before the round's acceptance test has finished (it is only used if the
         // test passes), which takes the test off the chain of dependent sorts.
         if (all_take && pos + P <= N) {                           // uniform
-            int32_t cmax = mine_exists ? count : 0;
-#pragma unroll
-            for (int d = 32; d >= 1; d >>= 1) cmax = max(cmax, __shfl_xor(cmax, d, WAVE));
-            const int avail = C - __builtin_amdgcn_readfirstlane(cmax);   // rounds before the first worker is full (>= 1)
+            uint32_t cmax = mine_exists ? (uint32_t)count : 0u;
+            wave_all_reduce([&](auto j) { cmax = max(cmax, lane_xor<decltype(j)::value>(cmax)); });
+            const int avail = C - __builtin_amdgcn_readfirstlane((int)cmax);   // rounds before the first worker is full (>= 1)
             const int64_t off = load - (int64_t)(key >> 6);       // what the key does not hold of my worker's load
             int64_t taken = 0;                                    // load taken off the keys by rebasing in here
             int rounds = 0;
@@ -376,22 +375,25 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
         if (all_take && pos + P <= N) {                           // uniform: every worker is open
             // (counts as the rows see them: PORTION counts from the call's start)
             const int32_t in_row = PORTION ? count - row_base : count;
-            int32_t cmax = mine_exists ? in_row : 0, cmin = mine_exists ? in_row : INT32_MAX;
-            int32_t gmax = mine_exists ? count : 0;
-#pragma unroll
-            for (int d = 32; d >= 1; d >>= 1) {
-                cmax = max(cmax, __shfl_xor(cmax, d, WAVE));
-                cmin = min(cmin, __shfl_xor(cmin, d, WAVE));
-                if constexpr (PORTION) gmax = max(gmax, __shfl_xor(gmax, d, WAVE));
-            }
-            const int c_hi = __builtin_amdgcn_readfirstlane(cmax), c_lo = __builtin_amdgcn_readfirstlane(cmin);
+            // (three butterflies of register exchanges, side by side: a shuffle through the LDS unit costs the lone
+            //  wave its whole latency at each of the 6 dependent steps)
+            uint32_t cmax = mine_exists ? (uint32_t)in_row : 0u, cmin = mine_exists ? (uint32_t)in_row : 0x7FFFFFFFu;
+            uint32_t gmax = mine_exists ? (uint32_t)count : 0u;
+            wave_all_reduce([&](auto j) {
+                constexpr int J = decltype(j)::value;
+                const uint32_t a = lane_xor<J>(cmax), b = lane_xor<J>(cmin);
+                cmax = max(cmax, a);
+                cmin = min(cmin, b);
+                if constexpr (PORTION) gmax = max(gmax, lane_xor<J>(gmax));
+            });
+            const int c_hi = __builtin_amdgcn_readfirstlane((int)cmax), c_lo = __builtin_amdgcn_readfirstlane((int)cmin);
             const bool level = c_hi == c_lo;                      // every row holds the same number of items
             const int64_t off = load - (int64_t)(key >> 6);       // what the key does not hold of my worker's load
             int64_t taken = 0;                                    // load taken off the keys by rebasing in here
             int rounds = 0;
             uint32_t sk = wave_sort_asc<WIDTH>(key);
             // >= 1: until a worker (PORTION: or a row) is full or the items run out
-            const int n_rounds = PORTION ? min(min(C - __builtin_amdgcn_readfirstlane(gmax), row_cap - c_hi), (N - pos) / P)
+            const int n_rounds = PORTION ? min(min(C - __builtin_amdgcn_readfirstlane((int)gmax), row_cap - c_hi), (N - pos) / P)
                                          : min(C - c_hi, (N - pos) / P);
             const uint32_t* next_item = items + pos + P + (int)lane;       // the item of the next round for this rank
             const int32_t count4 = in_row * 4;

@@ -73,6 +73,18 @@ __device__ __forceinline__ uint32_t lane_xor(uint32_t v) {
     }
 }
 
+// step(integral_constant J) for J = 1, 2, 4, 8, 16, 32: the six levels of a butterfly over the 64 lanes.  A step that
+// combines every value it keeps with lane_xor<J> of it leaves the reduction over all lanes in every lane.
+template <typename Step>
+__device__ __forceinline__ void wave_all_reduce(Step step) {
+    step(std::integral_constant<int, 1>{});
+    step(std::integral_constant<int, 2>{});
+    step(std::integral_constant<int, 4>{});
+    step(std::integral_constant<int, 8>{});
+    step(std::integral_constant<int, 16>{});
+    step(std::integral_constant<int, 32>{});
+}
+
 template <int K, int J, bool TIED = false>
 __device__ __forceinline__ uint32_t bitonic_step(uint32_t v, uint32_t after = 0) {
     const uint32_t lane = threadIdx.x & 63u;
