@@ -38,10 +38,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 TRAFFIC_SOURCE = "profiles/hbm_traffic_config5_pmc.txt"
 TRAFFIC = {
     # config: (fetch bytes + write bytes per gather launch, digest of csrc/gather.hip + csrc/dc_internal.h)
-    5: (1044678400 + 985062200, "0212e81ab9ea787e"),
+    5: (1044669300 + 985056500, "20a6592dc78a82a9"),
 }
 TRAFFIC_ADV = {                                          # the same for dc_gather_advantage's kernel
-    5: (867787700 + 983746300, "0212e81ab9ea787e"),
+    5: (867824600 + 983736100, "20a6592dc78a82a9"),
 }
 
 
@@ -189,18 +189,48 @@ def main() -> int:
                 b.step_no_rollout_adv(ev)
             else:
                 b.step_fused(ev)
+        elif ev is not None and timing["dispatch"]:
+            b.step_two_calls(None, True, ev)             # the gather's dispatch carries the two events
         else:
             b.step_two_calls(ev, per_token=not args.no_rollout_adv)
 
+    # How a gather launch is timed.  The step of the default mode hands the two events to dc_gather_timed, whose
+    # kernel dispatch updates them with the kernel's own begin and end times (what a profiler's kernel trace
+    # reports); the other modes record them before and after the call, which adds the gaps between the launches.
+    timing = {"dispatch": not (args.single_stream or args.two_streams or args.three_calls or args.no_rollout_adv)}
+
+    def fresh_events(n):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        if timing["dispatch"]:
+            for a, b in ev:                              # torch creates the HIP event at its first record
+                a.record()
+                b.record()
+        return ev
+
+    def check_dispatch_timing(sets):
+        """One step timed both ways; the dispatch's own figure must lie just below the bracketing one."""
+        if not timing["dispatch"]:
+            return
+        inner, outer = fresh_events(1)[0], (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+        torch.cuda.synchronize()
+        sets[0].step_two_calls(outer, True, inner)
+        torch.cuda.synchronize()
+        ti, to = inner[0].elapsed_time(inner[1]), outer[0].elapsed_time(outer[1])
+        if not (0.5 * to <= ti <= 1.02 * to):
+            print(f"bench.py: dispatch events give {ti:.4f} ms against {to:.4f} ms around the call; "
+                  "timing the gather by events around the call", file=sys.stderr)
+            timing["dispatch"] = False
+
     def timed_steps(w, sets, steps, warmup):
         """warmup untimed steps, then `steps` steps between two synchronisations.  Returns wall ms per
-        step, the gather launches' durations (HIP events round each) and the steps' own durations
+        step, the gather launches' durations (HIP events, see `timing`) and the steps' own durations
         (end of one step's gather to the end of the next one's: the steps are queued back to back)."""
         for i in range(warmup):
             one_step(sets[i % len(sets)])
         torch.cuda.synchronize()
         assert all(s.read_status() == 0 for s in sets)
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        check_dispatch_timing(sets)
+        ev = fresh_events(steps)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps):
@@ -523,6 +553,8 @@ def main() -> int:
                      "traffic_source": (TRAFFIC_SOURCE + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, taken earlier on "
                                         "these kernel sources; not measured in this run)") if traffic else None,
                      "algorithmic_bytes_per_launch": timed_gather_bytes, "avg_launch_ms": gather_ms,
+                     "launch_timing": ("begin and end of the kernel's own dispatch (dc_gather_timed)" if timing["dispatch"]
+                                       else "events recorded before and after the launch"),
                      "median_launch_ms": g["launch_ms"]["median"], "min_launch_ms": g["launch_ms"]["min"],
                      "frac_median": g["frac_median"], "frac_best": g["frac_best"]},
         "other_configs": other_configs,

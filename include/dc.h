@@ -275,6 +275,20 @@ dc_status dc_gather(const dc_params* prm, const dc_source* src, const dc_field* 
                     const void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream);
 
 /*
+ * dc_gather whose kernel dispatch carries two events of the caller (hipEvent_t, created with timing enabled;
+ * either may be NULL): hip_event_begins is updated with the time at which the gather kernel starts on the device,
+ * hip_event_ends with the time at which it ends, so that hipEventElapsedTime(begins, ends) is the kernel's own
+ * duration (what a profiler's kernel trace reports), without the gaps that events recorded before and after the
+ * call add.  For callers that measure the data movement of Sec. 6's re-partitioning (Sec. 7 reports its
+ * throughput) in place.  Same arguments, results and errors as dc_gather otherwise; with an empty batch (no
+ * sequences, fields or capacity) nothing is launched and the events are left as they are.
+ */
+dc_status dc_gather_timed(const dc_params* prm, const dc_source* src, const dc_field* fields, int32_t n_fields,
+                          int64_t dst_capacity_tokens, const int64_t* d_dst_tok_off,
+                          const void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream,
+                          void* hip_event_begins, void* hip_event_ends);
+
+/*
  * dc_gather that also makes the per-token advantage field (Sec. 1 payload list; App. B Table 2
  * "advantage") directly in the training layout, from the per-sequence advantages:
  *   d_adv_tok_dst[d_dst_tok_off[j] + t] = m != 0 ? d_adv_seq[d_perm[j]] : +0.0f,

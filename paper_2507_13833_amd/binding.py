@@ -34,7 +34,7 @@ DC_ERR_BAD_LAYOUT = 9
 
 EXPORTS = ("dc_workspace_bytes", "dc_balance", "dc_group_advantage", "dc_plan", "dc_gather",
            "dc_repack", "dc_scatter_workspace_bytes", "dc_scatter", "dc_gae", "dc_balance_group_advantage",
-           "dc_gather_advantage", "dc_balance_workspace_bytes", "dc_balance_ws", "dc_repack_noalloc", "dc_balance_plan_group_advantage", "dc_strerror")
+           "dc_gather_advantage", "dc_balance_workspace_bytes", "dc_balance_ws", "dc_repack_noalloc", "dc_balance_plan_group_advantage", "dc_gather_timed", "dc_strerror")
 
 
 class dc_params(C.Structure):
@@ -91,6 +91,9 @@ def load() -> C.CDLL:
         lib.dc_gather.restype = C.c_int
         lib.dc_gather.argtypes = [C.POINTER(dc_params), C.POINTER(dc_source), C.POINTER(dc_field), C.c_int32,
                                   C.c_int64, vp, vp, C.c_size_t, vp, vp]
+        lib.dc_gather_timed.restype = C.c_int
+        lib.dc_gather_timed.argtypes = [C.POINTER(dc_params), C.POINTER(dc_source), C.POINTER(dc_field), C.c_int32,
+                                        C.c_int64, vp, vp, C.c_size_t, vp, vp, vp, vp]
         lib.dc_gather_advantage.restype = C.c_int
         lib.dc_gather_advantage.argtypes = [C.POINTER(dc_params), C.POINTER(dc_source), C.POINTER(dc_field), C.c_int32,
                                             C.c_int32, vp, vp, vp, C.c_int64, vp, vp, C.c_size_t, vp, vp]
@@ -241,6 +244,28 @@ def dc_gather(prm: dc_params, src: Source, fields: Fields, dst_capacity_tokens: 
     _check(load().dc_gather(C.byref(prm), C.byref(src.struct), fields.array, fields.n, int(dst_capacity_tokens),
                             _ptr(d_dst_tok_off), _ptr(d_ws), int(ws_bytes), _ptr(d_status), _stream(stream)),
            "dc_gather")
+
+
+def _event(ev) -> Optional[int]:
+    """Raw hipEvent_t of a torch.cuda.Event that has been recorded at least once (torch creates the HIP event at
+    its first record), or of an integer handle; None stays None."""
+    if ev is None:
+        return None
+    if isinstance(ev, int):
+        return ev or None
+    h = ev.cuda_event
+    h = getattr(h, "value", h)
+    if not h:
+        raise ValueError("the event has no HIP handle yet: record it once before passing it")
+    return int(h)
+
+
+def dc_gather_timed(prm: dc_params, src: Source, fields: Fields, dst_capacity_tokens: int, d_dst_tok_off,
+                    d_ws, ws_bytes: int, d_status, event_begins, event_ends, stream=None) -> None:
+    _check(load().dc_gather_timed(C.byref(prm), C.byref(src.struct), fields.array, fields.n, int(dst_capacity_tokens),
+                                  _ptr(d_dst_tok_off), _ptr(d_ws), int(ws_bytes), _ptr(d_status), _stream(stream),
+                                  _event(event_begins), _event(event_ends)),
+           "dc_gather_timed")
 
 
 def dc_gather_advantage(prm: dc_params, src: Source, fields: Fields, mask_field: int, d_perm, d_adv_seq,

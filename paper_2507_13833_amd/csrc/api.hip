@@ -317,6 +317,14 @@ dc_status dc_plan(const dc_params* prm, const dc_source* src, const int32_t* d_s
 dc_status dc_gather(const dc_params* prm, const dc_source* src, const dc_field* fields, int32_t n_fields,
                     int64_t dst_capacity_tokens, const int64_t* d_dst_tok_off,
                     const void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream) {
+    return dc_gather_timed(prm, src, fields, n_fields, dst_capacity_tokens, d_dst_tok_off, d_ws, ws_bytes, d_status,
+                           hip_stream, nullptr, nullptr);
+}
+
+dc_status dc_gather_timed(const dc_params* prm, const dc_source* src, const dc_field* fields, int32_t n_fields,
+                          int64_t dst_capacity_tokens, const int64_t* d_dst_tok_off,
+                          const void* d_ws, size_t ws_bytes, int32_t* d_status, void* hip_stream,
+                          void* hip_event_begins, void* hip_event_ends) {
     (void)d_status;
     dc_status rc = check_params(prm);
     if (rc != DC_OK) return rc;
@@ -334,7 +342,8 @@ dc_status dc_gather(const dc_params* prm, const dc_source* src, const dc_field* 
     rc = fill_field_table(fields, n_fields, sd, dst_capacity_tokens, &ft);
     if (rc != DC_OK) return rc;
     hipError_t e = launch_gather(prm->n_seq, ft, dst_capacity_tokens, d_dst_tok_off, ws,
-                                 static_cast<hipStream_t>(hip_stream));
+                                 static_cast<hipStream_t>(hip_stream), static_cast<hipEvent_t>(hip_event_begins),
+                                 static_cast<hipEvent_t>(hip_event_ends));
     return e == hipSuccess ? DC_OK : DC_ERR_HIP;
 }
 

@@ -158,8 +158,11 @@ hipError_t launch_plan(const dc_params& prm, const SourceDesc& src, const int64_
                        int32_t* d_shard_mb_off, int32_t* d_mb_seq_off, int32_t* d_cu_seqlens,
                        int32_t* d_n_mb, const Workspace& ws, int32_t* d_status, hipStream_t st);
 
+// begins / ends (each may be null): events that the kernel's dispatch itself updates with the times at which the
+// kernel starts and ends on the device.
 hipError_t launch_gather(int32_t n_seq, const FieldTable& ft, int64_t dst_capacity,
-                         const int64_t* d_dst_tok_off, const Workspace& ws, hipStream_t st);
+                         const int64_t* d_dst_tok_off, const Workspace& ws, hipStream_t st,
+                         hipEvent_t begins = nullptr, hipEvent_t ends = nullptr);
 
 // launch_gather plus the float32 advantage arena d_adv_tok_dst, made from field mask_field (1-byte
 // elements) and the per-sequence advantages; the workgroups that make it also move the mask.

@@ -24,6 +24,7 @@
 // and a byte funnel shift for 1- and 2-byte fields) and one aligned 16-byte store;
 // a chunk that touches a slot boundary, padding or the arena end is copied element
 // by element.
+#include <hip/hip_ext.h>
 #include "dc_device.h"
 #include "dc_internal.h"
 
@@ -751,7 +752,8 @@ static int order_fields(const FieldTable& ft, int64_t tiles, FieldTable* sorted,
 }
 
 hipError_t launch_gather(int32_t n_seq, const FieldTable& ft, int64_t dst_capacity,
-                         const int64_t* d_dst_tok_off, const Workspace& ws, hipStream_t st) {
+                         const int64_t* d_dst_tok_off, const Workspace& ws, hipStream_t st,
+                         hipEvent_t begins, hipEvent_t ends) {
     if (n_seq == 0 || ft.n_fields == 0 || dst_capacity == 0) return hipSuccess;
     GatherArgs a;
     a.n_seq = n_seq;
@@ -767,7 +769,11 @@ hipError_t launch_gather(int32_t n_seq, const FieldTable& ft, int64_t dst_capaci
         return hipErrorInvalidValue;
     FieldTable sorted;
     order_fields(ft, tiles, &sorted, &a);
-    hipLaunchKernelGGL(gather_kernel, dim3((unsigned)(tiles * a.n_carriers)), dim3(GATHER_BLOCK), 0, st, a, sorted);
+    if (begins || ends)                                   // the dispatch itself carries the two events
+        hipExtLaunchKernelGGL(gather_kernel, dim3((unsigned)(tiles * a.n_carriers)), dim3(GATHER_BLOCK), 0, st, begins, ends,
+                              0, a, sorted);
+    else
+        hipLaunchKernelGGL(gather_kernel, dim3((unsigned)(tiles * a.n_carriers)), dim3(GATHER_BLOCK), 0, st, a, sorted);
     return hipGetLastError();
 }
 

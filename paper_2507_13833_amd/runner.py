@@ -104,7 +104,13 @@ class DeviceBatch:
                   self.dst_tok_off, self.shard_tok_off, self.shard_mb_off, self.mb_seq_off, self.cu_seqlens,
                   self.n_mb, self.ws, self.ws_bytes, self.status)
 
-    def gather(self) -> None:
+    def gather(self, dispatch_events=None) -> None:
+        """dispatch_events: optional (begins, ends) torch events, each recorded once before, that the gather kernel's
+        dispatch updates with its own start and end times (dc_gather_timed)."""
+        if dispatch_events is not None:
+            B.dc_gather_timed(self.prm, self.source, self.fields, self.capacity, self.dst_tok_off, self.ws,
+                              self.ws_bytes, self.status, dispatch_events[0], dispatch_events[1])
+            return
         B.dc_gather(self.prm, self.source, self.fields, self.capacity, self.dst_tok_off, self.ws,
                     self.ws_bytes, self.status)
 
@@ -155,15 +161,16 @@ class DeviceBatch:
                                           self.shard_tok_off, self.shard_mb_off, self.mb_seq_off, self.cu_seqlens,
                                           self.n_mb, self.ws, self.ws_bytes, self.status)
 
-    def step_two_calls(self, gather_events=None, per_token: bool = True) -> None:
+    def step_two_calls(self, gather_events=None, per_token: bool = True, dispatch_events=None) -> None:
         """The whole pass as two calls: dc_balance_plan_group_advantage (balance, advantage stage and plan: two
         launches where the shape allows it), then the gather.  gather_events: optional (start, end) torch events
-        recorded around the gather launch."""
+        recorded around the gather launch; dispatch_events: optional (begins, ends) events carried by the gather
+        kernel's dispatch itself (see gather)."""
         self.balance_plan_group_advantage(per_token)
         if gather_events is not None:
             gather_events[0].record()
         if per_token:
-            self.gather()
+            self.gather(dispatch_events)
         else:
             self.gather_advantage()
         if gather_events is not None:

@@ -215,6 +215,40 @@ def test_balance_and_plan_in_one_call_status_codes():
     assert not d.perm.any()                                            # nothing ran
 
 
+@pytest.mark.parametrize("cfg", [2, 5])
+def test_gather_whose_dispatch_carries_the_timing_events(cfg):
+    """dc_gather_timed: the same arenas as dc_gather, bit for bit, and two events that hold the kernel's own begin
+    and end: a positive duration that does not exceed the one of events recorded round the call."""
+    torch, binding, runner = _gpu()
+    w = workloads.make_workload(cfg)
+    d = check_step(w, label=f"config {cfg}, then dc_gather_timed", two_calls=True)
+    want = {k: v.clone() for k, v in d.dst_fields.items()}
+    for v in d.dst_fields.values():
+        v.view(torch.uint8).fill_(0x5A)
+    inner = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+    outer = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+    if not inner[0].cuda_event:                          # torch creates the HIP event at its first record:
+        with pytest.raises(ValueError):                  # before that there is no handle to pass
+            d.gather(inner)
+    for e in inner:
+        e.record()
+    torch.cuda.synchronize()
+    outer[0].record()
+    d.gather(inner)
+    outer[1].record()
+    torch.cuda.synchronize()
+    assert d.read_status() == 0
+    for k, v in d.dst_fields.items():
+        assert torch.equal(want[k], v), k
+    ti, to = inner[0].elapsed_time(inner[1]), outer[0].elapsed_time(outer[1])
+    print(f"[parity] gather timed by its dispatch: {ti:.4f} ms, by events round the call: {to:.4f} ms", flush=True)
+    assert 0.0 < ti <= to * 1.02
+    # one event alone, and none at all
+    d.gather((inner[0], None)); d.gather((None, None))
+    torch.cuda.synchronize()
+    assert d.read_status() == 0
+
+
 def test_step_replayed_from_a_hip_graph():
     """Every call only enqueues kernels on the given stream and allocates nothing, so a step can be captured
     in a HIP graph.  Each replay (with eager work and synchronisations in between) must reproduce the eager
