@@ -307,7 +307,12 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, co
 //   - takes the worker's count from a cross-lane read only when the workers' counts differ at the phase's
 //     start (they do not unless rounds with fewer takers came before);
 //   - runs FAST_BATCH rounds as one straight piece of code without a test when a bound says that all of
-//     them will stand, and one round at a time with the exact test otherwise.
+//     them will stand, and one round at a time with the exact test otherwise;
+//   - finishes a round that fails the test where it stands, as a short round (the accepted prefix of the ranks
+//     takes its items, the keys are sorted again, the workers that sat out are told so by one cross-lane write),
+//     instead of sending the keys back to the workers' lanes for a general round and sorting them twice more
+//     on the way back in.  While no worker is full a worker's place in its row is its place at the phase's
+//     start plus the round number minus the rounds it sat out.
 // The bound: keys come in ascending order and items in descending order.  With D = largest - smallest key,
 // a round stands if D < its smallest item (the largest key is then below every updated key), and it leaves
 // D' <= max(D, its largest - its smallest item).  So a run of rounds stands if D < L and F - L < L, where
@@ -387,7 +392,7 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
                 if constexpr (PORTION) gmax = max(gmax, lane_xor<J>(gmax));
             });
             const int c_hi = __builtin_amdgcn_readfirstlane((int)cmax), c_lo = __builtin_amdgcn_readfirstlane((int)cmin);
-            const bool level = c_hi == c_lo;                      // every row holds the same number of items
+            bool level = c_hi == c_lo;                            // every row holds the same number of items (until a short round)
             const int64_t off = load - (int64_t)(key >> 6);       // what the key does not hold of my worker's load
             int64_t taken = 0;                                    // load taken off the keys by rebasing in here
             int rounds = 0;
@@ -396,7 +401,8 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
             const int n_rounds = PORTION ? min(min(C - __builtin_amdgcn_readfirstlane((int)gmax), row_cap - c_hi), (N - pos) / P)
                                          : min(C - c_hi, (N - pos) / P);
             const uint32_t* next_item = items + pos + P + (int)lane;       // the item of the next round for this rank
-            const int32_t count4 = in_row * 4;
+            int32_t count4 = in_row * 4;                          // lane k: 4 x (worker k's place in its row at round 0 of the phase)
+            uint64_t refused_acc = 0;                             // ranks a refused round would have accepted
 
             // One round that is known to stand; r = rounds done before it in this phase.  LEVEL: all counts are c_lo.
             auto sure_round = [&](int r, auto level_c) {
@@ -421,8 +427,8 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
                 sk = v;
             };
             // One round with the exact test (every rank's key below the smallest updated key of the ranks before
-            // it); false, and nothing changed, if it does not stand.  The row entry is written before the outcome
-            // is known: after a refusal the general round files the worker's next item in the same place.
+            // it); false, and nothing changed but refused_acc, if it does not stand.  The row entry is written before
+            // the outcome is known: a worker that does not take the item files its next one in the same place.
             auto tested_round = [&](int r) -> bool {
                 const uint32_t sk_in = sk, e_in = e;
                 uint32_t v = sk + ((e >> 16) << 6);
@@ -448,10 +454,33 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
                     if constexpr (S == 11) m = dpp_mov<DPP_WAVE_SHR1>(NONE, m);
                     if constexpr (S == 13) e = e1;
                 });
-                if (__builtin_expect((__ballot(sk_in < m) & everyone) != everyone, 0)) { e = e_in; return false; }
+                const uint64_t acc = __ballot(sk_in < m) & everyone;
+                if (__builtin_expect(acc != everyone, 0)) { e = e_in; refused_acc = acc; return false; }
                 next_item += P;
                 sk = v;
                 return true;
+            };
+            // What a refused round turns into: the longest accepted prefix of the ranks takes the items the refused
+            // round offered them (its row entries are written already), the other workers stay where they are, and
+            // the phase goes on: a worker's place in its row falls one behind the round number for every round it
+            // sits out (count4, told to the worker's lane), and the next round's items start behind the ones taken.
+            auto short_round = [&]() {
+                const int took = __ffsll((long long)~refused_acc) - 1;     // >= 1: the lowest rank always takes
+                const bool take = (int)lane < took;
+                uint32_t v = take ? sk + ((e >> 16) << 6) : sk;
+                const uint32_t to = mine_exists ? (sk & 63u) : lane;        // lanes without a worker talk to themselves
+                const uint32_t* const at = items + pos + took + (int)lane;  // (the array is padded)
+                uint32_t e1 = 0;
+                int32_t behind4 = 0;
+                v = wave_sort_steps<WIDTH, 0, NS>(v, [&](auto slot) {
+                    constexpr int S = decltype(slot)::value;
+                    if constexpr (S == 0) e1 = *at;
+                    if constexpr (S == 1) behind4 = __builtin_amdgcn_ds_permute((int)(to << 2), take ? 0 : 4);
+                    if constexpr (S == 12) { count4 -= behind4; e = e1; }
+                });
+                sk = v;
+                next_item = at + P;
+                pos += took;
             };
 
             while (rounds < n_rounds) {
@@ -501,29 +530,26 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
                     // rounds with the exact test, in a loop of their own, until the next look or check
                     int burst = max(1, min(min(n_rounds - rounds, until_check), no_look + 1));
                     const int want = burst;
-                    bool stands = true;
                     do {
-                        stands = tested_round(rounds);
-                        if (!stands) break;
-                        pos += P;
+                        if (tested_round(rounds)) pos += P;
+                        else { short_round(); level = false; }
                         rounds += 1;
                     } while (--burst > 0);
                     until_check -= (want - burst) - 1;            // (one was taken off at the loop's top)
                     no_look -= want - burst;
-                    if (!stands) break;
                 }
             }
             // back to worker lanes: rank r sends its key to lane (sk & 63); lanes without a worker send theirs to themselves
             if (!mine_exists) sk = full;                          // (whatever the rounds left in their lanes)
             key = (uint32_t)__builtin_amdgcn_ds_permute((int)((sk & 63u) << 2), (int)sk);
             if (mine_exists) {
-                count += rounds;
+                count = (count4 >> 2) + rounds + (PORTION ? row_base : 0);      // one item per round but the ones sat out
                 load = off + taken + (int64_t)(key >> 6);
                 if (count == C) key = full;
             }
             until_check = 1;
             all_take = false;
-            if (rounds > 0) continue;                             // else: the general round below decides exactly
+            continue;                                             // (rounds >= 1: a worker is full now, or the items have run out)
         }
 
         // ---- a general round: the longest accepted prefix of the ranks takes one item each ----
