@@ -686,6 +686,113 @@ __device__ __forceinline__ int lpt_rounds_wide_portion(BalLds& L, int N, int P, 
     return pos;
 }
 
+// The same portion with lengths below 2^16 (max_len <= PACKED_MAX_LEN): 32-bit keys, (load - base) << 10 | k with
+// the base taken off whenever the smallest key has passed 2^30 (open workers lie within one longest sequence of the
+// smallest, a round adds at most one more, so the keys stay below 2^32: see lpt_rounds), and the ranks are found
+// without looking at every key: each wave sorts its 64 keys in registers, leaves the sorted run in the LDS, and a
+// key's rank is its place in its own run plus, by bisection, the keys below it in every other run (7 probes per
+// run where counting took one read and one compare per worker).  The carry is WideCarry's, the key in its low word.
+constexpr uint32_t W32_FULL = ~(uint32_t)WIDE_ID_MASK;               // | worker id: full (or absent) worker
+constexpr uint32_t W32_ID_MASK = (uint32_t)WIDE_ID_MASK;
+static_assert(((uint64_t)PACKED_MAX_LEN << WIDE_ID_BITS) < (1ull << 27), "a round adds less than 2^27 to a key");
+
+// Keys of run r (64 ascending words) below v, for four runs at a time (their probes do not depend on each other).
+__device__ __forceinline__ int keys_below4(const uint32_t* run, const int (&r)[4], const bool (&use)[4], uint32_t v) {
+    int lo[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int step = WAVE / 2; step >= 1; step >>= 1) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (run[r[i] * WAVE + lo[i] + step - 1] < v) lo[i] += step;
+    }
+    int below = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (run[r[i] * WAVE + lo[i]] < v) lo[i] += 1;                 // (all 64 below)
+        below += use[i] ? lo[i] : 0;
+    }
+    return below;
+}
+
+__device__ __forceinline__ int lpt_rounds_wide32_portion(BalLds& L, int N, int P, int C, const uint16_t* sorted,
+                                                         uint16_t* step_slot, WideCarry& carry) {
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
+    const int nw = (P + WAVE - 1) / WAVE;                             // waves that keep workers
+    uint32_t* run = reinterpret_cast<uint32_t*>(L.cnt);               // every wave's keys, sorted
+    uint32_t* sbuf = run + DC_MAX_SHARDS;                             // keys in rank order
+    uint32_t* kbuf = sbuf + DC_MAX_SHARDS;                            // the updated keys on their way back to the workers
+    static_assert(3 * DC_MAX_SHARDS <= 256 * BAL_WAVES, "three key tables fit the counters");
+    const uint32_t full = W32_FULL | (uint32_t)tid;
+    uint32_t key = carry.key >= WIDE_FULL ? full : (uint32_t)carry.key;
+    int32_t count = carry.count;
+    int64_t load = carry.load;
+    int pos = 0;
+    uint32_t low = 0;                                                 // the smallest key of the round before (uniform)
+    while (pos < N) {                                                 // pos is the same in every thread
+        if (low >= 0x40000000u && low < W32_FULL && key < W32_FULL) key -= low & ~W32_ID_MASK;      // rebase
+        uint32_t mine = 0xFFFFFFFFu;                                  // lane r of wave w: the r-th smallest key of the wave
+        if (w < nw) {                                                 // (uniform)
+            mine = wave_sort_asc<WAVE>(key);
+            run[tid] = mine;
+        }
+        __syncthreads();
+        if (w < nw) {
+            int rank = lane;
+            for (int q0 = 0; q0 < nw; q0 += 4) {                      // (uniform)
+                int r[4];
+                bool use[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    use[i] = q0 + i < nw && q0 + i != w;
+                    r[i] = min(q0 + i, nw - 1);
+                }
+                rank += keys_below4(run, r, use, mine);
+            }
+            sbuf[min(rank, DC_MAX_SHARDS - 1)] = mine;                // (keys are distinct: every rank is taken once)
+        }
+        __syncthreads();
+        // ---- rank view: thread r offers item I[pos + r] to the worker with the r-th smallest key ----
+        const uint32_t sk = tid < P ? sbuf[tid] : 0xFFFFFFFFu;
+        low = sbuf[0];
+        const int t = pos + tid;
+        const bool valid = tid < P && sk < W32_FULL && t < N;
+        const uint32_t s = valid ? (uint32_t)L.keys[sorted[t]] : 0u;
+        const uint32_t newk = valid ? sk + (s << WIDE_ID_BITS) : 0xFFFFFFFFu;
+        // smallest updated key among the ranks below mine
+        const uint32_t inc = wave_incl_scan_umin(newk);
+        uint32_t pm = dpp_mov<DPP_WAVE_SHR1>(0xFFFFFFFFu, inc);
+        if (lane == WAVE - 1) L.tmp32[w] = inc;
+        __syncthreads();
+        for (int q = 0; q < w; ++q) pm = umin32(pm, L.tmp32[q]);
+        // accepted prefix: ranks below the first one whose worker is no longer the minimum
+        const uint64_t fail = __ballot(!(valid && sk < pm));
+        if (lane == 0) L.red[w] = fail ? w * WAVE + (__ffsll((long long)fail) - 1) : BAL_BLOCK;
+        __syncthreads();
+        int m = BAL_BLOCK;
+        for (int q = 0; q < BAL_WAVES; ++q) m = min(m, L.red[q]);
+        if (m == 0) break;                                            // cannot happen: cap * P >= N (uniform)
+        // back to the workers: rank r sends its updated key, its own rank in place of the worker id
+        if (tid < m) kbuf[sk & W32_ID_MASK] = (newk & ~W32_ID_MASK) | (uint32_t)tid;
+        const uint32_t thr = sbuf[m - 1];
+        __syncthreads();
+        if (tid < P && key <= thr) {                                  // my worker is among the m smallest
+            const uint32_t recv = kbuf[tid];
+            const uint32_t nk = (recv & ~W32_ID_MASK) | (uint32_t)tid;
+            const int took = pos + (int)(recv & W32_ID_MASK);         // the item I took
+            step_slot[took] = (uint16_t)count;
+            L.keys[sorted[took]] = tid;                               // placed: its length is not needed again
+            load += (int64_t)((nk - key) >> WIDE_ID_BITS);
+            count += 1;
+            key = (count == C) ? full : nk;
+        }
+        pos += m;
+        // (the next round writes run[] first; sbuf and kbuf are rewritten two and four barriers from here)
+    }
+    carry.key = key >= W32_FULL ? (WIDE_FULL | (uint64_t)tid) : (uint64_t)key;
+    carry.count = count; carry.load = load;
+    return pos;
+}
+
 // After the last portion: part_off[0..P] gets the start of every P_k, the outputs their tables (N: all items).
 __device__ __forceinline__ void lpt_wide_finish(BalLds& L, int N, int P, const WideCarry& carry,
                                                 int32_t* __restrict__ shard_seq_off, int64_t* __restrict__ shard_load) {
@@ -699,9 +806,11 @@ __device__ __forceinline__ void lpt_wide_finish(BalLds& L, int N, int P, const W
 }
 
 __device__ __forceinline__ int lpt_rounds_wide(BalLds& L, int N, int P, int C, const uint16_t* sorted, uint16_t* step_slot,
-                                               int32_t* __restrict__ shard_seq_off, int64_t* __restrict__ shard_load) {
+                                               int32_t max_len, int32_t* __restrict__ shard_seq_off,
+                                               int64_t* __restrict__ shard_load) {
     WideCarry carry = wide_fresh(P, C);
-    const int placed = lpt_rounds_wide_portion(L, N, P, C, sorted, step_slot, carry);
+    const int placed = (uint32_t)max_len <= PACKED_MAX_LEN ? lpt_rounds_wide32_portion(L, N, P, C, sorted, step_slot, carry)
+                                                           : lpt_rounds_wide_portion(L, N, P, C, sorted, step_slot, carry);
     lpt_wide_finish(L, N, P, carry, shard_seq_off, shard_load);
     return placed;
 }
@@ -839,7 +948,7 @@ __device__ __forceinline__ void balance_body_t(BalLds& L, int32_t N, int32_t P, 
     uint16_t* step_slot = dst;                                    // place of I[t] inside its worker's partition
     // ---- b) assignment rounds: wave 0 for up to 64 workers, else the whole workgroup ----
     if (P > WAVE) {
-        const int n_placed = lpt_rounds_wide(L, N, P, C, sorted, step_slot, shard_seq_off, shard_load);
+        const int n_placed = lpt_rounds_wide(L, N, P, C, sorted, step_slot, mx, shard_seq_off, shard_load);
         if (tid == 0) *placed = n_placed;
     } else if (w == 0) {
         int32_t* worker_count = reinterpret_cast<int32_t*>(L.cnt) + WCOUNT_AT;

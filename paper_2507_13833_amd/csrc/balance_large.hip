@@ -97,7 +97,8 @@ __global__ __launch_bounds__(BAL_BLOCK) void balance_large_kernel(int32_t N, int
         }
         __syncthreads();
         if (P > WAVE) {
-            lpt_rounds_wide_portion(L, n, P, C, L.idx_a, L.idx_b, wide);
+            if ((uint32_t)mx <= PACKED_MAX_LEN) lpt_rounds_wide32_portion(L, n, P, C, L.idx_a, L.idx_b, wide);
+            else lpt_rounds_wide_portion(L, n, P, C, L.idx_a, L.idx_b, wide);
         } else if (w == 0) {
             if (P <= 16) lpt_rounds<16>(n, P, C, L.keys, L.idx_a, mx, L.idx_b, 0, L.spare, worker_count, shard_load, carry);
             else if (P <= 32) lpt_rounds<32>(n, P, C, L.keys, L.idx_a, mx, L.idx_b, 0, L.spare, worker_count, shard_load, carry);
