@@ -24,12 +24,20 @@
  *                       produced go back from the packed training layout to the
  *                       rollout layout (the collect / concat side of a stage
  *                       transition, App. B Table 2).
+ *   dc_gae              the advantage stage of PPO (Sec. 7.1 evaluates PPO with a critic).
+ *   dc_balance_group_advantage, dc_balance_plan_group_advantage
+ *                       the calls above that depend on nothing but the lengths and the rewards, issued
+ *                       as one and as two launches (same results).
+ *   dc_repack_noalloc, dc_gather_timed
+ *                       dc_repack without a workspace argument, for callers that cannot allocate;
+ *                       dc_gather whose dispatch carries the caller's timing events.
  *
  * Conventions
  *   - Pointers named d_* are DEVICE pointers (gfx950, current HIP device).  All
  *     other pointers are HOST pointers, read during the call only.
  *   - The caller owns every buffer: inputs, outputs and workspace.  The library
- *     allocates nothing and keeps no state between calls.
+ *     allocates nothing and keeps no state between calls (dc_repack_noalloc alone
+ *     plans in a device array of the library's own, see there).
  *   - Every call only enqueues kernels on `hip_stream` (a hipStream_t passed as
  *     void*, NULL = the default stream) and returns; nothing synchronises.
  *   - The return value reports what the host can check without a sync.  Errors
