@@ -52,3 +52,14 @@ def test_bf16_rounding_is_nearest_even():
     b = workloads.f32_to_bf16_bits(x)
     # 1.00390625 = 1 + 2^-8 is a tie between 1.0 and 1+2^-7 -> even mantissa (1.0)
     assert b.tolist() == [0x3F80, 0x3F80, 0x3F82, 0xC020, 0x4049]
+
+
+def test_sequence_lengths_are_the_workloads_own():
+    """sequence_lengths draws what make_workload draws first: the same lengths without the payload."""
+    for cfg in (1, 3, 5):
+        w = workloads.make_workload(cfg, prompts=24)
+        assert np.array_equal(workloads.sequence_lengths(cfg, w.n_seq), w.seq_len)
+    big = workloads.sequence_lengths(5, 65536)
+    assert big.shape == (65536,) and big.dtype == np.int32 and big.min() >= 512 + 64 and big.max() <= 4096 + 32768
+    with pytest.raises(ValueError):
+        workloads.sequence_lengths(5, 100)                 # not a multiple of the group size
