@@ -10,6 +10,9 @@ namespace dc {
 
 constexpr int BAL_BLOCK = 1024;
 constexpr int BAL_WAVES = BAL_BLOCK / WAVE;
+// Row length of the sort's (digit, wave) counters: odd, so that the digits' rows start in different LDS banks.  (With
+// rows of 16 words the 64 lanes of a wave, each at its own digit and all at the same wave index, met in two banks.)
+constexpr int CNT_PITCH = BAL_WAVES + 1;
 constexpr int BAL_ROUNDS = DC_MAX_SEQ / BAL_BLOCK;       // 64-item rounds per wave at the size limit
 constexpr uint32_t KEY_FULL = 0xFFFFFFC0u;               // | worker id: full (or absent) worker
 
@@ -24,7 +27,7 @@ struct BalLds {
     uint16_t idx_a[DC_MAX_SEQ + PLACE_PAD];   // sort ping
     uint16_t idx_b[DC_MAX_SEQ + PLACE_PAD];   // sort pong; after the sort the free one holds every item's place in its
                                               // partition, or (all partitions of equal size) the partitions themselves
-    alignas(16) uint32_t cnt[256 * BAL_WAVES];   // [digit][wave] counters of the sort passes; afterwards the workers' tables
+    alignas(16) uint32_t cnt[256 * CNT_PITCH];   // [digit][wave] counters of the sort passes; afterwards the workers' tables
     int32_t  red[2 * BAL_WAVES];
     uint32_t tmp32[16];
     int32_t  spare[2];                    // where lanes without a worker put the stores of a round
@@ -46,7 +49,7 @@ template <typename DigitFn, typename EmitFn>
 __device__ __forceinline__ void counting_pass(BalLds& L, int N, int rounds, DigitFn digit, EmitFn emit) {
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
     const int wave_base = w * rounds * WAVE;
-    for (int i = tid; i < 256 * BAL_WAVES; i += BAL_BLOCK) L.cnt[i] = 0;
+    for (int i = tid; i < 256 * CNT_PITCH; i += BAL_BLOCK) L.cnt[i] = 0;
     __syncthreads();
     uint32_t packed[BAL_ROUNDS];                                  // digit << 16 | rank before me in my wave
 #pragma unroll
@@ -74,7 +77,7 @@ __device__ __forceinline__ void counting_pass(BalLds& L, int N, int rounds, Digi
             const int leader = valid ? (__ffsll((long long)peers) - 1) : lane;
             uint32_t old = 0;
             if (valid && lane == leader) {                        // one lane per distinct digit
-                uint32_t* c = &L.cnt[d * BAL_WAVES + w];
+                uint32_t* c = &L.cnt[d * CNT_PITCH + w];
                 old = *c;
                 *c = old + (uint32_t)__popcll(peers);
             }
@@ -83,14 +86,16 @@ __device__ __forceinline__ void counting_pass(BalLds& L, int N, int rounds, Digi
         }
     }
     __syncthreads();
-    {   // exclusive scan of the 4096 counters in (digit, wave) order
+    {   // exclusive scan of the 4096 counters in (digit, wave) order: thread t takes digit t / 4, waves 4 (t % 4) ...
+        static_assert(BAL_BLOCK * 4 == 256 * BAL_WAVES, "four counters per thread");
+        uint32_t* mine = &L.cnt[(tid >> 2) * CNT_PITCH + (tid & 3) * 4];
         uint32_t c4[4], s = 0;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) { c4[q] = L.cnt[tid * 4 + q]; s += c4[q]; }
+        for (int q = 0; q < 4; ++q) { c4[q] = mine[q]; s += c4[q]; }
         uint32_t tot;
         uint32_t run = block_excl_scan_add<uint32_t>(s, L.tmp32, &tot);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) { L.cnt[tid * 4 + q] = run; run += c4[q]; }
+        for (int q = 0; q < 4; ++q) { mine[q] = run; run += c4[q]; }
     }
     __syncthreads();
 #pragma unroll
@@ -99,7 +104,7 @@ __device__ __forceinline__ void counting_pass(BalLds& L, int N, int rounds, Digi
             const int pos = wave_base + r * WAVE + lane;
             if (pos < N) {
                 const uint32_t d = packed[r] >> 16, rk = packed[r] & 0xFFFFu;
-                emit(pos, (int)(L.cnt[d * BAL_WAVES + w] + rk));
+                emit(pos, (int)(L.cnt[d * CNT_PITCH + w] + rk));
             }
         }
     }

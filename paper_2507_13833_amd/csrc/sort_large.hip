@@ -88,12 +88,13 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_scan_kernel(uint32_t* counts,
 }
 
 __global__ __launch_bounds__(SORT_BLOCK) void sort_scatter_kernel(SortArgs a) {
-    __shared__ uint32_t cnt[256 * SORT_WAVES];                    // [digit][wave]: first counts, then the wave's next place
+    constexpr int PITCH = SORT_WAVES + 1;                         // odd: the digits' rows start in different LDS banks
+    __shared__ uint32_t cnt[256 * PITCH];                         // [digit][wave]: first counts, then the wave's next place
     __shared__ uint32_t tmp[SORT_WAVES];
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
     uint32_t n_all;
     const uint32_t digit_start = block_excl_scan_add<uint32_t>(a.totals[tid], tmp, &n_all);      // tid = digit
-    for (int i = tid; i < 256 * SORT_WAVES; i += SORT_BLOCK) cnt[i] = 0;
+    for (int i = tid; i < 256 * PITCH; i += SORT_BLOCK) cnt[i] = 0;
     __syncthreads();
     const int begin = blockIdx.x * SORT_TILE + w * SORT_PER_WAVE, end = min(a.n, begin + SORT_PER_WAVE);
     for (int sweep = 0; sweep < 2; ++sweep) {
@@ -113,7 +114,7 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_scatter_kernel(SortArgs a) {
             const int leader = valid ? (__ffsll((long long)peers) - 1) : lane;
             uint32_t old = 0;
             if (valid && lane == leader) {                        // one lane per distinct digit
-                uint32_t* c = &cnt[d * SORT_WAVES + w];
+                uint32_t* c = &cnt[d * PITCH + w];
                 old = *c;
                 *c = old + (uint32_t)__popcll(peers);
             }
@@ -130,7 +131,7 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_scatter_kernel(SortArgs a) {
             const uint32_t start = digit_start + a.counts[(size_t)tid * a.n_tiles + blockIdx.x];
             uint32_t run = start;
 #pragma unroll
-            for (int q = 0; q < SORT_WAVES; ++q) { const uint32_t c = cnt[tid * SORT_WAVES + q]; cnt[tid * SORT_WAVES + q] = run; run += c; }
+            for (int q = 0; q < SORT_WAVES; ++q) { const uint32_t c = cnt[tid * PITCH + q]; cnt[tid * PITCH + q] = run; run += c; }
             __syncthreads();
         }
     }
