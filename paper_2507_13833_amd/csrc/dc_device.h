@@ -15,26 +15,49 @@ __device__ __forceinline__ void set_status(int32_t* d_status, int32_t code) {
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (WAVE - 1); }
 
-// ---- wave64 scans (shuffles lower to DPP / ds_bpermute) ----
+// ---- wave64 scans: six steps of register moves between lanes (DPP), nothing goes through the LDS unit ----
+// Step controls: lane i takes lane i - 1 / 2 / 4 / 8 of its row of 16; then lane 15 of a row is sent to every lane of
+// the next row (rows 1 and 3), then lane 31 to rows 2 and 3.  A lane that the step does not reach keeps `identity`.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ uint32_t scan_step(uint32_t identity, uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)identity, (int)v, CTRL, ROW_MASK, 0xF, false);
+}
+template <typename Combine>
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v, uint32_t identity, Combine combine) {
+    v = combine(v, scan_step<0x111>(identity, v));
+    v = combine(v, scan_step<0x112>(identity, v));
+    v = combine(v, scan_step<0x114>(identity, v));
+    v = combine(v, scan_step<0x118>(identity, v));
+    v = combine(v, scan_step<0x142, 0xA>(identity, v));
+    v = combine(v, scan_step<0x143, 0xC>(identity, v));
+    return v;
+}
+__device__ __forceinline__ uint64_t scan_step_add64(uint64_t v, uint32_t lo, uint32_t hi) { return v + (((uint64_t)hi << 32) | lo); }
+
 template <typename T>
 __device__ __forceinline__ T wave_incl_scan_add(T v) {
-    const int lane = lane_id();
-#pragma unroll
-    for (int d = 1; d < WAVE; d <<= 1) {
-        T o = __shfl_up(v, d, WAVE);
-        if (lane >= d) v += o;
+    static_assert(sizeof(T) == 4 || sizeof(T) == 8, "32- or 64-bit integers");
+    if constexpr (sizeof(T) == 4) {
+        return (T)wave_incl_scan_u32((uint32_t)v, 0u, [](uint32_t a, uint32_t b) { return a + b; });
+    } else {
+        uint64_t x = (uint64_t)v;                         // both halves take the same step; the carry is the adder's
+        x = scan_step_add64(x, scan_step<0x111>(0u, (uint32_t)x), scan_step<0x111>(0u, (uint32_t)(x >> 32)));
+        x = scan_step_add64(x, scan_step<0x112>(0u, (uint32_t)x), scan_step<0x112>(0u, (uint32_t)(x >> 32)));
+        x = scan_step_add64(x, scan_step<0x114>(0u, (uint32_t)x), scan_step<0x114>(0u, (uint32_t)(x >> 32)));
+        x = scan_step_add64(x, scan_step<0x118>(0u, (uint32_t)x), scan_step<0x118>(0u, (uint32_t)(x >> 32)));
+        x = scan_step_add64(x, scan_step<0x142, 0xA>(0u, (uint32_t)x), scan_step<0x142, 0xA>(0u, (uint32_t)(x >> 32)));
+        x = scan_step_add64(x, scan_step<0x143, 0xC>(0u, (uint32_t)x), scan_step<0x143, 0xC>(0u, (uint32_t)(x >> 32)));
+        return (T)x;
     }
-    return v;
 }
 
 __device__ __forceinline__ int32_t wave_incl_scan_max(int32_t v) {
-    const int lane = lane_id();
-#pragma unroll
-    for (int d = 1; d < WAVE; d <<= 1) {
-        int32_t o = __shfl_up(v, d, WAVE);
-        if (lane >= d) v = max(v, o);
-    }
-    return v;
+    return (int32_t)wave_incl_scan_u32((uint32_t)v, (uint32_t)INT32_MIN,
+                                       [](uint32_t a, uint32_t b) { return (uint32_t)max((int32_t)a, (int32_t)b); });
+}
+// The value of the lane before (lane 0: `first`).
+__device__ __forceinline__ int32_t wave_shift_up1(int32_t v, int32_t first) {
+    return (int32_t)scan_step<0x138>((uint32_t)first, (uint32_t)v);
 }
 
 // Block-wide exclusive add-scan of one value per thread.  `tmp` holds one T per
@@ -65,8 +88,7 @@ __device__ __forceinline__ int32_t block_excl_scan_max(int32_t v, int32_t* tmp) 
     __syncthreads();
     int32_t base = -1;
     for (int i = 0; i < w; ++i) base = max(base, tmp[i]);
-    int32_t up = __shfl_up(inc, 1, WAVE);
-    if (lane == 0) up = -1;
+    const int32_t up = wave_shift_up1(inc, -1);
     __syncthreads();
     return max(base, up);
 }

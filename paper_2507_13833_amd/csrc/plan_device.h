@@ -99,7 +99,23 @@ __device__ __forceinline__ void plan_body(PlanLds& L, const PlanArgs& a, int32_t
     __syncthreads();
 
     // ---- 2. shard bases: lane p takes shard p; exclusive scan of the loads rounded up to the alignment ----
-    {
+    if (P <= WAVE) {                                     // (uniform) one wave holds every shard: no barrier, the others go on
+        if (w == 0) {
+            const int64_t first = lane < P ? L.gpre[L.shard_off[lane]] : 0;
+            const int64_t load = lane < P ? L.gpre[L.shard_off[lane + 1]] - first : 0;
+            const int64_t padded = (load + a.align - 1) / a.align * a.align;
+            const int64_t inc = wave_incl_scan_add<int64_t>(padded);
+            const int64_t end = (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)((uint64_t)inc >> 32), WAVE - 1) << 32) |
+                                          (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)inc, WAVE - 1));
+            if (lane < P) { L.shard_base[lane] = inc - padded; a.shard_tok_off[lane] = inc - padded; }
+            if (lane == 0) {
+                L.shard_base[P] = end;
+                a.shard_tok_off[P] = end;
+                a.dst_tok_off[N] = end;
+                if (end > a.capacity) set_status(a.status, DC_ERR_OVERFLOW);
+            }
+        }
+    } else {
         const int64_t first = tid < P ? L.gpre[L.shard_off[tid]] : 0;
         const int64_t load = tid < P ? L.gpre[L.shard_off[tid + 1]] - first : 0;
         const int64_t padded = (load + a.align - 1) / a.align * a.align;
@@ -197,10 +213,20 @@ __device__ __forceinline__ void plan_body(PlanLds& L, const PlanArgs& a, int32_t
     // ---- 4. micro-batch index per slot, outputs ----
     // per word of 32 slots: starts in the words before it, and the last start before it
     int32_t M;
-    {
+    {   // (the two scans share their barriers)
         const uint32_t bits = tid < PLAN_WORDS ? L.start_bits[tid] : 0u;
-        const int32_t before = block_excl_scan_add<int32_t>((int32_t)__popc(bits), L.tmp32, &M);
-        const int32_t last = block_excl_scan_max(bits ? tid * 32 + 31 - __clz(bits) : -1, L.tmp32);
+        const int32_t n_here = (int32_t)__popc(bits), last_here = bits ? tid * 32 + 31 - __clz(bits) : -1;
+        const int32_t inc_n = wave_incl_scan_add<int32_t>(n_here), inc_l = wave_incl_scan_max(last_here);
+        int32_t* tmp_l = reinterpret_cast<int32_t*>(L.tmp64);
+        if (lane == WAVE - 1) { L.tmp32[w] = inc_n; tmp_l[w] = inc_l; }
+        __syncthreads();
+        int32_t before = inc_n - n_here, last = wave_shift_up1(inc_l, -1);
+        M = 0;
+        for (int i = 0; i < PLAN_WAVES; ++i) {
+            const int32_t x = L.tmp32[i];
+            if (i < w) { before += x; last = max(last, tmp_l[i]); }
+            M += x;
+        }
         if (tid < PLAN_WORDS) { L.word_starts[tid] = before; L.word_last[tid] = last; }
         if (tid == 0) L.word_starts[PLAN_WORDS] = M;
     }

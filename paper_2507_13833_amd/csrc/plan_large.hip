@@ -33,8 +33,7 @@ __device__ __forceinline__ int32_t block_excl_scan_max_total(int32_t v, int32_t*
         if (i < w) base = max(base, x);
         all = max(all, x);
     }
-    int32_t up = __shfl_up(inc, 1, WAVE);
-    if (lane == 0) up = -1;
+    const int32_t up = wave_shift_up1(inc, -1);
     __syncthreads();
     *total = all;
     return max(base, up);
