@@ -914,18 +914,23 @@ __device__ __forceinline__ void balance_body_t(BalLds& L, int32_t N, int32_t P, 
         // (gathered by sequence in the LDS, where the sorted items were, so that both outputs leave in index
         // order: 16 384 scattered 4-byte stores take longer to drain than the rounds save)
         uint32_t* const worker_of = items;
+        // (slot q = worker q / C, place q mod C: one division per lane, then steps of BAL_BLOCK slots)
+        const int step_k = BAL_BLOCK / C, step_r = BAL_BLOCK - step_k * C;
+        int k = tid / C, r = tid - k * C;
 #pragma unroll
         for (int qq = 0; qq < BAL_ROUNDS; ++qq) {
             const int q = qq * BAL_BLOCK + tid;
             if constexpr (FILL) { slots.seq[qq] = -1; slots.len[qq] = 0; }
             if (q < N) {
-                const int k = q / C;
-                const uint32_t e = rows[k * rpitch + (q - k * C)];
+                const uint32_t e = rows[k * rpitch + r];
                 const uint32_t u = min(e & 0xFFFFu, (uint32_t)(N - 1));      // (no index leaves the arrays whatever a word holds)
                 perm[q] = (int32_t)u;
                 worker_of[u] = (uint32_t)k;
                 if constexpr (FILL) { slots.seq[qq] = (int32_t)u; slots.len[qq] = (int32_t)(e >> 16); }
             }
+            k += step_k;
+            r += step_r;
+            if (r >= C) { r -= C; k += 1; }
         }
         __syncthreads();
         for (int i = tid; i < N; i += BAL_BLOCK) shard_of_seq[i] = (int32_t)worker_of[i];
@@ -978,13 +983,14 @@ __device__ __forceinline__ void balance_body_t(BalLds& L, int32_t N, int32_t P, 
     // ---- c) lay out P_0, P_1, ... each in insertion order ----
     const int n_placed = *placed;
     if (pitch) {                                                  // both stores in index order
+        const int step_k = BAL_BLOCK / C, step_r = BAL_BLOCK - step_k * C;
+        int k = tid / C, r = tid - k * C;                         // slot q = worker q / C, place q mod C
 #pragma unroll
         for (int qq = 0; qq < BAL_ROUNDS; ++qq) {
             const int q = qq * BAL_BLOCK + tid;
             if constexpr (FILL) { slots.seq[qq] = -1; slots.len[qq] = 0; }
             if (q < N) {
-                const int k = q / C;
-                const int u = min((int)step_slot[k * pitch + (q - k * C)], N - 1);
+                const int u = min((int)step_slot[k * pitch + r], N - 1);
                 perm[q] = u;
                 shard_of_seq[q] = L.keys[q];
                 if constexpr (FILL) {                             // (lengths of 2^16 and more: they are in global memory only)
@@ -993,6 +999,9 @@ __device__ __forceinline__ void balance_body_t(BalLds& L, int32_t N, int32_t P, 
                     slots.len[qq] = (s <= 0 || s > DC_MAX_SEQ_LEN) ? 1 : s;
                 }
             }
+            k += step_k;
+            r += step_r;
+            if (r >= C) { r -= C; k += 1; }
         }
         return;
     }

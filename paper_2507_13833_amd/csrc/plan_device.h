@@ -103,7 +103,7 @@ __device__ __forceinline__ void plan_body(PlanLds& L, const PlanArgs& a, int32_t
         if (w == 0) {
             const int64_t first = lane < P ? L.gpre[L.shard_off[lane]] : 0;
             const int64_t load = lane < P ? L.gpre[L.shard_off[lane + 1]] - first : 0;
-            const int64_t padded = (load + a.align - 1) / a.align * a.align;
+            const int64_t padded = a.align == 1 ? load : (load + a.align - 1) / a.align * a.align;   // (uniform)
             const int64_t inc = wave_incl_scan_add<int64_t>(padded);
             const int64_t end = (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)((uint64_t)inc >> 32), WAVE - 1) << 32) |
                                           (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)inc, WAVE - 1));
