@@ -476,6 +476,31 @@ def test_more_than_64_shards():
     check_step(_custom(rng.integers(1, 300, 200), 2, 200, 512), label="N=P=200")
 
 
+def test_more_than_64_shards_key_widths():
+    """The workgroup-wide rounds keep 32-bit keys while every length is below 2^16 (rebased whenever the smallest key
+    has passed 2^30) and 64-bit keys otherwise; in one piece and in portions."""
+    rng = np.random.default_rng(16)
+    heavy = lambda n: np.minimum(64 * (1.0 - rng.random(n)) ** (-1 / 1.3), 32768).astype(np.int32) + rng.integers(512, 4096, n)
+    # ~10 M tokens per worker: (load << 10) passes 2^32 several times over
+    _check_balance_ws(rng.integers(30000, 65536, 65 * 200), 65, label="65 workers, long sequences: 32-bit keys rebased")
+    _check_balance_ws(rng.integers(30000, 65536, 256 * 200), 256, label="256 workers in portions, 32-bit keys rebased")
+    _check_balance_ws(np.concatenate([[65535], rng.integers(1, 3, 128 * 100 - 1)]), 128, label="128 workers, 65535 and ones")
+    # one length of 2^16 or more: 64-bit keys, ranks by counting
+    _check_balance_ws(np.concatenate([[70000], rng.integers(1, 5000, 128 * 64 - 1)]), 128, label="128 workers, one length above 2^16")
+    _check_balance_ws(np.concatenate([[1 << 24], heavy(128 * 300 - 1)]), 128, label="128 workers in portions, the longest length there is")
+    _check_balance_ws(np.concatenate([[65536], rng.integers(100, 200, 1000 * 30 - 1)]), 1000, label="1000 workers, 64-bit keys")
+
+
+def test_packed_rounds_with_keys_rebased():
+    """16, 32 and 64 workers with tens of millions of tokens each: (load << 6) passes 2^30 again and again inside the
+    packed rounds (sure, tested and short ones), in one piece and in portions."""
+    rng = np.random.default_rng(17)
+    _check_balance_ws(rng.integers(30000, 65536, 16384), 16, label="16 workers, 49 M tokens each")
+    _check_balance_ws(rng.integers(30000, 65536, 32 * 400), 32, label="32 workers, 19 M tokens each")
+    _check_balance_ws(np.concatenate([[65535] * 3, rng.integers(20000, 24000, 64 * 256 - 3)]), 64, label="64 workers, three long ones")
+    _check_balance_ws(rng.integers(30000, 65536, 32768), 16, label="16 workers in portions, 98 M tokens each")
+
+
 def _check_balance_ws(lens, P, cap=0, label=""):
     torch, binding, runner = _gpu()
     lens = np.asarray(lens, np.int32)
