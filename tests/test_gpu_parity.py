@@ -1070,3 +1070,14 @@ def test_empty_batch():
     assert d.shard_seq_off.cpu().tolist() == [0] * 5
     assert d.shard_tok_off.cpu().tolist() == [0] * 5
     assert d.shard_mb_off.cpu().tolist() == [0] * 5
+    # the same through the calls bench.py issues, on a shard count that would take the one-launch form
+    for P in (4, 16):
+        d = runner.DeviceBatch(_custom(np.zeros(0, np.int32), 1, P, 128))
+        ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+        for e in ev:
+            e.record()
+        d.step_two_calls(None, True, ev); torch.cuda.synchronize()       # (nothing is launched: the events stay as they are)
+        assert d.read_status() == 0
+        assert int(d.n_mb.item()) == 0
+        assert d.shard_seq_off.cpu().tolist() == [0] * (P + 1)
+        assert d.shard_tok_off.cpu().tolist() == [0] * (P + 1)
