@@ -138,12 +138,12 @@ __device__ __forceinline__ void plan_body(PlanLds& L, const PlanArgs& a, int32_t
     // instead of log2 N per hop; the hops of a shard are one dependent chain).
     if (P <= PLAN_WAVES * 4) {
         // Few shards: a group of 64, 32 or 16 LANES walks a shard (every wave takes 1, 2 or 4 shards).  A
-        // hop probes the slots behind the micro-batch's start G at a time, one per lane: the prefix sums
-        // do not decrease, so the lanes that still fit are a prefix of the group and a ballot counts them -
-        // one LDS round trip per window where the dependent probes of a search take six to eight.  A
-        // micro-batch of more than two windows finishes with a bisection.
+        // hop probes G slots at once, one per lane: the prefix sums do not decrease, so the lanes that still fit
+        // are a prefix of the group and a ballot counts them - one LDS round trip per window where the
+        // dependent probes of a bisection take six to eight.
         const int spw = P <= PLAN_WAVES ? 1 : (P <= 2 * PLAN_WAVES ? 2 : 4);     // shards per wave
         const int G = WAVE / spw, g = lane / G, gl = lane - g * G;
+        const int lg_G = spw == 1 ? 6 : (spw == 2 ? 5 : 4);
         const uint64_t group_mask = (G == WAVE ? ~0ull : (1ull << G) - 1ull);
         const int p = w * spw + g;
         if (p < P) {
@@ -152,23 +152,27 @@ __device__ __forceinline__ void plan_body(PlanLds& L, const PlanArgs& a, int32_t
             while (j < b) {                                  // uniform over the group
                 if (gl == 0) atomicOr(&L.start_bits[j >> 5], 1u << (j & 31));
                 const int64_t limit = L.gpre[j] + a.budget;
-                int lo = j + 1, e = j + 1;                   // an over-budget slot still advances by one
-                for (int win = 0;; ++win) {
+                // the last e in (j, b] with gpre[e] <= limit (j + 1 if there is none: an over-budget slot still
+                // advances by one).  The first window probes the G slots behind the start one by one (most micro-batches
+                // end inside it); if they all fit, the group's lanes spread evenly over what is left of the shard,
+                // then over the stretch between the last probe that fits and the first that does not.
+                int lo = j + 1, e = j + 1;
+                {
                     const int c = lo + gl;
                     const bool fits = c <= b && L.gpre[min(c, b)] <= limit;
                     const int cnt = __popcll((__ballot(fits) >> (g * G)) & group_mask);
                     if (cnt > 0) e = lo + cnt - 1;
-                    if (cnt < G || lo + G > b) break;
-                    lo += G;
-                    if (win == 1) {                          // every lane of the group reads the same words
-                        int l = e, h = b;
-                        while (l < h) {
-                            const int mid = (l + h + 1) >> 1;
-                            if (L.gpre[mid] <= limit) l = mid; else h = mid - 1;
-                        }
-                        e = l;
-                        break;
-                    }
+                    lo = (cnt == G && lo + G <= b) ? lo + G : b + 1;         // b + 1: found
+                }
+                int hi = b;                                  // candidates [lo, hi]; everything below lo fits
+                while (lo <= hi) {
+                    const int S = (hi - lo + G) >> lg_G;     // ceil(candidates / G) >= 1
+                    const bool fits = L.gpre[min(lo + (gl + 1) * S - 1, hi)] <= limit;
+                    const int cnt = __popcll((__ballot(fits) >> (g * G)) & group_mask);
+                    if (cnt > 0) e = min(lo + cnt * S - 1, hi);
+                    if (cnt == G) break;                     // the last lane's probe is hi itself
+                    hi = min(lo + (cnt + 1) * S - 1, hi) - 1;
+                    lo += cnt * S;
                 }
                 j = e;
             }
