@@ -109,16 +109,62 @@ struct RecArgs {
     GranRec*       gran_rec;
 };
 
+// The first slot j of a token axis (starts[N + 1], the last entry its end) whose successor starts after `begin`, or N:
+// what build_record's bisection finds, for the REC_BLOCK consecutive granules of a workgroup together (every thread of
+// the workgroup must call it; begin must not decrease with the thread index).  A bisection of its own is 14 dependent
+// reads of global memory per lane at 16 384 slots.  Here the workgroup reads REC_BLOCK evenly spaced starts at once,
+// every lane finds its stretch between two of them in the LDS, the workgroup reads the stretches of all its lanes
+// (one run of starts: the granules are neighbours) and every lane bisects its own stretch in the LDS: two reads of
+// global memory in a row.  A run longer than REC_STAGE entries is bisected where it lies.
+constexpr int REC_STAGE = 1024;
+struct RecLds {
+    int64_t sample[REC_BLOCK];
+    int64_t stage[REC_STAGE];
+    int32_t run_lo, run_hi;
+};
+__device__ __forceinline__ int first_slot_after(RecLds& L, int N, const int64_t* starts, int64_t begin) {
+    const int tid = threadIdx.x;
+    const int stride = (N + REC_BLOCK - 1) / REC_BLOCK;              // >= 1 (N > 0)
+    L.sample[tid] = starts[min(tid * stride, N)];
+    __syncthreads();
+    // the last sample that does not lie after `begin` (sample 0 is starts[0] = 0 <= begin)
+    int i = 0;
+#pragma unroll
+    for (int step = REC_BLOCK / 2; step >= 1; step >>= 1)
+        if (L.sample[i + step] <= begin) i += step;
+    // the answer lies in [lo, hi]: everything before sample i starts at or before `begin`; the slot before sample i + 1
+    // has a successor behind `begin` (no sample i + 1: hi = N stands for "none")
+    int lo = min(i * stride, N);
+    int hi = i + 1 < REC_BLOCK ? min((i + 1) * stride, N) - 1 : N;
+    hi = max(hi, lo);
+    if (tid == 0) L.run_lo = lo;
+    if (tid == REC_BLOCK - 1) L.run_hi = hi;
+    __syncthreads();
+    const int run_lo = L.run_lo, run_hi = L.run_hi;                   // the bisections read starts[run_lo + 1 .. run_hi]
+    const bool staged = run_hi - run_lo + 1 <= REC_STAGE;             // (uniform)
+    if (staged)
+        for (int k = tid; k <= run_hi - run_lo; k += REC_BLOCK) L.stage[k] = starts[min(run_lo + k, N)];
+    __syncthreads();
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        const int64_t next = staged ? L.stage[mid + 1 - run_lo] : starts[mid + 1];
+        if (next > begin) hi = mid; else lo = mid + 1;
+    }
+    return lo;
+}
+
 // Tables of granule g of a token axis holding N slots (starts[N+1], the last entry its end);
 // usable = false leaves the granule empty.  desc(j, &ln, &so, &sh): the validated source of slot j.
+// found >= 0: the first slot whose successor starts after the granule's first token (else it is looked for here).
 template <typename Desc>
 __device__ __forceinline__ void build_record(int N, bool usable, const int64_t* starts, Desc desc, int64_t g,
-                                             int32_t* first_out, GranRec* rec_out) {
+                                             int32_t* first_out, GranRec* rec_out, int found = -1) {
     const int64_t begin = g * GATHER_GRAN;
     int first = N;
     if (usable && N > 0) {
         // first j whose successor starts after `begin` ...
         int lo = 0, hi = N;
+        if (found >= 0) lo = hi = found;
         while (lo < hi) {
             const int mid = (lo + hi) >> 1;
             if (starts[mid + 1] > begin) hi = mid; else lo = mid + 1;
@@ -168,10 +214,15 @@ struct StoredDesc {
 };
 
 __global__ __launch_bounds__(REC_BLOCK) void records_kernel(RecArgs a) {
+    __shared__ RecLds L;
     const int64_t g = (int64_t)blockIdx.x * REC_BLOCK + threadIdx.x;
+    const bool usable = *a.plan_ok != 0;
+    int found = -1;
+    if (usable && a.n_seq > 0)                                   // (uniform) lanes behind the last granule look for its slot
+        found = first_slot_after(L, a.n_seq, a.dst_tok_off, min(g, a.n_gran - 1) * GATHER_GRAN);
     if (g >= a.n_gran) return;
-    build_record(a.n_seq, *a.plan_ok != 0, a.dst_tok_off, StoredDesc{a.slot_src_off, a.slot_len, a.slot_shard}, g,
-                 a.gran_first + g, a.gran_rec + g);
+    build_record(a.n_seq, usable, a.dst_tok_off, StoredDesc{a.slot_src_off, a.slot_len, a.slot_shard}, g,
+                 a.gran_first + g, a.gran_rec + g, found);
 }
 
 // The granule tables straight behind a launch that planned without slots_kernel (the plan as the balance
@@ -180,12 +231,17 @@ __global__ __launch_bounds__(REC_BLOCK) void records_kernel(RecArgs a) {
 // gather reads those arrays only for tiles with many short sequences).  Both validate alike, so a record
 // never depends on what the other workgroups have written yet.
 __global__ __launch_bounds__(REC_BLOCK) void records_slots_kernel(RecArgs a, PlanArgs p, SourceDesc sd, uint32_t rec_blocks) {
-    if (blockIdx.x < rec_blocks) {
+    if (blockIdx.x < rec_blocks) {                               // (uniform)
+        __shared__ RecLds L;
         const int64_t g = (int64_t)blockIdx.x * REC_BLOCK + threadIdx.x;
+        const bool usable = *a.plan_ok != 0;
+        int found = -1;
+        if (usable && a.n_seq > 0)
+            found = first_slot_after(L, a.n_seq, a.dst_tok_off, min(g, a.n_gran - 1) * GATHER_GRAN);
         if (g >= a.n_gran) return;
-        build_record(a.n_seq, *a.plan_ok != 0, a.dst_tok_off,
+        build_record(a.n_seq, usable, a.dst_tok_off,
                      [&](int j, int32_t* ln, int64_t* so, int32_t* sh) { slot_source(p, sd, j, max(p.slot_len[j], 0), ln, so, sh); },
-                     g, a.gran_first + g, a.gran_rec + g);
+                     g, a.gran_first + g, a.gran_rec + g, found);
         return;
     }
     const int j = (int)(blockIdx.x - rec_blocks) * REC_BLOCK + (int)threadIdx.x;
