@@ -851,10 +851,12 @@ __device__ __forceinline__ void balance_body_t(BalLds& L, int32_t N, int32_t P, 
             mn = min(mn, s);
         }
     }
-    for (int d = 32; d >= 1; d >>= 1) {
-        mx = max(mx, __shfl_xor(mx, d, WAVE));
-        mn = min(mn, __shfl_xor(mn, d, WAVE));
-    }
+    wave_all_reduce([&](auto j) {                                 // (lengths are positive: unsigned order is theirs)
+        constexpr int J = decltype(j)::value;
+        const uint32_t hi = lane_xor<J>((uint32_t)mx), lo = lane_xor<J>((uint32_t)mn);
+        mx = max(mx, (int32_t)hi);
+        mn = min(mn, (int32_t)lo);
+    });
     if (lane == 0) { L.red[w] = mx; L.red[BAL_WAVES + w] = mn; }
     __syncthreads();
     mx = 0; mn = INT32_MAX;
