@@ -396,6 +396,40 @@ def _custom(seq_len, G, P, budget, n_src=1, seed=0, fields=("i32", "bf16", "u8")
                               src_shard_seq_off=sso, src_tok_off=sto, src_shard_tokens=stk, fields=fl)
 
 
+def test_seeded_random_shapes():
+    """Forty drawn shapes through the step as bench.py issues it and through the separate calls: shard counts on both
+    sides of every path's limits, partitions of equal and unequal size, length mixes from all ones to one sequence a
+    thousand times the others, 1 to 8 rollout shards, aligned shards, budgets that a single slot fills."""
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        P = int(rng.choice([1, 2, 3, 7, 16, 16, 32, 32, 64, 64, 65, 96, 200]))
+        C = int(rng.choice([1, 2, 3, 5, 17, 40, 64]))
+        n_src = int(rng.choice([1, 1, 2, 4, 8]))
+        N = P * C
+        G = int(rng.choice([g for g in (1, 2, 4, 8, 16) if N % g == 0]))
+        while N % n_src:
+            n_src //= 2
+        kind = int(rng.integers(0, 5))
+        if kind == 0:
+            lens = np.ones(N, np.int64)
+        elif kind == 1:
+            lens = rng.integers(1, 40, N)
+        elif kind == 2:
+            lens = np.minimum(rng.geometric(0.003, N), 5000)
+        elif kind == 3:
+            lens = rng.integers(1, 60, N); lens[int(rng.integers(0, N))] = 70000          # one length of 2^16 or more
+        else:
+            lens = np.full(N, int(rng.integers(1, 3000)))                                   # all equal: nothing to sort
+        if int(lens.sum()) > 6_000_000:
+            lens = np.minimum(lens, 2000)
+        budget = int(max(lens.max(), rng.choice([1, 64, 4096, 1 << 17])))
+        align = int(rng.choice([1, 1, 3, 16, 256]))
+        cap = 0 if rng.random() < 0.7 else C + int(rng.integers(1, 4))
+        w = _custom(lens.astype(np.int32), G, P, budget, n_src=n_src, seed=case, fields=("i32", "bf16") if case % 2 else ("i32",))
+        label = f"drawn shape {case}: P={P} C={C} kind={kind} G={G} rollout shards={n_src} budget={budget}"
+        check_step(w, align=align, cap=cap, label=label, two_calls=bool(case % 3))
+
+
 @pytest.mark.parametrize("align", [3, 16, 64, 4096])
 def test_alignment_padding(align):
     check_step(workloads.make_workload(1), align=align, label=f"config 1 align {align}")
@@ -556,6 +590,33 @@ def test_balance_beyond_the_lds():
     # the most sequences the call takes
     _check_balance_ws(heavy(1 << 20), 64, label="2^20 sequences, packed rounds in 64 portions")
     _check_balance_ws(rng.integers(1, 2000, 1 << 20), 1024, label="2^20 sequences on 1024 workers")
+
+
+def test_seeded_random_shapes_of_the_balance():
+    """Thirty drawn shapes of Algorithm 1 alone, on both sides of the LDS limit: every rounds variant (packed, general,
+    workgroup-wide with either key width), in one piece and in portions, equal and unequal partitions."""
+    rng = np.random.default_rng(2025)
+    for case in range(30):
+        P = int(rng.choice([1, 5, 16, 16, 32, 32, 64, 64, 64, 100, 128, 512, 1024]))
+        big = bool(rng.random() < 0.5)
+        C = int(rng.integers(max(1, 16385 // P + 1), max(2, 70000 // P))) if big else int(rng.integers(1, max(2, 16384 // P + 1)))
+        C = min(C, 65535)
+        N = P * C
+        kind = int(rng.integers(0, 5))
+        if kind == 0:
+            lens = np.minimum(64 * (1.0 - rng.random(N)) ** (-1 / 1.3), 32768).astype(np.int64) + rng.integers(512, 4096, N)
+        elif kind == 1:
+            lens = rng.integers(1, 10, N)                                                    # ties everywhere
+        elif kind == 2:
+            lens = rng.integers(20000, 65536, N)                                             # keys rebased again and again
+        elif kind == 3:
+            lens = rng.integers(1, 3000, N); lens[int(rng.integers(0, N))] = int(rng.choice([65536, 1 << 20, 1 << 24]))
+        else:
+            lens = np.full(N, int(rng.integers(1, 65536)))
+        cap = 0
+        if rng.random() < 0.3:
+            cap = min(C + int(rng.integers(1, 50)), 65535)
+        _check_balance_ws(lens, P, cap=cap, label=f"drawn shape {case}: kind={kind}")
 
 
 def test_more_sequences_than_the_lds_holds():
