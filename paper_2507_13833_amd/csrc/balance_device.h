@@ -24,13 +24,15 @@ __device__ __forceinline__ int place_pitch(int C) { return C + ((2 - C) & 3); }
 
 struct BalLds {
     int32_t  keys[DC_MAX_SEQ + PLACE_PAD];    // sequence lengths (sanitised); packed path: the sorted items, see lpt_rounds_packed
+    alignas(16) uint32_t cnt[256 * CNT_PITCH];   // [digit][wave] counters of the sort passes; afterwards the workers' tables
+                                              // (keys and cnt together: the bins of bin_sort_packed)
     uint16_t idx_a[DC_MAX_SEQ + PLACE_PAD];   // sort ping
     uint16_t idx_b[DC_MAX_SEQ + PLACE_PAD];   // sort pong; after the sort the free one holds every item's place in its
                                               // partition, or (all partitions of equal size) the partitions themselves
-    alignas(16) uint32_t cnt[256 * CNT_PITCH];   // [digit][wave] counters of the sort passes; afterwards the workers' tables
     int32_t  red[2 * BAL_WAVES];
     uint32_t tmp32[16];
     int32_t  spare[2];                    // where lanes without a worker put the stores of a round
+    alignas(16) uint32_t nowhere[4];      // where a lane with nothing to store puts a 16-byte store
     uint64_t tmp64[BAL_WAVES];
 };
 static_assert(sizeof(uint32_t) * 256 * BAL_WAVES >= 2 * sizeof(uint64_t) * DC_MAX_SHARDS, "two key tables fit the counters");
@@ -109,6 +111,168 @@ __device__ __forceinline__ void counting_pass(BalLds& L, int N, int rounds, Digi
         }
     }
     __syncthreads();
+}
+
+// The packed items (length << 16 | index, one per sequence) in the order of Algorithm 1's sorted list, longest
+// first and equal lengths by index, written to out[0, N) in ONE pass where the two passes of the radix sort
+// each rank every item among its wave's 64 by eight ballots: a bin per length value (bin b = longest - length,
+// 16 bits wide, two to a word, in the LDS that the rows of the workers take over afterwards) is counted by
+// atomic adds whose return value is the item's ticket within its bin, the bins are scanned, and start + ticket
+// is a place inside the run of the item's length.  Tickets come in no particular order, so a last step puts
+// every run of more than one item in index order: the thread at a place counts the words of the place's run
+// that are larger than the one it found there (a run is followed by shorter lengths, that is by smaller
+// words, and the words after the last item are zero, so the count may run past the run's end in steps of
+// four; neighbouring lanes stand in the same run and read the same words, which the LDS serves as one).
+// Lengths of a real batch repeat a few times each; false (and out[] undefined) if some length occurs more than
+// BIN_RUN_MAX times, where the counting would take longer than the radix passes.  range = longest - shortest,
+// at most BIN_RANGE_MAX; the caller has zeroed the BIN_WORDS words from L.keys on, with a barrier since.
+// Every lane of the workgroup must call it; len[q] = length of sequence q * BAL_BLOCK + tid, unchanged where the
+// result is false and used up otherwise.
+constexpr int BIN_WORDS = DC_MAX_SEQ + PLACE_PAD + 256 * CNT_PITCH;
+constexpr int BIN_QUADS = (BIN_WORDS / 4 + BAL_BLOCK - 1) / BAL_BLOCK;      // 16-byte pieces of the bins per thread, at most
+constexpr uint32_t BIN_RANGE_MAX = 2u * BIN_WORDS - 4u;
+constexpr uint32_t BIN_RUN_MAX = 32;
+constexpr int BIN_GROUP = 4;                                      // items a thread handles as one straight piece of code
+static_assert(offsetof(BalLds, cnt) == sizeof(int32_t) * (DC_MAX_SEQ + PLACE_PAD), "the counters follow the keys");
+static_assert(DC_MAX_SEQ < (1 << 15), "a place, and the sum of the counts, fit 16 bits with room to spare");
+static_assert(BAL_ROUNDS % BIN_GROUP == 0, "whole groups");
+
+__device__ __forceinline__ void bin_sort_clear(BalLds& L) {
+    static_assert(BIN_WORDS % 4 == 0 && offsetof(BalLds, keys) % 16 == 0, "whole 16-byte pieces");
+    uint4* z = reinterpret_cast<uint4*>(L.keys);
+    for (int j = threadIdx.x; j < BIN_WORDS / 4; j += BAL_BLOCK) z[j] = make_uint4(0u, 0u, 0u, 0u);
+}
+
+__device__ __forceinline__ bool bin_sort_packed(BalLds& L, int N, uint32_t longest, uint32_t range,
+                                                int32_t (&len)[BAL_ROUNDS], uint32_t* out) {
+    // The code below is laid out for the LDS's latency.  A thread's items go in groups of BIN_GROUP, a group being
+    // one straight piece of code that issues all its LDS operations before it uses the first result, under a
+    // uniform test of whether the group has items at all.  Inside a group no lane steps aside: a lane without an
+    // item adds nothing, reads what a neighbour reads and writes to a spare word, because a branch on a lane's
+    // own condition would end the straight piece.
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1);
+    uint32_t* bins = reinterpret_cast<uint32_t*>(L.keys);
+    const int nw = (int)((range + 4u) >> 1);                      // bins 0 .. range, one more for the end of the last run
+    const int rounds = (N + BAL_BLOCK - 1) / BAL_BLOCK;           // (uniform: the q that have items at all)
+    // one register per item: the length in the low half, the ticket above it
+#pragma unroll
+    for (int g = 0; g < BAL_ROUNDS; g += BIN_GROUP) {
+        if (g < rounds) {
+            uint32_t old[BIN_GROUP];
+#pragma unroll
+            for (int q = g; q < g + BIN_GROUP; ++q) {
+                const bool mine = q * BAL_BLOCK + tid < N;
+                const uint32_t b = mine ? longest - (uint32_t)len[q] : 0u;
+                const uint32_t one = (b & 1u) ? 0x10000u : 1u;
+                old[q - g] = atomicAdd(&bins[mine ? b >> 1 : (uint32_t)min(lane, nw - 1)], mine ? one : 0u);
+            }
+#pragma unroll
+            for (int q = g; q < g + BIN_GROUP; ++q) {
+                const bool odd = ((longest - (uint32_t)len[q]) & 1u) != 0u;
+                len[q] |= (int32_t)(odd ? old[q - g] & 0xFFFF0000u : old[q - g] << 16);
+            }
+        }
+    }
+    __syncthreads();
+    // counts -> starts: a thread takes `per` consecutive 16-byte pieces (an odd number of them where that fits, for the banks)
+    uint4* quads = reinterpret_cast<uint4*>(L.keys);
+    const int nq = (nw + 3) >> 2;
+    const int per = min(((nq + BAL_BLOCK - 1) / BAL_BLOCK) | 1, BIN_QUADS);
+    const int lo = tid * per;
+    uint4 w[BIN_QUADS];
+#pragma unroll
+    for (int k = 0; k < BIN_QUADS; ++k) w[k] = quads[min(lo + k, BIN_WORDS / 4 - 1)];
+    uint32_t sum = 0, big = 0;
+#pragma unroll
+    for (int k = 0; k < BIN_QUADS; ++k) {
+        if (!(k < per && lo + k < nq)) w[k] = make_uint4(0u, 0u, 0u, 0u);      // (bins beyond the last one hold zero already)
+        const uint32_t x[4] = {w[k].x, w[k].y, w[k].z, w[k].w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            sum += (x[c] & 0xFFFFu) + (x[c] >> 16);
+            big = max(big, max(x[c] & 0xFFFFu, x[c] >> 16));
+        }
+    }
+    uint32_t total;                                               // (a run above the limit rides the scan's high bits)
+    uint32_t run = block_excl_scan_add<uint32_t>(sum | (big > BIN_RUN_MAX ? 1u << 20 : 0u), L.tmp32, &total) & 0xFFFFFu;
+    if (total >> 20) {                                            // (uniform)
+#pragma unroll
+        for (int q = 0; q < BAL_ROUNDS; ++q) len[q] &= 0xFFFF;
+        return false;
+    }
+    uint4* const nowhere = reinterpret_cast<uint4*>(L.nowhere);
+#pragma unroll
+    for (int k = 0; k < BIN_QUADS; ++k) {
+        const uint32_t x[4] = {w[k].x, w[k].y, w[k].z, w[k].w};
+        uint32_t y[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t c0 = x[c] & 0xFFFFu;
+            y[c] = run | ((run + c0) << 16);
+            run += c0 + (x[c] >> 16);
+        }
+        *((k < per && lo + k < nq) ? quads + lo + k : nowhere) = make_uint4(y[0], y[1], y[2], y[3]);
+    }
+    __syncthreads();
+    auto run_of = [&](uint32_t b) {                               // start of the run of bin b | its size << 16
+        const uint32_t wa = bins[b >> 1], wb = bins[(b >> 1) + 1];
+        const uint32_t start = (b & 1u) ? wa >> 16 : wa & 0xFFFFu;
+        return start | ((((b & 1u) ? wb & 0xFFFFu : wa >> 16) - start) << 16);
+    };
+    constexpr int PAD_READ = (int)BIN_RUN_MAX + 4 + 4;            // how far beyond the last item the counting below may read
+    static_assert(PAD_READ <= 128 && 128 + 1 <= PLACE_PAD, "the zeroed words and the spare word lie in the array's padding");
+#pragma unroll
+    for (int g = 0; g < BAL_ROUNDS; g += BIN_GROUP) {
+        if (g < rounds) {
+            uint32_t at[BIN_GROUP];
+#pragma unroll
+            for (int q = g; q < g + BIN_GROUP; ++q) {
+                const bool mine = q * BAL_BLOCK + tid < N;
+                at[q - g] = run_of(mine ? longest - ((uint32_t)len[q] & 0xFFFFu) : 0u);
+            }
+#pragma unroll
+            for (int q = g; q < g + BIN_GROUP; ++q) {
+                const int i = q * BAL_BLOCK + tid;
+                const uint32_t to = (at[q - g] & 0xFFFFu) + ((uint32_t)len[q] >> 16);
+                out[i < N ? to : (uint32_t)N + 128u] = ((uint32_t)len[q] << 16) | (uint32_t)i;
+            }
+        }
+    }
+    out[N + (tid & 127)] = 0;
+    __syncthreads();
+    // index order inside the runs; from here on a thread looks after places q * BAL_BLOCK + tid, not after its
+    // sequences (a place beyond the last one repeats the last one's work)
+    uint32_t goes[BAL_ROUNDS];
+#pragma unroll
+    for (int g = 0; g < BAL_ROUNDS; g += BIN_GROUP) {
+        if (g < rounds) {
+            uint32_t ss[BIN_GROUP];
+#pragma unroll
+            for (int q = g; q < g + BIN_GROUP; ++q) len[q] = (int32_t)out[min(q * BAL_BLOCK + tid, N - 1)];
+#pragma unroll
+            for (int q = g; q < g + BIN_GROUP; ++q) ss[q - g] = run_of(longest - ((uint32_t)len[q] >> 16));
+#pragma unroll
+            for (int q = g; q < g + BIN_GROUP; ++q) {             // (one place at a time: the LDS is the limit here, not its latency)
+                const uint32_t e = (uint32_t)len[q], start = ss[q - g] & 0xFFFFu, size = ss[q - g] >> 16;
+                const uint32_t end = size > 1u ? start + size : start;                // (nothing to count for a run of one)
+                uint32_t above = 0;
+                for (uint32_t j = start; j < end; j += 4) {       // (past a run's end nothing is larger)
+                    above += (out[j] > e ? 1u : 0u) + (out[j + 1] > e ? 1u : 0u) + (out[j + 2] > e ? 1u : 0u) + (out[j + 3] > e ? 1u : 0u);
+                }
+                goes[q] = start + size - 1u - above;
+            }
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int g = 0; g < BAL_ROUNDS; g += BIN_GROUP) {
+        if (g < rounds) {
+#pragma unroll
+            for (int q = g; q < g + BIN_GROUP; ++q) out[goes[q]] = (uint32_t)len[q];
+        }
+    }
+    __syncthreads();
+    return true;
 }
 
 // The assignment rounds (wave 0 only).  WIDTH = 16, 32 or 64 >= P lanes take part in the sort.
@@ -836,6 +1000,11 @@ __device__ __forceinline__ void balance_body_t(BalLds& L, int32_t N, int32_t P, 
                                                int64_t* __restrict__ shard_load, int32_t* status, SlotRegs& slots) {
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), w = tid / WAVE;
 
+    // every partition ends with exactly C items (Algorithm 1 as printed: C = N / K): rows per worker
+    const int pitch = (P <= WAVE && C > 0 && (int64_t)P * C == N) ? place_pitch(C) : 0;
+    const bool tight = pitch != 0 && (P == 16 || P == 32 || P == 64);
+    if (tight) bin_sort_clear(L);                                 // (uniform; the barrier below stands between this and the bins' use)
+
     // ---- load lengths, range ----
     int32_t mx = 0, mn = INT32_MAX;
     int32_t mine_len[BAL_ROUNDS];
@@ -865,11 +1034,8 @@ __device__ __forceinline__ void balance_body_t(BalLds& L, int32_t N, int32_t P, 
     const int nbits = 32 - __clz(range | 1u);
     const int passes = range == 0 ? 0 : (nbits + 7) / 8;
     const int rounds = (N + BAL_BLOCK - 1) / BAL_BLOCK;           // <= BAL_ROUNDS
-    // every partition ends with exactly C items (Algorithm 1 as printed: C = N / K): rows per worker
-    const int pitch = (P <= WAVE && C > 0 && (int64_t)P * C == N) ? place_pitch(C) : 0;
     int32_t* part_off = reinterpret_cast<int32_t*>(L.cnt) + PART_OFF_AT;
     int32_t* placed = reinterpret_cast<int32_t*>(L.cnt) + PLACED_AT;
-    const bool tight = pitch != 0 && (P == 16 || P == 32 || P == 64);
 
     // ---- the printed algorithm on 16, 32 or 64 workers with lengths below 2^16 (lpt_rounds_packed) ----
     // One word per sequence, length << 16 | index, is all that is kept: the sort moves those words between
@@ -881,18 +1047,22 @@ __device__ __forceinline__ void balance_body_t(BalLds& L, int32_t N, int32_t P, 
                       offsetof(BalLds, idx_a) % 4 == 0, "the two index arrays are one run of words");
         uint32_t* src = reinterpret_cast<uint32_t*>(L.keys);      // DC_MAX_SEQ + PLACE_PAD words each
         uint32_t* dst = reinterpret_cast<uint32_t*>(L.idx_a);
-#pragma unroll
-        for (int q = 0; q < BAL_ROUNDS; ++q) {
-            const int i = q * BAL_BLOCK + tid;
-            if (i < N) src[i] = ((uint32_t)mine_len[q] << 16) | (uint32_t)i;
-        }
-        __syncthreads();
-        for (int pass = 0; pass < passes; ++pass) {
-            const int shift = pass * 8;
-            counting_pass(L, N, rounds,
-                          [&](int pos) { return ((uint32_t)mx - (src[pos] >> 16)) >> shift; },
-                          [&](int pos, int out) { dst[out] = src[pos]; });
+        if (range != 0u && range <= BIN_RANGE_MAX && bin_sort_packed(L, N, (uint32_t)mx, range, mine_len, dst)) {     // (uniform)
             uint32_t* t = src; src = dst; dst = t;
+        } else {
+#pragma unroll
+            for (int q = 0; q < BAL_ROUNDS; ++q) {
+                const int i = q * BAL_BLOCK + tid;
+                if (i < N) src[i] = ((uint32_t)mine_len[q] << 16) | (uint32_t)i;
+            }
+            __syncthreads();
+            for (int pass = 0; pass < passes; ++pass) {
+                const int shift = pass * 8;
+                counting_pass(L, N, rounds,
+                              [&](int pos) { return ((uint32_t)mx - (src[pos] >> 16)) >> shift; },
+                              [&](int pos, int out) { dst[out] = src[pos]; });
+                uint32_t* t = src; src = dst; dst = t;
+            }
         }
         uint32_t* const items = src;                              // I of Algorithm 1, each entry with its length
         uint32_t* const rows = dst;

@@ -60,34 +60,47 @@ __device__ __forceinline__ int32_t wave_shift_up1(int32_t v, int32_t first) {
     return (int32_t)scan_step<0x138>((uint32_t)first, (uint32_t)v);
 }
 
+// The value that lane `from` (the same in every lane of the wave) holds.
+template <typename T>
+__device__ __forceinline__ T wave_read_lane(T v, int from) {
+    static_assert(sizeof(T) == 4 || sizeof(T) == 8, "32- or 64-bit integers");
+    const int at = __builtin_amdgcn_readfirstlane(from);
+    if constexpr (sizeof(T) == 4) {
+        return (T)__builtin_amdgcn_readlane((int)v, at);
+    } else {
+        const uint64_t x = (uint64_t)v;
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, at);
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(x >> 32), at);
+        return (T)(((uint64_t)hi << 32) | lo);
+    }
+}
+
 // Block-wide exclusive add-scan of one value per thread.  `tmp` holds one T per
-// wave (at most 16).  Returns the exclusive prefix; *total gets the block sum.
+// wave (at most 64).  Returns the exclusive prefix; *total gets the block sum.
 // Contains __syncthreads(): every thread of the block must call it.
+// (The waves' sums are scanned by every wave for itself, lane i taking wave i's: one LDS read and a register
+// scan, where a loop over the waves would wait for the LDS once per wave.)
 template <typename T>
 __device__ __forceinline__ T block_excl_scan_add(T v, T* tmp, T* total) {
     const int lane = lane_id(), w = threadIdx.x / WAVE, nw = blockDim.x / WAVE;
     T inc = wave_incl_scan_add(v);
     if (lane == WAVE - 1) tmp[w] = inc;
     __syncthreads();
-    T base = 0, sum = 0;
-    for (int i = 0; i < nw; ++i) {
-        T x = tmp[i];
-        if (i < w) base += x;
-        sum += x;
-    }
+    const T mine = lane < nw ? tmp[lane] : T(0);
+    const T upto = wave_incl_scan_add(mine);
     __syncthreads();
-    *total = sum;
-    return base + inc - v;
+    *total = wave_read_lane(upto, WAVE - 1);
+    return wave_read_lane((T)(upto - mine), w) + inc - v;
 }
 
 // Block-wide exclusive max-scan (identity -1).
 __device__ __forceinline__ int32_t block_excl_scan_max(int32_t v, int32_t* tmp) {
-    const int lane = lane_id(), w = threadIdx.x / WAVE;
+    const int lane = lane_id(), w = threadIdx.x / WAVE, nw = blockDim.x / WAVE;
     int32_t inc = wave_incl_scan_max(v);
     if (lane == WAVE - 1) tmp[w] = inc;
     __syncthreads();
-    int32_t base = -1;
-    for (int i = 0; i < w; ++i) base = max(base, tmp[i]);
+    const int32_t upto = wave_incl_scan_max(lane < nw ? tmp[lane] : -1);
+    const int32_t base = wave_read_lane(wave_shift_up1(upto, -1), w);
     const int32_t up = wave_shift_up1(inc, -1);
     __syncthreads();
     return max(base, up);

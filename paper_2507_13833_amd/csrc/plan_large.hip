@@ -27,15 +27,11 @@ __device__ __forceinline__ int32_t block_excl_scan_max_total(int32_t v, int32_t*
     const int32_t inc = wave_incl_scan_max(v);
     if (lane == WAVE - 1) tmp[w] = inc;
     __syncthreads();
-    int32_t base = -1, all = -1;
-    for (int i = 0; i < nw; ++i) {
-        const int32_t x = tmp[i];
-        if (i < w) base = max(base, x);
-        all = max(all, x);
-    }
+    const int32_t upto = wave_incl_scan_max(lane < nw ? tmp[lane] : -1);      // (lane i: the waves up to wave i)
+    const int32_t base = wave_read_lane(wave_shift_up1(upto, -1), w);
     const int32_t up = wave_shift_up1(inc, -1);
     __syncthreads();
-    *total = all;
+    *total = wave_read_lane(upto, WAVE - 1);
     return max(base, up);
 }
 

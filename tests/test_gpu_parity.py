@@ -487,6 +487,53 @@ def test_partition_sizes_and_worker_counts():
                 assert np.array_equal(d.shard_load.cpu().numpy(), bal.shard_load), (P, C, cap)
 
 
+def test_one_pass_sort_of_the_packed_path():
+    """16, 32 or 64 workers, equal partitions, lengths below 2^16: the sorted list comes from one counting pass
+    over a bin per length (tickets from atomic adds, then index order restored inside every run of one length),
+    with the two radix passes as the way out.  Cases: runs of one length at, just below and just above the
+    limit of the one-pass sort; the shortest length (the last run, followed by the array's padding) as the
+    most frequent; few distinct lengths (always the way out); a range of lengths at and beyond what the bins
+    hold; batches that are no multiple of the workgroup, smaller than a wavefront, and the largest."""
+    torch, binding, runner = _gpu()
+    rng = np.random.default_rng(61)
+
+    def check(lens, P, label):
+        lens = np.asarray(lens, np.int32)
+        w = _custom(lens, 1, P, 1 << 17, fields=("i32",))
+        d = runner.DeviceBatch(w)
+        d.balance()
+        torch.cuda.synchronize()
+        assert d.read_status() == 0, label
+        bal = oracle.balance(w.seq_len, P, 0)
+        assert np.array_equal(d.perm.cpu().numpy(), bal.perm), label
+        assert np.array_equal(d.shard_seq_off.cpu().numpy(), bal.shard_seq_off), label
+        assert np.array_equal(d.shard_of_seq.cpu().numpy(), bal.shard_of_seq), label
+        assert np.array_equal(d.shard_load.cpu().numpy(), bal.shard_load), label
+
+    def with_runs(n, run, lo=100, hi=9000):
+        """n lengths in which one value occurs exactly `run` times and no other more often than three times"""
+        vals = rng.permutation(np.arange(lo, hi))[: n]
+        lens = np.concatenate([np.repeat(vals[: (n - run) // 3 + 1], 3)[: n - run], np.full(run, hi + 7)])
+        return rng.permutation(lens)
+
+    for run in (31, 32, 33, 64, 65):
+        check(with_runs(64 * 64, run), 64, f"a run of {run}")
+    lens = with_runs(32 * 100, 30)
+    lens[lens == lens.max()] = 5                                       # the longest run is the last one
+    check(lens, 32, "most frequent length is the shortest")
+    check(np.concatenate([np.full(20, 3), rng.permutation(np.arange(50, 50 + 16 * 64 - 20))]), 16, "the list ends in a run of 20")
+    check(rng.choice([700, 701, 9000], 64 * 128), 64, "three distinct lengths")
+    check(rng.choice(np.arange(1000, 1040), 16 * 1024), 16, "forty distinct lengths, 16 384 sequences")
+    for top in (41000, 41981, 41982, 41983, 41984, 65535):             # range = top - 1
+        lens = rng.integers(1, top + 1, 64 * 200)
+        lens[3] = top; lens[11] = 1
+        check(lens, 64, f"lengths 1..{top}")
+    check(rng.integers(40000, 65536, 64 * 256), 64, "long sequences, 16 384 of them")
+    for P, C in ((16, 1), (16, 3), (32, 33), (64, 17), (64, 100), (16, 1000), (32, 511), (64, 255)):
+        check(np.minimum(rng.geometric(0.002, P * C), 30000), P, f"P={P} C={C}")
+        check(rng.integers(200, 200 + max(2, P * C // 5), P * C), P, f"P={P} C={C}, five of every length")
+
+
 def test_max_sequences():
     rng = np.random.default_rng(10)
     lens = np.minimum(rng.geometric(0.02, 16384), 2000).astype(np.int32)
