@@ -202,6 +202,8 @@ __device__ __forceinline__ bool bin_sort_packed(BalLds& L, int N, uint32_t longe
     }
     uint4* const nowhere = reinterpret_cast<uint4*>(L.nowhere);
 #pragma unroll
+    for (int k = 0; k < BIN_QUADS; ++k) w[k] = quads[min(lo + k, BIN_WORDS / 4 - 1)];      // (read again rather than kept: registers)
+#pragma unroll
     for (int k = 0; k < BIN_QUADS; ++k) {
         const uint32_t x[4] = {w[k].x, w[k].y, w[k].z, w[k].w};
         uint32_t y[4];
@@ -992,7 +994,9 @@ struct SlotRegs {
     int32_t len[BAL_ROUNDS];
 };
 
-// FILL (only with P in {16, 32, 64} and P * C == N): also fill slots.
+// FILL (only with P in {16, 32, 64} and P * C == N): also fill slots; the code of other shapes is left out (the
+// kernel is executed once from front to back, most of it straight code that the instruction cache has not seen,
+// and its size shows in its time).
 template <bool FILL>
 __device__ __forceinline__ void balance_body_t(BalLds& L, int32_t N, int32_t P, int32_t C,
                                                const int32_t* __restrict__ seq_len, int32_t* __restrict__ perm,
@@ -1129,9 +1133,12 @@ __device__ __forceinline__ void balance_body_t(BalLds& L, int32_t N, int32_t P, 
     const uint16_t* sorted = src;                                 // I of Algorithm 1
     uint16_t* step_slot = dst;                                    // place of I[t] inside its worker's partition
     // ---- b) assignment rounds: wave 0 for up to 64 workers, else the whole workgroup ----
-    if (P > WAVE) {
-        const int n_placed = lpt_rounds_wide(L, N, P, C, sorted, step_slot, mx, shard_seq_off, shard_load);
-        if (tid == 0) *placed = n_placed;
+    // (FILL: the caller has 16, 32 or 64 workers and equal partitions; the other shapes' code stays out of its kernel)
+    if (!FILL && P > WAVE) {
+        if constexpr (!FILL) {
+            const int n_placed = lpt_rounds_wide(L, N, P, C, sorted, step_slot, mx, shard_seq_off, shard_load);
+            if (tid == 0) *placed = n_placed;
+        }
     } else if (w == 0) {
         int32_t* worker_count = reinterpret_cast<int32_t*>(L.cnt) + WCOUNT_AT;
         int32_t* spare = L.spare;
@@ -1139,10 +1146,12 @@ __device__ __forceinline__ void balance_body_t(BalLds& L, int32_t N, int32_t P, 
         int n_placed;
         if (tight && P == 16) n_placed = lpt_rounds<16, true>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
         else if (tight && P == 32) n_placed = lpt_rounds<32, true>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
-        else if (tight) n_placed = lpt_rounds<64, true>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
-        else if (P <= 16) n_placed = lpt_rounds<16>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
-        else if (P <= 32) n_placed = lpt_rounds<32>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
-        else n_placed = lpt_rounds<64>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
+        else if (FILL || tight) n_placed = lpt_rounds<64, true>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
+        else if constexpr (!FILL) {
+            if (P <= 16) n_placed = lpt_rounds<16>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
+            else if (P <= 32) n_placed = lpt_rounds<32>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
+            else n_placed = lpt_rounds<64>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
+        }
         // start of every P_k inside perm
         const int32_t c = worker_count[lane];
         const int32_t inc = (int32_t)wave_incl_scan_add_u32((uint32_t)c);
