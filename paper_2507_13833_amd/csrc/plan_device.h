@@ -28,7 +28,6 @@ struct PlanLds {
     int32_t  ok;
 };
 
-__device__ __forceinline__ bool start_bit(const PlanLds& L, int j) { return (L.start_bits[j >> 5] >> (j & 31)) & 1u; }
 
 // The caller holds, per lane, the sequence and the (validated) length of slots tid, tid + PLAN_BLOCK, ...
 // (seq = -1, len = 0 beyond N).  check_perm: seq comes from a caller's permutation and must be checked;
@@ -91,10 +90,11 @@ __device__ __forceinline__ void plan_body(PlanLds& L, const PlanArgs& a, int32_t
     }
     __syncthreads();
     // ... and their sum
+    const int whole_steps = N / PLAN_BLOCK;              // (uniform) steps in which every lane has a slot
 #pragma unroll
     for (int q = 0; q < PLAN_IPT; ++q) {
         const int j = q * PLAN_BLOCK + tid;
-        if (j < N) L.gpre[j] = L.wave_pref[q * PLAN_WAVES + w] + (inc[q] - len[q]);
+        if (q < whole_steps || j < N) L.gpre[j] = L.wave_pref[q * PLAN_WAVES + w] + (inc[q] - len[q]);
     }
     __syncthreads();
 
@@ -149,22 +149,25 @@ __device__ __forceinline__ void plan_body(PlanLds& L, const PlanArgs& a, int32_t
         if (p < P) {
             const int b = L.shard_off[p + 1];
             int j = L.shard_off[p];
+            int sz = 0;                                      // slots in the micro-batch before this one
             while (j < b) {                                  // uniform over the group
                 if (gl == 0) atomicOr(&L.start_bits[j >> 5], 1u << (j & 31));
                 const int64_t limit = L.gpre[j] + a.budget;
                 // the last e in (j, b] with gpre[e] <= limit (j + 1 if there is none: an over-budget slot still
-                // advances by one).  The first window probes the G slots behind the start one by one (most micro-batches
-                // end inside it); if they all fit, the group's lanes spread evenly over what is left of the shard,
-                // then over the stretch between the last probe that fits and the first that does not.
-                int lo = j + 1, e = j + 1;
+                // advances by one).  The first window probes G slots one by one, placed around the end that a micro-batch
+                // as long as the one before would have (slots of a shard come in descending length, so it holds a few
+                // more; the first one of a shard: the G slots behind the start).  Most micro-batches end inside it; if
+                // not, the group's lanes spread evenly over what is left on the side where the end lies, then over the
+                // stretch between the last probe that fits and the first that does not.
+                const int first = max(j + 1, j + sz + 1 - (G >> 2));
+                int lo, hi = b, e = j + 1;                   // candidates [lo, hi]; everything below lo fits
                 {
-                    const int c = lo + gl;
+                    const int c = first + gl;
                     const bool fits = c <= b && L.gpre[min(c, b)] <= limit;
                     const int cnt = __popcll((__ballot(fits) >> (g * G)) & group_mask);
-                    if (cnt > 0) e = lo + cnt - 1;
-                    lo = (cnt == G && lo + G <= b) ? lo + G : b + 1;         // b + 1: found
+                    if (cnt == 0) { lo = j + 1; hi = first - 1; }            // it ends before the window (or with its first slot)
+                    else { e = first + cnt - 1; lo = (cnt == G && first + G <= b) ? first + G : b + 1; }     // b + 1: found
                 }
-                int hi = b;                                  // candidates [lo, hi]; everything below lo fits
                 while (lo <= hi) {
                     const int S = (hi - lo + G) >> lg_G;     // ceil(candidates / G) >= 1
                     const bool fits = L.gpre[min(lo + (gl + 1) * S - 1, hi)] <= limit;
@@ -174,6 +177,7 @@ __device__ __forceinline__ void plan_body(PlanLds& L, const PlanArgs& a, int32_t
                     hi = min(lo + (cnt + 1) * S - 1, hi) - 1;
                     lo += cnt * S;
                 }
+                sz = e - j;
                 j = e;
             }
         }
@@ -235,32 +239,40 @@ __device__ __forceinline__ void plan_body(PlanLds& L, const PlanArgs& a, int32_t
         if (tid == 0) L.word_starts[PLAN_WORDS] = M;
     }
     __syncthreads();
-#pragma unroll 2
-    for (int q = 0; q < nb; ++q) {
-        const int j = q * PLAN_BLOCK + tid;
-        if (j < N) {
-            const uint32_t bits = L.start_bits[j >> 5];
-            const uint32_t upto = bits & (0xFFFFFFFFu >> (31 - (j & 31)));           // starts at slots <= j of the word
-            const int32_t m = L.word_starts[j >> 5] + (int32_t)__popc(upto) - 1;     // my micro-batch
-            const int32_t cur_start = upto ? (j & ~31) + 31 - __clz(upto) : L.word_last[j >> 5];
-            if ((bits >> (j & 31)) & 1u) a.mb_seq_off[m] = j;
-            const int64_t g = L.gpre[j];
-            int64_t d = g;
-            if (a.align != 1) {                          // uniform: shard of the slot, then its aligned base
-                int lo = 0, hi = P - 1;                  // largest p with shard_off[p] <= j
-                while (lo < hi) {
-                    const int mid = (lo + hi + 1) >> 1;
-                    if (L.shard_off[mid] <= j) lo = mid; else hi = mid - 1;
-                }
-                d = g + (L.shard_base[lo] - L.gpre[L.shard_off[lo]]);
+    // One slot per lane and step.  Nothing here depends on a lane's own condition except the stores of a last,
+    // partial step: every slot of a micro-batch stores the micro-batch's first slot (the same word with the same
+    // value), and every slot stores the cu_seqlens entry behind its own, which is either the entry that the next
+    // slot stores too or the end of the micro-batch.  Differences of prefix sums inside a micro-batch fit 32 bits,
+    // so they are taken between the low words.
+    const bool shift_bases = a.align != 1;               // (uniform)
+    auto low_word = [&](int at) { return reinterpret_cast<const uint32_t*>(&L.gpre[at])[0]; };
+    auto slot_out = [&](int q, bool whole) {             // whole (uniform): every lane has a slot in this step
+        const int jr = q * PLAN_BLOCK + tid, j = whole ? jr : min(jr, N - 1);
+        const uint32_t bits = L.start_bits[j >> 5];
+        const uint32_t upto = bits & (0xFFFFFFFFu >> (31 - (j & 31)));               // starts at slots <= j of the word
+        const int32_t m = L.word_starts[j >> 5] + (int32_t)__popc(upto) - 1;         // my micro-batch
+        const int32_t first = upto ? (j & ~31) + 31 - __clz(upto) : L.word_last[j >> 5];     // its first slot (slot 0 starts one)
+        const int64_t g = L.gpre[j];
+        const uint32_t g_next = low_word(j + 1), g_first = low_word(max(first, 0));
+        int64_t d = g;
+        if (shift_bases) {                               // shard of the slot, then its aligned base
+            int lo = 0, hi = P - 1;                      // largest p with shard_off[p] <= j
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if (L.shard_off[mid] <= j) lo = mid; else hi = mid - 1;
             }
-            a.dst_tok_off[j] = d;
-            const int64_t gs = L.gpre[cur_start >= 0 ? cur_start : 0];
-            a.cu_seqlens[j + m] = (int32_t)(g - gs);
-            const bool closes = (j + 1 == N) || start_bit(L, j + 1);
-            if (closes) a.cu_seqlens[j + m + 1] = (int32_t)(L.gpre[j + 1] - gs);
+            d = g + (L.shard_base[lo] - L.gpre[L.shard_off[lo]]);
         }
-    }
+        if (whole || jr < N) {
+            a.dst_tok_off[(uint32_t)j] = d;
+            a.mb_seq_off[(uint32_t)m] = first;
+            a.cu_seqlens[(uint32_t)(j + m)] = (int32_t)((uint32_t)g - g_first);
+            a.cu_seqlens[(uint32_t)(j + m) + 1u] = (int32_t)(g_next - g_first);
+        }
+    };
+#pragma unroll 4
+    for (int q = 0; q < whole_steps; ++q) slot_out(q, true);
+    if (whole_steps < nb) slot_out(whole_steps, false);
     for (int p = tid; p <= P; p += PLAN_BLOCK) {         // micro-batches before each shard's first slot
         const int js = L.shard_off[p];
         int32_t c = M;
