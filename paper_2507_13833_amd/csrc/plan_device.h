@@ -137,13 +137,16 @@ __device__ __forceinline__ void plan_body(PlanLds& L, const PlanArgs& a, int32_t
     // search gallops outwards from that guess and bisects what is left (a few probes of the prefix
     // instead of log2 N per hop; the hops of a shard are one dependent chain).
     if (P <= PLAN_WAVES * 4) {
-        // Few shards: a group of 64, 32 or 16 LANES walks a shard (every wave takes 1, 2 or 4 shards).  A
+        // Few shards: a group of 32 or 16 LANES walks a shard (every wave takes 2 or 4 shards).  A
         // hop probes G slots at once, one per lane: the prefix sums do not decrease, so the lanes that still fit
         // are a prefix of the group and a ballot counts them - one LDS round trip per window where the
-        // dependent probes of a bisection take six to eight.
-        const int spw = P <= PLAN_WAVES ? 1 : (P <= 2 * PLAN_WAVES ? 2 : 4);     // shards per wave
+        // dependent probes of a bisection take six to eight.  (Not a whole wave per shard, even where there are
+        // waves enough: a hop costs a wave the same instructions whatever its groups' width, sixteen waves
+        // walking at once are bound by the compute unit's issue rate, and eight or fewer by a hop's latency,
+        // which is the shorter of the two.)
+        const int spw = P <= PLAN_WAVES ? 2 : 4;             // shards per wave
         const int G = WAVE / spw, g = lane / G, gl = lane - g * G;
-        const int lg_G = spw == 1 ? 6 : (spw == 2 ? 5 : 4);
+        const int lg_G = spw == 2 ? 5 : 4;
         const uint64_t group_mask = (G == WAVE ? ~0ull : (1ull << G) - 1ull);
         const int p = w * spw + g;
         if (p < P) {
