@@ -33,6 +33,7 @@ struct BalLds {
     uint32_t tmp32[16];
     int32_t  spare[2];                    // where lanes without a worker put the stores of a round
     alignas(16) uint32_t nowhere[4];      // where a lane with nothing to store puts a 16-byte store
+    int32_t  turn;                        // bin_sort_packed: the wave whose turn it is to count
     uint64_t tmp64[BAL_WAVES];
 };
 static_assert(sizeof(uint32_t) * 256 * BAL_WAVES >= 2 * sizeof(uint64_t) * DC_MAX_SHARDS, "two key tables fit the counters");
@@ -118,20 +119,20 @@ __device__ __forceinline__ void counting_pass(BalLds& L, int N, int rounds, Digi
 // each rank every item among its wave's 64 by eight ballots: a bin per length value (bin b = longest - length,
 // 16 bits wide, two to a word, in the LDS that the rows of the workers take over afterwards) is counted by
 // atomic adds whose return value is the item's ticket within its bin, the bins are scanned, and start + ticket
-// is a place inside the run of the item's length.  Tickets come in no particular order, so a last step puts
-// every run of more than one item in index order: the thread at a place counts the words of the place's run
-// that are larger than the one it found there (a run is followed by shorter lengths, that is by smaller
-// words, and the words after the last item are zero, so the count may run past the run's end in steps of
-// four; neighbouring lanes stand in the same run and read the same words, which the LDS serves as one).
-// Lengths of a real batch repeat a few times each; false (and out[] undefined) if some length occurs more than
-// BIN_RUN_MAX times, where the counting would take longer than the radix passes.  range = longest - shortest,
-// at most BIN_RANGE_MAX; the caller has zeroed the BIN_WORDS words from L.keys on, with a barrier since.
-// Every lane of the workgroup must call it; len[q] = length of sequence q * BAL_BLOCK + tid, unchanged where the
-// result is false and used up otherwise.
+// is the item's place.  The order inside a run of one length is the order of the tickets.  The waves count one
+// after the other, wave w holding the w-th stretch of the sequences, a wave's LDS operations execute in the
+// order it issues them, and the adds of one instruction that meet in a word take effect in lane order: the last
+// of these is what the chip is seen to do, not what it is documented to do, so the result is checked (two
+// neighbours of one length in the wrong order, anywhere) and a list that fails is sorted by the radix passes
+// like one that the bins do not serve.  false (and out[] undefined) in that case, and if some length occurs more
+// than BIN_RUN_MAX times (adds that meet in one word take effect one by one): the caller then sorts by radix passes.
+// range = longest - shortest, at most BIN_RANGE_MAX; the caller has zeroed the BIN_WORDS words from L.keys on
+// and L.turn, with a barrier since.  Every lane of the workgroup must call it; len[q] = length of sequence
+// bal_item(q, rounds), unchanged where the result is false and used up otherwise.
 constexpr int BIN_WORDS = DC_MAX_SEQ + PLACE_PAD + 256 * CNT_PITCH;
 constexpr int BIN_QUADS = (BIN_WORDS / 4 + BAL_BLOCK - 1) / BAL_BLOCK;      // 16-byte pieces of the bins per thread, at most
 constexpr uint32_t BIN_RANGE_MAX = 2u * BIN_WORDS - 4u;
-constexpr uint32_t BIN_RUN_MAX = 32;
+constexpr uint32_t BIN_RUN_MAX = 1024;
 constexpr int BIN_GROUP = 4;                                      // items a thread handles as one straight piece of code
 static_assert(offsetof(BalLds, cnt) == sizeof(int32_t) * (DC_MAX_SEQ + PLACE_PAD), "the counters follow the keys");
 static_assert(DC_MAX_SEQ < (1 << 15), "a place, and the sum of the counts, fit 16 bits with room to spare");
@@ -141,6 +142,14 @@ __device__ __forceinline__ void bin_sort_clear(BalLds& L) {
     static_assert(BIN_WORDS % 4 == 0 && offsetof(BalLds, keys) % 16 == 0, "whole 16-byte pieces");
     uint4* z = reinterpret_cast<uint4*>(L.keys);
     for (int j = threadIdx.x; j < BIN_WORDS / 4; j += BAL_BLOCK) z[j] = make_uint4(0u, 0u, 0u, 0u);
+    if (threadIdx.x == 0) L.turn = 0;
+}
+
+// Which sequence a thread's q-th length register stands for: wave w holds the `rounds` * 64 consecutive sequences
+// from w * rounds * 64 on, 64 of them per register, so that (wave, register, lane) order is index order.
+__device__ __forceinline__ int bal_item(int q, int rounds) {
+    const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
+    return (w * rounds + q) * WAVE + lane;
 }
 
 __device__ __forceinline__ bool bin_sort_packed(BalLds& L, int N, uint32_t longest, uint32_t range,
@@ -154,22 +163,48 @@ __device__ __forceinline__ bool bin_sort_packed(BalLds& L, int N, uint32_t longe
     uint32_t* bins = reinterpret_cast<uint32_t*>(L.keys);
     const int nw = (int)((range + 4u) >> 1);                      // bins 0 .. range, one more for the end of the last run
     const int rounds = (N + BAL_BLOCK - 1) / BAL_BLOCK;           // (uniform: the q that have items at all)
-    // one register per item: the length in the low half, the ticket above it
+    // The count, wave after wave: a wave's LDS operations execute in the order it issues them, and the adds of one
+    // instruction that meet in a word take effect in lane order (measured; nothing below relies on it, see the
+    // check behind the scatter), so with the waves taking turns a bin's tickets rise with the sequence index and
+    // every run of one length comes out of the scatter in index order.  A wave passes the turn on with a store
+    // issued behind its adds, not behind their results.
+    // One register per item: the length in the low half, the ticket above it.
+    {
+        // (what the adds need is worked out before the wave's turn comes: the turn itself is the adds and nothing else)
+        uint32_t word[BAL_ROUNDS];                                // byte offset of the bin's word
+        uint32_t old[BAL_ROUNDS];                                 // first what to add, then what the add returned
 #pragma unroll
-    for (int g = 0; g < BAL_ROUNDS; g += BIN_GROUP) {
-        if (g < rounds) {
-            uint32_t old[BIN_GROUP];
+        for (int q = 0; q < BAL_ROUNDS; ++q) {
+            const bool mine = q < rounds && bal_item(q, rounds) < N;
+            const uint32_t b = mine ? longest - (uint32_t)len[q] : 0u;
+            word[q] = 4u * (mine ? b >> 1 : (uint32_t)min(lane, nw - 1));
+            old[q] = mine ? ((b & 1u) ? 0x10000u : 1u) : 0u;
+            asm volatile("" : "+v"(word[q]), "+v"(old[q]));       // (here, not behind the wait)
+        }
+        const int wv = __builtin_amdgcn_readfirstlane(tid / WAVE);
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+        while (__hip_atomic_load(&L.turn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < wv) __builtin_amdgcn_s_sleep(1);
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+        // (one straight run of adds, of all the registers or of their first half: a register without items adds nothing)
+        auto add = [&](int q) { old[q] = atomicAdd(reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(bins) + word[q]), old[q]); };
+        if (rounds > BAL_ROUNDS / 2) {
 #pragma unroll
-            for (int q = g; q < g + BIN_GROUP; ++q) {
-                const bool mine = q * BAL_BLOCK + tid < N;
-                const uint32_t b = mine ? longest - (uint32_t)len[q] : 0u;
-                const uint32_t one = (b & 1u) ? 0x10000u : 1u;
-                old[q - g] = atomicAdd(&bins[mine ? b >> 1 : (uint32_t)min(lane, nw - 1)], mine ? one : 0u);
-            }
+            for (int q = 0; q < BAL_ROUNDS; ++q) add(q);
+        } else {
 #pragma unroll
-            for (int q = g; q < g + BIN_GROUP; ++q) {
-                const bool odd = ((longest - (uint32_t)len[q]) & 1u) != 0u;
-                len[q] |= (int32_t)(odd ? old[q - g] & 0xFFFF0000u : old[q - g] << 16);
+            for (int q = 0; q < BAL_ROUNDS / 2; ++q) add(q);
+        }
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+        if (lane == 0) __hip_atomic_store(&L.turn, wv + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+#pragma unroll
+        for (int g = 0; g < BAL_ROUNDS; g += BIN_GROUP) {
+            if (g < rounds) {
+#pragma unroll
+                for (int q = g; q < g + BIN_GROUP; ++q) {
+                    const bool odd = ((longest - (uint32_t)len[q]) & 1u) != 0u;
+                    len[q] |= (int32_t)(odd ? old[q] & 0xFFFF0000u : old[q] << 16);
+                }
             }
         }
     }
@@ -221,60 +256,52 @@ __device__ __forceinline__ bool bin_sort_packed(BalLds& L, int N, uint32_t longe
         const uint32_t start = (b & 1u) ? wa >> 16 : wa & 0xFFFFu;
         return start | ((((b & 1u) ? wb & 0xFFFFu : wa >> 16) - start) << 16);
     };
-    constexpr int PAD_READ = (int)BIN_RUN_MAX + 4 + 4;            // how far beyond the last item the counting below may read
-    static_assert(PAD_READ <= 128 && 128 + 1 <= PLACE_PAD, "the zeroed words and the spare word lie in the array's padding");
+    static_assert(128 + 1 <= PLACE_PAD, "the zeroed words and the spare word lie in the array's padding");
 #pragma unroll
     for (int g = 0; g < BAL_ROUNDS; g += BIN_GROUP) {
         if (g < rounds) {
             uint32_t at[BIN_GROUP];
 #pragma unroll
             for (int q = g; q < g + BIN_GROUP; ++q) {
-                const bool mine = q * BAL_BLOCK + tid < N;
+                const bool mine = q < rounds && bal_item(q, rounds) < N;
                 at[q - g] = run_of(mine ? longest - ((uint32_t)len[q] & 0xFFFFu) : 0u);
             }
 #pragma unroll
             for (int q = g; q < g + BIN_GROUP; ++q) {
-                const int i = q * BAL_BLOCK + tid;
+                const int i = bal_item(q, rounds);
                 const uint32_t to = (at[q - g] & 0xFFFFu) + ((uint32_t)len[q] >> 16);
-                out[i < N ? to : (uint32_t)N + 128u] = ((uint32_t)len[q] << 16) | (uint32_t)i;
+                out[(q < rounds && i < N) ? to : (uint32_t)N + 128u] = ((uint32_t)len[q] << 16) | (uint32_t)i;
             }
         }
     }
     out[N + (tid & 127)] = 0;
     __syncthreads();
-    // index order inside the runs; from here on a thread looks after places q * BAL_BLOCK + tid, not after its
-    // sequences (a place beyond the last one repeats the last one's work)
-    uint32_t goes[BAL_ROUNDS];
+    // Is every run in index order?  (A thread looks at places q * BAL_BLOCK + tid here, not at its sequences; a
+    // place beyond the last one repeats the last one's work.)
+    {
+        bool wrong = false;
 #pragma unroll
-    for (int g = 0; g < BAL_ROUNDS; g += BIN_GROUP) {
-        if (g < rounds) {
-            uint32_t ss[BIN_GROUP];
+        for (int g = 0; g < BAL_ROUNDS; g += BIN_GROUP) {
+            if (g < rounds) {
 #pragma unroll
-            for (int q = g; q < g + BIN_GROUP; ++q) len[q] = (int32_t)out[min(q * BAL_BLOCK + tid, N - 1)];
-#pragma unroll
-            for (int q = g; q < g + BIN_GROUP; ++q) ss[q - g] = run_of(longest - ((uint32_t)len[q] >> 16));
-#pragma unroll
-            for (int q = g; q < g + BIN_GROUP; ++q) {             // (one place at a time: the LDS is the limit here, not its latency)
-                const uint32_t e = (uint32_t)len[q], start = ss[q - g] & 0xFFFFu, size = ss[q - g] >> 16;
-                const uint32_t end = size > 1u ? start + size : start;                // (nothing to count for a run of one)
-                uint32_t above = 0;
-                for (uint32_t j = start; j < end; j += 4) {       // (past a run's end nothing is larger)
-                    above += (out[j] > e ? 1u : 0u) + (out[j + 1] > e ? 1u : 0u) + (out[j + 2] > e ? 1u : 0u) + (out[j + 3] > e ? 1u : 0u);
+                for (int q = g; q < g + BIN_GROUP; ++q) {
+                    const int at = min(q * BAL_BLOCK + tid, N - 1);
+                    const uint32_t a = out[at], b = out[at + 1];
+                    wrong |= ((a ^ b) < 0x10000u) && a > b;
                 }
-                goes[q] = start + size - 1u - above;
             }
         }
-    }
-    __syncthreads();
+        const bool here = __ballot(wrong) != 0ull;
+        if (lane == 0) L.red[tid / WAVE] = here ? 1 : 0;
+        __syncthreads();
+        int any = 0;
 #pragma unroll
-    for (int g = 0; g < BAL_ROUNDS; g += BIN_GROUP) {
-        if (g < rounds) {
-#pragma unroll
-            for (int q = g; q < g + BIN_GROUP; ++q) out[goes[q]] = (uint32_t)len[q];
-        }
+        for (int i = 0; i < BAL_WAVES; ++i) any |= L.red[i];
+        if (!any) return true;                                    // (uniform)
     }
-    __syncthreads();
-    return true;
+#pragma unroll
+    for (int q = 0; q < BAL_ROUNDS; ++q) len[q] &= 0xFFFF;
+    return false;
 }
 
 // The assignment rounds (wave 0 only).  WIDTH = 16, 32 or 64 >= P lanes take part in the sort.
@@ -1009,14 +1036,15 @@ __device__ __forceinline__ void balance_body_t(BalLds& L, int32_t N, int32_t P, 
     const bool tight = pitch != 0 && (P == 16 || P == 32 || P == 64);
     if (tight) bin_sort_clear(L);                                 // (uniform; the barrier below stands between this and the bins' use)
 
-    // ---- load lengths, range ----
+    // ---- load lengths, range (register q of a thread: sequence bal_item(q, rounds)) ----
+    const int rounds = (N + BAL_BLOCK - 1) / BAL_BLOCK;           // <= BAL_ROUNDS
     int32_t mx = 0, mn = INT32_MAX;
     int32_t mine_len[BAL_ROUNDS];
 #pragma unroll
     for (int q = 0; q < BAL_ROUNDS; ++q) {
-        const int i = q * BAL_BLOCK + tid;
+        const int i = bal_item(q, rounds);
         mine_len[q] = 1;
-        if (i < N) {
+        if (q < rounds && i < N) {
             int32_t s = seq_len[i];
             if (s <= 0 || s > DC_MAX_SEQ_LEN) { set_status(status, DC_ERR_ZERO_LENGTH_SEQ); s = 1; }
             mine_len[q] = s;
@@ -1037,7 +1065,6 @@ __device__ __forceinline__ void balance_body_t(BalLds& L, int32_t N, int32_t P, 
     const uint32_t range = N > 0 ? (uint32_t)(mx - mn) : 0u;
     const int nbits = 32 - __clz(range | 1u);
     const int passes = range == 0 ? 0 : (nbits + 7) / 8;
-    const int rounds = (N + BAL_BLOCK - 1) / BAL_BLOCK;           // <= BAL_ROUNDS
     int32_t* part_off = reinterpret_cast<int32_t*>(L.cnt) + PART_OFF_AT;
     int32_t* placed = reinterpret_cast<int32_t*>(L.cnt) + PLACED_AT;
 
@@ -1056,8 +1083,8 @@ __device__ __forceinline__ void balance_body_t(BalLds& L, int32_t N, int32_t P, 
         } else {
 #pragma unroll
             for (int q = 0; q < BAL_ROUNDS; ++q) {
-                const int i = q * BAL_BLOCK + tid;
-                if (i < N) src[i] = ((uint32_t)mine_len[q] << 16) | (uint32_t)i;
+                const int i = bal_item(q, rounds);
+                if (q < rounds && i < N) src[i] = ((uint32_t)mine_len[q] << 16) | (uint32_t)i;
             }
             __syncthreads();
             for (int pass = 0; pass < passes; ++pass) {
@@ -1115,8 +1142,8 @@ __device__ __forceinline__ void balance_body_t(BalLds& L, int32_t N, int32_t P, 
 
 #pragma unroll
     for (int q = 0; q < BAL_ROUNDS; ++q) {
-        const int i = q * BAL_BLOCK + tid;
-        if (i < N) L.keys[i] = mine_len[q];
+        const int i = bal_item(q, rounds);
+        if (q < rounds && i < N) L.keys[i] = mine_len[q];
     }
     // ---- a) radix sort of indices by (mx - len) ascending, stable ----
     for (int i = tid; i < N; i += BAL_BLOCK) L.idx_a[i] = (uint16_t)i;

@@ -489,11 +489,12 @@ def test_partition_sizes_and_worker_counts():
 
 def test_one_pass_sort_of_the_packed_path():
     """16, 32 or 64 workers, equal partitions, lengths below 2^16: the sorted list comes from one counting pass
-    over a bin per length (tickets from atomic adds, then index order restored inside every run of one length),
-    with the two radix passes as the way out.  Cases: runs of one length at, just below and just above the
-    limit of the one-pass sort; the shortest length (the last run, followed by the array's padding) as the
-    most frequent; few distinct lengths (always the way out); a range of lengths at and beyond what the bins
-    hold; batches that are no multiple of the workgroup, smaller than a wavefront, and the largest."""
+    over a bin per length (tickets from atomic adds issued in index order, wave after wave, and a check of the
+    result), with the two radix passes as the way out.  Cases: runs of one length at, just below and just above
+    the limit of the one-pass sort, and long runs below it (many adds meeting in one word); the shortest length
+    (the last run, followed by the array's padding) as the most frequent; few distinct lengths (always the way
+    out); a range of lengths at and beyond what the bins hold; batches that are no multiple of the workgroup,
+    smaller than a wavefront, and the largest."""
     torch, binding, runner = _gpu()
     rng = np.random.default_rng(61)
 
@@ -516,7 +517,7 @@ def test_one_pass_sort_of_the_packed_path():
         lens = np.concatenate([np.repeat(vals[: (n - run) // 3 + 1], 3)[: n - run], np.full(run, hi + 7)])
         return rng.permutation(lens)
 
-    for run in (31, 32, 33, 64, 65):
+    for run in (2, 33, 64, 65, 700, 1023, 1024, 1025):
         check(with_runs(64 * 64, run), 64, f"a run of {run}")
     lens = with_runs(32 * 100, 30)
     lens[lens == lens.max()] = 5                                       # the longest run is the last one
