@@ -133,6 +133,7 @@ constexpr int BIN_WORDS = DC_MAX_SEQ + PLACE_PAD + 256 * CNT_PITCH;
 constexpr int BIN_QUADS = (BIN_WORDS / 4 + BAL_BLOCK - 1) / BAL_BLOCK;      // 16-byte pieces of the bins per thread, at most
 constexpr uint32_t BIN_RANGE_MAX = 2u * BIN_WORDS - 4u;
 constexpr uint32_t BIN_RUN_MAX = 1024;
+constexpr int BIN_SPINS = 1 << 16;                               // looks at the turn word before a wave stops waiting (a turn takes two)
 constexpr int BIN_GROUP = 4;                                      // items a thread handles as one straight piece of code
 static_assert(offsetof(BalLds, cnt) == sizeof(int32_t) * (DC_MAX_SEQ + PLACE_PAD), "the counters follow the keys");
 static_assert(DC_MAX_SEQ < (1 << 15), "a place, and the sum of the counts, fit 16 bits with room to spare");
@@ -183,7 +184,9 @@ __device__ __forceinline__ bool bin_sort_packed(BalLds& L, int N, uint32_t longe
         }
         const int wv = __builtin_amdgcn_readfirstlane(tid / WAVE);
         __atomic_signal_fence(__ATOMIC_SEQ_CST);
-        while (__hip_atomic_load(&L.turn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < wv) __builtin_amdgcn_s_sleep(1);
+        // (the wait is bounded: a wave that gave up would count out of turn, which the check below would see)
+        for (int spins = 0; spins < BIN_SPINS && __hip_atomic_load(&L.turn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < wv; ++spins)
+            __builtin_amdgcn_s_sleep(1);
         __atomic_signal_fence(__ATOMIC_SEQ_CST);
         // (one straight run of adds, of all the registers or of their first half: a register without items adds nothing)
         auto add = [&](int q) { old[q] = atomicAdd(reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(bins) + word[q]), old[q]); };
