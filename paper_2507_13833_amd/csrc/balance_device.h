@@ -133,7 +133,7 @@ constexpr int BIN_WORDS = DC_MAX_SEQ + PLACE_PAD + 256 * CNT_PITCH;
 constexpr int BIN_QUADS = (BIN_WORDS / 4 + BAL_BLOCK - 1) / BAL_BLOCK;      // 16-byte pieces of the bins per thread, at most
 constexpr uint32_t BIN_RANGE_MAX = 2u * BIN_WORDS - 4u;
 constexpr uint32_t BIN_RUN_MAX = 1024;
-constexpr int BIN_SPINS = 1 << 16;                               // looks at the turn word before a wave stops waiting (a turn takes two)
+constexpr int BIN_SPINS = 1 << 16;                               // looks at the turn word before a wave stops waiting (the last wave needs ~30)
 constexpr int BIN_GROUP = 4;                                      // items a thread handles as one straight piece of code
 static_assert(offsetof(BalLds, cnt) == sizeof(int32_t) * (DC_MAX_SEQ + PLACE_PAD), "the counters follow the keys");
 static_assert(DC_MAX_SEQ < (1 << 15), "a place, and the sum of the counts, fit 16 bits with room to spare");
