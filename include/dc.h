@@ -206,7 +206,7 @@ dc_status dc_balance_group_advantage(const dc_params* prm, const dc_source* src,
  * same results, same device errors, every argument checked before anything is enqueued): the three
  * steps that come before the data movement in the re-partitioning of Sec. 6 - Algorithm 1 ("Load
  * Balancing"), the advantage stage, and the layout the "Distributed Databuffer" redistributes into.
- * With Algorithm 1 as printed (cap = 0 or cap * P = N) on 16, 32 or 64 shards and up to DC_MAX_SEQ
+ * With Algorithm 1 as printed (cap = 0 or cap * P = N) on 1 .. 32 or on 64 shards and up to DC_MAX_SEQ
  * sequences, the plan runs as the tail of the workgroup that balances: that workgroup holds every output
  * slot's sequence and length when it is done, which is all the plan reads.  Two launches instead of
  * five; dc_gather (or dc_gather_advantage) follows as after dc_plan.  Other shapes: the two calls one after

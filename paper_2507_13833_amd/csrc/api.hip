@@ -237,8 +237,8 @@ dc_status dc_balance_plan_group_advantage(const dc_params* prm, const dc_source*
     if (ws_bytes < ws.bytes) return DC_ERR_WORKSPACE;
     if (ws.n_gran > 0x7FFFFFFFLL) return DC_ERR_UNSUPPORTED_SIZE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    // the printed algorithm on 16, 32 or 64 workers: the plan runs as the tail of the balance workgroup
-    const bool one_launch = prm->n_seq > 0 && (prm->n_shards == 16 || prm->n_shards == 32 || prm->n_shards == 64) &&
+    // the printed algorithm on up to 32 or on 64 workers: the plan runs as the tail of the balance workgroup
+    const bool one_launch = prm->n_seq > 0 && (prm->n_shards <= 32 || prm->n_shards == 64) &&
                             (int64_t)cap_eff * prm->n_shards == prm->n_seq;
     if (!one_launch) {
         rc = dc_balance_group_advantage(prm, src, d_seq_len, d_perm, d_shard_seq_off, d_shard_of_seq, d_shard_load, d_reward,

@@ -120,7 +120,7 @@ hipError_t launch_balance_plan_advantage(int32_t n_seq, int32_t n_shards, int32_
                                          int64_t* d_shard_load, const PlanArgs& plan, const AdvArgs& adv,
                                          const SourceDesc& src, int32_t n_groups, int32_t* d_status, hipStream_t st) {
     // (the kernel holds the code of these shapes only)
-    if (!(n_shards == 16 || n_shards == 32 || n_shards == 64) || (int64_t)cap_eff * n_shards != n_seq || n_seq <= 0 || n_seq > DC_MAX_SEQ)
+    if (!((n_shards >= 1 && n_shards <= 32) || n_shards == 64) || (int64_t)cap_eff * n_shards != n_seq || n_seq <= 0 || n_seq > DC_MAX_SEQ)
         return hipErrorInvalidValue;
     BalanceArgs b;
     b.N = n_seq; b.P = n_shards; b.C = cap_eff; b.seq_len = d_seq_len; b.perm = d_perm;

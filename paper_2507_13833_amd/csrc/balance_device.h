@@ -492,7 +492,7 @@ __device__ __forceinline__ int lpt_rounds(int N, int P, int C, int32_t* keys, co
 }
 
 // ---------------------------------------------------------------------------------------------------
-// The rounds once more for the printed algorithm on 16, 32 or 64 workers (P == WIDTH, N == P * C) with
+// The rounds once more for the printed algorithm on up to 32 or on 64 workers (P <= WIDTH = 16 or 32, or P = 64; N == P * C) with
 // lengths below 2^16: the common case, and the one in which the rounds are most of the kernel's time.
 //
 // A round of one wave is the sort of the 64 updated keys, a chain of dependent instructions with idle
@@ -555,7 +555,13 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
     const int check_every = (int)min(64u, fit - 2u);
     int until_check = 1;
     const uint32_t full = KEY_FULL | lane;
-    const bool mine_exists = (int)lane < P;                       // lane k keeps worker k (P == WIDTH)
+    const bool mine_exists = (int)lane < P;                       // lane k keeps worker k, and plays rank k of the sorted order
+    // WIDTH 64: P == 64.  WIDTH 16 and 32: any P <= WIDTH; the keys of the lanes without a worker sort behind the
+    // workers' and must stay where they are, so what is offered to their ranks is nothing: those lanes read the
+    // zero word behind the last item, round after round (a stride of their own, no instruction more per round).
+    constexpr bool SOME = WIDTH != WAVE && !PORTION;
+    const bool offers = !SOME || mine_exists;
+    const int stride = offers ? P : 0;                            // from a rank's item of one round to its item of the next
     const uint64_t everyone = P == WAVE ? ~0ull : (1ull << P) - 1ull;
     constexpr bool EVERY_LANE = WIDTH == WAVE;
     constexpr int NS = net_steps(WIDTH);
@@ -566,7 +572,7 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
     if constexpr (PORTION) { key = carry->key; count = carry->count; load = carry->load; }
     const int32_t row_base = count;                               // PORTION: my row's first entry is my item number row_base
     int pos = 0;
-    uint32_t e = items[lane];                                     // the item offered to rank `lane` (the array is padded)
+    uint32_t e = items[offers ? (int)lane : N];                   // the item offered to rank `lane` (the array is padded with zeros)
     bool all_take = C > 0;
     if constexpr (PORTION) all_take = __ballot(mine_exists && key >= KEY_FULL) == 0ull;
     const uint32_t pitch4 = (uint32_t)pitch * 4u;
@@ -601,7 +607,7 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
             // >= 1: until a worker (PORTION: or a row) is full or the items run out
             const int n_rounds = PORTION ? min(min(C - __builtin_amdgcn_readfirstlane((int)gmax), row_cap - c_hi), (N - pos) / P)
                                          : min(C - c_hi, (N - pos) / P);
-            const uint32_t* next_item = items + pos + P + (int)lane;       // the item of the next round for this rank
+            const uint32_t* next_item = offers ? items + pos + P + (int)lane : items + N;      // the item of the next round for this rank
             int32_t count4 = in_row * 4;                          // lane k: 4 x (worker k's place in its row at round 0 of the phase)
             uint64_t refused_acc = 0;                             // ranks a refused round would have accepted
 
@@ -617,7 +623,7 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
                     constexpr int S = decltype(slot)::value;
                     if constexpr (S == 0) e1 = *next_item;
                     if constexpr (S == 1 && !LEVEL) before4 = __builtin_amdgcn_ds_bpermute((int)(id << 2), count4);
-                    if constexpr (S == 3) next_item += P;
+                    if constexpr (S == 3) next_item += stride;
                     if constexpr (S == 8) {
                         char* at = rows_b + (__umul24(id, pitch4) + (uint32_t)before4 + row_at);
                         if constexpr (!EVERY_LANE) at = mine_exists ? at : spare_b;
@@ -657,7 +663,7 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
                 });
                 const uint64_t acc = __ballot(sk_in < m) & everyone;
                 if (__builtin_expect(acc != everyone, 0)) { e = e_in; refused_acc = acc; return false; }
-                next_item += P;
+                next_item += stride;
                 sk = v;
                 return true;
             };
@@ -670,7 +676,7 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
                 const bool take = (int)lane < took;
                 uint32_t v = take ? sk + ((e >> 16) << 6) : sk;
                 const uint32_t to = mine_exists ? (sk & 63u) : lane;        // lanes without a worker talk to themselves
-                const uint32_t* const at = items + pos + took + (int)lane;  // (the array is padded)
+                const uint32_t* const at = offers ? items + pos + took + (int)lane : items + N;      // (the array is padded)
                 uint32_t e1 = 0;
                 int32_t behind4 = 0;
                 v = wave_sort_steps<WIDTH, 0, NS>(v, [&](auto slot) {
@@ -680,7 +686,7 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
                     if constexpr (S == 12) { count4 -= behind4; e = e1; }
                 });
                 sk = v;
-                next_item = at + P;
+                next_item = at + stride;
                 pos += took;
             };
 
@@ -700,7 +706,7 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
                 const int may = min(n_rounds - rounds, until_check) / FAST_BATCH;      // batches before the phase ends / the next check
                 if (may > 0 && --no_look < 0) {
                     const uint32_t k_lo = (uint32_t)__builtin_amdgcn_readlane((int)sk, 0);
-                    const uint32_t k_hi = (uint32_t)__builtin_amdgcn_readlane((int)sk, WIDTH - 1);
+                    const uint32_t k_hi = (uint32_t)__builtin_amdgcn_readlane((int)sk, P - 1);        // (the workers' largest)
                     const uint32_t first = (uint32_t)__builtin_amdgcn_readlane((int)e, 0) >> 16;
                     const uint32_t need = max((k_hi - k_lo) >> 6, first >> 1);
                     const uint32_t probe = items[min(pos + ((int)lane + 1) * (FAST_BATCH * P) - 1, N - 1)] >> 16;
@@ -784,7 +790,7 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
             key = (count == C) ? full : nk;
         }
         pos += m;
-        e = next_e;
+        e = offers ? next_e : 0u;
         all_take = __ballot(mine_exists && key >= KEY_FULL) == 0ull;      // every worker is open: the next round is tried above
     }
     if (mine_exists) shard_load[lane] = load;
@@ -1024,7 +1030,7 @@ struct SlotRegs {
     int32_t len[BAL_ROUNDS];
 };
 
-// FILL (only with P in {16, 32, 64} and P * C == N): also fill slots; the code of other shapes is left out (the
+// FILL (only with P <= 32 or P == 64, and P * C == N): also fill slots; the code of other shapes is left out (the
 // kernel is executed once from front to back, most of it straight code that the instruction cache has not seen,
 // and its size shows in its time).
 template <bool FILL>
@@ -1036,7 +1042,8 @@ __device__ __forceinline__ void balance_body_t(BalLds& L, int32_t N, int32_t P, 
 
     // every partition ends with exactly C items (Algorithm 1 as printed: C = N / K): rows per worker
     const int pitch = (P <= WAVE && C > 0 && (int64_t)P * C == N) ? place_pitch(C) : 0;
-    const bool tight = pitch != 0 && (P == 16 || P == 32 || P == 64);
+    const bool tight = pitch != 0 && (P <= 32 || P == 64);                  // what the packed rounds serve
+    const bool exact = pitch != 0 && (P == 16 || P == 32 || P == 64);      // a worker in every lane of a 16-, 32- or 64-lane sort
     if (tight) bin_sort_clear(L);                                 // (uniform; the barrier below stands between this and the bins' use)
 
     // ---- load lengths, range (register q of a thread: sequence bal_item(q, rounds)) ----
@@ -1071,7 +1078,7 @@ __device__ __forceinline__ void balance_body_t(BalLds& L, int32_t N, int32_t P, 
     int32_t* part_off = reinterpret_cast<int32_t*>(L.cnt) + PART_OFF_AT;
     int32_t* placed = reinterpret_cast<int32_t*>(L.cnt) + PLACED_AT;
 
-    // ---- the printed algorithm on 16, 32 or 64 workers with lengths below 2^16 (lpt_rounds_packed) ----
+    // ---- the printed algorithm on up to 32 or on 64 workers with lengths below 2^16 (lpt_rounds_packed) ----
     // One word per sequence, length << 16 | index, is all that is kept: the sort moves those words between
     // the two halves of the LDS (a pass takes its digit from the word it moves, not from a table of lengths),
     // the rounds read them in sorted order, and the half the sort ends in leaves the other one to the workers'
@@ -1107,8 +1114,8 @@ __device__ __forceinline__ void balance_body_t(BalLds& L, int32_t N, int32_t P, 
             int32_t* worker_count = reinterpret_cast<int32_t*>(L.cnt) + WCOUNT_AT;
             uint32_t* spare = reinterpret_cast<uint32_t*>(L.spare);
             int n_placed;
-            if (P == 16) n_placed = lpt_rounds_packed<16>(N, P, C, items, mx, rows, rpitch, spare, worker_count, shard_load);
-            else if (P == 32) n_placed = lpt_rounds_packed<32>(N, P, C, items, mx, rows, rpitch, spare, worker_count, shard_load);
+            if (P <= 16) n_placed = lpt_rounds_packed<16>(N, P, C, items, mx, rows, rpitch, spare, worker_count, shard_load);
+            else if (P <= 32) n_placed = lpt_rounds_packed<32>(N, P, C, items, mx, rows, rpitch, spare, worker_count, shard_load);
             else n_placed = lpt_rounds_packed<64>(N, P, C, items, mx, rows, rpitch, spare, worker_count, shard_load);
             const int32_t c = worker_count[lane];
             const int32_t inc = (int32_t)wave_incl_scan_add_u32((uint32_t)c);
@@ -1163,7 +1170,7 @@ __device__ __forceinline__ void balance_body_t(BalLds& L, int32_t N, int32_t P, 
     const uint16_t* sorted = src;                                 // I of Algorithm 1
     uint16_t* step_slot = dst;                                    // place of I[t] inside its worker's partition
     // ---- b) assignment rounds: wave 0 for up to 64 workers, else the whole workgroup ----
-    // (FILL: the caller has 16, 32 or 64 workers and equal partitions; the other shapes' code stays out of its kernel)
+    // (FILL: the caller has up to 32 or 64 workers and equal partitions; the other shapes' code stays out of its kernel)
     if (!FILL && P > WAVE) {
         if constexpr (!FILL) {
             const int n_placed = lpt_rounds_wide(L, N, P, C, sorted, step_slot, mx, shard_seq_off, shard_load);
@@ -1173,15 +1180,13 @@ __device__ __forceinline__ void balance_body_t(BalLds& L, int32_t N, int32_t P, 
         int32_t* worker_count = reinterpret_cast<int32_t*>(L.cnt) + WCOUNT_AT;
         int32_t* spare = L.spare;
         LptCarry fresh = lpt_fresh(P, C);
-        int n_placed;
-        if (tight && P == 16) n_placed = lpt_rounds<16, true>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
-        else if (tight && P == 32) n_placed = lpt_rounds<32, true>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
-        else if (FILL || tight) n_placed = lpt_rounds<64, true>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
-        else if constexpr (!FILL) {
-            if (P <= 16) n_placed = lpt_rounds<16>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
-            else if (P <= 32) n_placed = lpt_rounds<32>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
-            else n_placed = lpt_rounds<64>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
-        }
+        int n_placed = 0;
+        if (exact && P == 16) n_placed = lpt_rounds<16, true>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
+        else if (exact && P == 32) n_placed = lpt_rounds<32, true>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
+        else if (exact) n_placed = lpt_rounds<64, true>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
+        else if (P <= 16) n_placed = lpt_rounds<16>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
+        else if (P <= 32) n_placed = lpt_rounds<32>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
+        else if constexpr (!FILL) n_placed = lpt_rounds<64>(N, P, C, L.keys, sorted, mx, step_slot, pitch, spare, worker_count, shard_load, fresh);
         // start of every P_k inside perm
         const int32_t c = worker_count[lane];
         const int32_t inc = (int32_t)wave_incl_scan_add_u32((uint32_t)c);

@@ -167,9 +167,15 @@ def test_balance_and_plan_in_one_call_shapes():
     check_step(_custom(np.full(64 * 30, 77), 8, 64, 1024), label="all equal", two_calls=True)
     heavy = np.minimum(64 * (1.0 - rng.random(64 * 64)) ** (-1 / 1.3), 32768).astype(np.int32) + rng.integers(512, 4096, 64 * 64)
     check_step(_custom(heavy, 16, 64, 65536, fields=("i32",)), label="long tail", two_calls=True)
-    # shapes the call hands to the separate kernels: partitions of unequal size, 8 shards, 128 shards
+    # fewer than 32 workers (16- and 32-lane rounds with lanes that offer nothing), also with a length of 2^16 and more
+    for P, C in ((8, 128), (4, 512), (2, 100), (1, 64), (5, 33), (12, 40), (15, 7), (17, 30), (24, 64), (31, 9)):
+        check_step(_custom(np.minimum(rng.geometric(0.004, P * C), 6000), 1, P, 16384), label=f"P={P} C={C}", two_calls=True)
+    lens = rng.integers(1, 3000, 8 * 64).astype(np.int32)
+    lens[3] = 66000
+    check_step(_custom(lens, 4, 8, 1 << 17, fields=("i32",)), label="P=8, a sequence of 66000 tokens", two_calls=True)
+    # shapes the call hands to the separate kernels: partitions of unequal size, 48 shards, 128 shards
     check_step(_custom(rng.integers(1, 500, 1000), 5, 16, 4096), cap=70, label="cap 70", two_calls=True)
-    check_step(_custom(rng.integers(1, 500, 1024), 8, 8, 4096), label="P=8", two_calls=True)
+    check_step(_custom(rng.integers(1, 500, 48 * 40), 8, 48, 4096), label="P=48", two_calls=True)
     check_step(_custom(rng.integers(1, 300, 128 * 20), 8, 128, 2048, n_src=2), label="P=128", two_calls=True)
     # and the training-layout advantage field made by the gather behind it
     w = workloads.make_workload(2, n_shards=16)
