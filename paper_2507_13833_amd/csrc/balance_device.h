@@ -556,7 +556,7 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
     int until_check = 1;
     const uint32_t full = KEY_FULL | lane;
     const bool mine_exists = (int)lane < P;                       // lane k keeps worker k, and plays rank k of the sorted order
-    // WIDTH 64: P == 64.  WIDTH 16 and 32: any P <= WIDTH; the keys of the lanes without a worker sort behind the
+    // WIDTH 64: P == 64.  WIDTH 8, 16 and 32: any P <= WIDTH; the keys of the lanes without a worker sort behind the
     // workers' and must stay where they are, so what is offered to their ranks is nothing: those lanes read the
     // zero word behind the last item, round after round (a stride of their own, no instruction more per round).
     constexpr bool SOME = WIDTH != WAVE && !PORTION;
@@ -565,6 +565,8 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
     const uint64_t everyone = P == WAVE ? ~0ull : (1ull << P) - 1ull;
     constexpr bool EVERY_LANE = WIDTH == WAVE;
     constexpr int NS = net_steps(WIDTH);
+    constexpr int LAST = 2 * NS - 1;                              // the last gap of the sort (what an 8-lane sort has no later gap for goes there)
+    static_assert(LAST >= 11, "the rounds' side work is laid out over twelve gaps at least");
     constexpr uint32_t NONE = 0xFFFFFFFFu;
     uint32_t key = (mine_exists && C > 0) ? lane : full;
     int32_t count = 0;
@@ -629,7 +631,7 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
                         if constexpr (!EVERY_LANE) at = mine_exists ? at : spare_b;
                         *reinterpret_cast<uint32_t*>(at) = e;      // filed with its worker
                     }
-                    if constexpr (S == 12) e = e1;
+                    if constexpr (S == (LAST < 12 ? LAST : 12)) e = e1;
                 });
                 sk = v;
             };
@@ -659,7 +661,7 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
                         *reinterpret_cast<uint32_t*>(at) = e;
                     }
                     if constexpr (S == 11) m = dpp_mov<DPP_WAVE_SHR1>(NONE, m);
-                    if constexpr (S == 13) e = e1;
+                    if constexpr (S == (LAST < 13 ? LAST : 13)) e = e1;
                 });
                 const uint64_t acc = __ballot(sk_in < m) & everyone;
                 if (__builtin_expect(acc != everyone, 0)) { e = e_in; refused_acc = acc; return false; }
@@ -683,7 +685,7 @@ __device__ __forceinline__ int lpt_rounds_packed(int N, int P, int C, const uint
                     constexpr int S = decltype(slot)::value;
                     if constexpr (S == 0) e1 = *at;
                     if constexpr (S == 1) behind4 = __builtin_amdgcn_ds_permute((int)(to << 2), take ? 0 : 4);
-                    if constexpr (S == 12) { count4 -= behind4; e = e1; }
+                    if constexpr (S == (LAST < 12 ? LAST : 12)) { count4 -= behind4; e = e1; }
                 });
                 sk = v;
                 next_item = at + stride;
@@ -1114,7 +1116,8 @@ __device__ __forceinline__ void balance_body_t(BalLds& L, int32_t N, int32_t P, 
             int32_t* worker_count = reinterpret_cast<int32_t*>(L.cnt) + WCOUNT_AT;
             uint32_t* spare = reinterpret_cast<uint32_t*>(L.spare);
             int n_placed;
-            if (P <= 16) n_placed = lpt_rounds_packed<16>(N, P, C, items, mx, rows, rpitch, spare, worker_count, shard_load);
+            if (P <= 8) n_placed = lpt_rounds_packed<8>(N, P, C, items, mx, rows, rpitch, spare, worker_count, shard_load);
+            else if (P <= 16) n_placed = lpt_rounds_packed<16>(N, P, C, items, mx, rows, rpitch, spare, worker_count, shard_load);
             else if (P <= 32) n_placed = lpt_rounds_packed<32>(N, P, C, items, mx, rows, rpitch, spare, worker_count, shard_load);
             else n_placed = lpt_rounds_packed<64>(N, P, C, items, mx, rows, rpitch, spare, worker_count, shard_load);
             const int32_t c = worker_count[lane];
