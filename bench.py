@@ -38,10 +38,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 TRAFFIC_SOURCE = "profiles/hbm_traffic_config5_pmc.txt"
 TRAFFIC = {
     # config: (fetch bytes + write bytes per gather launch, digest of csrc/gather.hip + csrc/dc_internal.h)
-    5: (1044623900 + 985061800, "20a6592dc78a82a9"),
+    5: (1044691600 + 985070200, "20a6592dc78a82a9"),
 }
 TRAFFIC_ADV = {                                          # the same for dc_gather_advantage's kernel
-    5: (867757000 + 983735900, "20a6592dc78a82a9"),
+    5: (867921100 + 983753400, "20a6592dc78a82a9"),
 }
 
 
