@@ -673,6 +673,40 @@ def test_seeded_random_shapes_of_the_balance():
         _check_balance_ws(lens, P, cap=cap, label=f"drawn shape {case}: kind={kind}")
 
 
+def test_seeded_random_shapes_with_fewer_workers_than_lanes():
+    """Twenty-five drawn batches of Algorithm 1 as printed on 1 to 32 workers: the packed rounds on an 8-, 16- or
+    32-lane sort whose upper lanes have no worker, batches from one item per worker to the LDS limit, heavy ties,
+    long tails, and a length of 2^16 or more (the general rounds with the same layout)."""
+    torch, binding, runner = _gpu()
+    rng = np.random.default_rng(2026)
+    for case in range(25):
+        P = int(rng.integers(1, 33))
+        C = int(rng.choice([1, 2, 3, int(rng.integers(4, 200)), int(rng.integers(200, 16384 // P + 1))]))
+        N = P * C
+        kind = int(rng.integers(0, 5))
+        if kind == 0:
+            lens = np.minimum(64 * (1.0 - rng.random(N)) ** (-1 / 1.3), 32768).astype(np.int64) + rng.integers(512, 4096, N)
+        elif kind == 1:
+            lens = rng.integers(1, 6, N)
+        elif kind == 2:
+            lens = np.minimum(rng.geometric(0.002, N), 20000)
+        elif kind == 3:
+            lens = rng.integers(1, 3000, N); lens[int(rng.integers(0, N))] = int(rng.choice([65536, 100000]))
+        else:
+            lens = rng.integers(30000, 65536, N)
+        w = _custom(lens.astype(np.int32), 1, P, 1 << 24, fields=("i32",))
+        d = runner.DeviceBatch(w)
+        d.balance()
+        torch.cuda.synchronize()
+        label = f"drawn shape {case}: P={P} C={C} kind={kind}"
+        assert d.read_status() == 0, label
+        bal = oracle.balance(w.seq_len, P, 0)
+        assert np.array_equal(d.perm.cpu().numpy(), bal.perm), label
+        assert np.array_equal(d.shard_seq_off.cpu().numpy(), bal.shard_seq_off), label
+        assert np.array_equal(d.shard_of_seq.cpu().numpy(), bal.shard_of_seq), label
+        assert np.array_equal(d.shard_load.cpu().numpy(), bal.shard_load), label
+
+
 def test_more_sequences_than_the_lds_holds():
     """The whole path above DC_MAX_SEQ sequences: dc_balance_ws, the plan through workspace memory, and the
     kernels that never cared (advantage, gather, scatter, GAE)."""
